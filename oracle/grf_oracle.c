@@ -1,0 +1,274 @@
+/*
+ * CPU checker for graph-random-feature (GRF) masked linear attention.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+ * method computes, written from the paper (arXiv 2410.03462).  Only the tests, the
+ * smoke check and the benchmark's "cpu_baseline" leg may call it.  It shares no code
+ * with the HIP library and is never a fallback for it.
+ *
+ * Everything is single-threaded, fp64 accumulation, host pointers.
+ *
+ * Parity pins (see tests): Philox against the published known-answer vectors;
+ * walks against the closed-form halting and transition laws; features against
+ * dense matrix powers (exactly on degree-1 graphs, in expectation elsewhere);
+ * factorised attention against the O(N^2) definition.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------ Philox4x32-10
+ * Counter-based generator of Salmon, Moraes, Dror, Shaw, "Parallel random numbers:
+ * as easy as 1, 2, 3" (SC'11).  The paper does not name a generator; the walks
+ * only need reproducible uniform 32-bit words keyed by (seed, node, walk).
+ */
+void grf_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* ------------------------------------------------------------------ one halting walk
+ * Sec. 3.3 (GRF definition) and Thm 3.1: a simple random walk out of `start` that,
+ * before every hop, halts with probability p_halt and otherwise moves to a
+ * uniformly chosen neighbour.  At most max_nodes nodes are visited (f vanishes
+ * beyond index max_nodes-1, so later deposits would be multiplied by zero).
+ *
+ * For the prefix of t hops the importance weight is
+ *     (product of traversed edge weights) / (probability of that prefix)
+ *   = prod_s  W[u_s, u_{s+1}] * deg(u_s) / (1 - p_halt),
+ * and 1 for the 0-hop prefix.
+ *
+ * Random stream: Philox counter (node, walk, block, 0), key (seed_lo, seed_hi).
+ * Block b serves hops 2b+1 and 2b+2: words 0,1 are the (halt, neighbour) draws of
+ * hop 2b+1, words 2,3 those of hop 2b+2.  halt iff draw < floor(p_halt * 2^32);
+ * neighbour index = floor(draw * deg / 2^32).
+ *
+ * nodes[t], loads[t] for t < returned length.
+ */
+static int one_walk(const int32_t* row_ptr, const int32_t* col, const float* w,
+                    int64_t start, int64_t walk, int max_nodes, double p_halt, uint64_t seed,
+                    int32_t* nodes, double* loads)
+{
+    const uint64_t threshold = (uint64_t)floor(p_halt * 4294967296.0);
+    const uint32_t key[2] = { (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32) };
+    uint32_t x[4] = {0, 0, 0, 0};
+    int64_t u = start;
+    double load = 1.0;
+    int len = 0;
+    nodes[len] = (int32_t)u; loads[len] = load; ++len;
+    for (int t = 1; t < max_nodes; ++t) {
+        const int64_t deg = (int64_t)row_ptr[u + 1] - (int64_t)row_ptr[u];
+        if (deg == 0) break;
+        const int within = (t - 1) & 1;
+        if (within == 0) {
+            const uint32_t ctr[4] = { (uint32_t)start, (uint32_t)walk, (uint32_t)((t - 1) >> 1), 0u };
+            grf_ref_philox4x32_10(ctr, key, x);
+        }
+        const uint32_t draw_halt = x[2 * within];
+        const uint32_t draw_nbr = x[2 * within + 1];
+        if ((uint64_t)draw_halt < threshold) break;
+        const int64_t pick = (int64_t)(((uint64_t)draw_nbr * (uint64_t)deg) >> 32);
+        const int64_t e = (int64_t)row_ptr[u] + pick;
+        load = load * (double)w[e] * (double)deg / (1.0 - p_halt);
+        u = col[e];
+        nodes[len] = (int32_t)u; loads[len] = load; ++len;
+    }
+    return len;
+}
+
+/* Trajectories only: traj[n][n_walks][max_nodes], -1 padded; loads_opt same shape or NULL. */
+void grf_ref_sample_walks(int64_t n, const int32_t* row_ptr, const int32_t* col, const float* w,
+                          double p_halt, int32_t n_walks, int32_t max_nodes, uint64_t seed,
+                          int32_t* traj, double* loads_opt)
+{
+    int32_t* nodes = (int32_t*)malloc(sizeof(int32_t) * (size_t)max_nodes);
+    double* loads = (double*)malloc(sizeof(double) * (size_t)max_nodes);
+    for (int64_t i = 0; i < n; ++i)
+        for (int32_t k = 0; k < n_walks; ++k) {
+            const int len = one_walk(row_ptr, col, w, i, k, max_nodes, p_halt, seed, nodes, loads);
+            int32_t* out = traj + ((size_t)i * n_walks + k) * max_nodes;
+            for (int t = 0; t < max_nodes; ++t) out[t] = t < len ? nodes[t] : -1;
+            if (loads_opt) {
+                double* lo = loads_opt + ((size_t)i * n_walks + k) * max_nodes;
+                for (int t = 0; t < max_nodes; ++t) lo[t] = t < len ? loads[t] : 0.0;
+            }
+        }
+    free(nodes); free(loads);
+}
+
+/* ------------------------------------------------------------------ GRF rows, Eq. (GRF definition)
+ *   phi_hat(v_i)_q = (1/n) * sum over walks k, over prefix subwalks ending at q, of
+ *                    weight(prefix) * f[len(prefix)]
+ * Every visited node is an entry of the row (kept even if its sum is 0).  Columns
+ * ascending.  Sums are taken in (walk, hop) order in fp64 and rounded once to fp32.
+ *
+ * Two-call protocol: with col_out == NULL only row_ptr_out[n+1] is written and nnz
+ * returned; otherwise col_out[nnz] and val_out[n_f][nnz] are filled as well.
+ * f is [n_f][f_len]; all n_f value planes share one set of walks (the features are
+ * linear in f).
+ */
+int64_t grf_ref_sample(int64_t n, const int32_t* row_ptr, const int32_t* col, const float* w,
+                       const float* f, int32_t f_len, int32_t n_f,
+                       double p_halt, int32_t n_walks, uint64_t seed,
+                       int32_t* row_ptr_out, int32_t* col_out, float* val_out)
+{
+    const size_t cap = (size_t)n_walks * (size_t)f_len;
+    int32_t* nodes = (int32_t*)malloc(sizeof(int32_t) * (size_t)f_len);
+    double* loads = (double*)malloc(sizeof(double) * (size_t)f_len);
+    int32_t* cols = (int32_t*)malloc(sizeof(int32_t) * cap);
+    double* sums = (double*)malloc(sizeof(double) * cap * (size_t)n_f);
+    int64_t nnz_total = (col_out == NULL) ? 0 : (int64_t)row_ptr_out[n];
+    int64_t running = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        size_t cnt = 0;
+        for (int32_t k = 0; k < n_walks; ++k) {
+            const int len = one_walk(row_ptr, col, w, i, k, f_len, p_halt, seed, nodes, loads);
+            for (int t = 0; t < len; ++t) {
+                size_t s = 0;
+                while (s < cnt && cols[s] != nodes[t]) ++s;
+                if (s == cnt) {
+                    cols[cnt] = nodes[t];
+                    for (int32_t h = 0; h < n_f; ++h) sums[cnt * n_f + h] = 0.0;
+                    ++cnt;
+                }
+                for (int32_t h = 0; h < n_f; ++h)
+                    sums[s * n_f + h] += loads[t] * (double)f[(size_t)h * f_len + t];
+            }
+        }
+        if (col_out == NULL) {
+            row_ptr_out[i] = (int32_t)running;
+        } else {
+            /* insertion sort of the row by column */
+            for (size_t a = 1; a < cnt; ++a) {
+                size_t b = a;
+                while (b > 0 && cols[b - 1] > cols[b]) {
+                    int32_t tc = cols[b]; cols[b] = cols[b - 1]; cols[b - 1] = tc;
+                    for (int32_t h = 0; h < n_f; ++h) {
+                        double tv = sums[b * n_f + h];
+                        sums[b * n_f + h] = sums[(b - 1) * n_f + h];
+                        sums[(b - 1) * n_f + h] = tv;
+                    }
+                    --b;
+                }
+            }
+            for (size_t s = 0; s < cnt; ++s) {
+                col_out[running + (int64_t)s] = cols[s];
+                for (int32_t h = 0; h < n_f; ++h)
+                    val_out[(size_t)h * (size_t)nnz_total + (size_t)running + s] =
+                        (float)(sums[s * n_f + h] / (double)n_walks);
+            }
+        }
+        running += (int64_t)cnt;
+    }
+    if (col_out == NULL) row_ptr_out[n] = (int32_t)running;
+    free(nodes); free(loads); free(cols); free(sums);
+    return running;
+}
+
+/* ------------------------------------------------------------------ feature map */
+static inline double feature(float x, int32_t feature_map)
+{
+    /* 0: ReLU (the map used in the paper's experiments), 1: identity (tests only) */
+    if (feature_map == 0) return x > 0.0f ? (double)x : 0.0;
+    return (double)x;
+}
+
+/* ------------------------------------------------------------------ Alg. 1, step 5, first product
+ * Block l of  Phi_{K,G}^T V  and of  Phi_{K,G}^T 1 :
+ *     S_l = sum_j phi_hat(v_j)_l * phi(k_j) v_j^T   (m x d),     z_l = sum_j phi_hat(v_j)_l * phi(k_j)   (m)
+ * with m = d for the elementwise feature maps used here.  One (batch, head) slice:
+ * K, V are [n][d]; phi is CSR (row_ptr, col, val); S is [n][d][d] (feature index
+ * first), z is [n][d]; both fp64, overwritten.  Contributors are met in ascending j.
+ */
+void grf_ref_buckets(int64_t n, int32_t d, const float* K, const float* V,
+                     const int32_t* phi_row_ptr, const int32_t* phi_col, const float* phi_val,
+                     int32_t feature_map, double* S, double* z)
+{
+    memset(S, 0, sizeof(double) * (size_t)n * d * d);
+    memset(z, 0, sizeof(double) * (size_t)n * d);
+    for (int64_t j = 0; j < n; ++j)
+        for (int64_t e = phi_row_ptr[j]; e < phi_row_ptr[j + 1]; ++e) {
+            const int64_t l = phi_col[e];
+            const double g = (double)phi_val[e];
+            double* Sl = S + (size_t)l * d * d;
+            double* zl = z + (size_t)l * d;
+            for (int32_t a = 0; a < d; ++a) {
+                const double ka = g * feature(K[j * d + a], feature_map);
+                zl[a] += ka;
+                for (int32_t b = 0; b < d; ++b) Sl[a * d + b] += ka * (double)V[j * d + b];
+            }
+        }
+}
+
+/* ------------------------------------------------------------------ Alg. 1, step 5, second product and D
+ *     num_i = sum_l phi_hat(v_i)_l * phi(q_i)^T S_l   (d),     den_i = sum_l phi_hat(v_i)_l * phi(q_i)^T z_l
+ * fp64, l ascending.  The attention output is num_i / den_i (no epsilon: Eq. 12 has none).
+ */
+void grf_ref_gather(int64_t n, int32_t d, const float* Q,
+                    const int32_t* phi_row_ptr, const int32_t* phi_col, const float* phi_val,
+                    int32_t feature_map, const double* S, const double* z,
+                    double* num, double* den)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        double* ni = num + (size_t)i * d;
+        for (int32_t b = 0; b < d; ++b) ni[b] = 0.0;
+        double di = 0.0;
+        for (int64_t e = phi_row_ptr[i]; e < phi_row_ptr[i + 1]; ++e) {
+            const int64_t l = phi_col[e];
+            const double g = (double)phi_val[e];
+            const double* Sl = S + (size_t)l * d * d;
+            const double* zl = z + (size_t)l * d;
+            for (int32_t a = 0; a < d; ++a) {
+                const double qa = g * feature(Q[i * d + a], feature_map);
+                di += qa * zl[a];
+                for (int32_t b = 0; b < d; ++b) ni[b] += qa * Sl[a * d + b];
+            }
+        }
+        den[i] = di;
+    }
+}
+
+/* ------------------------------------------------------------------ one output row from the definition
+ * Eq. (2) with M_hat = Phi_hat Phi_hat^T written out for a single query row i:
+ *     num_i = sum_j M_hat_ij (phi(q_i) . phi(k_j)) v_j,    den_i = sum_j M_hat_ij (phi(q_i) . phi(k_j)),
+ *     M_hat_ij = sum_l phi_hat(v_i)_l phi_hat(v_j)_l.
+ * Used to spot-check single rows at sizes where the full S array is too large.
+ * mask_row is caller scratch of n doubles.
+ */
+void grf_ref_row_direct(int64_t n, int32_t d, int64_t i, const float* Q, const float* K, const float* V,
+                        const int32_t* phi_row_ptr, const int32_t* phi_col, const float* phi_val,
+                        int32_t feature_map, double* mask_row, double* num_i, double* den_i)
+{
+    double* dense_i = (double*)calloc((size_t)n, sizeof(double));
+    for (int64_t e = phi_row_ptr[i]; e < phi_row_ptr[i + 1]; ++e) dense_i[phi_col[e]] = (double)phi_val[e];
+    for (int32_t b = 0; b < d; ++b) num_i[b] = 0.0;
+    double di = 0.0;
+    for (int64_t j = 0; j < n; ++j) {
+        double mij = 0.0;
+        for (int64_t e = phi_row_ptr[j]; e < phi_row_ptr[j + 1]; ++e)
+            mij += dense_i[phi_col[e]] * (double)phi_val[e];
+        mask_row[j] = mij;
+        if (mij == 0.0) continue;
+        double a = 0.0;
+        for (int32_t c = 0; c < d; ++c)
+            a += feature(Q[i * d + c], feature_map) * feature(K[j * d + c], feature_map);
+        di += mij * a;
+        for (int32_t b = 0; b < d; ++b) num_i[b] += mij * a * (double)V[j * d + b];
+    }
+    *den_i = di;
+    free(dense_i);
+}

@@ -1,0 +1,238 @@
+"""CPU checker for GRF-masked linear attention (arXiv 2410.03462) -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper over ``grf_oracle.c`` plus the dense, quadratic definitions in
+numpy that the C routines are themselves pinned against.  Nothing here is used by
+the HIP library and nothing here imports it.  Only the tests, the smoke check and the
+benchmark's ``cpu_baseline`` leg may import this module.
+
+All routines take and return numpy arrays on the host; accumulation is fp64.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "grf_oracle.c")
+_LIB_PATH = os.path.join(_HERE, "libgrf_oracle.so")
+_lib = None
+
+RELU, IDENTITY = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile grf_oracle.c with gcc (-O2, no fast-math)."""
+    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-o", _LIB_PATH, _SRC, "-lm"])
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB_PATH)
+        _lib.grf_ref_sample.restype = ctypes.c_int64
+    return _lib
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct)) if a is not None else None
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+# --------------------------------------------------------------------------- random stream
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c = np.asarray(ctr, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    out = np.zeros(4, dtype=np.uint32)
+    _load().grf_ref_philox4x32_10(_p(c, ctypes.c_uint32), _p(k, ctypes.c_uint32), _p(out, ctypes.c_uint32))
+    return out
+
+
+# --------------------------------------------------------------------------- walks and features
+
+def sample_walks(g, p_halt: float, n_walks: int, max_nodes: int, seed: int, with_loads: bool = False):
+    """Trajectories [n, n_walks, max_nodes] (int32, -1 padded) and optionally the fp64 loads."""
+    traj = np.empty((g.n, n_walks, max_nodes), dtype=np.int32)
+    loads = np.empty((g.n, n_walks, max_nodes), dtype=np.float64) if with_loads else None
+    rp, col, w = _i32(g.row_ptr), _i32(g.col), _f32(g.w)
+    _load().grf_ref_sample_walks(
+        ctypes.c_int64(g.n), _p(rp, ctypes.c_int32), _p(col, ctypes.c_int32), _p(w, ctypes.c_float),
+        ctypes.c_double(p_halt), ctypes.c_int32(n_walks), ctypes.c_int32(max_nodes), ctypes.c_uint64(seed),
+        _p(traj, ctypes.c_int32), _p(loads, ctypes.c_double))
+    return (traj, loads) if with_loads else traj
+
+
+def sample(g, f, p_halt: float, n_walks: int, seed: int):
+    """GRF matrix Phi_hat in CSR: (row_ptr int32[n+1], col int32[nnz], val float32[n_f, nnz])."""
+    f = _f32(np.atleast_2d(f))
+    n_f, f_len = f.shape
+    rp, col, w = _i32(g.row_ptr), _i32(g.col), _f32(g.w)
+    row_ptr = np.zeros(g.n + 1, dtype=np.int32)
+    lib = _load()
+
+    def call(col_out, val_out):
+        return lib.grf_ref_sample(
+            ctypes.c_int64(g.n), _p(rp, ctypes.c_int32), _p(col, ctypes.c_int32), _p(w, ctypes.c_float),
+            _p(f, ctypes.c_float), ctypes.c_int32(f_len), ctypes.c_int32(n_f),
+            ctypes.c_double(p_halt), ctypes.c_int32(n_walks), ctypes.c_uint64(seed),
+            _p(row_ptr, ctypes.c_int32), _p(col_out, ctypes.c_int32), _p(val_out, ctypes.c_float))
+
+    nnz = call(None, None)
+    col_out = np.empty(nnz, dtype=np.int32)
+    val_out = np.empty((n_f, nnz), dtype=np.float32)
+    call(col_out, val_out)
+    return row_ptr, col_out, val_out
+
+
+def phi_dense(n, row_ptr, col, val) -> np.ndarray:
+    """Dense fp64 copy of one value plane of Phi_hat."""
+    P = np.zeros((n, n), dtype=np.float64)
+    rows = np.repeat(np.arange(n), np.diff(row_ptr))
+    P[rows, col] = val.astype(np.float64)
+    return P
+
+
+# --------------------------------------------------------------------------- exact quantities (dense, tiny graphs)
+
+def exact_features(W: np.ndarray, f: np.ndarray) -> np.ndarray:
+    """Phi_G = sum_t f_t W^t  (Remark 3.1), dense fp64."""
+    n = W.shape[0]
+    P = np.eye(n)
+    out = np.zeros((n, n))
+    for ft in np.asarray(f, dtype=np.float64):
+        out += ft * P
+        P = P @ W
+    return out
+
+
+def exact_mask(W: np.ndarray, f: np.ndarray) -> np.ndarray:
+    """M_alpha = sum_k alpha_k W^k with alpha = f * f (discrete convolution; Eq. 4, Remark 3.1)."""
+    f = np.asarray(f, dtype=np.float64)
+    alpha = np.convolve(f, f)
+    n = W.shape[0]
+    P = np.eye(n)
+    out = np.zeros((n, n))
+    for a in alpha:
+        out += a * P
+        P = P @ W
+    return out
+
+
+# --------------------------------------------------------------------------- attention
+
+def _feature(x: np.ndarray, feature_map: int) -> np.ndarray:
+    x = x.astype(np.float64)
+    return np.maximum(x, 0.0) if feature_map == RELU else x
+
+
+def attention_bruteforce(Q, K, V, M, feature_map: int = RELU):
+    """Eq. (1)-(2): A_M = M .* (phi(Q) phi(K)^T); returns (num, den, out) in fp64.  One (b,h) slice."""
+    A = _feature(Q, feature_map) @ _feature(K, feature_map).T
+    AM = M * A
+    num = AM @ V.astype(np.float64)
+    den = AM.sum(axis=1)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        out = num / den[:, None]
+    return num, den, out
+
+
+def buckets(K, V, row_ptr, col, val, feature_map: int = RELU):
+    """S [n,d,d], z [n,d] in fp64 for one (b,h) slice (Alg. 1 step 5, the Phi_K^T products)."""
+    K, V = _f32(K), _f32(V)
+    n, d = K.shape
+    S = np.empty((n, d, d), dtype=np.float64)
+    z = np.empty((n, d), dtype=np.float64)
+    rp, c, v = _i32(row_ptr), _i32(col), _f32(val)
+    _load().grf_ref_buckets(
+        ctypes.c_int64(n), ctypes.c_int32(d), _p(K, ctypes.c_float), _p(V, ctypes.c_float),
+        _p(rp, ctypes.c_int32), _p(c, ctypes.c_int32), _p(v, ctypes.c_float), ctypes.c_int32(feature_map),
+        _p(S, ctypes.c_double), _p(z, ctypes.c_double))
+    return S, z
+
+
+def gather(Q, row_ptr, col, val, S, z, feature_map: int = RELU):
+    """num [n,d], den [n] in fp64 for one (b,h) slice (Alg. 1 step 5, the Phi_Q products)."""
+    Q = _f32(Q)
+    n, d = Q.shape
+    num = np.empty((n, d), dtype=np.float64)
+    den = np.empty(n, dtype=np.float64)
+    rp, c, v = _i32(row_ptr), _i32(col), _f32(val)
+    S = np.ascontiguousarray(S, dtype=np.float64)
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    _load().grf_ref_gather(
+        ctypes.c_int64(n), ctypes.c_int32(d), _p(Q, ctypes.c_float),
+        _p(rp, ctypes.c_int32), _p(c, ctypes.c_int32), _p(v, ctypes.c_float), ctypes.c_int32(feature_map),
+        _p(S, ctypes.c_double), _p(z, ctypes.c_double), _p(num, ctypes.c_double), _p(den, ctypes.c_double))
+    return num, den
+
+
+def masked_linear_attention(Q, K, V, row_ptr, col, val, feature_map: int = RELU, return_buckets: bool = False):
+    """Alg. 1 steps 3-5 for Q,K,V of shape [B,H,n,d].
+
+    ``val`` is [n_f, nnz] with n_f == 1 (shared by all heads) or n_f == H (one plane per head).
+    Returns dict with fp64 ``num`` [B,H,n,d], ``den`` [B,H,n], ``out`` = num/den, and optionally
+    ``S`` [B,H,n,d,d], ``z`` [B,H,n,d].
+    """
+    Q, K, V = (np.asarray(x, dtype=np.float32) for x in (Q, K, V))
+    B, H, n, d = Q.shape
+    val = np.atleast_2d(val)
+    assert val.shape[0] in (1, H)
+    num = np.empty((B, H, n, d), dtype=np.float64)
+    den = np.empty((B, H, n), dtype=np.float64)
+    Ss = np.empty((B, H, n, d, d), dtype=np.float64) if return_buckets else None
+    zs = np.empty((B, H, n, d), dtype=np.float64) if return_buckets else None
+    for b in range(B):
+        for h in range(H):
+            v = val[h if val.shape[0] > 1 else 0]
+            S, z = buckets(K[b, h], V[b, h], row_ptr, col, v, feature_map)
+            num[b, h], den[b, h] = gather(Q[b, h], row_ptr, col, v, S, z, feature_map)
+            if return_buckets:
+                Ss[b, h], zs[b, h] = S, z
+    with np.errstate(divide="ignore", invalid="ignore"):
+        out = num / den[..., None]
+    res = {"num": num, "den": den, "out": out}
+    if return_buckets:
+        res["S"], res["z"] = Ss, zs
+    return res
+
+
+def row_direct(i: int, Q, K, V, row_ptr, col, val, feature_map: int = RELU):
+    """(num_i [d], den_i, mask_row [n]) for one query row of one (b,h) slice, from Eq. (2) directly."""
+    Q, K, V = _f32(Q), _f32(K), _f32(V)
+    n, d = Q.shape
+    rp, c, v = _i32(row_ptr), _i32(col), _f32(val)
+    mask_row = np.empty(n, dtype=np.float64)
+    num = np.empty(d, dtype=np.float64)
+    den = ctypes.c_double(0.0)
+    _load().grf_ref_row_direct(
+        ctypes.c_int64(n), ctypes.c_int32(d), ctypes.c_int64(i),
+        _p(Q, ctypes.c_float), _p(K, ctypes.c_float), _p(V, ctypes.c_float),
+        _p(rp, ctypes.c_int32), _p(c, ctypes.c_int32), _p(v, ctypes.c_float), ctypes.c_int32(feature_map),
+        _p(mask_row, ctypes.c_double), _p(num, ctypes.c_double), ctypes.byref(den))
+    return num, den.value, mask_row
+
+
+def conditioning_floor(Q, row_ptr, col, val, z, feature_map: int = RELU) -> np.ndarray:
+    """sum_l |phi_hat_il| * |phi(q_i) . z_l| per row: the scale against which den_i is judged.
+
+    f may be signed, so den_i can cancel to ~0 (Eq. 12 has no epsilon).  Rows with
+    |den_i| below a small fraction of this scale are ill-conditioned for num/den.
+    """
+    n, d = Q.shape
+    fq = _feature(np.asarray(Q), feature_map)
+    rows = np.repeat(np.arange(n), np.diff(row_ptr))
+    dots = np.abs(np.einsum("ea,ea->e", fq[rows], z[col]))
+    return np.bincount(rows, weights=np.abs(val.astype(np.float64)) * dots, minlength=n)

@@ -1,0 +1,447 @@
+"""Pins of the CPU checker to what the paper and the mathematics fix (no GPU).
+
+Each test is chosen so that a plausible slip in the checker -- a dropped factor, a wrong
+hop index, a transposed operand, a wrong halting convention -- fails it.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from paper_2410_03462_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# --------------------------------------------------------------------------- random stream
+
+def test_philox_known_answers(oracle):
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) if l.strip() and l[0] != "#"]
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(x, 16) for x in r]
+        got = oracle.philox4x32_10(w[0:4], w[4:6])
+        assert [int(x) for x in got] == w[6:10]
+
+
+# --------------------------------------------------------------------------- halting law (Thm 3.1 / Lemma 3.2 conventions)
+
+@pytest.mark.parametrize("p,L", [(0.5, 8), (0.2, 16), (0.25, 12)])
+def test_halting_law_geometric(oracle, p, L):
+    """P(visited nodes = b) = p (1-p)^(b-1) for b < L and (1-p)^(L-1) for b = L;
+    mean = (1-(1-p)^L)/p.  Over 1.3e6 walks on a graph without isolated nodes."""
+    g = synth.ring_graph(4096)
+    n_walks = 320
+    traj = oracle.sample_walks(g, p, n_walks, L, seed=11)
+    lens = (traj >= 0).sum(-1).ravel()
+    # the -1 padding is a suffix
+    assert np.all((traj >= 0) == (np.arange(L)[None, None, :] < (traj >= 0).sum(-1)[..., None]))
+    total = lens.size
+    probs = np.array([p * (1 - p) ** (b - 1) for b in range(1, L)] + [(1 - p) ** (L - 1)])
+    counts = np.bincount(lens, minlength=L + 1)[1:]
+    assert counts.sum() == total
+    sigma = np.sqrt(total * probs * (1 - probs))
+    assert np.all(np.abs(counts - total * probs) <= 5 * sigma + 1)
+    mean_exact = (1 - (1 - p) ** L) / p
+    var = (probs * (np.arange(1, L + 1) - mean_exact) ** 2).sum()
+    assert abs(lens.mean() - mean_exact) <= 5 * math.sqrt(var / total)
+
+
+def test_halting_extremes(oracle):
+    g = synth.grid_graph(6, 7, 8)
+    f = np.array([[0.7, -0.3, 0.2, 0.1]], dtype=np.float32)
+    # p = 1: every walk halts before its first hop -> Phi = f_0 I
+    rp, col, val = oracle.sample(g, f, 1.0, 5, seed=3)
+    assert np.array_equal(rp, np.arange(g.n + 1))
+    assert np.array_equal(col, np.arange(g.n))
+    assert np.allclose(val[0], 0.7, rtol=1e-7)
+    # p = 0: never halts -> exactly L visited nodes per walk
+    traj = oracle.sample_walks(g, 0.0, 5, 4, seed=3)
+    assert np.all(traj >= 0)
+
+
+# --------------------------------------------------------------------------- neighbour law
+
+def test_neighbour_law_uniform(oracle):
+    """First hop out of the hub of a star lands on each leaf with probability 1/deg;
+    on a ring left/right are equally likely at every hop."""
+    g = synth.star_graph(8)
+    n_walks = 70000
+    traj = oracle.sample_walks(g, 0.0, n_walks, 2, seed=5)
+    first = traj[0, :, 1]
+    counts = np.bincount(first, minlength=8)
+    assert counts[0] == 0
+    pr = 1.0 / 7
+    assert np.all(np.abs(counts[1:] - n_walks * pr) <= 5 * math.sqrt(n_walks * pr * (1 - pr)))
+    # leaves have one neighbour: the hub
+    assert np.all(traj[1:, :, 1] == 0)
+
+    r = synth.ring_graph(64)
+    traj = oracle.sample_walks(r, 0.0, 500, 9, seed=6)
+    step = (traj[:, :, 1:] - traj[:, :, :-1]) % 64
+    assert set(np.unique(step)) == {1, 63}
+    frac = (step == 1).mean(axis=(0, 1))           # per hop index
+    m = 64 * 500
+    assert np.all(np.abs(frac - 0.5) <= 5 * 0.5 / math.sqrt(m))
+    # consecutive hops are independent: P(right, right) = 1/4
+    rr = ((step[:, :, :-1] == 1) & (step[:, :, 1:] == 1)).mean()
+    assert abs(rr - 0.25) <= 5 * math.sqrt(0.25 * 0.75 / (m * 7))
+
+
+def test_walks_follow_edges_and_are_keyed_by_node_and_walk(oracle):
+    rng = np.random.default_rng(0)
+    g = synth.random_graph(300, 5.0, rng, isolated=3)
+    W = g.dense()
+    traj = oracle.sample_walks(g, 0.3, 6, 7, seed=9)
+    a, b = traj[:, :, :-1], traj[:, :, 1:]
+    ok = b >= 0
+    assert np.all(W[a[ok], b[ok]] > 0)
+    assert np.all(traj[:, :, 0] == np.arange(g.n)[:, None])
+    # isolated nodes: only the start is visited
+    assert np.all(traj[-3:, :, 1:] == -1)
+    # the stream of (node, walk) does not depend on how many walks are drawn or on the seed of others
+    traj10 = oracle.sample_walks(g, 0.3, 10, 7, seed=9)
+    assert np.array_equal(traj10[:, :6], traj)
+    assert not np.array_equal(oracle.sample_walks(g, 0.3, 6, 7, seed=10), traj)
+    # a longer cap only extends walks that were cut by the cap
+    traj_long = oracle.sample_walks(g, 0.3, 6, 12, seed=9)
+    assert np.array_equal(traj_long[:, :, :7], traj)
+
+
+# --------------------------------------------------------------------------- load arithmetic, no randomness
+
+def test_degree_one_graph_gives_exact_power_series(oracle):
+    """On a perfect matching with p_halt = 0 every walk is forced, deg = 1 and
+    1 - p = 1, so Phi_hat = sum_t f_t W^t exactly (Remark 3.1), for any n."""
+    rng = np.random.default_rng(1)
+    g = synth.matching_graph(10, rng)
+    f = synth.modulation(7, rng, "decay", n_f=2)
+    for n_walks in (1, 3):
+        rp, col, val = oracle.sample(g, f, 0.0, n_walks, seed=0)
+        for h in range(2):
+            got = oracle.phi_dense(g.n, rp, col, val[h])
+            want = oracle.exact_features(g.dense(), f[h])
+            assert np.allclose(got, want, rtol=2e-7, atol=1e-9)
+
+
+def test_regular_graph_load_is_inverse_survival(oracle):
+    """W = A/deg on a regular graph: W_uv deg(u) = 1, so the load after t hops is (1-p)^-t."""
+    g = synth.grid_graph(8, 8, 4, periodic=True)   # torus, 4-regular
+    p = 0.3
+    traj, loads = oracle.sample_walks(g, p, 6, 9, seed=2, with_loads=True)
+    t = np.arange(9)[None, None, :]
+    want = np.where(traj >= 0, (1 - p) ** (-t.astype(np.float64)), 0.0)
+    assert np.allclose(loads, want, rtol=1e-6)
+
+
+def test_delta_modulation_gives_identity(oracle):
+    """f = (1, 0, 0, ...): only the 0-hop prefix deposits, with weight 1 and 1/n
+    normalisation -> Phi_hat has ones on the diagonal; all other visited entries are
+    stored zeros (App. D uses this case: Phi^(2) = I)."""
+    rng = np.random.default_rng(2)
+    g = synth.random_graph(80, 4.0, rng, weights="inv_deg")
+    f = np.array([[1.0, 0, 0, 0, 0]], dtype=np.float32)
+    rp, col, val = oracle.sample(g, f, 0.4, 7, seed=4)
+    P = oracle.phi_dense(g.n, rp, col, val[0])
+    assert np.array_equal(P, np.eye(g.n))
+
+
+# --------------------------------------------------------------------------- estimator: unbiasedness
+
+def _mean_phi_and_mask(oracle, g, f, p, n_walks, seeds):
+    n = g.n
+    sum_phi = np.zeros((n, n)); sq_phi = np.zeros((n, n))
+    sum_m = np.zeros((n, n)); sq_m = np.zeros((n, n))
+    for s in seeds:
+        rp, col, val = oracle.sample(g, f, p, n_walks, seed=s)
+        P = oracle.phi_dense(n, rp, col, val[0])
+        M = P @ P.T
+        sum_phi += P; sq_phi += P * P
+        sum_m += M; sq_m += M * M
+    k = len(seeds)
+    mp, mm = sum_phi / k, sum_m / k
+    sp = np.sqrt(np.maximum(sq_phi / k - mp * mp, 0) / k)
+    sm = np.sqrt(np.maximum(sq_m / k - mm * mm, 0) / k)
+    return mp, sp, mm, sm
+
+
+def test_features_unbiased_on_irregular_nonsymmetric_graph(oracle):
+    """E[Phi_hat] = sum_{t<L} f_t W^t entrywise (each deposit is weight/p(prefix) times an
+    indicator of expectation p(prefix); Sec. 3.3).  Irregular degrees and row-normalised
+    non-symmetric weights, so a missing deg, 1/(1-p) or 1/n factor, or f indexed off by one,
+    shows up as bias."""
+    rng = np.random.default_rng(3)
+    pts = rng.random((40, 3))
+    g = synth.knn_graph(pts, 3, "exp")
+    assert g.degrees().min() != g.degrees().max()
+    f = np.array([[0.9, -0.6, 0.5, 0.3, -0.2]], dtype=np.float32)
+    seeds = list(range(3000))
+    mp, sp, _, _ = _mean_phi_and_mask(oracle, g, f, 0.3, 6, seeds)
+    want = oracle.exact_features(g.dense(), f[0])
+    zscore = np.abs(mp - want) / np.maximum(sp, 1e-12)
+    active = sp > 0
+    assert active.sum() > 200
+    assert zscore[active].max() < 5.0
+    # entries never reached within L-1 hops are exactly zero on both sides
+    assert np.all(want[~active & (mp == 0)] == 0)
+    # and the match is tight in absolute terms too
+    assert np.abs(mp - want).max() < 0.05 * np.abs(want).max()
+
+
+def test_mask_estimate_unbiased_off_diagonal_symmetric_w(oracle):
+    """E[phi_hat_i . phi_hat_j] = (sum_k alpha_k W^k)_ij, alpha = f*f, for i != j and symmetric W
+    (Sec. 3.3; Remark 3.1).  The diagonal reuses the same walks on both sides and is biased at
+    finite n, so it is excluded."""
+    rng = np.random.default_rng(4)
+    g = synth.random_graph(36, 3.5, rng, weights="sym_norm")
+    W = g.dense()
+    assert np.allclose(W, W.T)
+    f = np.array([[1.0, 0.5, -0.4, 0.25]], dtype=np.float32)
+    seeds = list(range(4000))
+    _, _, mm, sm = _mean_phi_and_mask(oracle, g, f, 0.25, 5, seeds)
+    want = oracle.exact_mask(W, f[0])
+    assert np.allclose(want, oracle.exact_features(W, f[0]) @ oracle.exact_features(W, f[0]).T)
+    off = ~np.eye(g.n, dtype=bool) & (sm > 0)
+    z = np.abs(mm - want)[off] / sm[off]
+    assert z.max() < 5.0
+    assert np.abs(mm - want)[off].max() < 0.05 * np.abs(want).max()
+    # finite-n diagonal bias is positive (a variance term)
+    d = np.diag(mm - want)
+    assert d.mean() > 0
+
+
+def test_concentration_and_l1_bounds(oracle):
+    """Thm 3.1: per-walk L1 mass of deposits <= c = sum_k |f_k| (max |W_ij| d_i/(1-p))^k, and
+    deviations of the mask estimate exceed t no more often than 2 exp(-t^2 n^3 / (2 (2n-1)^2 c^4))."""
+    rng = np.random.default_rng(5)
+    g = synth.random_graph(30, 3.0, rng, weights="sym_norm")
+    W = g.dense()
+    p, n_walks = 0.2, 8
+    f = np.array([[1.0, 0.3, 0.1]], dtype=np.float32)
+    deg = g.degrees()
+    ratio = (np.abs(W) * deg[:, None] / (1 - p)).max()
+    c = float((np.abs(f[0]) * ratio ** np.arange(3)).sum())
+    traj, loads = oracle.sample_walks(g, p, 50, 3, seed=1, with_loads=True)
+    l1 = (np.abs(loads) * np.abs(f[0])[None, None, :]).sum(-1)
+    assert l1.max() <= c * (1 + 1e-12)
+    want = oracle.exact_mask(W, f[0])
+    devs = []
+    for s in range(300):
+        rp, col, val = oracle.sample(g, f, p, n_walks, seed=s)
+        P = oracle.phi_dense(g.n, rp, col, val[0])
+        devs.append(np.abs(P @ P.T - want)[~np.eye(g.n, dtype=bool)])
+    devs = np.concatenate(devs)
+    for t in (0.5 * c * c, c * c, 2 * c * c):
+        bound = 2 * math.exp(-t * t * n_walks ** 3 / (2 * (2 * n_walks - 1) ** 2 * c ** 4))
+        assert (devs > t).mean() <= bound
+
+
+# --------------------------------------------------------------------------- sparsity
+
+def test_sparsity_bounds_and_linear_growth(oracle):
+    """Lemma 3.2 (with n walkers): with prob >= 1-delta a row has at most
+    n log(1-(1-delta)^(1/n)) / log(1-p) entries; hard bound 1 + n(L-1).  On 1-D grids at n=4,
+    p=0.5 the total count grows linearly with N (the setting of the FLOP-count figure)."""
+    n_walks, p, L = 4, 0.5, 12
+    f = synth.modulation(L, np.random.default_rng(0))
+    per_node = []
+    for N in (256, 1024, 4096):
+        g = synth.path_graph(N)
+        rp, col, val = oracle.sample(g, f, p, n_walks, seed=0)
+        row_nnz = np.diff(rp)
+        assert row_nnz.max() <= 1 + n_walks * (L - 1)
+        assert row_nnz.min() >= 1
+        per_node.append(rp[-1] / N)
+        for delta in (0.1, 0.01):
+            bound = n_walks * math.log(1 - (1 - delta) ** (1 / n_walks)) / math.log(1 - p)
+            assert (row_nnz > bound).mean() <= delta
+    assert max(per_node) / min(per_node) < 1.05
+
+
+def test_csr_well_formed_and_pattern_is_visited_set(oracle):
+    wl = synth.workload("tiny_grid")
+    g = wl.graph
+    rp, col, val = oracle.sample(g, wl.f, wl.p_halt, wl.n_walks, seed=0)
+    traj = oracle.sample_walks(g, wl.p_halt, wl.n_walks, wl.f_len, seed=0)
+    assert rp[0] == 0 and np.all(np.diff(rp) >= 1) and rp[-1] == col.size
+    for i in range(g.n):
+        c = col[rp[i]:rp[i + 1]]
+        assert np.all(np.diff(c) > 0)
+        visited = np.unique(traj[i][traj[i] >= 0])
+        assert np.array_equal(c, visited)
+        assert i in c
+
+
+def test_value_planes_share_walks_and_are_linear_in_f(oracle):
+    rng = np.random.default_rng(6)
+    g = synth.grid_graph(9, 9, 8)
+    f = synth.modulation(6, rng, "decay", n_f=3)
+    rp, col, val = oracle.sample(g, f, 0.3, 5, seed=2)
+    for h in range(3):
+        rp1, col1, val1 = oracle.sample(g, f[h:h + 1], 0.3, 5, seed=2)
+        assert np.array_equal(rp1, rp) and np.array_equal(col1, col)
+        assert np.array_equal(val1[0], val[h])
+    fsum = (f[0] + 2 * f[1])[None, :]
+    _, _, vs = oracle.sample(g, fsum, 0.3, 5, seed=2)
+    assert np.allclose(vs[0], val[0] + 2 * val[1], rtol=1e-5, atol=1e-6)
+
+
+# --------------------------------------------------------------------------- attention
+
+def _small_case(oracle, seed=0, n_side=12, d=8, feature_map=0):
+    rng = np.random.default_rng(seed)
+    g = synth.grid_graph(n_side, n_side, 8)
+    f = synth.modulation(6, rng, "decay")
+    rp, col, val = oracle.sample(g, f, 0.4, 5, seed=seed)
+    Q, K, V = synth.qkv(2, 3, g.n, d, rng)
+    return g, rp, col, val, Q, K, V
+
+
+def test_factorised_equals_bruteforce_and_mask_symmetric(oracle):
+    """Alg. 1 step 5 equals Eq. (2) with M_hat = Phi_hat Phi_hat^T (the outer-product identity of
+    Sec. 3.2), and M_hat is symmetric."""
+    g, rp, col, val, Q, K, V = _small_case(oracle)
+    res = oracle.masked_linear_attention(Q, K, V, rp, col, val, return_buckets=True)
+    P = oracle.phi_dense(g.n, rp, col, val[0])
+    M = P @ P.T
+    assert np.array_equal(M, M.T)
+    for b in range(2):
+        for h in range(3):
+            num, den, out = oracle.attention_bruteforce(Q[b, h], K[b, h], V[b, h], M)
+            assert np.allclose(res["num"][b, h], num, rtol=1e-10, atol=1e-10)
+            assert np.allclose(res["den"][b, h], den, rtol=1e-10, atol=1e-10)
+            # buckets against their definition, with explicit operand order:
+            # S_l[a, c] = sum_j P[j, l] relu(K[j, a]) V[j, c]
+            fk = np.maximum(K[b, h].astype(np.float64), 0)
+            S = np.einsum("jl,ja,jc->lac", P, fk, V[b, h].astype(np.float64))
+            z = np.einsum("jl,ja->la", P, fk)
+            assert np.allclose(res["S"][b, h], S, rtol=1e-10, atol=1e-10)
+            assert np.allclose(res["z"][b, h], z, rtol=1e-10, atol=1e-10)
+
+
+def test_factorised_equals_bruteforce_vit_grid_size(oracle):
+    """Same identity at N = 1024 (32x32 8-neighbour grid, d = 64), one head."""
+    wl = synth.workload("vit_grid")
+    g = wl.graph
+    rp, col, val = oracle.sample(g, wl.f, wl.p_halt, wl.n_walks, seed=0)
+    rng = np.random.default_rng(1)
+    Q, K, V = synth.qkv(1, 1, g.n, 64, rng)
+    res = oracle.masked_linear_attention(Q, K, V, rp, col, val)
+    P = oracle.phi_dense(g.n, rp, col, val[0])
+    num, den, _ = oracle.attention_bruteforce(Q[0, 0], K[0, 0], V[0, 0], P @ P.T)
+    assert np.allclose(res["num"][0, 0], num, rtol=1e-9, atol=1e-9)
+    assert np.allclose(res["den"][0, 0], den, rtol=1e-9, atol=1e-9)
+
+
+def test_per_head_value_planes(oracle):
+    rng = np.random.default_rng(7)
+    g = synth.grid_graph(8, 8, 4)
+    f = synth.modulation(5, rng, "decay", n_f=3)
+    rp, col, val = oracle.sample(g, f, 0.4, 4, seed=1)
+    Q, K, V = synth.qkv(2, 3, g.n, 8, rng)
+    res = oracle.masked_linear_attention(Q, K, V, rp, col, val)
+    for h in range(3):
+        P = oracle.phi_dense(g.n, rp, col, val[h])
+        num, den, _ = oracle.attention_bruteforce(Q[1, h], K[1, h], V[1, h], P @ P.T)
+        assert np.allclose(res["num"][1, h], num, rtol=1e-10, atol=1e-10)
+        assert np.allclose(res["den"][1, h], den, rtol=1e-10, atol=1e-10)
+
+
+def test_identity_features_return_values(oracle):
+    """Phi_hat = I: M_hat = I, so out_i = v_i wherever phi(q_i).phi(k_i) != 0."""
+    rng = np.random.default_rng(8)
+    n, d = 50, 8
+    Q, K, V = synth.qkv(1, 1, n, d, rng)
+    rp = np.arange(n + 1, dtype=np.int32); col = np.arange(n, dtype=np.int32); val = np.ones((1, n), np.float32)
+    res = oracle.masked_linear_attention(Q, K, V, rp, col, val)
+    ok = res["den"][0, 0] != 0
+    assert ok.sum() > 40
+    assert np.allclose(res["out"][0, 0][ok], V[0, 0][ok].astype(np.float64), rtol=1e-12)
+
+
+def test_single_ones_column_is_unmasked_linear_attention(oracle):
+    """Phi_hat = one all-ones column: M_hat is all ones and the method reduces to Eq. (3),
+    D^-1 (Phi_Q (Phi_K^T V)), evaluated here with dense matrix products."""
+    rng = np.random.default_rng(9)
+    n, d = 70, 16
+    Q, K, V = synth.qkv(1, 2, n, d, rng)
+    rp = np.arange(n + 1, dtype=np.int32); col = np.full(n, 3, dtype=np.int32); val = np.ones((1, n), np.float32)
+    res = oracle.masked_linear_attention(Q, K, V, rp, col, val)
+    for h in range(2):
+        fq = np.maximum(Q[0, h].astype(np.float64), 0); fk = np.maximum(K[0, h].astype(np.float64), 0)
+        num = fq @ (fk.T @ V[0, h].astype(np.float64))
+        den = fq @ (fk.T @ np.ones(n))
+        assert np.allclose(res["num"][0, h], num, rtol=1e-11)
+        assert np.allclose(res["den"][0, h], den, rtol=1e-11)
+        assert np.allclose(res["out"][0, h], num / den[:, None], rtol=1e-11)
+
+
+def test_attention_invariances(oracle):
+    g, rp, col, val, Q, K, V = _small_case(oracle, seed=3)
+    base = oracle.masked_linear_attention(Q, K, V, rp, col, val)
+    # V = 1 -> out = 1 (rows are affine combinations with weights summing to one)
+    ones = oracle.masked_linear_attention(Q, K, np.ones_like(V), rp, col, val)
+    ok = np.abs(ones["den"]) > 1e-9
+    assert np.allclose(ones["out"][ok], 1.0, rtol=1e-9)
+    # scaling Phi_hat by c: num, den scale by c^2, out unchanged
+    # (c = 4 is exact in fp32, so the identity holds to fp64 rounding)
+    sc = oracle.masked_linear_attention(Q, K, V, rp, col, 4.0 * val)
+    assert np.allclose(sc["num"], 16 * base["num"], rtol=1e-12, atol=1e-12)
+    assert np.allclose(sc["den"], 16 * base["den"], rtol=1e-12, atol=1e-12)
+    # linear in V
+    V2 = np.random.default_rng(0).standard_normal(V.shape).astype(np.float32)
+    r2 = oracle.masked_linear_attention(Q, K, V2, rp, col, val)
+    r12 = oracle.masked_linear_attention(Q, K, (V.astype(np.float64) + V2).astype(np.float32), rp, col, val)
+    assert np.allclose(r12["num"], base["num"] + r2["num"], rtol=1e-5, atol=1e-5)
+    # symmetry of M_hat seen through the denominators: sum_i den_i(Q,K) = sum_i den_i(K,Q)
+    sw = oracle.masked_linear_attention(K, Q, V, rp, col, val)
+    assert np.allclose(base["den"].sum(-1), sw["den"].sum(-1), rtol=1e-10)
+    # identity feature map differs from ReLU (the flag is honoured)
+    ident = oracle.masked_linear_attention(Q, K, V, rp, col, val, feature_map=oracle.IDENTITY)
+    assert not np.allclose(ident["num"], base["num"])
+    P = oracle.phi_dense(g.n, rp, col, val[0])
+    num, den, _ = oracle.attention_bruteforce(Q[0, 0], K[0, 0], V[0, 0], P @ P.T, feature_map=oracle.IDENTITY)
+    assert np.allclose(ident["num"][0, 0], num, rtol=1e-10, atol=1e-10)
+
+
+def test_row_direct_matches_factorised(oracle):
+    g, rp, col, val, Q, K, V = _small_case(oracle, seed=5)
+    res = oracle.masked_linear_attention(Q, K, V, rp, col, val)
+    P = oracle.phi_dense(g.n, rp, col, val[0])
+    M = P @ P.T
+    for i in (0, 17, g.n - 1):
+        num, den, mrow = oracle.row_direct(i, Q[1, 2], K[1, 2], V[1, 2], rp, col, val[0])
+        assert np.allclose(mrow, M[i], rtol=1e-12, atol=1e-14)
+        assert np.allclose(num, res["num"][1, 2, i], rtol=1e-10, atol=1e-10)
+        assert np.isclose(den, res["den"][1, 2, i], rtol=1e-10, atol=1e-10)
+
+
+def test_large_n_limit_approaches_exact_mask_attention(oracle):
+    """As n grows the GRF-masked attention approaches attention masked with the exact
+    M_alpha (the n -> infinity limit named in Sec. 4)."""
+    rng = np.random.default_rng(10)
+    g = synth.grid_graph(5, 5, 4, periodic=True, weights="sym_norm")
+    f = np.array([[1.0, 0.6, 0.3]], dtype=np.float32)
+    Q, K, V = synth.qkv(1, 1, g.n, 8, rng)
+    M = oracle.exact_mask(g.dense(), f[0])
+    _, _, want = oracle.attention_bruteforce(Q[0, 0], K[0, 0], V[0, 0], M)
+    errs = []
+    for n_walks in (4, 4000):
+        rp, col, val = oracle.sample(g, f, 0.3, n_walks, seed=0)
+        got = oracle.masked_linear_attention(Q, K, V, rp, col, val)["out"][0, 0]
+        errs.append(np.abs(got - want).max())
+    assert errs[1] < 0.05
+    assert errs[1] < 0.25 * errs[0]
+
+
+# --------------------------------------------------------------------------- input helpers
+
+def test_bf16_rounding_helper():
+    x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.1415927, 0.0], dtype=np.float32)
+    bits = synth.f32_to_bf16_bits(x)
+    back = synth.bf16_bits_to_f32(bits)
+    # 1 + 2^-8 is a tie between 1.0 and 1 + 2^-7 -> even mantissa (1.0); 1 + 3*2^-8 ties to 1 + 2^-6
+    assert back[0] == 1.0 and back[1] == 1.0 and back[2] == 1.015625 and back[3] == -2.5
+    assert abs(back[4] - 3.1415927) < 2 ** -7 * 2
+    assert np.array_equal(synth.f32_to_bf16_bits(back), bits)
