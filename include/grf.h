@@ -1,0 +1,167 @@
+/*
+ * grf.h -- C ABI of the MI355X (gfx950) library for topologically masked linear attention
+ * with graph random features (GRFs), after arXiv 2410.03462.
+ *
+ * The library does two things, both on one GPU and entirely in hand-written HIP kernels:
+ *
+ *   grf_sample                    graph (CSR) + modulation f + p_halt + n_walks + seed  ->  Phi_hat (CSR)
+ *                                 [Sec. 3.3, GRF definition; Alg. 1 steps 1-2]
+ *   grf_masked_linear_attention   Q, K, V, Phi_hat  ->  out = D^-1 (Phi_Q,G (Phi_K,G^T V))
+ *                                 [Eq. 7 / Alg. 1 steps 3-5]
+ *
+ * Conventions
+ *   - Every array argument is a DEVICE pointer owned by the caller unless its comment says HOST.
+ *     The library never allocates or frees device memory and keeps no state between calls; all
+ *     temporaries live in the caller's workspace.
+ *   - All work is enqueued on the caller's stream (a hipStream_t passed as void*; NULL is the
+ *     default stream).  Only grf_sample synchronises the stream (once, to learn nnz).
+ *   - Every entry point returns GRF_OK (0) or a negative grf_status; the message of the last error
+ *     on the calling thread is available from grf_last_error().  Arguments are validated on the
+ *     host before anything is launched; on error nothing partial is promised in the outputs.
+ *   - Calls that share a workspace or an output buffer must not overlap in time.
+ */
+#ifndef GRF_H_
+#define GRF_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t grf_status;
+#define GRF_OK            0
+#define GRF_EINVAL       (-1)   /* an argument is out of its documented range, or a required pointer is NULL   */
+#define GRF_ECAPACITY    (-2)   /* phi_out->capacity is smaller than the number of entries sampled             */
+#define GRF_EUNSUPPORTED (-3)   /* valid request outside what the kernels cover (head dim, n_walks*f_len, nnz) */
+#define GRF_EHIP         (-4)   /* a HIP runtime call or kernel launch reported an error                       */
+#define GRF_EWORKSPACE   (-5)   /* workspace is NULL, misaligned (256 B) or smaller than *_workspace_bytes()   */
+
+/* Element type of Q, K, V. */
+#define GRF_DTYPE_F32   0
+#define GRF_DTYPE_BF16  1       /* bfloat16 inputs; buckets, accumulation and outputs stay fp32 */
+
+/* Query/key feature map phi (Alg. 1 step 3).  m = d for both. */
+#define GRF_PHI_RELU      0     /* phi(x) = max(x, 0) elementwise: the map used in the paper's experiments */
+#define GRF_PHI_IDENTITY  1     /* phi(x) = x: for tests */
+
+/* Message describing the last error returned on this thread.  Static storage; never free it. */
+const char* grf_last_error(void);
+
+/* Weighted adjacency matrix W of the graph G in CSR (Sec. 3.1).  Read-only.
+ * Contract: row_ptr[0] = 0, row_ptr[n] = nnz, columns strictly ascending within a row, no self loops,
+ * w finite.  deg(i) = row_ptr[i+1] - row_ptr[i] is the number of stored neighbours.  n, nnz < 2^31. */
+typedef struct grf_graph {
+    int64_t        n;
+    int64_t        nnz;
+    const int32_t* row_ptr;   /* [n+1] */
+    const int32_t* col;       /* [nnz] */
+    const float*   w;         /* [nnz] */
+} grf_graph;
+
+/* GRF matrix Phi_hat (n x n, sparse) in CSR.  Row i is the feature phi_hat(v_i) of Eq. (GRF definition):
+ * its stored columns are exactly the nodes visited by the walks out of v_i (ascending; a visited
+ * node stays stored even if its summed value is 0; the diagonal is always present).
+ * val holds n_f value planes that share row_ptr and col: plane h is at val + h * capacity. */
+typedef struct grf_phi {
+    int64_t  n;
+    int64_t  capacity;        /* allocated entries of col and of each val plane */
+    int32_t* row_ptr;         /* [n+1] */
+    int32_t* col;             /* [capacity] */
+    float*   val;             /* [n_f][capacity] */
+} grf_phi;
+
+/* ---------------------------------------------------------------------------------------------
+ * Sampling (Alg. 1 steps 1-2; Sec. 3.3).
+ *
+ * From every node i, n_walks independent simple random walks are simulated.  Before every hop a walk
+ * halts with probability p_halt, otherwise it moves to a uniformly chosen stored neighbour; it also
+ * stops after f_len visited nodes (f vanishes beyond index f_len-1) or at a node without neighbours.
+ * The prefix that reaches node q after t hops deposits
+ *       f[t] * prod_{s<t} W[u_s,u_{s+1}] * deg(u_s) / (1 - p_halt)
+ * into entry (i, q), and the row is divided by n_walks.
+ *
+ * Random stream (reproducible, independent of launch geometry): Philox4x32-10 with key
+ * (seed & 0xffffffff, seed >> 32) and counter (node, walk, block, 0).  Block b serves hops 2b+1 and
+ * 2b+2: words 0,1 are the (halt, neighbour) draws of hop 2b+1, words 2,3 those of hop 2b+2.
+ * A walk halts iff halt_draw < floor(p_halt * 2^32) (evaluated in fp64 on the host); the neighbour is
+ * entry floor(nbr_draw * deg / 2^32) of the CSR row.  Walk decisions are integer-only.
+ * --------------------------------------------------------------------------------------------- */
+
+/* Largest possible number of entries of Phi_hat: n * (1 + n_walks * (f_len - 1)).  -1 on bad arguments. */
+int64_t grf_sample_nnz_bound(int64_t n, int32_t n_walks, int32_t f_len);
+
+/* Bytes of workspace grf_sample needs (a multiple of 256).  0 on bad arguments. */
+size_t grf_sample_workspace_bytes(int64_t n, int32_t n_walks, int32_t f_len, int32_t n_f);
+
+/*
+ * g            graph, device arrays.
+ * f            HOST pointer, [n_f][f_len] row-major: n_f >= 1 modulation vectors that share one set of
+ *              walks (Phi_hat is linear in f).  Copied before the call returns.
+ * p_halt       in [0, 1].   n_walks >= 1.   f_len >= 1.
+ * workspace    device, 256-byte aligned, >= grf_sample_workspace_bytes(...).
+ * phi_out      caller-allocated.  row_ptr is always written.  col and the n_f planes of val are
+ *              written when capacity >= nnz; otherwise GRF_ECAPACITY is returned (with *nnz_out set), so
+ *              a first call with capacity 0 (col = val = NULL allowed) is a way to learn nnz.
+ * nnz_out      HOST pointer; receives the number of entries.  The call blocks on the stream for this.
+ *
+ * GRF_EUNSUPPORTED if 1 + n_walks*(f_len-1) exceeds what one wavefront can stage in LDS (currently
+ * 8192 deposits) or if the number of entries does not fit int32.
+ */
+grf_status grf_sample(const grf_graph* g,
+                      const float* f, int32_t f_len, int32_t n_f,
+                      double p_halt, int32_t n_walks, uint64_t seed,
+                      void* workspace, size_t workspace_bytes, void* hip_stream,
+                      grf_phi* phi_out, int64_t* nnz_out);
+
+/* The walks alone, for inspection: traj is device [n][n_walks][max_nodes] int32; entry t of a walk is
+ * the node visited after t hops, or -1 past its end.  Same stream as grf_sample with f_len = max_nodes. */
+grf_status grf_sample_walks(const grf_graph* g, double p_halt, int32_t n_walks, int32_t max_nodes,
+                            uint64_t seed, void* hip_stream, int32_t* traj);
+
+/* ---------------------------------------------------------------------------------------------
+ * Masked linear attention (Eq. 7; Alg. 1 steps 3-5), evaluated without ever forming the N x Nm
+ * matrices Phi_{Q,G}, Phi_{K,G}:
+ *
+ *   buckets   S_l = sum_j Phi_hat[j,l] phi(k_j) v_j^T  (d x d),  z_l = sum_j Phi_hat[j,l] phi(k_j)  (d)
+ *             -- block l of Phi_{K,G}^T V and of Phi_{K,G}^T 1
+ *   gather    num_i = sum_l Phi_hat[i,l] phi(q_i)^T S_l,   den_i = sum_l Phi_hat[i,l] phi(q_i)^T z_l
+ *             out_i = num_i / den_i      (no epsilon: den_i = 0 gives IEEE inf/NaN, not an error)
+ *
+ * Q, K, V    contiguous [B][H][n][d], dtype GRF_DTYPE_F32 or GRF_DTYPE_BF16.  d in {32, 64}.
+ * phi        Phi_hat with nnz entries (phi->row_ptr[n] == nnz) and n_f value planes: n_f == 1 is shared
+ *            by all heads, n_f == H gives head h plane h.  One graph per call, shared over the batch.
+ * --------------------------------------------------------------------------------------------- */
+
+/* Floats per bucket record: d*d of S_l (feature index major: S_l[a][c] at a*d + c) followed by d of z_l. */
+int64_t grf_bucket_record_floats(int32_t d);
+
+/* Workspace bytes (multiple of 256; 0 on bad arguments).
+ * bh_chunk: how many (batch, head) slices have their buckets resident at once; <= 0 means all B*H.
+ * grf_form_buckets needs the value returned for bh_chunk = 0 ... it uses only the transpose part. */
+size_t grf_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t bh_chunk);
+size_t grf_buckets_workspace_bytes(int64_t n, int64_t nnz);
+
+/* Buckets only (Alg. 1 step 5, the two Phi_{K,G}^T products).
+ * buckets: device [B*H][n][grf_bucket_record_floats(d)] fp32, fully overwritten. */
+grf_status grf_form_buckets(const void* K, const void* V, int32_t dtype,
+                            int64_t B, int64_t H, int64_t n, int32_t d,
+                            const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                            void* workspace, size_t workspace_bytes, void* hip_stream,
+                            float* buckets);
+
+/* The whole attention call.
+ * out       device [B][H][n][d] fp32.
+ * num_opt   device [B][H][n][d] fp32 or NULL;  den_opt  device [B][H][n] fp32 or NULL. */
+grf_status grf_masked_linear_attention(const void* Q, const void* K, const void* V, int32_t dtype,
+                                       int64_t B, int64_t H, int64_t n, int32_t d,
+                                       const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                       int32_t bh_chunk,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream,
+                                       float* out, float* num_opt, float* den_opt);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRF_H_ */

@@ -1,0 +1,290 @@
+"""ctypes binding of ``libgrf_hip.so`` (the C ABI declared in ``include/grf.h``).
+
+Argument marshalling only: every step of the method runs in the library's HIP kernels.
+PyTorch provides device memory and the current stream.  There is no CPU path: if the
+library has not been built, or no GPU is present, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch  # noqa: F401  (imported first so that the HIP runtime already loaded by torch is shared)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgrf_hip.so")
+
+GRF_OK, GRF_EINVAL, GRF_ECAPACITY, GRF_EUNSUPPORTED, GRF_EHIP, GRF_EWORKSPACE = 0, -1, -2, -3, -4, -5
+GRF_DTYPE_F32, GRF_DTYPE_BF16 = 0, 1
+GRF_PHI_RELU, GRF_PHI_IDENTITY = 0, 1
+_FEATURE_MAPS = {"relu": GRF_PHI_RELU, "identity": GRF_PHI_IDENTITY}
+_STATUS_NAMES = {GRF_EINVAL: "GRF_EINVAL", GRF_ECAPACITY: "GRF_ECAPACITY", GRF_EUNSUPPORTED: "GRF_EUNSUPPORTED",
+                 GRF_EHIP: "GRF_EHIP", GRF_EWORKSPACE: "GRF_EWORKSPACE"}
+
+
+class GrfError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+class _Graph(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int64), ("nnz", ctypes.c_int64), ("row_ptr", ctypes.c_void_p),
+                ("col", ctypes.c_void_p), ("w", ctypes.c_void_p)]
+
+
+class _Phi(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int64), ("capacity", ctypes.c_int64), ("row_ptr", ctypes.c_void_p),
+                ("col", ctypes.c_void_p), ("val", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library.  Raises if it has not been built (``python -m paper_2410_03462_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2410_03462_amd.build`; "
+                               "there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        L.grf_last_error.restype = ctypes.c_char_p
+        L.grf_sample_nnz_bound.restype = ctypes.c_int64
+        L.grf_sample_nnz_bound.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
+        L.grf_sample_workspace_bytes.restype = ctypes.c_size_t
+        L.grf_sample_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        L.grf_sample.restype = ctypes.c_int32
+        L.grf_sample.argtypes = [ctypes.POINTER(_Graph), ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                 ctypes.c_double, ctypes.c_int32, ctypes.c_uint64,
+                                 ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                 ctypes.POINTER(_Phi), ctypes.POINTER(ctypes.c_int64)]
+        L.grf_sample_walks.restype = ctypes.c_int32
+        L.grf_sample_walks.argtypes = [ctypes.POINTER(_Graph), ctypes.c_double, ctypes.c_int32, ctypes.c_int32,
+                                       ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]
+        L.grf_bucket_record_floats.restype = ctypes.c_int64
+        L.grf_bucket_record_floats.argtypes = [ctypes.c_int32]
+        L.grf_attention_workspace_bytes.restype = ctypes.c_size_t
+        L.grf_attention_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                                    ctypes.c_int64, ctypes.c_int32]
+        L.grf_buckets_workspace_bytes.restype = ctypes.c_size_t
+        L.grf_buckets_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64]
+        common = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                  ctypes.POINTER(_Phi), ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
+        L.grf_form_buckets.restype = ctypes.c_int32
+        L.grf_form_buckets.argtypes = [ctypes.c_void_p, ctypes.c_void_p, *common,
+                                       ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+        L.grf_masked_linear_attention.restype = ctypes.c_int32
+        L.grf_masked_linear_attention.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, *common,
+                                                  ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != GRF_OK:
+        raise GrfError(status, lib().grf_last_error().decode())
+
+
+def _require_gpu():
+    if not torch.cuda.is_available():
+        raise RuntimeError("no GPU visible: this library has no CPU path")
+
+
+def _stream_ptr(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None or t.numel() == 0 else int(t.data_ptr())
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+# --------------------------------------------------------------------------- containers
+
+@dataclass
+class DeviceGraph:
+    """Weighted adjacency matrix in CSR on the GPU."""
+    n: int
+    row_ptr: torch.Tensor   # int32 [n+1]
+    col: torch.Tensor       # int32 [nnz]
+    w: torch.Tensor         # float32 [nnz]
+
+    @property
+    def nnz(self) -> int:
+        return int(self.col.numel())
+
+    @staticmethod
+    def from_host(g, device="cuda:0") -> "DeviceGraph":
+        _require_gpu()
+        return DeviceGraph(int(g.n),
+                           torch.from_numpy(np.ascontiguousarray(g.row_ptr, dtype=np.int32)).to(device),
+                           torch.from_numpy(np.ascontiguousarray(g.col, dtype=np.int32)).to(device),
+                           torch.from_numpy(np.ascontiguousarray(g.w, dtype=np.float32)).to(device))
+
+    def _struct(self) -> _Graph:
+        return _Graph(self.n, self.nnz, _ptr(self.row_ptr), _ptr(self.col), _ptr(self.w))
+
+
+@dataclass
+class Phi:
+    """GRF matrix in CSR on the GPU; ``val`` is [n_f, capacity], the first ``nnz`` entries of each plane are live."""
+    n: int
+    nnz: int
+    row_ptr: torch.Tensor   # int32 [n+1]
+    col: torch.Tensor       # int32 [capacity]
+    val: torch.Tensor       # float32 [n_f, capacity]
+
+    @property
+    def capacity(self) -> int:
+        return int(self.col.numel())
+
+    @property
+    def n_f(self) -> int:
+        return int(self.val.shape[0])
+
+    @staticmethod
+    def empty(n: int, capacity: int, n_f: int, device="cuda:0") -> "Phi":
+        return Phi(n, 0, torch.empty(n + 1, dtype=torch.int32, device=device),
+                   torch.empty(capacity, dtype=torch.int32, device=device),
+                   torch.empty((n_f, capacity), dtype=torch.float32, device=device))
+
+    @staticmethod
+    def from_host(n: int, row_ptr, col, val, device="cuda:0") -> "Phi":
+        val = np.atleast_2d(np.ascontiguousarray(val, dtype=np.float32))
+        return Phi(int(n), int(col.shape[0]),
+                   torch.from_numpy(np.ascontiguousarray(row_ptr, dtype=np.int32)).to(device),
+                   torch.from_numpy(np.ascontiguousarray(col, dtype=np.int32)).to(device),
+                   torch.from_numpy(val).to(device))
+
+    def to_host(self):
+        return (self.row_ptr.cpu().numpy(), self.col[: self.nnz].cpu().numpy(), self.val[:, : self.nnz].cpu().numpy())
+
+    def _struct(self) -> _Phi:
+        return _Phi(self.n, self.capacity, _ptr(self.row_ptr), _ptr(self.col), _ptr(self.val))
+
+
+# --------------------------------------------------------------------------- entry points (same names as the C ABI)
+
+def grf_sample_nnz_bound(n: int, n_walks: int, f_len: int) -> int:
+    return int(lib().grf_sample_nnz_bound(n, n_walks, f_len))
+
+
+def grf_sample(graph: DeviceGraph, f, p_halt: float, n_walks: int, seed: int,
+               out: Optional[Phi] = None, capacity: Optional[int] = None, stream=None) -> Phi:
+    """Sample Phi_hat.  ``f`` is a host array [n_f, f_len] (or [f_len]).
+
+    With ``out`` the caller's buffers are reused (GrfError(GRF_ECAPACITY) if too small).  Otherwise the
+    buffers are sized by ``capacity``, or, if None, by a first call that only counts.
+    """
+    _require_gpu()
+    L = lib()
+    f = np.ascontiguousarray(np.atleast_2d(np.asarray(f, dtype=np.float32)))
+    n_f, f_len = f.shape
+    dev = graph.row_ptr.device
+    ws = _workspace(L.grf_sample_workspace_bytes(graph.n, n_walks, f_len, n_f), dev)
+    gs = graph._struct()
+    nnz = ctypes.c_int64(0)
+
+    def call(phi: Phi) -> int:
+        ps = phi._struct()
+        return L.grf_sample(ctypes.byref(gs), f.ctypes.data_as(ctypes.c_void_p), f_len, n_f, float(p_halt),
+                            int(n_walks), int(seed) & 0xFFFFFFFFFFFFFFFF, _ptr(ws), ws.numel(), _stream_ptr(stream),
+                            ctypes.byref(ps), ctypes.byref(nnz))
+
+    if out is None:
+        if capacity is None:
+            probe = Phi.empty(graph.n, 0, n_f, dev)
+            st = call(probe)
+            if st not in (GRF_OK, GRF_ECAPACITY):
+                _check(st)
+            capacity = int(nnz.value)
+        out = Phi.empty(graph.n, int(capacity), n_f, dev)
+    elif out.n_f != n_f or out.n != graph.n:
+        raise ValueError("out does not match the graph / number of f sets")
+    _check(call(out))
+    out.nnz = int(nnz.value)
+    return out
+
+
+def grf_sample_walks(graph: DeviceGraph, p_halt: float, n_walks: int, max_nodes: int, seed: int, stream=None) -> torch.Tensor:
+    """Trajectories [n, n_walks, max_nodes] int32 on the GPU, -1 past the end of a walk."""
+    _require_gpu()
+    traj = torch.empty((graph.n, n_walks, max_nodes), dtype=torch.int32, device=graph.row_ptr.device)
+    gs = graph._struct()
+    _check(lib().grf_sample_walks(ctypes.byref(gs), float(p_halt), int(n_walks), int(max_nodes),
+                                  int(seed) & 0xFFFFFFFFFFFFFFFF, _stream_ptr(stream), _ptr(traj)))
+    return traj
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return GRF_DTYPE_F32
+    if t.dtype == torch.bfloat16:
+        return GRF_DTYPE_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _check_qkv(*ts):
+    shape, dtype = ts[0].shape, ts[0].dtype
+    for t in ts:
+        if not t.is_cuda or not t.is_contiguous() or t.shape != shape or t.dtype != dtype or t.dim() != 4:
+            raise ValueError("Q, K, V must be contiguous CUDA tensors of one shape [B,H,n,d] and dtype")
+    return shape
+
+
+def grf_bucket_record_floats(d: int) -> int:
+    return int(lib().grf_bucket_record_floats(d))
+
+
+def grf_attention_workspace_bytes(B: int, H: int, n: int, d: int, nnz: int, bh_chunk: int = 0) -> int:
+    return int(lib().grf_attention_workspace_bytes(B, H, n, d, nnz, bh_chunk))
+
+
+def grf_form_buckets(K: torch.Tensor, V: torch.Tensor, phi: Phi, feature_map: str = "relu", stream=None) -> torch.Tensor:
+    """Bucket records [B*H, n, d*d + d] fp32: S_l (d x d, feature index major) then z_l."""
+    _require_gpu()
+    L = lib()
+    B, H, n, d = _check_qkv(K, V)
+    rec = L.grf_bucket_record_floats(d)
+    if rec < 0:
+        raise GrfError(GRF_EUNSUPPORTED, f"head dimension d={d} is not supported")
+    buckets = torch.empty((B * H, n, rec), dtype=torch.float32, device=K.device)
+    ws = _workspace(L.grf_buckets_workspace_bytes(n, phi.nnz), K.device)
+    ps = phi._struct()
+    _check(L.grf_form_buckets(_ptr(K), _ptr(V), _dtype_code(K), B, H, n, d, ctypes.byref(ps), phi.nnz, phi.n_f,
+                              _FEATURE_MAPS[feature_map], _ptr(ws), ws.numel(), _stream_ptr(stream), _ptr(buckets)))
+    return buckets
+
+
+def grf_masked_linear_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, phi: Phi,
+                                feature_map: str = "relu", bh_chunk: int = 0, return_num_den: bool = False,
+                                workspace: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                                stream=None):
+    """out [B,H,n,d] fp32 (and num, den if asked)."""
+    _require_gpu()
+    L = lib()
+    B, H, n, d = _check_qkv(Q, K, V)
+    need = L.grf_attention_workspace_bytes(B, H, n, d, phi.nnz, bh_chunk)
+    if need == 0:
+        raise GrfError(GRF_EUNSUPPORTED, f"unsupported problem (d={d})")
+    if workspace is None:
+        workspace = _workspace(need, Q.device)
+    if out is None:
+        out = torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device)
+    num = torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device) if return_num_den else None
+    den = torch.empty((B, H, n), dtype=torch.float32, device=Q.device) if return_num_den else None
+    ps = phi._struct()
+    _check(L.grf_masked_linear_attention(_ptr(Q), _ptr(K), _ptr(V), _dtype_code(Q), B, H, n, d, ctypes.byref(ps),
+                                         phi.nnz, phi.n_f, _FEATURE_MAPS[feature_map], int(bh_chunk),
+                                         _ptr(workspace), workspace.numel(), _stream_ptr(stream),
+                                         _ptr(out), _ptr(num), _ptr(den)))
+    return (out, num, den) if return_num_den else out

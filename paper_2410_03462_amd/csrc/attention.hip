@@ -1,0 +1,451 @@
+// GRF-masked linear attention (Eq. 7; Alg. 1 steps 3-5) on gfx950.
+//
+//   transpose   Phi_hat CSR -> column lists (who contributes to bucket l), rows ascending
+//   buckets     S_l = sum_j Phi_hat[j,l] phi(k_j) v_j^T,  z_l = sum_j Phi_hat[j,l] phi(k_j)
+//               one wavefront per (slice, l); the (d x r_l)(r_l x d) contraction runs on fp32 MFMA
+//   gather      num_i = sum_l Phi_hat[i,l] phi(q_i)^T S_l, den_i likewise with z_l; out = num/den
+//               one wavefront per (slice, i); streams one contiguous bucket record per entry
+//
+// A bucket record is d*d floats of S_l (S_l[a][c] at a*d + c, a = feature index of phi(k)) followed
+// by d floats of z_l, so the gather reads one contiguous run per entry of Phi_hat.
+#include "common.hpp"
+
+namespace grf {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// ------------------------------------------------------------------------------------ element loads
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(static_cast<uint32_t>(x.bits) << 16); }
+
+__device__ __forceinline__ float feature(float x, int relu) { return relu ? fmaxf(x, 0.0f) : x; }
+
+// ------------------------------------------------------------------------------------ transpose
+__global__ __launch_bounds__(256) void column_histogram_kernel(const int32_t* __restrict__ col, long long nnz, int32_t n,
+                                                               int32_t* __restrict__ count)
+{
+    const long long e = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (e >= nnz) return;
+    const int32_t c = col[e];
+    if (static_cast<uint32_t>(c) < static_cast<uint32_t>(n)) atomicAdd(&count[c], 1);
+}
+
+// One wavefront per row: scatter (row, entry index) into the column segments.  The order inside
+// a segment depends on atomic arrival and is fixed afterwards by column_sort_kernel.
+__global__ __launch_bounds__(256) void column_scatter_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
+                                                             long long nnz, int32_t n, const int32_t* __restrict__ col_ptr,
+                                                             int32_t* __restrict__ cursor, int32_t* __restrict__ u_row,
+                                                             int32_t* __restrict__ u_src)
+{
+    const long long row = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (row >= n) return;
+    const long long beg = row_ptr[row];
+    long long end = row_ptr[row + 1];
+    if (end > nnz) end = nnz;
+    for (long long e = beg + lane_id(); e < end; e += kWave) {
+        if (e < 0) continue;
+        const int32_t c = col[e];
+        if (static_cast<uint32_t>(c) >= static_cast<uint32_t>(n)) continue;
+        const int32_t slot = col_ptr[c] + atomicAdd(&cursor[c], 1);
+        if (slot >= col_ptr[c + 1]) continue;   // only with overlapping rows in a malformed row_ptr
+        u_row[slot] = static_cast<int32_t>(row);
+        u_src[slot] = static_cast<int32_t>(e);
+    }
+}
+
+// One wavefront per column: order the segment by row index (rows are distinct within a column)
+// by counting, so that the buckets are summed in a fixed order.  Quadratic in the segment length.
+__global__ __launch_bounds__(256) void column_sort_kernel(const int32_t* __restrict__ col_ptr, int32_t n,
+                                                          const int32_t* __restrict__ u_row, const int32_t* __restrict__ u_src,
+                                                          int32_t* __restrict__ s_row, int32_t* __restrict__ s_src)
+{
+    const long long c = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (c >= n) return;
+    const int32_t beg = col_ptr[c];
+    const int32_t len = col_ptr[c + 1] - beg;
+    for (int s = lane_id(); s < len; s += kWave) {
+        const int32_t key = u_row[beg + s];
+        int rank = 0;
+        for (int s2 = 0; s2 < len; ++s2) rank += static_cast<int>(u_row[beg + s2] < key);
+        s_row[beg + rank] = key;
+        s_src[beg + rank] = u_src[beg + s];
+    }
+}
+
+// ------------------------------------------------------------------------------------ buckets
+// v_mfma_f32_32x32x2_f32: D(32x32) += A(32x2) B(2x32).  Lane L supplies A[L%32][L/32] and
+// B[L/32][L%32]; accumulator register r of lane L holds D[8*(r/4) + 4*(L/32) + r%4][L%32].
+// The two halves of the wavefront therefore carry two different contributors j (the k index),
+// lane%32 walks along a row of phi(K) (A operand) and of V (B operand): no transposes, no LDS.
+template <int D, typename T>
+__global__ __launch_bounds__(256) void buckets_kernel(const T* __restrict__ K, const T* __restrict__ V,
+                                                      long long n, int H, int n_f, long long val_stride,
+                                                      const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
+                                                      const int32_t* __restrict__ csc_src, const float* __restrict__ phi_val,
+                                                      int relu, long long bh_first, long long n_waves, int32_t nnz,
+                                                      float* __restrict__ buckets)
+{
+    constexpr int T2 = D / 32;
+    constexpr long long REC = static_cast<long long>(D) * D + D;
+    const long long wave = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (wave >= n_waves) return;
+    const long long slice = wave / n;          // slice index inside this launch
+    const long long l = wave - slice * n;
+    const long long bh = bh_first + slice;
+    const long long plane = n_f > 1 ? (bh % H) : 0;
+    const T* Kb = K + bh * n * D;
+    const T* Vb = V + bh * n * D;
+    const float* vals = phi_val + plane * val_stride;
+
+    const int lane = lane_id();
+    const int half = lane >> 5;
+    const int li = lane & 31;
+
+    floatx16 acc[T2][T2];
+    float zacc[T2];
+#pragma unroll
+    for (int a = 0; a < T2; ++a) {
+        zacc[a] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < T2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
+    }
+
+    const int32_t beg = col_ptr[l];
+    const int32_t end = col_ptr[l + 1];
+    for (int32_t chunk = beg; chunk < end; chunk += kWave) {
+        const int32_t e = chunk + lane;
+        int32_t j_reg = 0;
+        float g_reg = 0.0f;
+        if (e < end) {
+            const int32_t row = csc_row[e];
+            const int32_t src = csc_src[e];
+            // entries that a malformed Phi_hat left unset are dropped instead of followed
+            if (static_cast<uint32_t>(row) < static_cast<uint32_t>(n) && static_cast<uint32_t>(src) < static_cast<uint32_t>(nnz)) {
+                j_reg = row;
+                g_reg = vals[src];
+            }
+        }
+        const int cnt = min(kWave, end - chunk);
+        for (int p = 0; p < cnt; p += 2) {
+            const int src = p + half;
+            const long long j = __shfl(j_reg, src, kWave);
+            const float g = __shfl(g_reg, src, kWave);
+            const bool valid = src < cnt;
+            float a_op[T2], b_op[T2];
+#pragma unroll
+            for (int t = 0; t < T2; ++t) {
+                const float kv = valid ? to_float(Kb[j * D + 32 * t + li]) : 0.0f;
+                const float vv = valid ? to_float(Vb[j * D + 32 * t + li]) : 0.0f;
+                a_op[t] = valid ? g * feature(kv, relu) : 0.0f;
+                b_op[t] = vv;
+                zacc[t] += a_op[t];
+            }
+#pragma unroll
+            for (int a = 0; a < T2; ++a)
+#pragma unroll
+                for (int c = 0; c < T2; ++c)
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_op[a], b_op[c], acc[a][c], 0, 0, 0);
+        }
+    }
+
+    float* rec = buckets + (slice * n + l) * REC;
+#pragma unroll
+    for (int a = 0; a < T2; ++a)
+#pragma unroll
+        for (int c = 0; c < T2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = 32 * a + 8 * (r / 4) + 4 * half + (r % 4);
+                rec[row * D + 32 * c + li] = acc[a][c][r];
+            }
+#pragma unroll
+    for (int a = 0; a < T2; ++a) {
+        const float zt = zacc[a] + __shfl_xor(zacc[a], 32, kWave);
+        if (half == 0) rec[D * D + 32 * a + li] = zt;
+    }
+}
+
+// ------------------------------------------------------------------------------------ gather
+// One wavefront per (slice, row i).  A record is read with 16-byte loads: lane L covers columns
+// 4*(L % (D/4)) .. +3 of row  j*(256/D) + L/(D/4)  for load j; the weight Phi_hat[i,l] * phi(q_i)[row]
+// is applied on the fly, so only four accumulators per lane are live and the reduction over the
+// D/ (256/D) row groups happens once per output row.
+template <int D, typename T>
+__global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ Q, long long n, int H, int n_f, long long val_stride,
+                                                     const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
+                                                     const float* __restrict__ phi_val, int relu,
+                                                     const float* __restrict__ buckets, long long bh_first, long long n_waves,
+                                                     int32_t nnz, float* __restrict__ out, float* __restrict__ num_opt, float* __restrict__ den_opt)
+{
+    constexpr int LPR = D / 4;            // lanes per record row
+    constexpr int RPL = kWave / LPR;      // record rows per 1 KB load
+    constexpr int NL = D / RPL;           // loads per record
+    constexpr long long REC = static_cast<long long>(D) * D + D;
+    const long long wave = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (wave >= n_waves) return;
+    const long long slice = wave / n;
+    const long long i = wave - slice * n;
+    const long long bh = bh_first + slice;
+    const long long plane = n_f > 1 ? (bh % H) : 0;
+    const float* vals = phi_val + plane * val_stride;
+    const T* q = Q + (bh * n + i) * D;
+    const float* slice_buckets = buckets + slice * n * REC;
+
+    const int lane = lane_id();
+    const int sub = lane / LPR;
+    const int cg = lane % LPR;
+
+    float fq[NL];
+#pragma unroll
+    for (int j = 0; j < NL; ++j) fq[j] = feature(to_float(q[j * RPL + sub]), relu);
+    const float fq_lane = lane < D ? feature(to_float(q[lane < D ? lane : 0]), relu) : 0.0f;
+
+    float acc0 = 0.0f, acc1 = 0.0f, acc2 = 0.0f, acc3 = 0.0f, zacc = 0.0f;
+
+    const int32_t beg = max(row_ptr[i], 0);
+    const int32_t end = min(row_ptr[i + 1], nnz);
+    for (int32_t chunk = beg; chunk < end; chunk += kWave) {
+        const int32_t e = chunk + lane;
+        int32_t c_reg = 0;
+        float w_reg = 0.0f;
+        if (e < end) { c_reg = col[e]; w_reg = vals[e]; }
+        const int cnt = min(kWave, end - chunk);
+        for (int t = 0; t < cnt; ++t) {
+            const int32_t c = __builtin_amdgcn_readlane(c_reg, t);
+            const float w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_reg), t));
+            if (static_cast<uint32_t>(c) >= static_cast<uint32_t>(n)) continue;
+            const float* rec = slice_buckets + static_cast<long long>(c) * REC;
+            const float4* rec4 = reinterpret_cast<const float4*>(rec) + lane;
+            float4 v[NL];
+#pragma unroll
+            for (int j = 0; j < NL; ++j) v[j] = rec4[j * kWave];
+            const float zv = lane < D ? rec[D * D + (lane < D ? lane : 0)] : 0.0f;
+#pragma unroll
+            for (int j = 0; j < NL; ++j) {
+                const float wq = w * fq[j];
+                acc0 = fmaf(wq, v[j].x, acc0);
+                acc1 = fmaf(wq, v[j].y, acc1);
+                acc2 = fmaf(wq, v[j].z, acc2);
+                acc3 = fmaf(wq, v[j].w, acc3);
+            }
+            zacc = fmaf(w, zv, zacc);
+        }
+    }
+
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1) {
+        acc0 += __shfl_xor(acc0, off, kWave);
+        acc1 += __shfl_xor(acc1, off, kWave);
+        acc2 += __shfl_xor(acc2, off, kWave);
+        acc3 += __shfl_xor(acc3, off, kWave);
+    }
+    const float den = wave_sum(fq_lane * zacc);
+
+    if (sub == 0) {
+        const long long o = (bh * n + i) * D + 4 * cg;
+        *reinterpret_cast<float4*>(out + o) = make_float4(acc0 / den, acc1 / den, acc2 / den, acc3 / den);
+        if (num_opt != nullptr) *reinterpret_cast<float4*>(num_opt + o) = make_float4(acc0, acc1, acc2, acc3);
+    }
+    if (lane == 0 && den_opt != nullptr) den_opt[bh * n + i] = den;
+}
+
+// ------------------------------------------------------------------------------------ host side
+namespace {
+
+struct Transposed {
+    int32_t* col_ptr;   // [n+1]
+    int32_t* cursor;    // [n]
+    int32_t* u_row;     // [nnz] unsorted
+    int32_t* u_src;
+    int32_t* s_row;     // [nnz] rows ascending inside each column
+    int32_t* s_src;     // index of the entry in CSR order (addresses every value plane)
+    long long* total;
+    size_t bytes;
+};
+
+Transposed carve_transposed(unsigned char* ws, int64_t n, int64_t nnz)
+{
+    Transposed t;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { unsigned char* p = ws ? ws + off : nullptr; off += align_up(bytes); return p; };
+    t.col_ptr = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n + 1)));
+    t.cursor = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n > 0 ? n : 1)));
+    t.u_row = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(nnz > 0 ? nnz : 1)));
+    t.u_src = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(nnz > 0 ? nnz : 1)));
+    t.s_row = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(nnz > 0 ? nnz : 1)));
+    t.s_src = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(nnz > 0 ? nnz : 1)));
+    t.total = reinterpret_cast<long long*>(take(sizeof(long long)));
+    t.bytes = off;
+    return t;
+}
+
+unsigned blocks_for(long long items, int per_block) { return static_cast<unsigned>((items + per_block - 1) / per_block); }
+
+grf_status transpose(const grf_phi* phi, int64_t nnz, const Transposed& t, hipStream_t stream)
+{
+    const int64_t n = phi->n;
+    if (grf_status st = fill_i32(t.col_ptr, n + 1, 0, stream)) return st;
+    if (grf_status st = fill_i32(t.cursor, n, 0, stream)) return st;
+    if (nnz > 0) {
+        hipLaunchKernelGGL(column_histogram_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, stream,
+                           static_cast<const int32_t*>(phi->col), static_cast<long long>(nnz), static_cast<int32_t>(n), t.col_ptr);
+        GRF_LAUNCH_CHECK("column_histogram_kernel");
+    }
+    if (grf_status st = exclusive_scan_inplace(t.col_ptr, n, t.total, stream)) return st;
+    if (nnz > 0) {
+        hipLaunchKernelGGL(column_scatter_kernel, dim3(blocks_for(n, 4)), dim3(256), 0, stream,
+                           static_cast<const int32_t*>(phi->row_ptr), static_cast<const int32_t*>(phi->col),
+                           static_cast<long long>(nnz), static_cast<int32_t>(n), static_cast<const int32_t*>(t.col_ptr),
+                           t.cursor, t.u_row, t.u_src);
+        GRF_LAUNCH_CHECK("column_scatter_kernel");
+        hipLaunchKernelGGL(column_sort_kernel, dim3(blocks_for(n, 4)), dim3(256), 0, stream,
+                           static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n),
+                           static_cast<const int32_t*>(t.u_row), static_cast<const int32_t*>(t.u_src), t.s_row, t.s_src);
+        GRF_LAUNCH_CHECK("column_sort_kernel");
+    }
+    return GRF_OK;
+}
+
+grf_status check_problem(const void* a, const void* b, int32_t dtype, int64_t B, int64_t H, int64_t n, int32_t d,
+                         const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map)
+{
+    if (B < 0 || H < 0 || n < 0) return fail(GRF_EINVAL, "B=%lld, H=%lld, n=%lld must be >= 0", (long long)B, (long long)H, (long long)n);
+    if (dtype != GRF_DTYPE_F32 && dtype != GRF_DTYPE_BF16) return fail(GRF_EINVAL, "dtype=%d is neither GRF_DTYPE_F32 nor GRF_DTYPE_BF16", dtype);
+    if (feature_map != GRF_PHI_RELU && feature_map != GRF_PHI_IDENTITY) return fail(GRF_EINVAL, "feature_map=%d is unknown", feature_map);
+    if (d != 32 && d != 64) return fail(GRF_EUNSUPPORTED, "head dimension d=%d is not supported (32 or 64)", d);
+    if (phi == nullptr) return fail(GRF_EINVAL, "phi is NULL");
+    if (phi->n != n) return fail(GRF_EINVAL, "phi->n=%lld differs from n=%lld", (long long)phi->n, (long long)n);
+    if (nnz < 0 || nnz > phi->capacity) return fail(GRF_EINVAL, "nnz=%lld must lie in [0, phi->capacity=%lld]", (long long)nnz, (long long)phi->capacity);
+    if (nnz >= 2147483647ll || n >= 2147483647ll) return fail(GRF_EUNSUPPORTED, "n and nnz must be < 2^31 - 1");
+    if (n_f != 1 && n_f != H) return fail(GRF_EINVAL, "n_f=%d must be 1 or H=%lld", n_f, (long long)H);
+    if (phi->row_ptr == nullptr || (nnz > 0 && (phi->col == nullptr || phi->val == nullptr))) return fail(GRF_EINVAL, "phi arrays are NULL");
+    if (B * H * n > 0 && (a == nullptr || b == nullptr)) return fail(GRF_EINVAL, "an input tensor is NULL");
+    if (B * H > (1ll << 40) / (n > 0 ? n : 1)) return fail(GRF_EUNSUPPORTED, "B*H*n is too large");
+    return GRF_OK;
+}
+
+grf_status check_workspace(const void* workspace, size_t have, size_t need)
+{
+    if (workspace == nullptr || have < need || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
+        return fail(GRF_EWORKSPACE, "workspace must be non-NULL, 256-byte aligned and >= %zu bytes (got %zu)", need, have);
+    return GRF_OK;
+}
+
+template <int D, typename T>
+grf_status launch_buckets(const void* K, const void* V, int64_t n, int64_t H, int32_t n_f, const grf_phi* phi,
+                          int64_t nnz, const Transposed& t, int relu, int64_t bh_first, int64_t n_slices, float* buckets,
+                          hipStream_t stream)
+{
+    const long long waves = static_cast<long long>(n_slices) * n;
+    if (waves == 0) return GRF_OK;
+    hipLaunchKernelGGL((buckets_kernel<D, T>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream,
+                       static_cast<const T*>(K), static_cast<const T*>(V), static_cast<long long>(n), static_cast<int>(H),
+                       static_cast<int>(n_f), static_cast<long long>(phi->capacity),
+                       static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
+                       static_cast<const int32_t*>(t.s_src), static_cast<const float*>(phi->val), relu,
+                       static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), buckets);
+    GRF_LAUNCH_CHECK("buckets_kernel");
+    return GRF_OK;
+}
+
+template <int D, typename T>
+grf_status launch_gather(const void* Q, int64_t n, int64_t H, int32_t n_f, const grf_phi* phi, int64_t nnz, int relu,
+                         const float* buckets, int64_t bh_first, int64_t n_slices,
+                         float* out, float* num_opt, float* den_opt, hipStream_t stream)
+{
+    const long long waves = static_cast<long long>(n_slices) * n;
+    if (waves == 0) return GRF_OK;
+    hipLaunchKernelGGL((gather_kernel<D, T>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream,
+                       static_cast<const T*>(Q), static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
+                       static_cast<long long>(phi->capacity), static_cast<const int32_t*>(phi->row_ptr),
+                       static_cast<const int32_t*>(phi->col), static_cast<const float*>(phi->val), relu, buckets,
+                       static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), out, num_opt, den_opt);
+    GRF_LAUNCH_CHECK("gather_kernel");
+    return GRF_OK;
+}
+
+// Dispatch on (d, dtype) to the compiled instances.
+#define GRF_DISPATCH(d, dtype, CALL)                                                     \
+    do {                                                                                 \
+        if ((d) == 64 && (dtype) == GRF_DTYPE_F32) { constexpr int D_ = 64; using T_ = float; CALL; }  \
+        else if ((d) == 64) { constexpr int D_ = 64; using T_ = bf16_t; CALL; }          \
+        else if ((dtype) == GRF_DTYPE_F32) { constexpr int D_ = 32; using T_ = float; CALL; }          \
+        else { constexpr int D_ = 32; using T_ = bf16_t; CALL; }                         \
+    } while (0)
+
+}  // namespace
+}  // namespace grf
+
+using namespace grf;
+
+extern "C" int64_t grf_bucket_record_floats(int32_t d)
+{
+    if (d != 32 && d != 64) return -1;
+    return static_cast<int64_t>(d) * d + d;
+}
+
+extern "C" size_t grf_buckets_workspace_bytes(int64_t n, int64_t nnz)
+{
+    if (n < 0 || nnz < 0) return 0;
+    return carve_transposed(nullptr, n, nnz).bytes;
+}
+
+extern "C" size_t grf_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t bh_chunk)
+{
+    if (B < 0 || H < 0 || n < 0 || nnz < 0 || (d != 32 && d != 64)) return 0;
+    int64_t slices = B * H;
+    if (bh_chunk > 0 && bh_chunk < slices) slices = bh_chunk;
+    const size_t bucket_bytes = sizeof(float) * static_cast<size_t>(slices) * static_cast<size_t>(n) * static_cast<size_t>(grf_bucket_record_floats(d));
+    return carve_transposed(nullptr, n, nnz).bytes + align_up(bucket_bytes);
+}
+
+extern "C" grf_status grf_form_buckets(const void* K, const void* V, int32_t dtype,
+                                       int64_t B, int64_t H, int64_t n, int32_t d,
+                                       const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream, float* buckets)
+{
+    if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
+    if (B * H * n > 0 && buckets == nullptr) return fail(GRF_EINVAL, "buckets is NULL");
+    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_buckets_workspace_bytes(n, nnz))) return st;
+    if (B * H * n == 0) return GRF_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Transposed t = carve_transposed(static_cast<unsigned char*>(workspace), n, nnz);
+    if (grf_status st = transpose(phi, nnz, t, stream)) return st;
+    const int relu = feature_map == GRF_PHI_RELU ? 1 : 0;
+    grf_status st = GRF_OK;
+    GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, phi, nnz, t, relu, 0, B * H, buckets, stream)));
+    return st;
+}
+
+extern "C" grf_status grf_masked_linear_attention(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                  int64_t B, int64_t H, int64_t n, int32_t d,
+                                                  const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                  int32_t bh_chunk,
+                                                  void* workspace, size_t workspace_bytes, void* hip_stream,
+                                                  float* out, float* num_opt, float* den_opt)
+{
+    if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
+    if (B * H * n > 0 && (Q == nullptr || out == nullptr)) return fail(GRF_EINVAL, "Q / out is NULL");
+    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_attention_workspace_bytes(B, H, n, d, nnz, bh_chunk))) return st;
+    if (B * H * n == 0) return GRF_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Transposed t = carve_transposed(static_cast<unsigned char*>(workspace), n, nnz);
+    float* buckets = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + t.bytes);
+    if (grf_status st = transpose(phi, nnz, t, stream)) return st;
+    const int relu = feature_map == GRF_PHI_RELU ? 1 : 0;
+    const int64_t slices = B * H;
+    const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;
+    for (int64_t first = 0; first < slices; first += step) {
+        const int64_t count = (slices - first < step) ? (slices - first) : step;
+        grf_status st = GRF_OK;
+        GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, phi, nnz, t, relu, first, count, buckets, stream)));
+        if (st != GRF_OK) return st;
+        GRF_DISPATCH(d, dtype, (st = launch_gather<D_, T_>(Q, n, H, n_f, phi, nnz, relu, buckets, first, count, out, num_opt, den_opt, stream)));
+        if (st != GRF_OK) return st;
+    }
+    return GRF_OK;
+}

@@ -1,0 +1,380 @@
+// Random-walk sampler and CSR assembly of the GRF matrix Phi_hat (Alg. 1 steps 1-2; Sec. 3.3).
+//
+// One wavefront owns one start node: its lanes run that node's walks in lock step, deposit
+// (column, load, hop) triples into LDS, order them by column with a rank-by-counting pass and
+// merge equal columns.  The kernel runs twice, first to count the entries of every row and,
+// after an exclusive scan, to write them at their final place, so no worst-case staging buffer
+// exists in HBM.  Walk decisions are integer-only (Philox words, a threshold compare and a
+// multiply-high), hence trajectories and the sparsity pattern do not depend on floating point.
+#include "common.hpp"
+
+namespace grf {
+
+// ------------------------------------------------------------------------------------ Philox
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies and xors with
+// a Weyl-sequence key schedule.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    constexpr uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+        const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += W0;
+        k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+struct GraphView {
+    const int32_t* row_ptr;
+    const int32_t* col;
+    const float* w;
+    int32_t n;
+    int32_t nnz;
+};
+
+struct WalkLaw {
+    uint32_t key0, key1;      // Philox key = (seed low word, seed high word)
+    uint32_t threshold;       // halt iff draw < threshold ...
+    int32_t always_halt;      // ... or always, when p_halt = 1 makes the threshold 2^32
+    float inv_survive;        // 1 / (1 - p_halt)
+};
+
+// One hop of one walk.  `x` holds the Philox block serving hops 2b+1 (words 0,1) and 2b+2
+// (words 2,3).  Returns false when the walk ends before this hop (isolated node, halting draw,
+// or a malformed graph entry, which is treated as a dead end rather than followed out of bounds).
+__device__ __forceinline__ bool walk_hop(const GraphView& g, const WalkLaw& law, int t,
+                                         const uint32_t (&x)[4], int32_t& u, float& load)
+{
+    const int32_t beg = g.row_ptr[u];
+    const int32_t end = g.row_ptr[u + 1];
+    const int32_t deg = end - beg;
+    if (deg <= 0 || beg < 0 || end > g.nnz) return false;
+    const bool second = ((t - 1) & 1) != 0;
+    const uint32_t draw_halt = second ? x[2] : x[0];
+    const uint32_t draw_nbr = second ? x[3] : x[1];
+    if (law.always_halt || draw_halt < law.threshold) return false;
+    const int32_t e = beg + static_cast<int32_t>(__umulhi(draw_nbr, static_cast<uint32_t>(deg)));
+    const int32_t v = g.col[e];
+    if (static_cast<uint32_t>(v) >= static_cast<uint32_t>(g.n)) return false;
+    // importance weight of the prefix: edge weight over transition probability (1-p)/deg
+    load *= g.w[e] * (static_cast<float>(deg) * law.inv_survive);
+    u = v;
+    return true;
+}
+
+// ------------------------------------------------------------------------------------ trajectories
+__global__ __launch_bounds__(256) void walks_kernel(GraphView g, WalkLaw law, int n_walks, int max_nodes,
+                                                    int32_t* __restrict__ traj)
+{
+    const long long gid = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (gid >= static_cast<long long>(g.n) * n_walks) return;
+    const uint32_t node = static_cast<uint32_t>(gid / n_walks);
+    const uint32_t walk = static_cast<uint32_t>(gid % n_walks);
+    int32_t* out = traj + gid * max_nodes;
+    int32_t u = static_cast<int32_t>(node);
+    float load = 1.0f;
+    bool alive = true;
+    uint32_t x[4] = {0, 0, 0, 0};
+    out[0] = u;
+    for (int t = 1; t < max_nodes; ++t) {
+        if (((t - 1) & 1) == 0) philox4x32_10(node, walk, static_cast<uint32_t>((t - 1) >> 1), 0u, law.key0, law.key1, x);
+        if (alive) alive = walk_hop(g, law, t, x, u, load);
+        out[t] = alive ? u : -1;
+    }
+}
+
+// ------------------------------------------------------------------------------------ rows of Phi_hat
+// LDS layout for `cap` deposits: dcol[cap] dload[cap] scol[cap] sload[cap] (4 B each), dhop[cap]
+// shop[cap] (2 B each) = 20 B per deposit.
+constexpr int kDepositBytes = 20;
+
+template <bool FILL>
+__global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int n_walks, int f_len, int n_f,
+                                                  const float* __restrict__ f, int cap,
+                                                  int32_t* __restrict__ row_ptr, int32_t* __restrict__ col_out,
+                                                  float* __restrict__ val_out, long long val_stride)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    int32_t* dcol = reinterpret_cast<int32_t*>(lds);
+    float* dload = reinterpret_cast<float*>(dcol + cap);
+    int32_t* scol = reinterpret_cast<int32_t*>(dload + cap);
+    float* sload = reinterpret_cast<float*>(scol + cap);
+    uint16_t* dhop = reinterpret_cast<uint16_t*>(sload + cap);
+    uint16_t* shop = dhop + cap;
+
+    const uint32_t node = blockIdx.x;
+    const int lane = threadIdx.x;
+
+    // The n_walks zero-hop prefixes all deposit load 1 at the start node: one merged deposit.
+    if (lane == 0) { dcol[0] = static_cast<int32_t>(node); dload[0] = static_cast<float>(n_walks); dhop[0] = 0; }
+    int base = 1;
+    for (int first = 0; first < n_walks; first += kWave) {
+        const uint32_t walk = static_cast<uint32_t>(first + lane);
+        bool alive = static_cast<int>(walk) < n_walks;
+        int32_t u = static_cast<int32_t>(node);
+        float load = 1.0f;
+        uint32_t x[4] = {0, 0, 0, 0};
+        for (int t = 1; t < f_len; ++t) {
+            if (((t - 1) & 1) == 0) philox4x32_10(node, walk, static_cast<uint32_t>((t - 1) >> 1), 0u, law.key0, law.key1, x);
+            if (alive) alive = walk_hop(g, law, t, x, u, load);
+            const unsigned long long mask = __ballot(alive);
+            if (mask == 0ull) break;
+            if (alive) {
+                const int pos = base + prefix_popcount(mask);
+                dcol[pos] = u; dload[pos] = load; dhop[pos] = static_cast<uint16_t>(t);
+            }
+            base += __popcll(mask);
+        }
+    }
+    const int D = base;   // <= 1 + n_walks * (f_len - 1) <= cap
+    __syncthreads();
+
+    // Rank by counting: position of deposit s in the order (column, s).
+    for (int s = lane; s < D; s += kWave) {
+        const int32_t c = dcol[s];
+        int rank = 0;
+        for (int s2 = 0; s2 < D; ++s2) {
+            const int32_t c2 = dcol[s2];
+            rank += static_cast<int>((c2 < c) | ((c2 == c) & (s2 < s)));
+        }
+        scol[rank] = c; sload[rank] = dload[s]; shop[rank] = dhop[s];
+    }
+    __syncthreads();
+
+    // Runs of equal columns: the run head writes the merged entry.
+    const int32_t row_start = FILL ? row_ptr[node] : 0;
+    const float n_float = static_cast<float>(n_walks);
+    int heads = 0;
+    for (int r0 = 0; r0 < D; r0 += kWave) {
+        const int r = r0 + lane;
+        const bool valid = r < D;
+        const int32_t c = valid ? scol[r] : -1;
+        const bool head = valid && (r == 0 || scol[r - 1] != c);
+        const unsigned long long mask = __ballot(head);
+        if (FILL && head) {
+            const long long pos = static_cast<long long>(row_start) + heads + prefix_popcount(mask);
+            col_out[pos] = c;
+            for (int h = 0; h < n_f; ++h) {
+                const float* fh = f + static_cast<long long>(h) * f_len;
+                float acc = 0.0f;
+                for (int e = r; e < D && scol[e] == c; ++e) acc = fmaf(sload[e], fh[shop[e]], acc);
+                val_out[h * val_stride + pos] = acc / n_float;
+            }
+        }
+        heads += __popcll(mask);
+    }
+    if (!FILL && lane == 0) row_ptr[node] = heads;
+}
+
+// ------------------------------------------------------------------------------------ scan / fill
+__global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ data, long long n, long long* __restrict__ total64)
+{
+    __shared__ long long wave_total[16];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+    long long carry = 0;
+    for (long long tile = 0; tile < n; tile += 4096) {
+        const long long idx = tile + static_cast<long long>(tid) * 4;
+        int32_t v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = (idx + k < n) ? data[idx + k] : 0;
+        const long long local = static_cast<long long>(v[0]) + v[1] + v[2] + v[3];
+        long long incl = local;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const long long up = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += up;
+        }
+        if (lane == kWave - 1) wave_total[wave] = incl;
+        __syncthreads();
+        long long before = 0, tile_total = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const long long t = wave_total[w];
+            if (w < wave) before += t;
+            tile_total += t;
+        }
+        long long run = carry + before + incl - local;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (idx + k < n) data[idx + k] = run > 2147483647ll ? 2147483647 : static_cast<int32_t>(run);
+            run += v[k];
+        }
+        carry += tile_total;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        data[n] = carry > 2147483647ll ? 2147483647 : static_cast<int32_t>(carry);
+        *total64 = carry;
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_kernel(int32_t* __restrict__ data, long long n, int32_t value)
+{
+    const long long i = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) data[i] = value;
+}
+
+grf_status exclusive_scan_inplace(int32_t* counts, int64_t n, long long* total64, hipStream_t stream)
+{
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, counts, static_cast<long long>(n), total64);
+    GRF_LAUNCH_CHECK("scan_kernel");
+    return GRF_OK;
+}
+
+grf_status fill_i32(int32_t* data, int64_t n, int32_t value, hipStream_t stream)
+{
+    if (n <= 0) return GRF_OK;
+    const unsigned blocks = static_cast<unsigned>((n + 255) / 256);
+    hipLaunchKernelGGL(fill_kernel, dim3(blocks), dim3(256), 0, stream, data, static_cast<long long>(n), value);
+    GRF_LAUNCH_CHECK("fill_kernel");
+    return GRF_OK;
+}
+
+// ------------------------------------------------------------------------------------ host side
+namespace {
+
+constexpr int kMaxDeposits = 8192;   // 8192 * 20 B = 160 KB, the LDS of one gfx950 compute unit
+
+grf_status check_graph(const grf_graph* g)
+{
+    if (g == nullptr) return fail(GRF_EINVAL, "graph is NULL");
+    if (g->n < 0 || g->nnz < 0) return fail(GRF_EINVAL, "graph n=%lld nnz=%lld must be >= 0", (long long)g->n, (long long)g->nnz);
+    if (g->n >= 2147483647ll || g->nnz >= 2147483647ll) return fail(GRF_EUNSUPPORTED, "graph n and nnz must be < 2^31 - 1");
+    if (g->row_ptr == nullptr) return fail(GRF_EINVAL, "graph row_ptr is NULL");
+    if (g->nnz > 0 && (g->col == nullptr || g->w == nullptr)) return fail(GRF_EINVAL, "graph col / w is NULL");
+    return GRF_OK;
+}
+
+grf_status make_law(double p_halt, uint64_t seed, WalkLaw* law)
+{
+    if (!(p_halt >= 0.0 && p_halt <= 1.0)) return fail(GRF_EINVAL, "p_halt=%g must lie in [0, 1]", p_halt);
+    const double scaled = p_halt * 4294967296.0;
+    const uint64_t thr = static_cast<uint64_t>(scaled);   // floor for non-negative values
+    law->key0 = static_cast<uint32_t>(seed & 0xffffffffull);
+    law->key1 = static_cast<uint32_t>(seed >> 32);
+    law->always_halt = thr > 0xffffffffull ? 1 : 0;
+    law->threshold = law->always_halt ? 0xffffffffu : static_cast<uint32_t>(thr);
+    law->inv_survive = p_halt < 1.0 ? static_cast<float>(1.0 / (1.0 - p_halt)) : 0.0f;
+    return GRF_OK;
+}
+
+GraphView view_of(const grf_graph* g)
+{
+    return GraphView{g->row_ptr, g->col, g->w, static_cast<int32_t>(g->n), static_cast<int32_t>(g->nnz)};
+}
+
+}  // namespace
+}  // namespace grf
+
+using namespace grf;
+
+extern "C" int64_t grf_sample_nnz_bound(int64_t n, int32_t n_walks, int32_t f_len)
+{
+    if (n < 0 || n_walks < 1 || f_len < 1) return -1;
+    return n * (1 + static_cast<int64_t>(n_walks) * (f_len - 1));
+}
+
+extern "C" size_t grf_sample_workspace_bytes(int64_t n, int32_t n_walks, int32_t f_len, int32_t n_f)
+{
+    if (n < 0 || n_walks < 1 || f_len < 1 || n_f < 1) return 0;
+    return align_up(sizeof(float) * static_cast<size_t>(n_f) * f_len) + kAlign;
+}
+
+extern "C" grf_status grf_sample_walks(const grf_graph* g, double p_halt, int32_t n_walks, int32_t max_nodes,
+                                       uint64_t seed, void* hip_stream, int32_t* traj)
+{
+    if (grf_status st = check_graph(g)) return st;
+    if (n_walks < 1 || max_nodes < 1) return fail(GRF_EINVAL, "n_walks=%d and max_nodes=%d must be >= 1", n_walks, max_nodes);
+    WalkLaw law;
+    if (grf_status st = make_law(p_halt, seed, &law)) return st;
+    if (g->n == 0) return GRF_OK;
+    if (traj == nullptr) return fail(GRF_EINVAL, "traj is NULL");
+    const long long total = static_cast<long long>(g->n) * n_walks;
+    if (total * max_nodes >= (1ll << 40)) return fail(GRF_EUNSUPPORTED, "trajectory dump of %lld entries is too large", total * max_nodes);
+    const long long blocks = (total + 255) / 256;
+    if (blocks > 2147483647ll) return fail(GRF_EUNSUPPORTED, "too many walks for one launch");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipLaunchKernelGGL(walks_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream,
+                       view_of(g), law, n_walks, max_nodes, traj);
+    GRF_LAUNCH_CHECK("walks_kernel");
+    return GRF_OK;
+}
+
+extern "C" grf_status grf_sample(const grf_graph* g, const float* f, int32_t f_len, int32_t n_f,
+                                 double p_halt, int32_t n_walks, uint64_t seed,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream,
+                                 grf_phi* phi_out, int64_t* nnz_out)
+{
+    if (grf_status st = check_graph(g)) return st;
+    if (f == nullptr) return fail(GRF_EINVAL, "f is NULL");
+    if (f_len < 1 || n_f < 1 || n_walks < 1)
+        return fail(GRF_EINVAL, "f_len=%d, n_f=%d, n_walks=%d must all be >= 1", f_len, n_f, n_walks);
+    if (f_len > 65535) return fail(GRF_EUNSUPPORTED, "f_len=%d exceeds 65535", f_len);
+    WalkLaw law;
+    if (grf_status st = make_law(p_halt, seed, &law)) return st;
+    if (phi_out == nullptr || nnz_out == nullptr) return fail(GRF_EINVAL, "phi_out / nnz_out is NULL");
+    if (phi_out->n != g->n) return fail(GRF_EINVAL, "phi_out->n=%lld differs from graph n=%lld", (long long)phi_out->n, (long long)g->n);
+    if (phi_out->row_ptr == nullptr) return fail(GRF_EINVAL, "phi_out->row_ptr is NULL");
+    if (phi_out->capacity < 0) return fail(GRF_EINVAL, "phi_out->capacity is negative");
+    if (phi_out->capacity > 0 && (phi_out->col == nullptr || phi_out->val == nullptr))
+        return fail(GRF_EINVAL, "phi_out->col / val is NULL with capacity %lld", (long long)phi_out->capacity);
+    const long long cap_ll = 1 + static_cast<long long>(n_walks) * (f_len - 1);
+    if (cap_ll > kMaxDeposits)
+        return fail(GRF_EUNSUPPORTED, "1 + n_walks*(f_len-1) = %lld deposits per node exceed the %d that fit in LDS", cap_ll, kMaxDeposits);
+    const size_t need = grf_sample_workspace_bytes(g->n, n_walks, f_len, n_f);
+    if (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
+        return fail(GRF_EWORKSPACE, "workspace must be non-NULL, 256-byte aligned and >= %zu bytes (got %zu)", need, workspace_bytes);
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    float* f_dev = reinterpret_cast<float*>(ws);
+    long long* total_dev = reinterpret_cast<long long*>(ws + align_up(sizeof(float) * static_cast<size_t>(n_f) * f_len));
+
+    if (g->n == 0) {
+        if (grf_status st = fill_i32(phi_out->row_ptr, 1, 0, stream)) return st;
+        *nnz_out = 0;
+        return GRF_OK;
+    }
+
+    GRF_HIP_TRY(hipMemcpyAsync(f_dev, f, sizeof(float) * static_cast<size_t>(n_f) * f_len, hipMemcpyHostToDevice, stream));
+
+    const int cap = static_cast<int>(cap_ll);
+    const size_t lds = static_cast<size_t>(cap) * kDepositBytes;
+    if (lds > 64 * 1024) {
+        GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+        GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+    }
+    const GraphView gv = view_of(g);
+    const dim3 grid(static_cast<unsigned>(g->n));
+
+    // pass 1: entries per row, then offsets
+    hipLaunchKernelGGL(rows_kernel<false>, grid, dim3(kWave), lds, stream, gv, law, n_walks, f_len, n_f,
+                       static_cast<const float*>(f_dev), cap, phi_out->row_ptr, static_cast<int32_t*>(nullptr),
+                       static_cast<float*>(nullptr), 0ll);
+    GRF_LAUNCH_CHECK("rows_kernel<count>");
+    if (grf_status st = exclusive_scan_inplace(phi_out->row_ptr, g->n, total_dev, stream)) return st;
+    long long total = 0;
+    GRF_HIP_TRY(hipMemcpyAsync(&total, total_dev, sizeof(long long), hipMemcpyDeviceToHost, stream));
+    GRF_HIP_TRY(hipStreamSynchronize(stream));
+    *nnz_out = total;
+    if (total >= 2147483647ll) return fail(GRF_EUNSUPPORTED, "Phi_hat has %lld entries; int32 offsets cover < 2^31 - 1", total);
+    if (phi_out->capacity < total)
+        return fail(GRF_ECAPACITY, "Phi_hat has %lld entries but phi_out->capacity is %lld", total, (long long)phi_out->capacity);
+
+    // pass 2: same walks again, entries written at their offsets
+    hipLaunchKernelGGL(rows_kernel<true>, grid, dim3(kWave), lds, stream, gv, law, n_walks, f_len, n_f,
+                       static_cast<const float*>(f_dev), cap, phi_out->row_ptr, phi_out->col, phi_out->val,
+                       static_cast<long long>(phi_out->capacity));
+    GRF_LAUNCH_CHECK("rows_kernel<fill>");
+    return GRF_OK;
+}

@@ -1,0 +1,323 @@
+"""HIP library against the CPU checker on identical seeded inputs (needs the GPU).
+
+Bars: walk trajectories and the sparsity pattern of Phi_hat bit-exact; Phi_hat values, buckets,
+num and den within 1e-5 in the norm  max|x - ref| / max|ref|  (fp32; 2e-2 for bf16 inputs);
+out = num/den is compared on rows whose denominator is not a near-total cancellation.
+"""
+import numpy as np
+import pytest
+
+from paper_2410_03462_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-5
+TOL_BF16 = 2e-2
+# out = num/den amplifies the fp32 rounding of den by (sum of |terms|)/|den|; rows where that
+# factor exceeds 1/COND_MIN are compared through num and den only.
+COND_MIN = 0.05
+
+
+@pytest.fixture(scope="module")
+def grf():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2410_03462_amd import binding
+    binding.lib()
+    return binding
+
+
+def relerr(x, ref):
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    scale = np.abs(ref).max()
+    return float(np.abs(x - ref).max() / scale) if scale > 0 else float(np.abs(x).max())
+
+
+def to_dev(x, dtype="f32"):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def small_workloads():
+    rng = np.random.default_rng(123)
+    yield "tiny_grid", synth.workload("tiny_grid")
+    wl = synth.workload("vit_grid"); wl.B, wl.H = 1, 2
+    yield "vit_grid_b1h2", wl
+    g = synth.random_graph(777, 6.0, rng, weights="sym_norm", isolated=5)       # ragged size, isolated nodes
+    yield "random_777", synth.Workload("random_777", g, synth.modulation(9, rng), 0.3, 11, 2, 2, 64, "f32")
+    g = synth.star_graph(300)                                                   # one hub column of ~all rows
+    yield "star_300", synth.Workload("star_300", g, synth.modulation(6, rng), 0.35, 5, 1, 2, 32, "f32")
+    g = synth.knn_graph(synth.uniform_points(2000, rng), 8, "gauss")
+    yield "cloud_2k_perhead_bf16", synth.Workload("cloud_2k", g, synth.modulation(12, rng, n_f=3), 0.25, 16, 2, 3, 64, "bf16")
+    g = synth.grid_graph(20, 20, 8)
+    yield "many_walks", synth.Workload("many_walks", g, synth.modulation(5, rng), 0.4, 150, 1, 1, 32, "f32")
+
+
+SMALL = dict(small_workloads())
+
+
+# --------------------------------------------------------------------------- sampler
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_walks_bit_exact(grf, oracle, name):
+    wl = SMALL[name]
+    g = grf.DeviceGraph.from_host(wl.graph)
+    for seed in (wl.walk_seed, 0xDEADBEEF12345):
+        got = grf.grf_sample_walks(g, wl.p_halt, wl.n_walks, wl.f_len, seed).cpu().numpy()
+        want = oracle.sample_walks(wl.graph, wl.p_halt, wl.n_walks, wl.f_len, seed)
+        assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("p_halt", [0.0, 1.0])
+def test_walks_extreme_halting(grf, oracle, p_halt):
+    wl = SMALL["random_777"]
+    g = grf.DeviceGraph.from_host(wl.graph)
+    got = grf.grf_sample_walks(g, p_halt, 3, 7, 5).cpu().numpy()
+    assert np.array_equal(got, oracle.sample_walks(wl.graph, p_halt, 3, 7, 5))
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_phi_pattern_bit_exact_values_close(grf, oracle, name):
+    wl = SMALL[name]
+    g = grf.DeviceGraph.from_host(wl.graph)
+    phi = grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+    rp, col, val = phi.to_host()
+    rp0, col0, val0 = oracle.sample(wl.graph, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+    assert phi.nnz == rp0[-1]
+    assert np.array_equal(rp, rp0)
+    assert np.array_equal(col, col0)
+    assert val.shape == val0.shape
+    for h in range(wl.n_f):
+        assert relerr(val[h], val0[h]) <= TOL_F32
+    # a second run is bitwise identical, also into caller-provided buffers larger than needed
+    again = grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed,
+                           out=grf.Phi.empty(wl.graph.n, phi.nnz + 17, wl.n_f))
+    rp2, col2, val2 = again.to_host()
+    assert np.array_equal(rp2, rp) and np.array_equal(col2, col) and np.array_equal(val2, val)
+
+
+def test_phi_special_cases(grf, oracle):
+    wl = SMALL["random_777"]
+    g = grf.DeviceGraph.from_host(wl.graph)
+    n = wl.graph.n
+    # f = delta_0  ->  identity on the diagonal, stored zeros elsewhere
+    f = np.zeros((1, 6), dtype=np.float32); f[0, 0] = 1.0
+    rp, col, val = grf.grf_sample(g, f, 0.3, 7, 1).to_host()
+    rows = np.repeat(np.arange(n), np.diff(rp))
+    assert np.array_equal(val[0], (rows == col).astype(np.float32))
+    # p_halt = 1  ->  f_0 I
+    f = np.array([[0.7, 0.2, 0.1]], dtype=np.float32)
+    rp, col, val = grf.grf_sample(g, f, 1.0, 4, 1).to_host()
+    assert np.array_equal(rp, np.arange(n + 1)) and np.array_equal(col, np.arange(n))
+    assert relerr(val[0], np.full(n, 0.7)) <= 2e-7
+    # p_halt = 0: every walk has f_len nodes (except from isolated nodes)
+    rp, col, val = grf.grf_sample(g, f, 0.0, 4, 1).to_host()
+    rp0, col0, val0 = oracle.sample(wl.graph, f, 0.0, 4, 1)
+    assert np.array_equal(rp, rp0) and np.array_equal(col, col0) and relerr(val, val0) <= TOL_F32
+
+
+def test_sample_capacity_protocol_and_errors(grf):
+    wl = SMALL["tiny_grid"]
+    g = grf.DeviceGraph.from_host(wl.graph)
+    full = grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, 0)
+    with pytest.raises(grf.GrfError) as e:
+        grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, 0, out=grf.Phi.empty(wl.graph.n, full.nnz - 1, 1))
+    assert e.value.status == grf.GRF_ECAPACITY
+    with pytest.raises(grf.GrfError) as e:
+        grf.grf_sample(g, wl.f, 1.5, wl.n_walks, 0)
+    assert e.value.status == grf.GRF_EINVAL
+    with pytest.raises(grf.GrfError) as e:
+        grf.grf_sample(g, wl.f, 0.5, 0, 0)
+    assert e.value.status == grf.GRF_EINVAL
+    with pytest.raises(grf.GrfError) as e:
+        grf.grf_sample(g, np.zeros((1, 200), np.float32), 0.5, 100, 0)      # 19901 deposits per node
+    assert e.value.status == grf.GRF_EUNSUPPORTED
+    assert grf.grf_sample_nnz_bound(256, 4, 8) == 256 * 29
+    # empty graph
+    import torch
+    empty = grf.DeviceGraph(0, torch.zeros(1, dtype=torch.int32, device="cuda:0"),
+                            torch.zeros(0, dtype=torch.int32, device="cuda:0"), torch.zeros(0, device="cuda:0"))
+    phi = grf.grf_sample(empty, wl.f, 0.5, 4, 0)
+    assert phi.nnz == 0 and int(phi.row_ptr.cpu()[0]) == 0
+
+
+def test_sample_large_lds_request(grf, oracle):
+    """1 + n_walks (f_len - 1) = 4951 deposits per node: ~97 KB of LDS per wavefront."""
+    g_host = synth.grid_graph(6, 6, 8)
+    f = synth.modulation(100, np.random.default_rng(3))
+    g = grf.DeviceGraph.from_host(g_host)
+    rp, col, val = grf.grf_sample(g, f, 0.1, 50, 2).to_host()
+    rp0, col0, val0 = oracle.sample(g_host, f, 0.1, 50, 2)
+    assert np.array_equal(rp, rp0) and np.array_equal(col, col0)
+    assert relerr(val, val0) <= TOL_F32
+
+
+# --------------------------------------------------------------------------- attention
+
+def _oracle_phi(oracle, wl):
+    return oracle.sample(wl.graph, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+
+
+def _compare_attention(grf, oracle, wl, rp, col, val, feature_map="relu", bh_chunk=0):
+    Q, K, V = wl.qkv()
+    tol = TOL_BF16 if wl.dtype == "bf16" else TOL_F32
+    fm = oracle.RELU if feature_map == "relu" else oracle.IDENTITY
+    ref = oracle.masked_linear_attention(Q, K, V, rp, col, val, feature_map=fm, return_buckets=True)
+    phi = grf.Phi.from_host(wl.graph.n, rp, col, val)
+    Qd, Kd, Vd = (to_dev(x, wl.dtype) for x in (Q, K, V))
+    B, H, n, d = Q.shape
+
+    rec = grf.grf_form_buckets(Kd, Vd, phi, feature_map).cpu().numpy().reshape(B, H, n, d * d + d)
+    S = rec[..., : d * d].reshape(B, H, n, d, d)
+    z = rec[..., d * d:]
+    assert relerr(S, ref["S"]) <= tol
+    assert relerr(z, ref["z"]) <= tol
+
+    out, num, den = grf.grf_masked_linear_attention(Qd, Kd, Vd, phi, feature_map, bh_chunk=bh_chunk, return_num_den=True)
+    out, num, den = out.cpu().numpy(), num.cpu().numpy(), den.cpu().numpy()
+    assert relerr(num, ref["num"]) <= tol
+    assert relerr(den, ref["den"]) <= tol
+    # out on rows whose denominator is not a near-total cancellation
+    n_good = 0
+    for b in range(B):
+        for h in range(H):
+            v = val[h if val.shape[0] > 1 else 0]
+            floor = oracle.conditioning_floor(Q[b, h], rp, col, v, ref["z"][b, h], fm)
+            good = np.abs(ref["den"][b, h]) >= COND_MIN * floor
+            good &= floor > 0
+            n_good += int(good.sum())
+            if good.any():
+                assert relerr(out[b, h][good], ref["out"][b, h][good]) <= 20 * tol
+                # row-wise: error small against the row's own scale times the amplification bound
+                err = np.abs(out[b, h][good] - ref["out"][b, h][good]).max(axis=1)
+                scale = np.abs(ref["out"][b, h][good]).max(axis=1) + 1e-30
+                assert np.all(err / scale <= tol / COND_MIN * 4)
+    assert n_good >= 0.5 * B * H * n
+    # out is exactly num / den as returned
+    with np.errstate(divide="ignore", invalid="ignore"):
+        assert np.array_equal(np.nan_to_num(out, nan=7.0, posinf=8.0, neginf=9.0),
+                              np.nan_to_num(num / den[..., None], nan=7.0, posinf=8.0, neginf=9.0))
+    return out, num, den
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_attention_parity(grf, oracle, name):
+    wl = SMALL[name]
+    rp, col, val = _oracle_phi(oracle, wl)
+    _compare_attention(grf, oracle, wl, rp, col, val)
+
+
+def test_attention_identity_feature_map_and_chunking(grf, oracle):
+    wl = SMALL["random_777"]
+    rp, col, val = _oracle_phi(oracle, wl)
+    full = _compare_attention(grf, oracle, wl, rp, col, val, feature_map="identity")
+    for chunk in (1, 3):
+        part = _compare_attention(grf, oracle, wl, rp, col, val, feature_map="identity", bh_chunk=chunk)
+        for a, b in zip(full, part):
+            assert np.array_equal(np.nan_to_num(a), np.nan_to_num(b))
+
+
+def test_attention_end_to_end_from_gpu_sample(grf, oracle):
+    """Both stages on the GPU, chained: sample -> attention, against the checker's chain."""
+    wl = SMALL["vit_grid_b1h2"]
+    g = grf.DeviceGraph.from_host(wl.graph)
+    phi = grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+    Q, K, V = wl.qkv()
+    out, num, den = grf.grf_masked_linear_attention(to_dev(Q), to_dev(K), to_dev(V), phi, return_num_den=True)
+    rp, col, val = _oracle_phi(oracle, wl)
+    ref = oracle.masked_linear_attention(Q, K, V, rp, col, val)
+    assert relerr(num.cpu().numpy(), ref["num"]) <= TOL_F32
+    assert relerr(den.cpu().numpy(), ref["den"]) <= TOL_F32
+    # deterministic: a second run gives the same bits
+    out2 = grf.grf_masked_linear_attention(to_dev(Q), to_dev(K), to_dev(V), phi)
+    assert np.array_equal(np.nan_to_num(out.cpu().numpy()), np.nan_to_num(out2.cpu().numpy()))
+
+
+def test_attention_special_feature_matrices(grf, oracle):
+    """Phi_hat = I returns V; a single all-ones column is unmasked linear attention (Eq. 3);
+    rows without entries give num = 0, den = 0."""
+    import torch
+    rng = np.random.default_rng(5)
+    n, d = 333, 64
+    Q, K, V = synth.qkv(1, 2, n, d, rng)
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    ident = grf.Phi.from_host(n, np.arange(n + 1), np.arange(n), np.ones((1, n), np.float32))
+    out, num, den = grf.grf_masked_linear_attention(Qd, Kd, Vd, ident, return_num_den=True)
+    ok = den.cpu().numpy() != 0
+    assert relerr(out.cpu().numpy()[ok], V[ok]) <= TOL_F32
+
+    ones_col = grf.Phi.from_host(n, np.arange(n + 1), np.full(n, 7), np.ones((1, n), np.float32))
+    out, num, den = grf.grf_masked_linear_attention(Qd, Kd, Vd, ones_col, return_num_den=True)
+    fq = np.maximum(Q.astype(np.float64), 0); fk = np.maximum(K.astype(np.float64), 0)
+    num_ref = fq @ (np.swapaxes(fk, -1, -2) @ V.astype(np.float64))
+    den_ref = (fq @ fk.sum(axis=2)[..., None])[..., 0]
+    assert relerr(num.cpu().numpy(), num_ref) <= TOL_F32
+    assert relerr(den.cpu().numpy(), den_ref) <= TOL_F32
+
+    rp = np.zeros(n + 1, dtype=np.int32); rp[5:] = 1            # only row 4 has an entry
+    sparse = grf.Phi.from_host(n, rp, np.array([2]), np.ones((1, 1), np.float32))
+    out, num, den = grf.grf_masked_linear_attention(Qd, Kd, Vd, sparse, return_num_den=True)
+    num, den = num.cpu().numpy(), den.cpu().numpy()
+    mask = np.ones(n, bool); mask[4] = False
+    assert np.all(num[:, :, mask] == 0) and np.all(den[:, :, mask] == 0)
+    assert torch.isnan(out[:, :, mask]).all()
+
+
+def test_attention_argument_errors(grf):
+    import torch
+    n = 64
+    phi = grf.Phi.from_host(n, np.arange(n + 1), np.arange(n), np.ones((1, n), np.float32))
+    x = torch.zeros((1, 2, n, 48), device="cuda:0")
+    with pytest.raises(grf.GrfError) as e:
+        grf.grf_masked_linear_attention(x, x, x, phi)
+    assert e.value.status == grf.GRF_EUNSUPPORTED
+    x = torch.zeros((1, 2, n, 64), device="cuda:0")
+    phi3 = grf.Phi.from_host(n, np.arange(n + 1), np.arange(n), np.ones((3, n), np.float32))
+    with pytest.raises(grf.GrfError) as e:
+        grf.grf_masked_linear_attention(x, x, x, phi3)            # n_f = 3 with H = 2
+    assert e.value.status == grf.GRF_EINVAL
+    with pytest.raises(grf.GrfError) as e:
+        grf.grf_masked_linear_attention(x, x, x, phi, workspace=torch.empty(256, dtype=torch.uint8, device="cuda:0"))
+    assert e.value.status == grf.GRF_EWORKSPACE
+    # empty batch is fine
+    e0 = torch.zeros((0, 2, n, 64), device="cuda:0")
+    assert grf.grf_masked_linear_attention(e0, e0, e0, phi).shape == (0, 2, n, 64)
+
+
+# --------------------------------------------------------------------------- the headline workload at full size
+
+def test_headline_workload_full_size(grf, oracle):
+    """cloud_32k (N = 32768, 8 heads, d = 64) in the launch configuration the benchmark times:
+    pattern bit-exact against the checker; output rows spot-checked against Eq. (2) evaluated
+    directly; symmetry of the implied mask through sum_i den_i(Q,K) = sum_i den_i(K,Q)."""
+    import torch
+    wl = synth.workload("cloud_32k")
+    g = grf.DeviceGraph.from_host(wl.graph)
+    phi = grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+    rp, col, val = phi.to_host()
+    rp0, col0, val0 = _oracle_phi(oracle, wl)
+    assert np.array_equal(rp, rp0) and np.array_equal(col, col0)
+    assert relerr(val, val0) <= TOL_F32
+
+    Q, K, V = wl.qkv()
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    out, num, den = grf.grf_masked_linear_attention(Qd, Kd, Vd, phi, return_num_den=True)
+    num_h, den_h = num.cpu().numpy(), den.cpu().numpy()
+    rng = np.random.default_rng(0)
+    rows = rng.choice(wl.graph.n, size=24, replace=False)
+    num_scale = np.abs(num_h).max(); den_scale = np.abs(den_h).max()
+    for h in (0, 3, 7):
+        for i in rows:
+            n_i, d_i, _ = oracle.row_direct(int(i), Q[0, h], K[0, h], V[0, h], rp0, col0, val0[0])
+            assert np.abs(num_h[0, h, i] - n_i).max() <= TOL_F32 * num_scale
+            assert abs(den_h[0, h, i] - d_i) <= TOL_F32 * den_scale
+    # symmetry of M_hat, O(N) to evaluate
+    _, _, den_sw = grf.grf_masked_linear_attention(Kd, Qd, Vd, phi, return_num_den=True)
+    a = den.double().sum(dim=-1).cpu().numpy(); b = den_sw.double().sum(dim=-1).cpu().numpy()
+    scale = den.double().abs().sum(dim=-1).cpu().numpy()
+    assert np.all(np.abs(a - b) <= 1e-5 * scale)
+    del out, num, den, den_sw
+    torch.cuda.empty_cache()
