@@ -137,10 +137,12 @@ grf_status grf_sample_walks(const grf_graph* g, double p_halt, int32_t n_walks, 
 /* Floats per bucket record: d*d of S_l (feature index major: S_l[a][c] at a*d + c) followed by d of z_l. */
 int64_t grf_bucket_record_floats(int32_t d);
 
-/* Workspace bytes (multiple of 256; 0 on bad arguments).
- * bh_chunk: how many (batch, head) slices have their buckets resident at once; <= 0 means all B*H.
- * grf_form_buckets needs the value returned for bh_chunk = 0 ... it uses only the transpose part. */
+/* Workspace bytes of grf_masked_linear_attention (multiple of 256; 0 on bad arguments): the column
+ * lists of Phi_hat plus the bucket records of bh_chunk slices.
+ * bh_chunk: how many (batch, head) slices have their buckets resident at once; <= 0 means all B*H. */
 size_t grf_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t bh_chunk);
+
+/* Workspace bytes of grf_form_buckets (the column lists of Phi_hat only). */
 size_t grf_buckets_workspace_bytes(int64_t n, int64_t nnz);
 
 /* Buckets only (Alg. 1 step 5, the two Phi_{K,G}^T products).
@@ -151,7 +153,15 @@ grf_status grf_form_buckets(const void* K, const void* V, int32_t dtype,
                             void* workspace, size_t workspace_bytes, void* hip_stream,
                             float* buckets);
 
-/* The whole attention call.
+/* Gather only (Alg. 1 step 5, the Phi_{Q,G} products and D^-1), from records laid out as
+ * grf_form_buckets writes them.  Needs no workspace.  Outputs as below. */
+grf_status grf_gather_buckets(const void* Q, int32_t dtype,
+                              int64_t B, int64_t H, int64_t n, int32_t d,
+                              const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                              const float* buckets, void* hip_stream,
+                              float* out, float* num_opt, float* den_opt);
+
+/* The whole attention call: column lists, then buckets and gather per chunk of slices.
  * out       device [B][H][n][d] fp32.
  * num_opt   device [B][H][n][d] fp32 or NULL;  den_opt  device [B][H][n] fp32 or NULL. */
 grf_status grf_masked_linear_attention(const void* Q, const void* K, const void* V, int32_t dtype,

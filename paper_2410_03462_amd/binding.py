@@ -77,6 +77,9 @@ def lib() -> ctypes.CDLL:
         L.grf_form_buckets.restype = ctypes.c_int32
         L.grf_form_buckets.argtypes = [ctypes.c_void_p, ctypes.c_void_p, *common,
                                        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+        L.grf_gather_buckets.restype = ctypes.c_int32
+        L.grf_gather_buckets.argtypes = [ctypes.c_void_p, *common, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.grf_masked_linear_attention.restype = ctypes.c_int32
         L.grf_masked_linear_attention.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, *common,
                                                   ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
@@ -249,7 +252,12 @@ def grf_attention_workspace_bytes(B: int, H: int, n: int, d: int, nnz: int, bh_c
     return int(lib().grf_attention_workspace_bytes(B, H, n, d, nnz, bh_chunk))
 
 
-def grf_form_buckets(K: torch.Tensor, V: torch.Tensor, phi: Phi, feature_map: str = "relu", stream=None) -> torch.Tensor:
+def grf_buckets_workspace_bytes(n: int, nnz: int) -> int:
+    return int(lib().grf_buckets_workspace_bytes(n, nnz))
+
+
+def grf_form_buckets(K: torch.Tensor, V: torch.Tensor, phi: Phi, feature_map: str = "relu",
+                     out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """Bucket records [B*H, n, d*d + d] fp32: S_l (d x d, feature index major) then z_l."""
     _require_gpu()
     L = lib()
@@ -257,12 +265,36 @@ def grf_form_buckets(K: torch.Tensor, V: torch.Tensor, phi: Phi, feature_map: st
     rec = L.grf_bucket_record_floats(d)
     if rec < 0:
         raise GrfError(GRF_EUNSUPPORTED, f"head dimension d={d} is not supported")
-    buckets = torch.empty((B * H, n, rec), dtype=torch.float32, device=K.device)
-    ws = _workspace(L.grf_buckets_workspace_bytes(n, phi.nnz), K.device)
+    buckets = out if out is not None else torch.empty((B * H, n, rec), dtype=torch.float32, device=K.device)
+    if buckets.numel() != B * H * n * rec or buckets.dtype != torch.float32 or not buckets.is_contiguous():
+        raise ValueError("bucket buffer has the wrong size, dtype or layout")
+    ws = workspace if workspace is not None else _workspace(L.grf_buckets_workspace_bytes(n, phi.nnz), K.device)
     ps = phi._struct()
     _check(L.grf_form_buckets(_ptr(K), _ptr(V), _dtype_code(K), B, H, n, d, ctypes.byref(ps), phi.nnz, phi.n_f,
                               _FEATURE_MAPS[feature_map], _ptr(ws), ws.numel(), _stream_ptr(stream), _ptr(buckets)))
     return buckets
+
+
+def grf_gather_buckets(Q: torch.Tensor, phi: Phi, buckets: torch.Tensor, feature_map: str = "relu",
+                       return_num_den: bool = False, out: Optional[torch.Tensor] = None, stream=None):
+    """out [B,H,n,d] fp32 (and num, den if asked) from records written by grf_form_buckets."""
+    _require_gpu()
+    L = lib()
+    B, H, n, d = _check_qkv(Q)
+    rec = L.grf_bucket_record_floats(d)
+    if rec < 0:
+        raise GrfError(GRF_EUNSUPPORTED, f"head dimension d={d} is not supported")
+    if buckets.numel() != B * H * n * rec or buckets.dtype != torch.float32 or not buckets.is_contiguous():
+        raise ValueError("bucket buffer has the wrong size, dtype or layout")
+    if out is None:
+        out = torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device)
+    num = torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device) if return_num_den else None
+    den = torch.empty((B, H, n), dtype=torch.float32, device=Q.device) if return_num_den else None
+    ps = phi._struct()
+    _check(L.grf_gather_buckets(_ptr(Q), _dtype_code(Q), B, H, n, d, ctypes.byref(ps), phi.nnz, phi.n_f,
+                                _FEATURE_MAPS[feature_map], _ptr(buckets), _stream_ptr(stream),
+                                _ptr(out), _ptr(num), _ptr(den)))
+    return (out, num, den) if return_num_den else out
 
 
 def grf_masked_linear_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, phi: Phi,

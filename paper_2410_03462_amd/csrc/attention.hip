@@ -421,6 +421,22 @@ extern "C" grf_status grf_form_buckets(const void* K, const void* V, int32_t dty
     return st;
 }
 
+extern "C" grf_status grf_gather_buckets(const void* Q, int32_t dtype,
+                                         int64_t B, int64_t H, int64_t n, int32_t d,
+                                         const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                         const float* buckets, void* hip_stream,
+                                         float* out, float* num_opt, float* den_opt)
+{
+    if (grf_status st = check_problem(Q, buckets, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
+    if (B * H * n > 0 && out == nullptr) return fail(GRF_EINVAL, "out is NULL");
+    if (B * H * n == 0) return GRF_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int relu = feature_map == GRF_PHI_RELU ? 1 : 0;
+    grf_status st = GRF_OK;
+    GRF_DISPATCH(d, dtype, (st = launch_gather<D_, T_>(Q, n, H, n_f, phi, nnz, relu, buckets, 0, B * H, out, num_opt, den_opt, stream)));
+    return st;
+}
+
 extern "C" grf_status grf_masked_linear_attention(const void* Q, const void* K, const void* V, int32_t dtype,
                                                   int64_t B, int64_t H, int64_t n, int32_t d,
                                                   const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
