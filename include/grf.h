@@ -171,6 +171,24 @@ grf_status grf_masked_linear_attention(const void* Q, const void* K, const void*
                                        void* workspace, size_t workspace_bytes, void* hip_stream,
                                        float* out, float* num_opt, float* den_opt);
 
+/* ---------------------------------------------------------------------------------------------
+ * Bucket-fused variant of the whole attention call: same inputs, outputs and error behaviour as
+ * grf_masked_linear_attention, same num, den, out up to fp32 summation order, but S_l is never
+ * written to memory.  It rests on Eq. 6: queries and keys share the graph features, so the rows that
+ * consume bucket l are the rows that contribute to it; per bucket the kernel forms S_l and z_l in
+ * registers, multiplies them at once by the weighted phi(q) of the same rows, and streams out one
+ * d-float partial numerator and one partial denominator per entry of Phi_hat; a second kernel sums
+ * each row's partials in ascending-l order (deterministic; no float atomics).
+ * Workspace: column lists plus (d + 1) floats per entry of Phi_hat per resident slice. */
+size_t grf_fused_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t bh_chunk);
+
+grf_status grf_masked_linear_attention_fused(const void* Q, const void* K, const void* V, int32_t dtype,
+                                             int64_t B, int64_t H, int64_t n, int32_t d,
+                                             const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                             int32_t bh_chunk,
+                                             void* workspace, size_t workspace_bytes, void* hip_stream,
+                                             float* out, float* num_opt, float* den_opt);
+
 #ifdef __cplusplus
 }
 #endif

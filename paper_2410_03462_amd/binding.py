@@ -84,6 +84,10 @@ def lib() -> ctypes.CDLL:
         L.grf_masked_linear_attention.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, *common,
                                                   ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.grf_fused_attention_workspace_bytes.restype = ctypes.c_size_t
+        L.grf_fused_attention_workspace_bytes.argtypes = L.grf_attention_workspace_bytes.argtypes
+        L.grf_masked_linear_attention_fused.restype = ctypes.c_int32
+        L.grf_masked_linear_attention_fused.argtypes = L.grf_masked_linear_attention.argtypes
         _lib = L
     return _lib
 
@@ -297,15 +301,32 @@ def grf_gather_buckets(Q: torch.Tensor, phi: Phi, buckets: torch.Tensor, feature
     return (out, num, den) if return_num_den else out
 
 
+def grf_fused_attention_workspace_bytes(B: int, H: int, n: int, d: int, nnz: int, bh_chunk: int = 0) -> int:
+    return int(lib().grf_fused_attention_workspace_bytes(B, H, n, d, nnz, bh_chunk))
+
+
+def grf_masked_linear_attention_fused(Q, K, V, phi: Phi, feature_map: str = "relu", bh_chunk: int = 0,
+                                      return_num_den: bool = False, workspace: Optional[torch.Tensor] = None,
+                                      out: Optional[torch.Tensor] = None, stream=None):
+    """Bucket-fused variant: same results as grf_masked_linear_attention without bucket records in HBM."""
+    return _attention_call("grf_masked_linear_attention_fused", "grf_fused_attention_workspace_bytes",
+                           Q, K, V, phi, feature_map, bh_chunk, return_num_den, workspace, out, stream)
+
+
 def grf_masked_linear_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, phi: Phi,
                                 feature_map: str = "relu", bh_chunk: int = 0, return_num_den: bool = False,
                                 workspace: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
                                 stream=None):
     """out [B,H,n,d] fp32 (and num, den if asked)."""
+    return _attention_call("grf_masked_linear_attention", "grf_attention_workspace_bytes",
+                           Q, K, V, phi, feature_map, bh_chunk, return_num_den, workspace, out, stream)
+
+
+def _attention_call(entry: str, ws_query: str, Q, K, V, phi, feature_map, bh_chunk, return_num_den, workspace, out, stream):
     _require_gpu()
     L = lib()
     B, H, n, d = _check_qkv(Q, K, V)
-    need = L.grf_attention_workspace_bytes(B, H, n, d, phi.nnz, bh_chunk)
+    need = getattr(L, ws_query)(B, H, n, d, phi.nnz, bh_chunk)
     if need == 0:
         raise GrfError(GRF_EUNSUPPORTED, f"unsupported problem (d={d})")
     if workspace is None:
@@ -315,8 +336,8 @@ def grf_masked_linear_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tenso
     num = torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device) if return_num_den else None
     den = torch.empty((B, H, n), dtype=torch.float32, device=Q.device) if return_num_den else None
     ps = phi._struct()
-    _check(L.grf_masked_linear_attention(_ptr(Q), _ptr(K), _ptr(V), _dtype_code(Q), B, H, n, d, ctypes.byref(ps),
-                                         phi.nnz, phi.n_f, _FEATURE_MAPS[feature_map], int(bh_chunk),
-                                         _ptr(workspace), workspace.numel(), _stream_ptr(stream),
-                                         _ptr(out), _ptr(num), _ptr(den)))
+    _check(getattr(L, entry)(_ptr(Q), _ptr(K), _ptr(V), _dtype_code(Q), B, H, n, d, ctypes.byref(ps),
+                             phi.nnz, phi.n_f, _FEATURE_MAPS[feature_map], int(bh_chunk),
+                             _ptr(workspace), workspace.numel(), _stream_ptr(stream),
+                             _ptr(out), _ptr(num), _ptr(den)))
     return (out, num, den) if return_num_den else out

@@ -8,19 +8,9 @@
 //
 // A bucket record is d*d floats of S_l (S_l[a][c] at a*d + c, a = feature index of phi(k)) followed
 // by d floats of z_l, so the gather reads one contiguous run per entry of Phi_hat.
-#include "common.hpp"
+#include "attention_common.hpp"
 
 namespace grf {
-
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-// ------------------------------------------------------------------------------------ element loads
-struct bf16_t { uint16_t bits; };
-
-__device__ __forceinline__ float to_float(float x) { return x; }
-__device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(static_cast<uint32_t>(x.bits) << 16); }
-
-__device__ __forceinline__ float feature(float x, int relu) { return relu ? fmaxf(x, 0.0f) : x; }
 
 // ------------------------------------------------------------------------------------ transpose
 __global__ __launch_bounds__(256) void column_histogram_kernel(const int32_t* __restrict__ col, long long nnz, int32_t n,
@@ -59,7 +49,8 @@ __global__ __launch_bounds__(256) void column_scatter_kernel(const int32_t* __re
 // by counting, so that the buckets are summed in a fixed order.  Quadratic in the segment length.
 __global__ __launch_bounds__(256) void column_sort_kernel(const int32_t* __restrict__ col_ptr, int32_t n,
                                                           const int32_t* __restrict__ u_row, const int32_t* __restrict__ u_src,
-                                                          int32_t* __restrict__ s_row, int32_t* __restrict__ s_src)
+                                                          int32_t* __restrict__ s_row, int32_t* __restrict__ s_src,
+                                                          int32_t* __restrict__ csr_to_csc)
 {
     const long long c = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
     if (c >= n) return;
@@ -69,8 +60,10 @@ __global__ __launch_bounds__(256) void column_sort_kernel(const int32_t* __restr
         const int32_t key = u_row[beg + s];
         int rank = 0;
         for (int s2 = 0; s2 < len; ++s2) rank += static_cast<int>(u_row[beg + s2] < key);
+        const int32_t src = u_src[beg + s];
         s_row[beg + rank] = key;
-        s_src[beg + rank] = u_src[beg + s];
+        s_src[beg + rank] = src;
+        csr_to_csc[src] = beg + rank;
     }
 }
 
@@ -254,36 +247,23 @@ __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ Q, lo
 }
 
 // ------------------------------------------------------------------------------------ host side
-namespace {
-
-struct Transposed {
-    int32_t* col_ptr;   // [n+1]
-    int32_t* cursor;    // [n]
-    int32_t* u_row;     // [nnz] unsorted
-    int32_t* u_src;
-    int32_t* s_row;     // [nnz] rows ascending inside each column
-    int32_t* s_src;     // index of the entry in CSR order (addresses every value plane)
-    long long* total;
-    size_t bytes;
-};
-
 Transposed carve_transposed(unsigned char* ws, int64_t n, int64_t nnz)
 {
     Transposed t;
     size_t off = 0;
     auto take = [&](size_t bytes) { unsigned char* p = ws ? ws + off : nullptr; off += align_up(bytes); return p; };
+    const size_t entries = static_cast<size_t>(nnz > 0 ? nnz : 1);
     t.col_ptr = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n + 1)));
     t.cursor = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n > 0 ? n : 1)));
-    t.u_row = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(nnz > 0 ? nnz : 1)));
-    t.u_src = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(nnz > 0 ? nnz : 1)));
-    t.s_row = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(nnz > 0 ? nnz : 1)));
-    t.s_src = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(nnz > 0 ? nnz : 1)));
+    t.u_row = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
+    t.u_src = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
+    t.s_row = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
+    t.s_src = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
+    t.csr_to_csc = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
     t.total = reinterpret_cast<long long*>(take(sizeof(long long)));
     t.bytes = off;
     return t;
 }
-
-unsigned blocks_for(long long items, int per_block) { return static_cast<unsigned>((items + per_block - 1) / per_block); }
 
 grf_status transpose(const grf_phi* phi, int64_t nnz, const Transposed& t, hipStream_t stream)
 {
@@ -291,6 +271,8 @@ grf_status transpose(const grf_phi* phi, int64_t nnz, const Transposed& t, hipSt
     if (grf_status st = fill_i32(t.col_ptr, n + 1, 0, stream)) return st;
     if (grf_status st = fill_i32(t.cursor, n, 0, stream)) return st;
     if (nnz > 0) {
+        // entries that a malformed Phi_hat never reaches must not point anywhere
+        if (grf_status st = fill_i32(t.csr_to_csc, nnz, -1, stream)) return st;
         hipLaunchKernelGGL(column_histogram_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, stream,
                            static_cast<const int32_t*>(phi->col), static_cast<long long>(nnz), static_cast<int32_t>(n), t.col_ptr);
         GRF_LAUNCH_CHECK("column_histogram_kernel");
@@ -304,7 +286,8 @@ grf_status transpose(const grf_phi* phi, int64_t nnz, const Transposed& t, hipSt
         GRF_LAUNCH_CHECK("column_scatter_kernel");
         hipLaunchKernelGGL(column_sort_kernel, dim3(blocks_for(n, 4)), dim3(256), 0, stream,
                            static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n),
-                           static_cast<const int32_t*>(t.u_row), static_cast<const int32_t*>(t.u_src), t.s_row, t.s_src);
+                           static_cast<const int32_t*>(t.u_row), static_cast<const int32_t*>(t.u_src), t.s_row, t.s_src,
+                           t.csr_to_csc);
         GRF_LAUNCH_CHECK("column_sort_kernel");
     }
     return GRF_OK;
@@ -334,6 +317,8 @@ grf_status check_workspace(const void* workspace, size_t have, size_t need)
         return fail(GRF_EWORKSPACE, "workspace must be non-NULL, 256-byte aligned and >= %zu bytes (got %zu)", need, have);
     return GRF_OK;
 }
+
+namespace {
 
 template <int D, typename T>
 grf_status launch_buckets(const void* K, const void* V, int64_t n, int64_t H, int32_t n_f, const grf_phi* phi,
@@ -367,15 +352,6 @@ grf_status launch_gather(const void* Q, int64_t n, int64_t H, int32_t n_f, const
     GRF_LAUNCH_CHECK("gather_kernel");
     return GRF_OK;
 }
-
-// Dispatch on (d, dtype) to the compiled instances.
-#define GRF_DISPATCH(d, dtype, CALL)                                                     \
-    do {                                                                                 \
-        if ((d) == 64 && (dtype) == GRF_DTYPE_F32) { constexpr int D_ = 64; using T_ = float; CALL; }  \
-        else if ((d) == 64) { constexpr int D_ = 64; using T_ = bf16_t; CALL; }          \
-        else if ((dtype) == GRF_DTYPE_F32) { constexpr int D_ = 32; using T_ = float; CALL; }          \
-        else { constexpr int D_ = 32; using T_ = bf16_t; CALL; }                         \
-    } while (0)
 
 }  // namespace
 }  // namespace grf

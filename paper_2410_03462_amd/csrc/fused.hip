@@ -1,0 +1,333 @@
+// Bucket-fused evaluation of GRF-masked linear attention (Eq. 7; Alg. 1 steps 3-5): the same
+// num, den, out as the bucket + gather pair, but S_l never leaves the registers.
+//
+// Queries and keys use the same graph features (Eq. 6), so the rows that consume bucket l are
+// exactly the rows that contribute to it: the column list C_l of Phi_hat.  Per bucket,
+//     S_l = A^T V_l,            A  = diag(Phi_hat[C_l, l]) phi(K[C_l])      (r_l x d)
+//     P_l = Qw S_l,             Qw = diag(Phi_hat[C_l, l]) phi(Q[C_l])      (r_l x d)
+//     pden_l = Qw z_l,          z_l = A^T 1
+// and then num_i = sum_l P_l[i], den_i = sum_l pden_l[i] over the entries of row i.  Both
+// contractions run on v_mfma_f32_32x32x2_f32; P_l and pden_l are streamed out in column-list
+// order (one d-float row per entry of Phi_hat) and a second kernel sums each row's entries in
+// ascending-l order, so the result is deterministic and no float atomics are used.
+//
+// Index convention (T2 = d/32): MFMA row/column x of tile t stands for feature / value column
+// T2*x + t, so that a lane's T2 operands are adjacent in memory (one 8-byte load at d = 64).
+#include "attention_common.hpp"
+
+namespace grf {
+
+// N consecutive elements starting at p (p aligned to N elements), widened to fp32.
+template <typename T, int N>
+__device__ __forceinline__ void load_run(const T* __restrict__ p, float (&out)[N])
+{
+    if constexpr (sizeof(T) == 4) {
+        if constexpr (N == 1) {
+            out[0] = *reinterpret_cast<const float*>(p);
+        } else if constexpr (N == 2) {
+            const float2 v = *reinterpret_cast<const float2*>(p);
+            out[0] = v.x; out[1] = v.y;
+        } else {
+#pragma unroll
+            for (int k = 0; k < N / 4; ++k) {
+                const float4 v = reinterpret_cast<const float4*>(p)[k];
+                out[4 * k] = v.x; out[4 * k + 1] = v.y; out[4 * k + 2] = v.z; out[4 * k + 3] = v.w;
+            }
+        }
+    } else {
+        if constexpr (N == 1) {
+            out[0] = __uint_as_float(static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(p)) << 16);
+        } else {
+            uint32_t w[N / 2];
+            if constexpr (N == 2) {
+                w[0] = *reinterpret_cast<const uint32_t*>(p);
+            } else if constexpr (N == 4) {
+                const uint2 v = *reinterpret_cast<const uint2*>(p);
+                w[0] = v.x; w[1] = v.y;
+            } else {
+                const uint4 v = *reinterpret_cast<const uint4*>(p);
+                w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+            }
+#pragma unroll
+            for (int k = 0; k < N / 2; ++k) {
+                out[2 * k] = __uint_as_float(w[k] << 16);
+                out[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u);
+            }
+        }
+    }
+}
+
+// One wavefront per (slice, bucket l).
+template <int D, typename T>
+__global__ __launch_bounds__(256) void fused_bucket_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+                                                           long long n, int H, int n_f, long long val_stride,
+                                                           const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
+                                                           const int32_t* __restrict__ csc_src, const float* __restrict__ phi_val,
+                                                           int relu, long long bh_first, long long n_waves, int32_t nnz,
+                                                           float* __restrict__ partial, float* __restrict__ pden)
+{
+    constexpr int T2 = D / 32;
+    constexpr int QN = 4 * T2;     // features a lane holds per group of four accumulator registers
+    const long long wave = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (wave >= n_waves) return;
+    const long long slice = wave / n;
+    const long long l = wave - slice * n;
+    const long long bh = bh_first + slice;
+    const long long plane = n_f > 1 ? (bh % H) : 0;
+    const T* Qb = Q + bh * n * D;
+    const T* Kb = K + bh * n * D;
+    const T* Vb = V + bh * n * D;
+    const float* vals = phi_val + plane * val_stride;
+
+    const int lane = lane_id();
+    const int half = lane >> 5;
+    const int li = lane & 31;
+
+    // ---- S_l = A^T V_l: the two half-waves carry two contributors (the k index of the MFMA)
+    floatx16 acc[T2][T2];
+    float zacc[T2];
+#pragma unroll
+    for (int a = 0; a < T2; ++a) {
+        zacc[a] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < T2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
+    }
+    const int32_t beg = col_ptr[l];
+    const int32_t end = col_ptr[l + 1];
+    for (int32_t chunk = beg; chunk < end; chunk += kWave) {
+        const int32_t e = chunk + lane;
+        int32_t j_reg = -1;
+        float g_reg = 0.0f;
+        if (e < end) {
+            const int32_t row = csc_row[e];
+            const int32_t src = csc_src[e];
+            if (static_cast<uint32_t>(row) < static_cast<uint32_t>(n) && static_cast<uint32_t>(src) < static_cast<uint32_t>(nnz)) {
+                j_reg = row;
+                g_reg = vals[src];
+            }
+        }
+        const int cnt = min(kWave, end - chunk);
+        for (int p = 0; p < cnt; p += 2) {
+            const int src = p + half;
+            const long long j = __shfl(j_reg, src, kWave);
+            const float g = __shfl(g_reg, src, kWave);
+            const bool valid = src < cnt && j >= 0;
+            float kx[T2], vx[T2];
+#pragma unroll
+            for (int t = 0; t < T2; ++t) { kx[t] = 0.0f; vx[t] = 0.0f; }
+            if (valid) {
+                load_run<T, T2>(Kb + j * D + T2 * li, kx);
+                load_run<T, T2>(Vb + j * D + T2 * li, vx);
+            }
+            float a_op[T2];
+#pragma unroll
+            for (int t = 0; t < T2; ++t) {
+                a_op[t] = valid ? g * feature(kx[t], relu) : 0.0f;
+                zacc[t] += a_op[t];
+            }
+#pragma unroll
+            for (int a = 0; a < T2; ++a)
+#pragma unroll
+                for (int c = 0; c < T2; ++c)
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_op[a], vx[c], acc[a][c], 0, 0, 0);
+        }
+    }
+
+    // ---- z_l laid out the way this lane will meet it in the second contraction
+    float zq[4][QN];
+    {
+        float zfull[T2];
+#pragma unroll
+        for (int t = 0; t < T2; ++t) zfull[t] = zacc[t] + __shfl_xor(zacc[t], 32, kWave);
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int e = 0; e < QN; ++e) zq[b][e] = __shfl(zfull[e % T2], 8 * b + 4 * half + e / T2, kWave);
+    }
+
+    // ---- P_l = Qw S_l, 32 consumers at a time.  Accumulator register r of tile (t, c) holds
+    // S[T2*(8*(r/4) + 4*half + r%4) + t][T2*li + c]: fed back unchanged as the B operand, it pairs the
+    // feature held by the lower half-wave (k = 0) with the one held by the upper (k = 1); the A operand
+    // takes the same two features of consumer li's weighted phi(q).
+    const long long pbase = slice * static_cast<long long>(nnz);
+    for (int32_t tile = beg; tile < end; tile += 32) {
+        const int32_t pos = tile + li;
+        long long i = -1;
+        float gq = 0.0f;
+        if (pos < end) {
+            const int32_t row = csc_row[pos];
+            const int32_t src = csc_src[pos];
+            if (static_cast<uint32_t>(row) < static_cast<uint32_t>(n) && static_cast<uint32_t>(src) < static_cast<uint32_t>(nnz)) {
+                i = row;
+                gq = vals[src];
+            }
+        }
+        float qv[4][QN];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+#pragma unroll
+            for (int e = 0; e < QN; ++e) qv[b][e] = 0.0f;
+            if (i >= 0) load_run<T, QN>(Qb + i * D + T2 * (8 * b + 4 * half), qv[b]);
+#pragma unroll
+            for (int e = 0; e < QN; ++e) qv[b][e] = i >= 0 ? gq * feature(qv[b][e], relu) : 0.0f;
+        }
+        floatx16 pc[T2];
+#pragma unroll
+        for (int c = 0; c < T2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) pc[c][r] = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+#pragma unroll
+            for (int t = 0; t < T2; ++t)
+#pragma unroll
+                for (int c = 0; c < T2; ++c)
+                    pc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(qv[r / 4][T2 * (r % 4) + t], acc[t][c][r], pc[c], 0, 0, 0);
+
+        float dl = 0.0f;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int e = 0; e < QN; ++e) dl = fmaf(qv[b][e], zq[b][e], dl);
+        dl += __shfl_xor(dl, 32, kWave);
+        if (half == 0 && pos < end) pden[pbase + pos] = dl;
+
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int32_t ppos = tile + 8 * (r / 4) + 4 * half + (r % 4);
+            if (ppos < end) {
+                float* dst = partial + (pbase + ppos) * D + T2 * li;
+                if constexpr (T2 == 2) {
+                    *reinterpret_cast<float2*>(dst) = make_float2(pc[0][r], pc[1][r]);
+                } else {
+                    dst[0] = pc[0][r];
+                }
+            }
+        }
+    }
+}
+
+// One wavefront per (slice, row i): sums the row's partial numerators and denominators in
+// ascending-l order and divides.
+template <int D>
+__global__ __launch_bounds__(256) void fused_reduce_kernel(long long n, const int32_t* __restrict__ row_ptr,
+                                                           const int32_t* __restrict__ csr_to_csc, int32_t nnz,
+                                                           const float* __restrict__ partial, const float* __restrict__ pden,
+                                                           long long bh_first, long long n_waves,
+                                                           float* __restrict__ out, float* __restrict__ num_opt, float* __restrict__ den_opt)
+{
+    constexpr int EPW = kWave / D;     // entries per wavefront step (1 at d = 64, 2 at d = 32)
+    const long long wave = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (wave >= n_waves) return;
+    const long long slice = wave / n;
+    const long long i = wave - slice * n;
+    const long long bh = bh_first + slice;
+    const int lane = lane_id();
+    const int sub = lane / D;
+    const int c = lane % D;
+    const float* slice_partial = partial + slice * static_cast<long long>(nnz) * D;
+    const float* slice_pden = pden + slice * static_cast<long long>(nnz);
+
+    const int32_t beg = max(row_ptr[i], 0);
+    const int32_t end = min(row_ptr[i + 1], nnz);
+    float acc = 0.0f, dacc = 0.0f;
+    for (int32_t chunk = beg; chunk < end; chunk += kWave) {
+        const int32_t e = chunk + lane;
+        const int32_t pos_reg = e < end ? csr_to_csc[e] : -1;
+        const int cnt = min(kWave, end - chunk);
+        // the shuffle is executed by every lane (a disabled source lane would read as 0)
+#pragma unroll 8
+        for (int t0 = 0; t0 < cnt; t0 += EPW) {
+            const int t = t0 + sub;
+            const int32_t pos = __shfl(pos_reg, t & (kWave - 1), kWave);
+            if (t < cnt && pos >= 0) {
+                acc += slice_partial[static_cast<long long>(pos) * D + c];
+                dacc += slice_pden[pos];
+            }
+        }
+    }
+    if constexpr (EPW == 2) {
+        acc += __shfl_xor(acc, 32, kWave);
+        dacc += __shfl_xor(dacc, 32, kWave);
+    }
+    if (sub == 0) {
+        const long long o = (bh * n + i) * D + c;
+        out[o] = acc / dacc;
+        if (num_opt != nullptr) num_opt[o] = acc;
+        if (c == 0 && den_opt != nullptr) den_opt[bh * n + i] = dacc;
+    }
+}
+
+namespace {
+
+template <int D, typename T>
+grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, int64_t H, int32_t n_f, const grf_phi* phi,
+                        int64_t nnz, const Transposed& t, int relu, int64_t bh_first, int64_t n_slices,
+                        float* partial, float* pden, float* out, float* num_opt, float* den_opt, hipStream_t stream)
+{
+    const long long waves = static_cast<long long>(n_slices) * n;
+    if (waves == 0) return GRF_OK;
+    hipLaunchKernelGGL((fused_bucket_kernel<D, T>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream,
+                       static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+                       static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
+                       static_cast<long long>(phi->capacity), static_cast<const int32_t*>(t.col_ptr),
+                       static_cast<const int32_t*>(t.s_row), static_cast<const int32_t*>(t.s_src),
+                       static_cast<const float*>(phi->val), relu, static_cast<long long>(bh_first), waves,
+                       static_cast<int32_t>(nnz), partial, pden);
+    GRF_LAUNCH_CHECK("fused_bucket_kernel");
+    hipLaunchKernelGGL((fused_reduce_kernel<D>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream,
+                       static_cast<long long>(n), static_cast<const int32_t*>(phi->row_ptr),
+                       static_cast<const int32_t*>(t.csr_to_csc), static_cast<int32_t>(nnz),
+                       static_cast<const float*>(partial), static_cast<const float*>(pden),
+                       static_cast<long long>(bh_first), waves, out, num_opt, den_opt);
+    GRF_LAUNCH_CHECK("fused_reduce_kernel");
+    return GRF_OK;
+}
+
+size_t partial_bytes(int64_t slices, int64_t nnz, int32_t d) { return align_up(sizeof(float) * static_cast<size_t>(slices) * static_cast<size_t>(nnz > 0 ? nnz : 1) * d); }
+size_t pden_bytes(int64_t slices, int64_t nnz) { return align_up(sizeof(float) * static_cast<size_t>(slices) * static_cast<size_t>(nnz > 0 ? nnz : 1)); }
+
+}  // namespace
+}  // namespace grf
+
+using namespace grf;
+
+extern "C" size_t grf_fused_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t bh_chunk)
+{
+    if (B < 0 || H < 0 || n < 0 || nnz < 0 || (d != 32 && d != 64)) return 0;
+    int64_t slices = B * H;
+    if (bh_chunk > 0 && bh_chunk < slices) slices = bh_chunk;
+    return carve_transposed(nullptr, n, nnz).bytes + partial_bytes(slices, nnz, d) + pden_bytes(slices, nnz);
+}
+
+extern "C" grf_status grf_masked_linear_attention_fused(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                        int64_t B, int64_t H, int64_t n, int32_t d,
+                                                        const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                        int32_t bh_chunk,
+                                                        void* workspace, size_t workspace_bytes, void* hip_stream,
+                                                        float* out, float* num_opt, float* den_opt)
+{
+    if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
+    if (B * H * n > 0 && (Q == nullptr || out == nullptr)) return fail(GRF_EINVAL, "Q / out is NULL");
+    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_fused_attention_workspace_bytes(B, H, n, d, nnz, bh_chunk))) return st;
+    if (B * H * n == 0) return GRF_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t slices = B * H;
+    const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    const Transposed t = carve_transposed(ws, n, nnz);
+    float* partial = reinterpret_cast<float*>(ws + t.bytes);
+    float* pden = reinterpret_cast<float*>(ws + t.bytes + partial_bytes(step, nnz, d));
+    if (grf_status st = transpose(phi, nnz, t, stream)) return st;
+    const int relu = feature_map == GRF_PHI_RELU ? 1 : 0;
+    for (int64_t first = 0; first < slices; first += step) {
+        const int64_t count = (slices - first < step) ? (slices - first) : step;
+        grf_status st = GRF_OK;
+        GRF_DISPATCH(d, dtype, (st = launch_fused<D_, T_>(Q, K, V, n, H, n_f, phi, nnz, t, relu, first, count, partial, pden,
+                                                          out, num_opt, den_opt, stream)));
+        if (st != GRF_OK) return st;
+    }
+    return GRF_OK;
+}

@@ -321,3 +321,137 @@ def test_headline_workload_full_size(grf, oracle):
     assert np.all(np.abs(a - b) <= 1e-5 * scale)
     del out, num, den, den_sw
     torch.cuda.empty_cache()
+
+
+def _spot_check_full_size(grf, oracle, wl, heads, n_rows, tol):
+    """Pattern bit-exact, values close, and sampled output rows against Eq. (2) evaluated directly."""
+    import torch
+    g = grf.DeviceGraph.from_host(wl.graph)
+    phi = grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+    rp, col, val = phi.to_host()
+    rp0, col0, val0 = _oracle_phi(oracle, wl)
+    assert np.array_equal(rp, rp0) and np.array_equal(col, col0)
+    for h in range(wl.n_f):
+        assert relerr(val[h], val0[h]) <= TOL_F32
+    Q, K, V = wl.qkv()
+    Qd, Kd, Vd = (to_dev(x, wl.dtype) for x in (Q, K, V))
+    out, num, den = grf.grf_masked_linear_attention(Qd, Kd, Vd, phi, return_num_den=True)
+    num_h, den_h = num.cpu().numpy(), den.cpu().numpy()
+    rng = np.random.default_rng(1)
+    rows = rng.choice(wl.graph.n, size=n_rows, replace=False)
+    worst = 0.0
+    for b, h in heads:
+        plane = val0[h if wl.n_f > 1 else 0]
+        num_scale = np.abs(num_h[b, h]).max(); den_scale = np.abs(den_h[b, h]).max()
+        for i in rows:
+            n_i, d_i, _ = oracle.row_direct(int(i), Q[b, h], K[b, h], V[b, h], rp0, col0, plane)
+            worst = max(worst, np.abs(num_h[b, h, i] - n_i).max() / num_scale, abs(den_h[b, h, i] - d_i) / den_scale)
+    assert worst <= tol, worst
+    # chunked evaluation gives the same bits as the all-slices launch
+    out_c = grf.grf_masked_linear_attention(Qd, Kd, Vd, phi, bh_chunk=3)
+    assert torch.equal(torch.nan_to_num(out), torch.nan_to_num(out_c))
+    del out, num, den, out_c
+    torch.cuda.empty_cache()
+
+
+def test_cloud_8k_full_size(grf, oracle):
+    wl = synth.workload("cloud_8k")
+    _spot_check_full_size(grf, oracle, wl, heads=[(0, 0), (3, 5), (7, 7)], n_rows=16, tol=TOL_F32)
+
+
+def test_cloud_128k_bf16_per_head_full_size(grf, oracle):
+    """131072 nodes, 16 heads with per-head f, bf16 inputs, fp32 buckets (35 GB of records)."""
+    wl = synth.workload("cloud_128k")
+    _spot_check_full_size(grf, oracle, wl, heads=[(0, 0), (0, 9), (0, 15)], n_rows=12, tol=TOL_BF16)
+
+
+# --------------------------------------------------------------------------- bucket-fused variant
+
+def _compare_fused(grf, oracle, wl, rp, col, val, feature_map="relu", bh_chunk=0):
+    Q, K, V = wl.qkv()
+    tol = TOL_BF16 if wl.dtype == "bf16" else TOL_F32
+    fm = oracle.RELU if feature_map == "relu" else oracle.IDENTITY
+    ref = oracle.masked_linear_attention(Q, K, V, rp, col, val, feature_map=fm)
+    phi = grf.Phi.from_host(wl.graph.n, rp, col, val)
+    Qd, Kd, Vd = (to_dev(x, wl.dtype) for x in (Q, K, V))
+    out, num, den = grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, feature_map, bh_chunk=bh_chunk, return_num_den=True)
+    out, num, den = out.cpu().numpy(), num.cpu().numpy(), den.cpu().numpy()
+    assert relerr(num, ref["num"]) <= tol
+    assert relerr(den, ref["den"]) <= tol
+    with np.errstate(divide="ignore", invalid="ignore"):
+        assert np.array_equal(np.nan_to_num(out, nan=7.0, posinf=8.0, neginf=9.0),
+                              np.nan_to_num(num / den[..., None], nan=7.0, posinf=8.0, neginf=9.0))
+    # and against the bucket + gather pair of the same library
+    out2, num2, den2 = grf.grf_masked_linear_attention(Qd, Kd, Vd, phi, feature_map, return_num_den=True)
+    assert relerr(num, num2.cpu().numpy()) <= tol
+    assert relerr(den, den2.cpu().numpy()) <= tol
+    return out, num, den
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_fused_attention_parity(grf, oracle, name):
+    wl = SMALL[name]
+    rp, col, val = _oracle_phi(oracle, wl)
+    _compare_fused(grf, oracle, wl, rp, col, val)
+
+
+def test_fused_identity_map_chunking_determinism(grf, oracle):
+    wl = SMALL["random_777"]
+    rp, col, val = _oracle_phi(oracle, wl)
+    full = _compare_fused(grf, oracle, wl, rp, col, val, feature_map="identity")
+    again = _compare_fused(grf, oracle, wl, rp, col, val, feature_map="identity")
+    part = _compare_fused(grf, oracle, wl, rp, col, val, feature_map="identity", bh_chunk=3)
+    for a, b, c in zip(full, again, part):
+        assert np.array_equal(np.nan_to_num(a), np.nan_to_num(b))
+        assert np.array_equal(np.nan_to_num(a), np.nan_to_num(c))
+
+
+def test_fused_special_feature_matrices(grf):
+    import torch
+    rng = np.random.default_rng(6)
+    n, d = 333, 64
+    Q, K, V = synth.qkv(1, 2, n, d, rng)
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    ident = grf.Phi.from_host(n, np.arange(n + 1), np.arange(n), np.ones((1, n), np.float32))
+    out, num, den = grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, ident, return_num_den=True)
+    ok = den.cpu().numpy() != 0
+    assert relerr(out.cpu().numpy()[ok], V[ok]) <= TOL_F32
+    # a single column consumed by every row: one bucket with r_l = n (many consumer tiles)
+    ones_col = grf.Phi.from_host(n, np.arange(n + 1), np.full(n, 7), np.ones((1, n), np.float32))
+    out, num, den = grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, ones_col, return_num_den=True)
+    fq = np.maximum(Q.astype(np.float64), 0); fk = np.maximum(K.astype(np.float64), 0)
+    num_ref = fq @ (np.swapaxes(fk, -1, -2) @ V.astype(np.float64))
+    den_ref = (fq @ fk.sum(axis=2)[..., None])[..., 0]
+    assert relerr(num.cpu().numpy(), num_ref) <= TOL_F32
+    assert relerr(den.cpu().numpy(), den_ref) <= TOL_F32
+    # rows without entries
+    rp = np.zeros(n + 1, dtype=np.int32); rp[5:] = 1
+    sparse = grf.Phi.from_host(n, rp, np.array([2]), np.ones((1, 1), np.float32))
+    out, num, den = grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, sparse, return_num_den=True)
+    mask = np.ones(n, bool); mask[4] = False
+    assert np.all(num.cpu().numpy()[:, :, mask] == 0) and np.all(den.cpu().numpy()[:, :, mask] == 0)
+    e0 = torch.zeros((0, 2, n, 64), device="cuda:0")
+    assert grf.grf_masked_linear_attention_fused(e0, e0, e0, ident).shape == (0, 2, n, 64)
+
+
+def test_fused_headline_workload_full_size(grf, oracle):
+    import torch
+    wl = synth.workload("cloud_32k")
+    rp0, col0, val0 = _oracle_phi(oracle, wl)
+    phi = grf.Phi.from_host(wl.graph.n, rp0, col0, val0)
+    Q, K, V = wl.qkv()
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    out, num, den = grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, return_num_den=True)
+    num_h, den_h = num.cpu().numpy(), den.cpu().numpy()
+    rows = np.random.default_rng(2).choice(wl.graph.n, size=24, replace=False)
+    for h in (1, 4, 6):
+        num_scale = np.abs(num_h[0, h]).max(); den_scale = np.abs(den_h[0, h]).max()
+        for i in rows:
+            n_i, d_i, _ = oracle.row_direct(int(i), Q[0, h], K[0, h], V[0, h], rp0, col0, val0[0])
+            assert np.abs(num_h[0, h, i] - n_i).max() <= TOL_F32 * num_scale
+            assert abs(den_h[0, h, i] - d_i) <= TOL_F32 * den_scale
+    out2, num2, den2 = grf.grf_masked_linear_attention(Qd, Kd, Vd, phi, return_num_den=True)
+    assert relerr(num_h, num2.cpu().numpy()) <= TOL_F32
+    assert relerr(den_h, den2.cpu().numpy()) <= TOL_F32
+    del out, num, den, out2, num2, den2
+    torch.cuda.empty_cache()
