@@ -78,7 +78,7 @@ def main() -> int:
     nnz = phi.nnz
     rec = grf.grf_bucket_record_floats(d)
     buckets = torch.empty((B * H, N, rec), dtype=torch.float32, device=dev)
-    ws = torch.empty(grf.grf_buckets_workspace_bytes(N, nnz), dtype=torch.uint8, device=dev)
+    ws = torch.empty(grf.grf_buckets_workspace_bytes(N, nnz, phi.n_f), dtype=torch.uint8, device=dev)
     out = torch.empty((B, H, N, d), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
 
@@ -117,6 +117,42 @@ def main() -> int:
                 "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                 "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": round(gather_ms, 4)}
 
+    # the bucket-fused variant of the attention call on the same inputs: its own numbers, never `value`
+    fws = torch.empty(grf.grf_fused_attention_workspace_bytes(B, H, N, d, nnz, phi.n_f), dtype=torch.uint8, device=dev)
+    fout = torch.empty_like(out)
+
+    def fused_step(events=None):
+        if events: events[0].record(stream)
+        grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed, out=phi)
+        if events: events[1].record(stream)
+        grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, workspace=fws, out=fout)
+        if events: events[2].record(stream)
+
+    for _ in range(args.warmup):
+        fused_step()
+    torch.cuda.synchronize()
+    fevents = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    f0 = time.perf_counter()
+    for k in range(args.steps):
+        fused_step(fevents[k])
+    torch.cuda.synchronize()
+    f1 = time.perf_counter()
+    fused_ms_per_step = (f1 - f0) * 1e3 / args.steps
+    fused_attn_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in fevents]))
+    # two contractions per entry of Phi_hat: S_l += a v^T and P = qw S_l, 2*d*d flops each
+    fused_flops = 4.0 * nnz * d * d * B * H
+    fused = {
+        "entry_point": "grf_masked_linear_attention_fused",
+        "ms_per_step": round(fused_ms_per_step, 4),
+        "tokens_per_s_per_head": round(tokens / (fused_ms_per_step * 1e-3), 1),
+        "attention_ms": round(fused_attn_ms, 4),
+        "attention_only_tokens_per_s_per_head": round(tokens / (fused_attn_ms * 1e-3), 1),
+        "roofline": {"bound": "mfma", "unit": "TFLOP/s", "peak": 157.3,
+                     "achieved_whole_call": round(fused_flops / (fused_attn_ms * 1e-3) / 1e12, 2),
+                     "flops_per_call": fused_flops,
+                     "note": "whole attention call (column lists + fused buckets + row reduce); per-kernel times in profiles/"},
+    }
+
     result = {
         "metric": "GRF-masked linear attention tokens/s/head at N=%d" % N,
         "value": round(value, 1), "unit": "tokens/s/head",
@@ -129,6 +165,7 @@ def main() -> int:
         "stage_ms": {"sample": round(sample_ms, 4), "buckets": round(buckets_ms, 4), "gather": round(gather_ms, 4)},
         "attention_only_tokens_per_s_per_head": round(tokens / ((buckets_ms + gather_ms) * 1e-3), 1),
         "roofline": roofline,
+        "fused_variant": fused,
     }
 
     if not args.no_cpu_baseline:

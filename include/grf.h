@@ -140,10 +140,10 @@ int64_t grf_bucket_record_floats(int32_t d);
 /* Workspace bytes of grf_masked_linear_attention (multiple of 256; 0 on bad arguments): the column
  * lists of Phi_hat plus the bucket records of bh_chunk slices.
  * bh_chunk: how many (batch, head) slices have their buckets resident at once; <= 0 means all B*H. */
-size_t grf_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t bh_chunk);
+size_t grf_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t n_f, int32_t bh_chunk);
 
-/* Workspace bytes of grf_form_buckets (the column lists of Phi_hat only). */
-size_t grf_buckets_workspace_bytes(int64_t n, int64_t nnz);
+/* Workspace bytes of grf_form_buckets (the column lists of Phi_hat only, with n_f value planes). */
+size_t grf_buckets_workspace_bytes(int64_t n, int64_t nnz, int32_t n_f);
 
 /* Buckets only (Alg. 1 step 5, the two Phi_{K,G}^T products).
  * buckets: device [B*H][n][grf_bucket_record_floats(d)] fp32, fully overwritten. */
@@ -180,7 +180,7 @@ grf_status grf_masked_linear_attention(const void* Q, const void* K, const void*
  * d-float partial numerator and one partial denominator per entry of Phi_hat; a second kernel sums
  * each row's partials in ascending-l order (deterministic; no float atomics).
  * Workspace: column lists plus (d + 1) floats per entry of Phi_hat per resident slice. */
-size_t grf_fused_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t bh_chunk);
+size_t grf_fused_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t n_f, int32_t bh_chunk);
 
 grf_status grf_masked_linear_attention_fused(const void* Q, const void* K, const void* V, int32_t dtype,
                                              int64_t B, int64_t H, int64_t n, int32_t d,

@@ -69,9 +69,9 @@ def lib() -> ctypes.CDLL:
         L.grf_bucket_record_floats.argtypes = [ctypes.c_int32]
         L.grf_attention_workspace_bytes.restype = ctypes.c_size_t
         L.grf_attention_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
-                                                    ctypes.c_int64, ctypes.c_int32]
+                                                    ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
         L.grf_buckets_workspace_bytes.restype = ctypes.c_size_t
-        L.grf_buckets_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64]
+        L.grf_buckets_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32]
         common = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
                   ctypes.POINTER(_Phi), ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
         L.grf_form_buckets.restype = ctypes.c_int32
@@ -252,12 +252,12 @@ def grf_bucket_record_floats(d: int) -> int:
     return int(lib().grf_bucket_record_floats(d))
 
 
-def grf_attention_workspace_bytes(B: int, H: int, n: int, d: int, nnz: int, bh_chunk: int = 0) -> int:
-    return int(lib().grf_attention_workspace_bytes(B, H, n, d, nnz, bh_chunk))
+def grf_attention_workspace_bytes(B: int, H: int, n: int, d: int, nnz: int, n_f: int = 1, bh_chunk: int = 0) -> int:
+    return int(lib().grf_attention_workspace_bytes(B, H, n, d, nnz, n_f, bh_chunk))
 
 
-def grf_buckets_workspace_bytes(n: int, nnz: int) -> int:
-    return int(lib().grf_buckets_workspace_bytes(n, nnz))
+def grf_buckets_workspace_bytes(n: int, nnz: int, n_f: int = 1) -> int:
+    return int(lib().grf_buckets_workspace_bytes(n, nnz, n_f))
 
 
 def grf_form_buckets(K: torch.Tensor, V: torch.Tensor, phi: Phi, feature_map: str = "relu",
@@ -272,7 +272,7 @@ def grf_form_buckets(K: torch.Tensor, V: torch.Tensor, phi: Phi, feature_map: st
     buckets = out if out is not None else torch.empty((B * H, n, rec), dtype=torch.float32, device=K.device)
     if buckets.numel() != B * H * n * rec or buckets.dtype != torch.float32 or not buckets.is_contiguous():
         raise ValueError("bucket buffer has the wrong size, dtype or layout")
-    ws = workspace if workspace is not None else _workspace(L.grf_buckets_workspace_bytes(n, phi.nnz), K.device)
+    ws = workspace if workspace is not None else _workspace(L.grf_buckets_workspace_bytes(n, phi.nnz, phi.n_f), K.device)
     ps = phi._struct()
     _check(L.grf_form_buckets(_ptr(K), _ptr(V), _dtype_code(K), B, H, n, d, ctypes.byref(ps), phi.nnz, phi.n_f,
                               _FEATURE_MAPS[feature_map], _ptr(ws), ws.numel(), _stream_ptr(stream), _ptr(buckets)))
@@ -301,8 +301,8 @@ def grf_gather_buckets(Q: torch.Tensor, phi: Phi, buckets: torch.Tensor, feature
     return (out, num, den) if return_num_den else out
 
 
-def grf_fused_attention_workspace_bytes(B: int, H: int, n: int, d: int, nnz: int, bh_chunk: int = 0) -> int:
-    return int(lib().grf_fused_attention_workspace_bytes(B, H, n, d, nnz, bh_chunk))
+def grf_fused_attention_workspace_bytes(B: int, H: int, n: int, d: int, nnz: int, n_f: int = 1, bh_chunk: int = 0) -> int:
+    return int(lib().grf_fused_attention_workspace_bytes(B, H, n, d, nnz, n_f, bh_chunk))
 
 
 def grf_masked_linear_attention_fused(Q, K, V, phi: Phi, feature_map: str = "relu", bh_chunk: int = 0,
@@ -326,7 +326,7 @@ def _attention_call(entry: str, ws_query: str, Q, K, V, phi, feature_map, bh_chu
     _require_gpu()
     L = lib()
     B, H, n, d = _check_qkv(Q, K, V)
-    need = getattr(L, ws_query)(B, H, n, d, phi.nnz, bh_chunk)
+    need = getattr(L, ws_query)(B, H, n, d, phi.nnz, phi.n_f, bh_chunk)
     if need == 0:
         raise GrfError(GRF_EUNSUPPORTED, f"unsupported problem (d={d})")
     if workspace is None:

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256) void column_scatter_kernel(const int32_t* __re
 
 // One wavefront per column: order the segment by row index (rows are distinct within a column)
 // by counting, so that the buckets are summed in a fixed order.  Quadratic in the segment length.
-__global__ __launch_bounds__(256) void column_sort_kernel(const int32_t* __restrict__ col_ptr, int32_t n,
+__global__ __launch_bounds__(256) void column_sort_kernel(const int32_t* __restrict__ col_ptr, int32_t n, int32_t nnz,
                                                           const int32_t* __restrict__ u_row, const int32_t* __restrict__ u_src,
                                                           int32_t* __restrict__ s_row, int32_t* __restrict__ s_src,
                                                           int32_t* __restrict__ csr_to_csc)
@@ -61,10 +61,24 @@ __global__ __launch_bounds__(256) void column_sort_kernel(const int32_t* __restr
         int rank = 0;
         for (int s2 = 0; s2 < len; ++s2) rank += static_cast<int>(u_row[beg + s2] < key);
         const int32_t src = u_src[beg + s];
-        s_row[beg + rank] = key;
-        s_src[beg + rank] = src;
-        csr_to_csc[src] = beg + rank;
+        // Slots that a malformed Phi_hat (overlapping rows) left unset hold arbitrary bits: whatever is
+        // written downstream is a valid index, so the kernels that follow need no guards.
+        const bool ok = static_cast<uint32_t>(key) < static_cast<uint32_t>(n) && static_cast<uint32_t>(src) < static_cast<uint32_t>(nnz);
+        s_row[beg + rank] = ok ? key : 0;
+        s_src[beg + rank] = ok ? src : 0;
+        if (ok) csr_to_csc[src] = beg + rank;
     }
+}
+
+// Value planes in column-list order: s_val[h][pos] = val[h][s_src[pos]].
+__global__ __launch_bounds__(256) void column_values_kernel(const int32_t* __restrict__ s_src, long long nnz, int n_f,
+                                                            const float* __restrict__ val, long long val_stride,
+                                                            float* __restrict__ s_val)
+{
+    const long long pos = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (pos >= nnz) return;
+    const int32_t src = s_src[pos];
+    for (int h = 0; h < n_f; ++h) s_val[h * nnz + pos] = val[h * val_stride + src];
 }
 
 // ------------------------------------------------------------------------------------ buckets
@@ -73,16 +87,16 @@ __global__ __launch_bounds__(256) void column_sort_kernel(const int32_t* __restr
 // The two halves of the wavefront therefore carry two different contributors j (the k index),
 // lane%32 walks along a row of phi(K) (A operand) and of V (B operand): no transposes, no LDS.
 template <int D, typename T>
-__global__ __launch_bounds__(256) void buckets_kernel(const T* __restrict__ K, const T* __restrict__ V,
-                                                      long long n, int H, int n_f, long long val_stride,
+__global__ __launch_bounds__(64) void buckets_kernel(const T* __restrict__ K, const T* __restrict__ V,
+                                                      long long n, int H, int n_f,
                                                       const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
-                                                      const int32_t* __restrict__ csc_src, const float* __restrict__ phi_val,
+                                                      const float* __restrict__ csc_val,
                                                       int relu, long long bh_first, long long n_waves, int32_t nnz,
                                                       float* __restrict__ buckets)
 {
     constexpr int T2 = D / 32;
     constexpr long long REC = static_cast<long long>(D) * D + D;
-    const long long wave = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const long long wave = blockIdx.x;         // one wavefront per workgroup: column lists differ in length
     if (wave >= n_waves) return;
     const long long slice = wave / n;          // slice index inside this launch
     const long long l = wave - slice * n;
@@ -90,7 +104,7 @@ __global__ __launch_bounds__(256) void buckets_kernel(const T* __restrict__ K, c
     const long long plane = n_f > 1 ? (bh % H) : 0;
     const T* Kb = K + bh * n * D;
     const T* Vb = V + bh * n * D;
-    const float* vals = phi_val + plane * val_stride;
+    const float* vals = csc_val + plane * nnz;
 
     const int lane = lane_id();
     const int half = lane >> 5;
@@ -98,52 +112,7 @@ __global__ __launch_bounds__(256) void buckets_kernel(const T* __restrict__ K, c
 
     floatx16 acc[T2][T2];
     float zacc[T2];
-#pragma unroll
-    for (int a = 0; a < T2; ++a) {
-        zacc[a] = 0.0f;
-#pragma unroll
-        for (int c = 0; c < T2; ++c)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
-    }
-
-    const int32_t beg = col_ptr[l];
-    const int32_t end = col_ptr[l + 1];
-    for (int32_t chunk = beg; chunk < end; chunk += kWave) {
-        const int32_t e = chunk + lane;
-        int32_t j_reg = 0;
-        float g_reg = 0.0f;
-        if (e < end) {
-            const int32_t row = csc_row[e];
-            const int32_t src = csc_src[e];
-            // entries that a malformed Phi_hat left unset are dropped instead of followed
-            if (static_cast<uint32_t>(row) < static_cast<uint32_t>(n) && static_cast<uint32_t>(src) < static_cast<uint32_t>(nnz)) {
-                j_reg = row;
-                g_reg = vals[src];
-            }
-        }
-        const int cnt = min(kWave, end - chunk);
-        for (int p = 0; p < cnt; p += 2) {
-            const int src = p + half;
-            const long long j = __shfl(j_reg, src, kWave);
-            const float g = __shfl(g_reg, src, kWave);
-            const bool valid = src < cnt;
-            float a_op[T2], b_op[T2];
-#pragma unroll
-            for (int t = 0; t < T2; ++t) {
-                const float kv = valid ? to_float(Kb[j * D + 32 * t + li]) : 0.0f;
-                const float vv = valid ? to_float(Vb[j * D + 32 * t + li]) : 0.0f;
-                a_op[t] = valid ? g * feature(kv, relu) : 0.0f;
-                b_op[t] = vv;
-                zacc[t] += a_op[t];
-            }
-#pragma unroll
-            for (int a = 0; a < T2; ++a)
-#pragma unroll
-                for (int c = 0; c < T2; ++c)
-                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_op[a], b_op[c], acc[a][c], 0, 0, 0);
-        }
-    }
+    bucket_first_contraction<D, T, false>(Kb, Vb, csc_row, vals, col_ptr[l], col_ptr[l + 1], relu, acc, zacc);
 
     float* rec = buckets + (slice * n + l) * REC;
 #pragma unroll
@@ -247,7 +216,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ Q, lo
 }
 
 // ------------------------------------------------------------------------------------ host side
-Transposed carve_transposed(unsigned char* ws, int64_t n, int64_t nnz)
+Transposed carve_transposed(unsigned char* ws, int64_t n, int64_t nnz, int32_t n_f)
 {
     Transposed t;
     size_t off = 0;
@@ -260,12 +229,13 @@ Transposed carve_transposed(unsigned char* ws, int64_t n, int64_t nnz)
     t.s_row = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
     t.s_src = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
     t.csr_to_csc = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
+    t.s_val = reinterpret_cast<float*>(take(sizeof(float) * entries * static_cast<size_t>(n_f > 0 ? n_f : 1)));
     t.total = reinterpret_cast<long long*>(take(sizeof(long long)));
     t.bytes = off;
     return t;
 }
 
-grf_status transpose(const grf_phi* phi, int64_t nnz, const Transposed& t, hipStream_t stream)
+grf_status transpose(const grf_phi* phi, int64_t nnz, int32_t n_f, const Transposed& t, hipStream_t stream)
 {
     const int64_t n = phi->n;
     if (grf_status st = fill_i32(t.col_ptr, n + 1, 0, stream)) return st;
@@ -273,6 +243,8 @@ grf_status transpose(const grf_phi* phi, int64_t nnz, const Transposed& t, hipSt
     if (nnz > 0) {
         // entries that a malformed Phi_hat never reaches must not point anywhere
         if (grf_status st = fill_i32(t.csr_to_csc, nnz, -1, stream)) return st;
+        if (grf_status st = fill_i32(t.s_row, nnz, 0, stream)) return st;
+        if (grf_status st = fill_i32(t.s_src, nnz, 0, stream)) return st;
         hipLaunchKernelGGL(column_histogram_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, stream,
                            static_cast<const int32_t*>(phi->col), static_cast<long long>(nnz), static_cast<int32_t>(n), t.col_ptr);
         GRF_LAUNCH_CHECK("column_histogram_kernel");
@@ -285,10 +257,14 @@ grf_status transpose(const grf_phi* phi, int64_t nnz, const Transposed& t, hipSt
                            t.cursor, t.u_row, t.u_src);
         GRF_LAUNCH_CHECK("column_scatter_kernel");
         hipLaunchKernelGGL(column_sort_kernel, dim3(blocks_for(n, 4)), dim3(256), 0, stream,
-                           static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n),
+                           static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n), static_cast<int32_t>(nnz),
                            static_cast<const int32_t*>(t.u_row), static_cast<const int32_t*>(t.u_src), t.s_row, t.s_src,
                            t.csr_to_csc);
         GRF_LAUNCH_CHECK("column_sort_kernel");
+        hipLaunchKernelGGL(column_values_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, stream,
+                           static_cast<const int32_t*>(t.s_src), static_cast<long long>(nnz), static_cast<int>(n_f),
+                           static_cast<const float*>(phi->val), static_cast<long long>(phi->capacity), t.s_val);
+        GRF_LAUNCH_CHECK("column_values_kernel");
     }
     return GRF_OK;
 }
@@ -303,7 +279,7 @@ grf_status check_problem(const void* a, const void* b, int32_t dtype, int64_t B,
     if (phi == nullptr) return fail(GRF_EINVAL, "phi is NULL");
     if (phi->n != n) return fail(GRF_EINVAL, "phi->n=%lld differs from n=%lld", (long long)phi->n, (long long)n);
     if (nnz < 0 || nnz > phi->capacity) return fail(GRF_EINVAL, "nnz=%lld must lie in [0, phi->capacity=%lld]", (long long)nnz, (long long)phi->capacity);
-    if (nnz >= 2147483647ll || n >= 2147483647ll) return fail(GRF_EUNSUPPORTED, "n and nnz must be < 2^31 - 1");
+    if (nnz >= 2147483647ll - 256 || n >= 2147483647ll - 256) return fail(GRF_EUNSUPPORTED, "n and nnz must be < 2^31 - 257");
     if (n_f != 1 && n_f != H) return fail(GRF_EINVAL, "n_f=%d must be 1 or H=%lld", n_f, (long long)H);
     if (phi->row_ptr == nullptr || (nnz > 0 && (phi->col == nullptr || phi->val == nullptr))) return fail(GRF_EINVAL, "phi arrays are NULL");
     if (B * H * n > 0 && (a == nullptr || b == nullptr)) return fail(GRF_EINVAL, "an input tensor is NULL");
@@ -327,11 +303,11 @@ grf_status launch_buckets(const void* K, const void* V, int64_t n, int64_t H, in
 {
     const long long waves = static_cast<long long>(n_slices) * n;
     if (waves == 0) return GRF_OK;
-    hipLaunchKernelGGL((buckets_kernel<D, T>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream,
+    hipLaunchKernelGGL((buckets_kernel<D, T>), dim3(blocks_for(waves, 1)), dim3(kWave), 0, stream,
                        static_cast<const T*>(K), static_cast<const T*>(V), static_cast<long long>(n), static_cast<int>(H),
-                       static_cast<int>(n_f), static_cast<long long>(phi->capacity),
+                       static_cast<int>(n_f),
                        static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
-                       static_cast<const int32_t*>(t.s_src), static_cast<const float*>(phi->val), relu,
+                       static_cast<const float*>(t.s_val), relu,
                        static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), buckets);
     GRF_LAUNCH_CHECK("buckets_kernel");
     return GRF_OK;
@@ -364,19 +340,19 @@ extern "C" int64_t grf_bucket_record_floats(int32_t d)
     return static_cast<int64_t>(d) * d + d;
 }
 
-extern "C" size_t grf_buckets_workspace_bytes(int64_t n, int64_t nnz)
+extern "C" size_t grf_buckets_workspace_bytes(int64_t n, int64_t nnz, int32_t n_f)
 {
-    if (n < 0 || nnz < 0) return 0;
-    return carve_transposed(nullptr, n, nnz).bytes;
+    if (n < 0 || nnz < 0 || n_f < 1) return 0;
+    return carve_transposed(nullptr, n, nnz, n_f).bytes;
 }
 
-extern "C" size_t grf_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t bh_chunk)
+extern "C" size_t grf_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t n_f, int32_t bh_chunk)
 {
-    if (B < 0 || H < 0 || n < 0 || nnz < 0 || (d != 32 && d != 64)) return 0;
+    if (B < 0 || H < 0 || n < 0 || nnz < 0 || n_f < 1 || (d != 32 && d != 64)) return 0;
     int64_t slices = B * H;
     if (bh_chunk > 0 && bh_chunk < slices) slices = bh_chunk;
     const size_t bucket_bytes = sizeof(float) * static_cast<size_t>(slices) * static_cast<size_t>(n) * static_cast<size_t>(grf_bucket_record_floats(d));
-    return carve_transposed(nullptr, n, nnz).bytes + align_up(bucket_bytes);
+    return carve_transposed(nullptr, n, nnz, n_f).bytes + align_up(bucket_bytes);
 }
 
 extern "C" grf_status grf_form_buckets(const void* K, const void* V, int32_t dtype,
@@ -386,11 +362,11 @@ extern "C" grf_status grf_form_buckets(const void* K, const void* V, int32_t dty
 {
     if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
     if (B * H * n > 0 && buckets == nullptr) return fail(GRF_EINVAL, "buckets is NULL");
-    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_buckets_workspace_bytes(n, nnz))) return st;
+    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_buckets_workspace_bytes(n, nnz, n_f))) return st;
     if (B * H * n == 0) return GRF_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const Transposed t = carve_transposed(static_cast<unsigned char*>(workspace), n, nnz);
-    if (grf_status st = transpose(phi, nnz, t, stream)) return st;
+    const Transposed t = carve_transposed(static_cast<unsigned char*>(workspace), n, nnz, n_f);
+    if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
     const int relu = feature_map == GRF_PHI_RELU ? 1 : 0;
     grf_status st = GRF_OK;
     GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, phi, nnz, t, relu, 0, B * H, buckets, stream)));
@@ -422,12 +398,12 @@ extern "C" grf_status grf_masked_linear_attention(const void* Q, const void* K, 
 {
     if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
     if (B * H * n > 0 && (Q == nullptr || out == nullptr)) return fail(GRF_EINVAL, "Q / out is NULL");
-    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_attention_workspace_bytes(B, H, n, d, nnz, bh_chunk))) return st;
+    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_attention_workspace_bytes(B, H, n, d, nnz, n_f, bh_chunk))) return st;
     if (B * H * n == 0) return GRF_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const Transposed t = carve_transposed(static_cast<unsigned char*>(workspace), n, nnz);
+    const Transposed t = carve_transposed(static_cast<unsigned char*>(workspace), n, nnz, n_f);
     float* buckets = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + t.bytes);
-    if (grf_status st = transpose(phi, nnz, t, stream)) return st;
+    if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
     const int relu = feature_map == GRF_PHI_RELU ? 1 : 0;
     const int64_t slices = B * H;
     const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;

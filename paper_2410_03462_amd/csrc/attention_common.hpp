@@ -13,7 +13,8 @@ struct bf16_t { uint16_t bits; };
 __device__ __forceinline__ float to_float(float x) { return x; }
 __device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(static_cast<uint32_t>(x.bits) << 16); }
 
-__device__ __forceinline__ float feature(float x, int relu) { return relu ? fmaxf(x, 0.0f) : x; }
+// phi(x): max(x, 0) as one v_med3_f32 (median of x, 0, +inf), or the identity.
+__device__ __forceinline__ float feature(float x, int relu) { return relu ? __builtin_amdgcn_fmed3f(x, 0.0f, __builtin_inff()) : x; }
 
 // Column lists of Phi_hat, carved out of the caller's workspace.
 struct Transposed {
@@ -24,15 +25,140 @@ struct Transposed {
     int32_t* s_row;     // [nnz] rows ascending inside each column
     int32_t* s_src;     // index of the entry in CSR order (addresses every value plane)
     int32_t* csr_to_csc;  // [nnz] position in the column lists of CSR entry e
+    float* s_val;       // [n_f][nnz] value planes permuted into column-list order
     long long* total;
     size_t bytes;
 };
 
-Transposed carve_transposed(unsigned char* ws, int64_t n, int64_t nnz);
-grf_status transpose(const grf_phi* phi, int64_t nnz, const Transposed& t, hipStream_t stream);
+Transposed carve_transposed(unsigned char* ws, int64_t n, int64_t nnz, int32_t n_f);
+grf_status transpose(const grf_phi* phi, int64_t nnz, int32_t n_f, const Transposed& t, hipStream_t stream);
 grf_status check_problem(const void* a, const void* b, int32_t dtype, int64_t B, int64_t H, int64_t n, int32_t d,
                          const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map);
 grf_status check_workspace(const void* workspace, size_t have, size_t need);
+
+// Workgroups are handed to the eight XCDs round-robin by id, and each XCD has an L2 of its own.
+// This maps a workgroup id to a logical index such that every XCD works through one contiguous
+// range of logical indices (ids congruent mod 8 become neighbours), so that work items that are
+// adjacent in the logical order share an L2.
+__device__ __forceinline__ long long xcd_contiguous_block(unsigned block, unsigned n_blocks)
+{
+    constexpr unsigned kXcds = 8;
+    const unsigned q = n_blocks / kXcds, rem = n_blocks % kXcds;
+    const unsigned x = block % kXcds, k = block / kXcds;
+    return static_cast<long long>(x) * q + (x < rem ? x : rem) + k;
+}
+
+// First contraction of a bucket, shared by the bucket-forming and the bucket-fused kernels:
+//     acc[a][c] (32x32 tiles) += A^T V over the column list [beg, end) of bucket l,   zacc[a] += column sums of A,
+// A = weight * phi(K row).  The two half-waves carry the two contributors of a pair (the k index
+// of v_mfma_f32_32x32x2_f32).  MFMA row/column x of tile t stands for element 32*t + x of the K/V
+// row, or, INTERLEAVED, element T2*x + t, so that a lane's operands are adjacent in memory.
+//
+// The column list is walked in blocks of 128 entries (64 contributor pairs; most lists fit in one):
+//   - the (row, weight) of a block's entries are fetched up front, one entry per lane in two
+//     register pairs, and a pair's two entries (wave-uniform) are pulled out with v_readlane, so
+//     that inside the block the only memory instructions are the row loads: the load counter
+//     retires in order, and any wait on a recently issued index load would drain every row load
+//     issued before it;
+//   - a pair's rows of K and V are fetched RING pairs ahead into a ring of RING register slots,
+//     the slot that the current pair has just vacated;
+//   - row loads are unconditional (pairs past the end re-read the last entry with weight 0), since
+//     a load skipped on one control path would force a full wait where the paths join;
+//   - a scheduling barrier per pair keeps each pair's fetch work next to the previous pair's MFMAs:
+//     an MFMA holds the matrix pipe for 64 cycles, in which the fetch instructions issue for free.
+template <int D, typename T, bool INTERLEAVED>
+__device__ __forceinline__ void bucket_first_contraction(const T* __restrict__ Kb, const T* __restrict__ Vb,
+                                                         const int32_t* __restrict__ csc_row, const float* __restrict__ vals,
+                                                         int32_t beg_in, int32_t end_in, int relu,
+                                                         floatx16 (&acc)[D / 32][D / 32], float (&zacc)[D / 32])
+{
+    constexpr int T2 = D / 32;
+    constexpr int RING = 16;
+    const int32_t beg = beg_in, end = end_in;
+    const int lane = lane_id();
+    const bool upper = lane >= 32;
+    const int li = lane & 31;
+#pragma unroll
+    for (int a = 0; a < T2; ++a) {
+        zacc[a] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < T2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
+    }
+    if (beg >= end) return;
+
+    // rows of the pair held in lanes (s, s + 1) of (jv, gv): lower half-wave takes s, upper s + 1
+    auto row_load = [&](int32_t jv, float gv, int s, float (&kk)[T2], float (&vv)[T2], float& gg) {
+        const int32_t j0 = __builtin_amdgcn_readlane(jv, s), j1 = __builtin_amdgcn_readlane(jv, s + 1);
+        const float g0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), s));
+        const float g1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), s + 1));
+        const uint32_t j = static_cast<uint32_t>(upper ? j1 : j0);
+        gg = upper ? g1 : g0;
+        if constexpr (INTERLEAVED) {
+            const uint32_t off = j * D + T2 * li;
+            if constexpr (sizeof(T) == 4 && T2 == 2) {
+                const float2 kx = *reinterpret_cast<const float2*>(Kb + off);
+                const float2 vx = *reinterpret_cast<const float2*>(Vb + off);
+                kk[0] = kx.x; kk[1] = kx.y; vv[0] = vx.x; vv[1] = vx.y;
+            } else if constexpr (sizeof(T) == 2 && T2 == 2) {
+                const uint32_t kx = *reinterpret_cast<const uint32_t*>(Kb + off);
+                const uint32_t vx = *reinterpret_cast<const uint32_t*>(Vb + off);
+                kk[0] = __uint_as_float(kx << 16); kk[1] = __uint_as_float(kx & 0xffff0000u);
+                vv[0] = __uint_as_float(vx << 16); vv[1] = __uint_as_float(vx & 0xffff0000u);
+            } else {
+                kk[0] = to_float(Kb[off]); vv[0] = to_float(Vb[off]);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < T2; ++t) {
+                kk[t] = to_float(Kb[j * D + 32 * t + li]);
+                vv[t] = to_float(Vb[j * D + 32 * t + li]);
+            }
+        }
+    };
+
+    for (int32_t block = beg; block < end; block += 2 * kWave) {
+        // entries block + lane and block + 64 + lane (clamped to the last entry, weight 0 past the end)
+        const int32_t ea = min(block + lane, end - 1), eb = min(block + kWave + lane, end - 1);
+        const int32_t j_a = csc_row[ea], j_b = csc_row[eb];
+        const float va = vals[ea], vb_ = vals[eb];
+        const float g_a = block + lane < end ? va : 0.0f;
+        const float g_b = block + kWave + lane < end ? vb_ : 0.0f;
+        const int pairs = min((end - block + 1) >> 1, kWave);      // pairs of this block
+
+        float kb[RING][T2], vb[RING][T2], gb[RING];
+#pragma unroll
+        for (int u = 0; u < RING; ++u) row_load(j_a, g_a, 2 * u, kb[u], vb[u], gb[u]);
+        for (int q0 = 0; q0 < pairs; q0 += RING) {
+            // this round fetches pairs q0 + RING .. q0 + 2 RING - 1 of the block: lanes of j_a for pairs
+            // below 32, of j_b above (past pair 63 the fetch is redundant and re-reads j_b's tail)
+            const int ahead = q0 + RING;
+            const bool second = ahead >= 32;
+            const int32_t j_sel = second ? j_b : j_a;
+            const float g_sel = second ? g_b : g_a;
+            const int lane0 = (2 * ahead) & (kWave - 1);
+#pragma unroll
+            for (int u = 0; u < RING; ++u) {
+                if (q0 + u < pairs) {
+                    float a_op[T2];
+#pragma unroll
+                    for (int t = 0; t < T2; ++t) {
+                        a_op[t] = gb[u] * feature(kb[u][t], relu);
+                        zacc[t] += a_op[t];
+                    }
+#pragma unroll
+                    for (int a = 0; a < T2; ++a)
+#pragma unroll
+                        for (int c = 0; c < T2; ++c)
+                            acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_op[a], vb[u][c], acc[a][c], 0, 0, 0);
+                }
+                row_load(j_sel, g_sel, lane0 + 2 * u, kb[u], vb[u], gb[u]);     // into the slot just vacated
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+}
 
 inline unsigned blocks_for(long long items, int per_block) { return static_cast<unsigned>((items + per_block - 1) / per_block); }
 

@@ -57,18 +57,24 @@ __device__ __forceinline__ void load_run(const T* __restrict__ p, float (&out)[N
     }
 }
 
-// One wavefront per (slice, bucket l).
+// One wavefront per (slice, bucket l), one wavefront per workgroup: column lists differ in length,
+// and a workgroup's slots are only handed on when its slowest wavefront is done.
+//
+// Every global load below is unconditional: lanes past the end of the column list re-read its last
+// entry with weight 0, so there are no branches around loads and the loads of the next stage
+// (next group of K/V rows, next tile's Q rows, the indices after that) are issued before the
+// matrix work of the current stage and waited for only afterwards.
 template <int D, typename T>
-__global__ __launch_bounds__(256) void fused_bucket_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-                                                           long long n, int H, int n_f, long long val_stride,
+__global__ __launch_bounds__(64) void fused_bucket_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+                                                           long long n, int H, int n_f,
                                                            const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
-                                                           const int32_t* __restrict__ csc_src, const float* __restrict__ phi_val,
+                                                           const float* __restrict__ csc_val,
                                                            int relu, long long bh_first, long long n_waves, int32_t nnz,
                                                            float* __restrict__ partial, float* __restrict__ pden)
 {
     constexpr int T2 = D / 32;
     constexpr int QN = 4 * T2;     // features a lane holds per group of four accumulator registers
-    const long long wave = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const long long wave = xcd_contiguous_block(blockIdx.x, gridDim.x);     // one wavefront per workgroup
     if (wave >= n_waves) return;
     const long long slice = wave / n;
     const long long l = wave - slice * n;
@@ -77,75 +83,44 @@ __global__ __launch_bounds__(256) void fused_bucket_kernel(const T* __restrict__
     const T* Qb = Q + bh * n * D;
     const T* Kb = K + bh * n * D;
     const T* Vb = V + bh * n * D;
-    const float* vals = phi_val + plane * val_stride;
+    const float* vals = csc_val + plane * nnz;
 
     const int lane = lane_id();
     const int half = lane >> 5;
     const int li = lane & 31;
 
-    // ---- S_l = A^T V_l: the two half-waves carry two contributors (the k index of the MFMA)
+    const int32_t beg = __builtin_amdgcn_readfirstlane(col_ptr[l]);
+    const int32_t end = __builtin_amdgcn_readfirstlane(col_ptr[l + 1]);
+    if (beg >= end) return;      // nobody visits node l: no partial rows belong to it
+
+    // consumers of tile `tile`: row index and weight of entry tile + li (clamped, weight 0 past the end)
+    auto fetch_index = [&](int32_t tile, int32_t& row, float& g) {
+        const int32_t pos = min(tile + li, end - 1);
+        row = csc_row[pos];
+        g = tile + li < end ? vals[pos] : 0.0f;
+    };
+    auto fetch_q = [&](long long row, float (&qq)[4][QN]) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) load_run<T, QN>(Qb + row * D + T2 * (8 * b + 4 * half), qq[b]);
+    };
+
+    // the first two consumer tiles' indices and the first tile's rows of Q go out before the first
+    // contraction starts, so that they have arrived when it ends
+    int32_t qrow_cur, qrow_next;
+    float gq_cur, gq_next;
+    fetch_index(beg, qrow_cur, gq_cur);
+    fetch_index(beg + 32, qrow_next, gq_next);
+    float qn[4][QN];
+    fetch_q(qrow_cur, qn);
+
+    // ---- S_l = A^T V_l
     floatx16 acc[T2][T2];
     float zacc[T2];
-#pragma unroll
-    for (int a = 0; a < T2; ++a) {
-        zacc[a] = 0.0f;
-#pragma unroll
-        for (int c = 0; c < T2; ++c)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
-    }
-    const int32_t beg = col_ptr[l];
-    const int32_t end = col_ptr[l + 1];
-    for (int32_t chunk = beg; chunk < end; chunk += kWave) {
-        const int32_t e = chunk + lane;
-        int32_t j_reg = -1;
-        float g_reg = 0.0f;
-        if (e < end) {
-            const int32_t row = csc_row[e];
-            const int32_t src = csc_src[e];
-            if (static_cast<uint32_t>(row) < static_cast<uint32_t>(n) && static_cast<uint32_t>(src) < static_cast<uint32_t>(nnz)) {
-                j_reg = row;
-                g_reg = vals[src];
-            }
-        }
-        const int cnt = min(kWave, end - chunk);
-        for (int p = 0; p < cnt; p += 2) {
-            const int src = p + half;
-            const long long j = __shfl(j_reg, src, kWave);
-            const float g = __shfl(g_reg, src, kWave);
-            const bool valid = src < cnt && j >= 0;
-            float kx[T2], vx[T2];
-#pragma unroll
-            for (int t = 0; t < T2; ++t) { kx[t] = 0.0f; vx[t] = 0.0f; }
-            if (valid) {
-                load_run<T, T2>(Kb + j * D + T2 * li, kx);
-                load_run<T, T2>(Vb + j * D + T2 * li, vx);
-            }
-            float a_op[T2];
-#pragma unroll
-            for (int t = 0; t < T2; ++t) {
-                a_op[t] = valid ? g * feature(kx[t], relu) : 0.0f;
-                zacc[t] += a_op[t];
-            }
-#pragma unroll
-            for (int a = 0; a < T2; ++a)
-#pragma unroll
-                for (int c = 0; c < T2; ++c)
-                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_op[a], vx[c], acc[a][c], 0, 0, 0);
-        }
-    }
+    bucket_first_contraction<D, T, true>(Kb, Vb, csc_row, vals, beg, end, relu, acc, zacc);
 
-    // ---- z_l laid out the way this lane will meet it in the second contraction
-    float zq[4][QN];
-    {
-        float zfull[T2];
+    float zfull[T2];
 #pragma unroll
-        for (int t = 0; t < T2; ++t) zfull[t] = zacc[t] + __shfl_xor(zacc[t], 32, kWave);
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int e = 0; e < QN; ++e) zq[b][e] = __shfl(zfull[e % T2], 8 * b + 4 * half + e / T2, kWave);
-    }
+    for (int t = 0; t < T2; ++t) zfull[t] = zacc[t] + __shfl_xor(zacc[t], 32, kWave);
 
     // ---- P_l = Qw S_l, 32 consumers at a time.  Accumulator register r of tile (t, c) holds
     // S[T2*(8*(r/4) + 4*half + r%4) + t][T2*li + c]: fed back unchanged as the B operand, it pairs the
@@ -153,46 +128,40 @@ __global__ __launch_bounds__(256) void fused_bucket_kernel(const T* __restrict__
     // takes the same two features of consumer li's weighted phi(q).
     const long long pbase = slice * static_cast<long long>(nnz);
     for (int32_t tile = beg; tile < end; tile += 32) {
-        const int32_t pos = tile + li;
-        long long i = -1;
-        float gq = 0.0f;
-        if (pos < end) {
-            const int32_t row = csc_row[pos];
-            const int32_t src = csc_src[pos];
-            if (static_cast<uint32_t>(row) < static_cast<uint32_t>(n) && static_cast<uint32_t>(src) < static_cast<uint32_t>(nnz)) {
-                i = row;
-                gq = vals[src];
-            }
-        }
         float qv[4][QN];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int e = 0; e < QN; ++e) qv[b][e] = 0.0f;
-            if (i >= 0) load_run<T, QN>(Qb + i * D + T2 * (8 * b + 4 * half), qv[b]);
-#pragma unroll
-            for (int e = 0; e < QN; ++e) qv[b][e] = i >= 0 ? gq * feature(qv[b][e], relu) : 0.0f;
-        }
+            for (int e2 = 0; e2 < QN; ++e2) qv[b][e2] = gq_cur * feature(qn[b][e2], relu);
+        // next tile's rows of Q, and the indices of the tile after it
+        fetch_q(qrow_next, qn);
+        gq_cur = gq_next;
+        fetch_index(tile + 64, qrow_next, gq_next);
+
+        __builtin_amdgcn_sched_barrier(0);
+
+        // 4*T2 MFMAs per accumulator register r of S; in their shadow, the two terms of the partial
+        // denominator that use the same features: weighted phi(q) against z_l, which sits in the lanes in
+        // the order of the first contraction's rows.
         floatx16 pc[T2];
 #pragma unroll
         for (int c = 0; c < T2; ++c)
 #pragma unroll
             for (int r = 0; r < 16; ++r) pc[c][r] = 0.0f;
+        float dl = 0.0f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
+        for (int r = 0; r < 16; ++r) {
 #pragma unroll
-            for (int t = 0; t < T2; ++t)
+            for (int t = 0; t < T2; ++t) {
 #pragma unroll
                 for (int c = 0; c < T2; ++c)
                     pc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(qv[r / 4][T2 * (r % 4) + t], acc[t][c][r], pc[c], 0, 0, 0);
-
-        float dl = 0.0f;
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int e = 0; e < QN; ++e) dl = fmaf(qv[b][e], zq[b][e], dl);
+                dl = fmaf(qv[r / 4][T2 * (r % 4) + t], __shfl(zfull[t], 8 * (r / 4) + 4 * half + (r % 4), kWave), dl);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
         dl += __shfl_xor(dl, 32, kWave);
-        if (half == 0 && pos < end) pden[pbase + pos] = dl;
+        if (half == 0 && tile + li < end) pden[pbase + tile + li] = dl;
 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -237,15 +206,20 @@ __global__ __launch_bounds__(256) void fused_reduce_kernel(long long n, const in
         const int32_t e = chunk + lane;
         const int32_t pos_reg = e < end ? csr_to_csc[e] : -1;
         const int cnt = min(kWave, end - chunk);
-        // the shuffle is executed by every lane (a disabled source lane would read as 0)
-#pragma unroll 8
-        for (int t0 = 0; t0 < cnt; t0 += EPW) {
-            const int t = t0 + sub;
-            const int32_t pos = __shfl(pos_reg, t & (kWave - 1), kWave);
-            if (t < cnt && pos >= 0) {
-                acc += slice_partial[static_cast<long long>(pos) * D + c];
-                dacc += slice_pden[pos];
+        // eight entries' loads are issued together; the shuffles are executed by every lane (a
+        // disabled source lane would read as 0)
+        for (int t0 = 0; t0 < cnt; t0 += 8 * EPW) {
+            float v[8], dv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int t = t0 + u * EPW + sub;
+                const int32_t pos = __shfl(pos_reg, t & (kWave - 1), kWave);
+                const bool ok = t < cnt && pos >= 0;
+                v[u] = ok ? slice_partial[static_cast<long long>(pos) * D + c] : 0.0f;
+                dv[u] = ok ? slice_pden[pos] : 0.0f;
             }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { acc += v[u]; dacc += dv[u]; }
         }
     }
     if constexpr (EPW == 2) {
@@ -269,12 +243,11 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
 {
     const long long waves = static_cast<long long>(n_slices) * n;
     if (waves == 0) return GRF_OK;
-    hipLaunchKernelGGL((fused_bucket_kernel<D, T>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream,
+    hipLaunchKernelGGL((fused_bucket_kernel<D, T>), dim3(blocks_for(waves, 1)), dim3(kWave), 0, stream,
                        static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                        static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
-                       static_cast<long long>(phi->capacity), static_cast<const int32_t*>(t.col_ptr),
-                       static_cast<const int32_t*>(t.s_row), static_cast<const int32_t*>(t.s_src),
-                       static_cast<const float*>(phi->val), relu, static_cast<long long>(bh_first), waves,
+                       static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
+                       static_cast<const float*>(t.s_val), relu, static_cast<long long>(bh_first), waves,
                        static_cast<int32_t>(nnz), partial, pden);
     GRF_LAUNCH_CHECK("fused_bucket_kernel");
     hipLaunchKernelGGL((fused_reduce_kernel<D>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream,
@@ -294,12 +267,12 @@ size_t pden_bytes(int64_t slices, int64_t nnz) { return align_up(sizeof(float) *
 
 using namespace grf;
 
-extern "C" size_t grf_fused_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t bh_chunk)
+extern "C" size_t grf_fused_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t n_f, int32_t bh_chunk)
 {
-    if (B < 0 || H < 0 || n < 0 || nnz < 0 || (d != 32 && d != 64)) return 0;
+    if (B < 0 || H < 0 || n < 0 || nnz < 0 || n_f < 1 || (d != 32 && d != 64)) return 0;
     int64_t slices = B * H;
     if (bh_chunk > 0 && bh_chunk < slices) slices = bh_chunk;
-    return carve_transposed(nullptr, n, nnz).bytes + partial_bytes(slices, nnz, d) + pden_bytes(slices, nnz);
+    return carve_transposed(nullptr, n, nnz, n_f).bytes + partial_bytes(slices, nnz, d) + pden_bytes(slices, nnz);
 }
 
 extern "C" grf_status grf_masked_linear_attention_fused(const void* Q, const void* K, const void* V, int32_t dtype,
@@ -311,16 +284,16 @@ extern "C" grf_status grf_masked_linear_attention_fused(const void* Q, const voi
 {
     if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
     if (B * H * n > 0 && (Q == nullptr || out == nullptr)) return fail(GRF_EINVAL, "Q / out is NULL");
-    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_fused_attention_workspace_bytes(B, H, n, d, nnz, bh_chunk))) return st;
+    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_fused_attention_workspace_bytes(B, H, n, d, nnz, n_f, bh_chunk))) return st;
     if (B * H * n == 0) return GRF_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int64_t slices = B * H;
     const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;
     unsigned char* ws = static_cast<unsigned char*>(workspace);
-    const Transposed t = carve_transposed(ws, n, nnz);
+    const Transposed t = carve_transposed(ws, n, nnz, n_f);
     float* partial = reinterpret_cast<float*>(ws + t.bytes);
     float* pden = reinterpret_cast<float*>(ws + t.bytes + partial_bytes(step, nnz, d));
-    if (grf_status st = transpose(phi, nnz, t, stream)) return st;
+    if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
     const int relu = feature_map == GRF_PHI_RELU ? 1 : 0;
     for (int64_t first = 0; first < slices; first += step) {
         const int64_t count = (slices - first < step) ? (slices - first) : step;

@@ -55,14 +55,15 @@ def test_size_queries(binding):
     assert ws >= 2 * 10 * 4 + 8 and ws % 256 == 0
     assert L.grf_sample_workspace_bytes(1000, 0, 10, 2) == 0
     n, nnz, d = 32768, 2_440_000, 64
-    all_heads = L.grf_attention_workspace_bytes(1, 8, n, d, nnz, 0)
-    one_head = L.grf_attention_workspace_bytes(1, 8, n, d, nnz, 1)
+    all_heads = L.grf_attention_workspace_bytes(1, 8, n, d, nnz, 1, 0)
+    one_head = L.grf_attention_workspace_bytes(1, 8, n, d, nnz, 1, 1)
     per_head = n * (d * d + d) * 4
     assert all_heads % 256 == 0 and one_head % 256 == 0
     assert all_heads - one_head == 7 * per_head
-    assert one_head - per_head == L.grf_buckets_workspace_bytes(n, nnz)
-    assert one_head - per_head >= (2 * n + 4 * nnz) * 4
-    assert L.grf_attention_workspace_bytes(1, 8, n, 48, nnz, 0) == 0
+    assert one_head - per_head == L.grf_buckets_workspace_bytes(n, nnz, 1)
+    assert one_head - per_head >= (2 * n + 6 * nnz) * 4
+    assert L.grf_buckets_workspace_bytes(n, nnz, 8) - L.grf_buckets_workspace_bytes(n, nnz, 1) >= 7 * nnz * 4
+    assert L.grf_attention_workspace_bytes(1, 8, n, 48, nnz, 1, 0) == 0
 
 
 def test_argument_validation_precedes_device_work(binding):
