@@ -189,6 +189,20 @@ grf_status grf_masked_linear_attention_fused(const void* Q, const void* K, const
                                              void* workspace, size_t workspace_bytes, void* hip_stream,
                                              float* out, float* num_opt, float* den_opt);
 
+/* ---------------------------------------------------------------------------------------------
+ * Asymmetric graph random features (App. D, Alg. 2): the keys use the one-hot feature (f^(2) = delta_0,
+ * Phi^(2) = I), so the mask estimate is the sampled matrix itself.  phi must have been sampled with
+ * f = alpha (the mask's own Taylor coefficients), and
+ *     num_i = sum_j Phi_hat[i,j] (phi(q_i) . phi(k_j)) v_j,    den_i = sum_j Phi_hat[i,j] (phi(q_i) . phi(k_j)),
+ *     out_i = num_i / den_i
+ * (the appendix's per-walk accumulation, with a row's deposits already summed per end node; the
+ * factor n in its printed normalisation has no counterpart in the accumulations and is not applied).
+ * Arguments, layouts, n_f and error behaviour as for grf_masked_linear_attention; needs no workspace. */
+grf_status grf_asymmetric_masked_attention(const void* Q, const void* K, const void* V, int32_t dtype,
+                                           int64_t B, int64_t H, int64_t n, int32_t d,
+                                           const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                           void* hip_stream, float* out, float* num_opt, float* den_opt);
+
 #ifdef __cplusplus
 }
 #endif

@@ -272,3 +272,42 @@ void grf_ref_row_direct(int64_t n, int32_t d, int64_t i, const float* Q, const f
     *den_i = di;
     free(dense_i);
 }
+
+/* ------------------------------------------------------------------ App. D, Alg. 2: asymmetric GRFs
+ * Keys use the one-hot feature (f^(2) = delta_0, Phi^(2) = I), queries the walks with modulation
+ * f^(1) = f (so f plays the role of alpha).  Following the algorithm's own loop structure, for every
+ * node i, every walk out of i and every visited (t, v_j):
+ *     w = phi(q_i)^T phi(k_j) * f_t * weight(prefix of t hops)
+ *     F_i += w * v_j,     S_i += w
+ * One (batch, head) slice.  num_i = F_i / n_walks and den_i = S_i / n_walks are returned (the 1/n of
+ * the GRF definition on both; it cancels in the output F_i / S_i -- the extra factor n that the
+ * printed normalisation line carries has no counterpart in the accumulations and is not applied).
+ */
+void grf_ref_asymmetric_walks(int64_t n, const int32_t* row_ptr, const int32_t* col, const float* w,
+                              const float* f, int32_t f_len, double p_halt, int32_t n_walks, uint64_t seed,
+                              int32_t d, const float* Q, const float* K, const float* V, int32_t feature_map,
+                              double* num, double* den)
+{
+    int32_t* nodes = (int32_t*)malloc(sizeof(int32_t) * (size_t)f_len);
+    double* loads = (double*)malloc(sizeof(double) * (size_t)f_len);
+    for (int64_t i = 0; i < n; ++i) {
+        double* Fi = num + (size_t)i * d;
+        for (int32_t b = 0; b < d; ++b) Fi[b] = 0.0;
+        double Si = 0.0;
+        for (int32_t k = 0; k < n_walks; ++k) {
+            const int len = one_walk(row_ptr, col, w, i, k, f_len, p_halt, seed, nodes, loads);
+            for (int t = 0; t < len; ++t) {
+                const int64_t j = nodes[t];
+                double a = 0.0;
+                for (int32_t c = 0; c < d; ++c)
+                    a += feature(Q[i * d + c], feature_map) * feature(K[j * d + c], feature_map);
+                const double wgt = a * (double)f[t] * loads[t];
+                Si += wgt;
+                for (int32_t b = 0; b < d; ++b) Fi[b] += wgt * (double)V[j * d + b];
+            }
+        }
+        for (int32_t b = 0; b < d; ++b) Fi[b] /= (double)n_walks;
+        den[i] = Si / (double)n_walks;
+    }
+    free(nodes); free(loads);
+}

@@ -209,6 +209,34 @@ def masked_linear_attention(Q, K, V, row_ptr, col, val, feature_map: int = RELU,
     return res
 
 
+def asymmetric_attention_walks(g, f, p_halt: float, n_walks: int, seed: int, Q, K, V, feature_map: int = RELU):
+    """App. D, Alg. 2 walk by walk, for Q,K,V of shape [B,H,n,d] and one modulation vector f (= alpha).
+
+    Returns dict with fp64 ``num`` [B,H,n,d], ``den`` [B,H,n] and ``out`` = num/den.
+    """
+    Q, K, V = (np.ascontiguousarray(x, dtype=np.float32) for x in (Q, K, V))
+    B, H, n, d = Q.shape
+    f = _f32(np.asarray(f).reshape(-1))
+    rp, col, w = _i32(g.row_ptr), _i32(g.col), _f32(g.w)
+    num = np.empty((B, H, n, d), dtype=np.float64)
+    den = np.empty((B, H, n), dtype=np.float64)
+    lib = _load()
+    for b in range(B):
+        for h in range(H):
+            nb = np.empty((n, d), dtype=np.float64)
+            db = np.empty(n, dtype=np.float64)
+            lib.grf_ref_asymmetric_walks(
+                ctypes.c_int64(n), _p(rp, ctypes.c_int32), _p(col, ctypes.c_int32), _p(w, ctypes.c_float),
+                _p(f, ctypes.c_float), ctypes.c_int32(f.shape[0]), ctypes.c_double(p_halt), ctypes.c_int32(n_walks),
+                ctypes.c_uint64(seed), ctypes.c_int32(d),
+                _p(Q[b, h], ctypes.c_float), _p(K[b, h], ctypes.c_float), _p(V[b, h], ctypes.c_float),
+                ctypes.c_int32(feature_map), _p(nb, ctypes.c_double), _p(db, ctypes.c_double))
+            num[b, h], den[b, h] = nb, db
+    with np.errstate(divide="ignore", invalid="ignore"):
+        out = num / den[..., None]
+    return {"num": num, "den": den, "out": out}
+
+
 def row_direct(i: int, Q, K, V, row_ptr, col, val, feature_map: int = RELU):
     """(num_i [d], den_i, mask_row [n]) for one query row of one (b,h) slice, from Eq. (2) directly."""
     Q, K, V = _f32(Q), _f32(K), _f32(V)

@@ -88,6 +88,9 @@ def lib() -> ctypes.CDLL:
         L.grf_fused_attention_workspace_bytes.argtypes = L.grf_attention_workspace_bytes.argtypes
         L.grf_masked_linear_attention_fused.restype = ctypes.c_int32
         L.grf_masked_linear_attention_fused.argtypes = L.grf_masked_linear_attention.argtypes
+        L.grf_asymmetric_masked_attention.restype = ctypes.c_int32
+        L.grf_asymmetric_masked_attention.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, *common,
+                                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -340,4 +343,21 @@ def _attention_call(entry: str, ws_query: str, Q, K, V, phi, feature_map, bh_chu
                              phi.nnz, phi.n_f, _FEATURE_MAPS[feature_map], int(bh_chunk),
                              _ptr(workspace), workspace.numel(), _stream_ptr(stream),
                              _ptr(out), _ptr(num), _ptr(den)))
+    return (out, num, den) if return_num_den else out
+
+
+def grf_asymmetric_masked_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, phi: Phi, feature_map: str = "relu",
+                                    return_num_den: bool = False, out: Optional[torch.Tensor] = None, stream=None):
+    """Asymmetric-GRF masked attention (mask estimate = phi itself, sampled with f = alpha)."""
+    _require_gpu()
+    L = lib()
+    B, H, n, d = _check_qkv(Q, K, V)
+    if out is None:
+        out = torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device)
+    num = torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device) if return_num_den else None
+    den = torch.empty((B, H, n), dtype=torch.float32, device=Q.device) if return_num_den else None
+    ps = phi._struct()
+    _check(L.grf_asymmetric_masked_attention(_ptr(Q), _ptr(K), _ptr(V), _dtype_code(Q), B, H, n, d, ctypes.byref(ps),
+                                             phi.nnz, phi.n_f, _FEATURE_MAPS[feature_map], _stream_ptr(stream),
+                                             _ptr(out), _ptr(num), _ptr(den)))
     return (out, num, den) if return_num_den else out

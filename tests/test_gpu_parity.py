@@ -455,3 +455,67 @@ def test_fused_headline_workload_full_size(grf, oracle):
     assert relerr(den_h, den2.cpu().numpy()) <= TOL_F32
     del out, num, den, out2, num2, den2
     torch.cuda.empty_cache()
+
+
+# --------------------------------------------------------------------------- asymmetric GRFs (App. D, Alg. 2)
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_asymmetric_attention_parity(grf, oracle, name):
+    """GPU: grf_sample with f = alpha, then the CSR kernel.  Checker: Alg. 2 walk by walk."""
+    wl = SMALL[name]
+    tol = TOL_BF16 if wl.dtype == "bf16" else TOL_F32
+    g = grf.DeviceGraph.from_host(wl.graph)
+    alpha = wl.f[:1]
+    phi = grf.grf_sample(g, alpha, wl.p_halt, wl.n_walks, wl.walk_seed)
+    Q, K, V = wl.qkv()
+    Qd, Kd, Vd = (to_dev(x, wl.dtype) for x in (Q, K, V))
+    out, num, den = grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi, return_num_den=True)
+    ref = oracle.asymmetric_attention_walks(wl.graph, alpha[0], wl.p_halt, wl.n_walks, wl.walk_seed, Q, K, V)
+    out, num, den = out.cpu().numpy(), num.cpu().numpy(), den.cpu().numpy()
+    assert relerr(num, ref["num"]) <= tol
+    assert relerr(den, ref["den"]) <= tol
+    with np.errstate(divide="ignore", invalid="ignore"):
+        assert np.array_equal(np.nan_to_num(out, nan=7.0, posinf=8.0, neginf=9.0),
+                              np.nan_to_num(num / den[..., None], nan=7.0, posinf=8.0, neginf=9.0))
+    out2 = grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi).cpu().numpy()
+    assert np.array_equal(np.nan_to_num(out), np.nan_to_num(out2))
+
+
+def test_asymmetric_per_head_planes_and_identity(grf, oracle):
+    wl = SMALL["cloud_2k_perhead_bf16"]
+    g = grf.DeviceGraph.from_host(wl.graph)
+    phi = grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)        # three planes, H = 3
+    Q, K, V = wl.qkv()
+    Qd, Kd, Vd = (to_dev(x, wl.dtype) for x in (Q, K, V))
+    _, num, den = grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi, return_num_den=True)
+    for h in range(3):
+        ref = oracle.asymmetric_attention_walks(wl.graph, wl.f[h], wl.p_halt, wl.n_walks, wl.walk_seed,
+                                                Q[:, h:h + 1], K[:, h:h + 1], V[:, h:h + 1])
+        assert relerr(num[:, h].cpu().numpy(), ref["num"][:, 0]) <= TOL_BF16
+        assert relerr(den[:, h].cpu().numpy(), ref["den"][:, 0]) <= TOL_BF16
+    n = wl.graph.n
+    ident = grf.Phi.from_host(n, np.arange(n + 1), np.arange(n), np.ones((1, n), np.float32))
+    out, _, den = grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, ident, return_num_den=True)
+    ok = den.cpu().numpy() != 0
+    assert relerr(out.cpu().numpy()[ok], V[ok]) <= TOL_BF16
+
+
+def test_asymmetric_headline_workload_full_size(grf, oracle):
+    """cloud_32k: sampled rows against Eq. (2) with the mask row taken from Phi_hat itself."""
+    wl = synth.workload("cloud_32k")
+    g = grf.DeviceGraph.from_host(wl.graph)
+    phi = grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+    rp, col, val = _oracle_phi(oracle, wl)
+    Q, K, V = wl.qkv()
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    _, num, den = grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi, return_num_den=True)
+    num, den = num.cpu().numpy(), den.cpu().numpy()
+    rows = np.random.default_rng(3).choice(wl.graph.n, size=40, replace=False)
+    for h in (0, 5):
+        fq = np.maximum(Q[0, h].astype(np.float64), 0); fk = np.maximum(K[0, h].astype(np.float64), 0)
+        ns, ds = np.abs(num[0, h]).max(), np.abs(den[0, h]).max()
+        for i in rows:
+            js = col[rp[i]:rp[i + 1]]; w = val[0, rp[i]:rp[i + 1]].astype(np.float64)
+            a = w * (fk[js] @ fq[i])
+            assert np.abs(num[0, h, i] - a @ V[0, h][js].astype(np.float64)).max() <= TOL_F32 * ns
+            assert abs(den[0, h, i] - a.sum()) <= TOL_F32 * ds

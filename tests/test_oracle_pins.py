@@ -445,3 +445,43 @@ def test_bf16_rounding_helper():
     assert back[0] == 1.0 and back[1] == 1.0 and back[2] == 1.015625 and back[3] == -2.5
     assert abs(back[4] - 3.1415927) < 2 ** -7 * 2
     assert np.array_equal(synth.f32_to_bf16_bits(back), bits)
+
+
+# --------------------------------------------------------------------------- asymmetric GRFs (App. D)
+
+def test_asymmetric_walk_algorithm_equals_masking_with_phi(oracle):
+    """Alg. 2 accumulated walk by walk equals (A .* Phi_hat) V with the dense GRF matrix as the mask
+    (the sparse-computation identity of App. D), because Phi^(2) = I."""
+    rng = np.random.default_rng(11)
+    g = synth.grid_graph(7, 9, 8)
+    alpha = synth.modulation(6, rng, "decay")
+    Q, K, V = synth.qkv(2, 2, g.n, 8, rng)
+    got = oracle.asymmetric_attention_walks(g, alpha[0], 0.35, 6, 3, Q, K, V)
+    rp, col, val = oracle.sample(g, alpha, 0.35, 6, seed=3)
+    M = oracle.phi_dense(g.n, rp, col, val[0])
+    assert not np.allclose(M, M.T)                    # the asymmetric mask estimate is not symmetric
+    for b in range(2):
+        for h in range(2):
+            num, den, _ = oracle.attention_bruteforce(Q[b, h], K[b, h], V[b, h], M)
+            assert np.allclose(got["num"][b, h], num, rtol=1e-6, atol=1e-7)
+            assert np.allclose(got["den"][b, h], den, rtol=1e-6, atol=1e-7)
+
+
+def test_asymmetric_special_cases(oracle):
+    rng = np.random.default_rng(12)
+    g = synth.random_graph(60, 4.0, rng, weights="inv_deg")
+    Q, K, V = synth.qkv(1, 1, g.n, 8, rng)
+    # alpha = delta_0: the mask is the identity, out_i = v_i wherever phi(q_i).phi(k_i) != 0
+    res = oracle.asymmetric_attention_walks(g, np.array([1.0, 0, 0, 0], np.float32), 0.3, 5, 1, Q, K, V)
+    ok = res["den"][0, 0] != 0
+    assert ok.sum() > 40
+    assert np.allclose(res["out"][0, 0][ok], V[0, 0][ok].astype(np.float64), rtol=1e-12)
+    # deterministic walks on a perfect matching with p = 0: mask = sum_t alpha_t W^t exactly
+    m = synth.matching_graph(12, rng)
+    alpha = np.array([0.8, -0.5, 0.3], dtype=np.float32)
+    Q, K, V = synth.qkv(1, 1, m.n, 8, rng)
+    res = oracle.asymmetric_attention_walks(m, alpha, 0.0, 3, 0, Q, K, V)
+    M = oracle.exact_features(m.dense(), alpha)
+    num, den, _ = oracle.attention_bruteforce(Q[0, 0], K[0, 0], V[0, 0], M)
+    assert np.allclose(res["num"][0, 0], num, rtol=1e-6, atol=1e-8)
+    assert np.allclose(res["den"][0, 0], den, rtol=1e-6, atol=1e-8)
