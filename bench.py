@@ -153,6 +153,31 @@ def main() -> int:
                      "note": "whole attention call (column lists + fused buckets + row reduce); per-kernel times in profiles/"},
     }
 
+    # asymmetric GRFs (App. D): the same sampled matrix used directly as the mask estimate
+    aout = torch.empty_like(out)
+    for _ in range(args.warmup):
+        grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi, out=aout)
+    torch.cuda.synchronize()
+    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a0.record(stream)
+    for _ in range(args.steps):
+        grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi, out=aout)
+    a1.record(stream)
+    torch.cuda.synchronize()
+    asym_ms = a0.elapsed_time(a1) / args.steps
+    elem = 2 if wl.dtype == "bf16" else 4
+    asym_bytes = B * H * (nnz * (2 * d * elem + 8) + N * d * (elem + 4))     # k_j, v_j, (col, val) per entry; q_i in, out_i out
+    asymmetric = {
+        "entry_point": "grf_asymmetric_masked_attention",
+        "attention_ms": round(asym_ms, 4),
+        "attention_only_tokens_per_s_per_head": round(tokens / (asym_ms * 1e-3), 1),
+        "roofline": {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
+                     "achieved": round(asym_bytes / (asym_ms * 1e-3) / 1e9, 1),
+                     "frac": round(asym_bytes / (asym_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "algorithmic_bytes_per_launch": asym_bytes,
+                     "note": "K and V of one head (16.8 MB) are re-read from L2 / Infinity Cache, so the algorithmic rate may exceed the HBM peak"},
+    }
+
     result = {
         "metric": "GRF-masked linear attention tokens/s/head at N=%d" % N,
         "value": round(value, 1), "unit": "tokens/s/head",
@@ -166,6 +191,7 @@ def main() -> int:
         "attention_only_tokens_per_s_per_head": round(tokens / ((buckets_ms + gather_ms) * 1e-3), 1),
         "roofline": roofline,
         "fused_variant": fused,
+        "asymmetric_variant": asymmetric,
     }
 
     if not args.no_cpu_baseline:
