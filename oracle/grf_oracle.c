@@ -182,9 +182,21 @@ int64_t grf_ref_sample(int64_t n, const int32_t* row_ptr, const int32_t* col, co
 /* ------------------------------------------------------------------ feature map */
 static inline double feature(float x, int32_t feature_map)
 {
-    /* 0: ReLU (the map used in the paper's experiments), 1: identity (tests only) */
+    /* 0: ReLU (the map used in the paper's experiments); 1: identity (tests only);
+     * 2: elu(x) + 1, the deterministic map of the linear transformer that Sec. 2 and Alg. 1
+     *    step 3 name as an alternative (the paper prints it as "elu(x)+x"; the cited work's
+     *    map is elu(x)+1 = x+1 for x > 0 and exp(x) otherwise, which is what keeps it positive). */
     if (feature_map == 0) return x > 0.0f ? (double)x : 0.0;
+    if (feature_map == 2) return x > 0.0f ? (double)x + 1.0 : exp((double)x);
     return (double)x;
+}
+
+/* d phi(x) / dx for the same maps (ReLU: 0 at x = 0). */
+static inline double feature_grad(float x, int32_t feature_map)
+{
+    if (feature_map == 0) return x > 0.0f ? 1.0 : 0.0;
+    if (feature_map == 2) return x > 0.0f ? 1.0 : exp((double)x);
+    return 1.0;
 }
 
 /* ------------------------------------------------------------------ Alg. 1, step 5, first product
@@ -310,4 +322,187 @@ void grf_ref_asymmetric_walks(int64_t n, const int32_t* row_ptr, const int32_t* 
         den[i] = Si / (double)n_walks;
     }
     free(nodes); free(loads);
+}
+
+/* ------------------------------------------------------------------ gradients of Eq. 7 (training; Alg. 1 has learnable f)
+ * One (batch, head) slice.  The forward pass is
+ *     num_i = sum_l Phi_il phi(q_i)^T S_l,   den_i = sum_l Phi_il phi(q_i)^T z_l,   out_i = num_i / den_i,
+ *     S_l = sum_j Phi_jl phi(k_j) v_j^T,     z_l = sum_j Phi_jl phi(k_j).
+ * With v'_j = [v_j, 1] (length d+1) both products are one: num'_i = [num_i, den_i] = sum_l Phi_il phi(q_i)^T S'_l,
+ * S'_l = sum_j Phi_jl phi(k_j) v'_j^T.  Given dout = dL/dout, the chain rule through the division gives
+ *     g'_i = dL/dnum'_i = [ dout_i / den_i ,  -(dout_i . out_i) / den_i ],
+ * and L depends on the inputs through  sum_{i,l,j} Phi_il Phi_jl (phi(q_i) . phi(k_j)) (v'_j . g'_i).  Hence, with
+ *     T'_l = sum_i Phi_il phi(q_i) g'_i^T   (d x (d+1), the query-side counterpart of S'_l),
+ *     dL/dphi(q_i) = sum_l Phi_il S'_l g'_i
+ *     dL/dphi(k_j) = sum_l Phi_jl T'_l v'_j
+ *     dL/dv_j      = sum_l Phi_jl T_l^T phi(k_j)            (T_l = first d columns of T'_l)
+ *     dL/dPhi_il   = phi(q_i)^T S'_l g'_i + phi(k_i)^T T'_l v'_i     (entry (i,l) acts once as a query-side
+ *                                                                      and once as a key-side factor)
+ * and dL/dq = dL/dphi(q) * phi'(q) elementwise, likewise for k.
+ *
+ * out [n][d] and den [n] are the forward results the caller saved (fp64 here).  dphi has one value per stored
+ * entry of Phi_hat, in CSR order.  Everything fp64.
+ */
+void grf_ref_attention_backward(int64_t n, int32_t d, const float* Q, const float* K, const float* V,
+                                const int32_t* phi_row_ptr, const int32_t* phi_col, const float* phi_val,
+                                int32_t feature_map, const double* out, const double* den, const double* dout,
+                                double* dQ, double* dK, double* dV, double* dphi)
+{
+    const int32_t e1 = d + 1;
+    double* Sp = (double*)calloc((size_t)n * d * e1, sizeof(double));
+    double* Tp = (double*)calloc((size_t)n * d * e1, sizeof(double));
+    double* gp = (double*)malloc(sizeof(double) * (size_t)n * e1);
+    double* fq = (double*)malloc(sizeof(double) * (size_t)n * d);
+    double* fk = (double*)malloc(sizeof(double) * (size_t)n * d);
+    for (int64_t i = 0; i < n; ++i) {
+        double dot = 0.0;
+        for (int32_t c = 0; c < d; ++c) {
+            gp[i * e1 + c] = dout[i * d + c] / den[i];
+            dot += dout[i * d + c] * out[i * d + c];
+            fq[i * d + c] = feature(Q[i * d + c], feature_map);
+            fk[i * d + c] = feature(K[i * d + c], feature_map);
+        }
+        gp[i * e1 + d] = -dot / den[i];
+    }
+    /* key-side buckets S'_l and query-side buckets T'_l */
+    for (int64_t j = 0; j < n; ++j)
+        for (int64_t e = phi_row_ptr[j]; e < phi_row_ptr[j + 1]; ++e) {
+            const int64_t l = phi_col[e];
+            const double g = (double)phi_val[e];
+            double* Sl = Sp + (size_t)l * d * e1;
+            double* Tl = Tp + (size_t)l * d * e1;
+            for (int32_t a = 0; a < d; ++a) {
+                const double ka = g * fk[j * d + a], qa = g * fq[j * d + a];
+                for (int32_t c = 0; c < d; ++c) Sl[a * e1 + c] += ka * (double)V[j * d + c];
+                Sl[a * e1 + d] += ka;
+                for (int32_t c = 0; c < e1; ++c) Tl[a * e1 + c] += qa * gp[j * e1 + c];
+            }
+        }
+    memset(dV, 0, sizeof(double) * (size_t)n * d);
+    for (int64_t i = 0; i < n; ++i) {
+        double* dfq = dQ + (size_t)i * d;
+        double* dfk = dK + (size_t)i * d;
+        for (int32_t a = 0; a < d; ++a) { dfq[a] = 0.0; dfk[a] = 0.0; }
+        for (int64_t e = phi_row_ptr[i]; e < phi_row_ptr[i + 1]; ++e) {
+            const int64_t l = phi_col[e];
+            const double g = (double)phi_val[e];
+            const double* Sl = Sp + (size_t)l * d * e1;
+            const double* Tl = Tp + (size_t)l * d * e1;
+            double de = 0.0;
+            for (int32_t a = 0; a < d; ++a) {
+                double u = 0.0, r = 0.0;
+                for (int32_t c = 0; c < e1; ++c) u += Sl[a * e1 + c] * gp[i * e1 + c];
+                for (int32_t c = 0; c < d; ++c) r += Tl[a * e1 + c] * (double)V[i * d + c];
+                r += Tl[a * e1 + d];
+                dfq[a] += g * u;
+                dfk[a] += g * r;
+                de += fq[i * d + a] * u + fk[i * d + a] * r;
+                for (int32_t c = 0; c < d; ++c) dV[i * d + c] += g * Tl[a * e1 + c] * fk[i * d + a];
+            }
+            dphi[e] = de;
+        }
+        for (int32_t a = 0; a < d; ++a) {
+            dfq[a] *= feature_grad(Q[i * d + a], feature_map);
+            dfk[a] *= feature_grad(K[i * d + a], feature_map);
+        }
+    }
+    free(Sp); free(Tp); free(gp); free(fq); free(fk);
+}
+
+/* ------------------------------------------------------------------ gradient with respect to the modulation f
+ * Eq. (GRF definition): Phi_iq = (1/n) sum_k sum_t [omega_k(t) = q] load_{k,t} f_t  is linear in f, so
+ *     dL/df_t = (1/n) sum_i sum_k load_{k,t} * (dL/dPhi)[i, omega_k(t)]
+ * over the same walks (same seed).  dphi is [n_f][nnz] in the CSR order of the pattern (phi_row_ptr, phi_col),
+ * df is [n_f][f_len]; fp64.
+ */
+void grf_ref_sample_backward(int64_t n, const int32_t* row_ptr, const int32_t* col, const float* w,
+                             int32_t f_len, int32_t n_f, double p_halt, int32_t n_walks, uint64_t seed,
+                             const int32_t* phi_row_ptr, const int32_t* phi_col, int64_t nnz,
+                             const double* dphi, double* df)
+{
+    int32_t* nodes = (int32_t*)malloc(sizeof(int32_t) * (size_t)f_len);
+    double* loads = (double*)malloc(sizeof(double) * (size_t)f_len);
+    for (int64_t x = 0; x < (int64_t)n_f * f_len; ++x) df[x] = 0.0;
+    for (int64_t i = 0; i < n; ++i)
+        for (int32_t k = 0; k < n_walks; ++k) {
+            const int len = one_walk(row_ptr, col, w, i, k, f_len, p_halt, seed, nodes, loads);
+            for (int t = 0; t < len; ++t) {
+                int64_t e = phi_row_ptr[i];
+                while (e < phi_row_ptr[i + 1] && phi_col[e] != nodes[t]) ++e;
+                if (e == phi_row_ptr[i + 1]) continue;      /* cannot happen for a pattern sampled with the same arguments */
+                for (int32_t h = 0; h < n_f; ++h)
+                    df[(size_t)h * f_len + t] += loads[t] * dphi[(size_t)h * (size_t)nnz + (size_t)e] / (double)n_walks;
+            }
+        }
+    free(nodes); free(loads);
+}
+
+/* ------------------------------------------------------------------ gradients of single rows from Eq. (2) directly
+ * For node i, with M_hat_ij = sum_l Phi_il Phi_jl (symmetric) and g' as above (gp is [n][d+1], precomputed):
+ *     dL/dphi(q_i) = sum_j M_hat_ij (v'_j . g'_i) phi(k_j)
+ *     dL/dphi(k_i) = sum_j M_hat_ij (v'_i . g'_j) phi(q_j)
+ *     dL/dv_i      = sum_j M_hat_ij (phi(q_j) . phi(k_i)) g_j
+ * O(N r) per row; used to spot-check rows at sizes where the bucket arrays are too large.
+ */
+void grf_ref_row_direct_backward(int64_t n, int32_t d, int64_t i, const float* Q, const float* K, const float* V,
+                                 const int32_t* phi_row_ptr, const int32_t* phi_col, const float* phi_val,
+                                 int32_t feature_map, const double* gp, double* dq_i, double* dk_i, double* dv_i)
+{
+    const int32_t e1 = d + 1;
+    double* dense_i = (double*)calloc((size_t)n, sizeof(double));
+    for (int64_t e = phi_row_ptr[i]; e < phi_row_ptr[i + 1]; ++e) dense_i[phi_col[e]] = (double)phi_val[e];
+    for (int32_t a = 0; a < d; ++a) { dq_i[a] = 0.0; dk_i[a] = 0.0; dv_i[a] = 0.0; }
+    for (int64_t j = 0; j < n; ++j) {
+        double mij = 0.0;
+        for (int64_t e = phi_row_ptr[j]; e < phi_row_ptr[j + 1]; ++e)
+            mij += dense_i[phi_col[e]] * (double)phi_val[e];
+        if (mij == 0.0) continue;
+        double vj_gi = gp[i * e1 + d], vi_gj = gp[j * e1 + d], qj_ki = 0.0;
+        for (int32_t c = 0; c < d; ++c) {
+            vj_gi += (double)V[j * d + c] * gp[i * e1 + c];
+            vi_gj += (double)V[i * d + c] * gp[j * e1 + c];
+            qj_ki += feature(Q[j * d + c], feature_map) * feature(K[i * d + c], feature_map);
+        }
+        for (int32_t a = 0; a < d; ++a) {
+            dq_i[a] += mij * vj_gi * feature(K[j * d + a], feature_map);
+            dk_i[a] += mij * vi_gj * feature(Q[j * d + a], feature_map);
+            dv_i[a] += mij * qj_ki * gp[j * e1 + a];
+        }
+    }
+    for (int32_t a = 0; a < d; ++a) {
+        dq_i[a] *= feature_grad(Q[i * d + a], feature_map);
+        dk_i[a] *= feature_grad(K[i * d + a], feature_map);
+    }
+    free(dense_i);
+}
+
+/* dL/dPhi for the single stored entry e = (i, l) from the formula above, with S'_l and T'_l formed by a scan
+ * over all entries of column l. */
+double grf_ref_dphi_entry_direct(int64_t n, int32_t d, int64_t i, int64_t l, const float* Q, const float* K, const float* V,
+                                 const int32_t* phi_row_ptr, const int32_t* phi_col, const float* phi_val,
+                                 int32_t feature_map, const double* gp)
+{
+    const int32_t e1 = d + 1;
+    double* Sl = (double*)calloc((size_t)d * e1, sizeof(double));
+    double* Tl = (double*)calloc((size_t)d * e1, sizeof(double));
+    for (int64_t j = 0; j < n; ++j)
+        for (int64_t e = phi_row_ptr[j]; e < phi_row_ptr[j + 1]; ++e) {
+            if (phi_col[e] != l) continue;
+            const double g = (double)phi_val[e];
+            for (int32_t a = 0; a < d; ++a) {
+                const double ka = g * feature(K[j * d + a], feature_map), qa = g * feature(Q[j * d + a], feature_map);
+                for (int32_t c = 0; c < d; ++c) Sl[a * e1 + c] += ka * (double)V[j * d + c];
+                Sl[a * e1 + d] += ka;
+                for (int32_t c = 0; c < e1; ++c) Tl[a * e1 + c] += qa * gp[j * e1 + c];
+            }
+        }
+    double de = 0.0;
+    for (int32_t a = 0; a < d; ++a) {
+        double u = 0.0, r = Tl[a * e1 + d];
+        for (int32_t c = 0; c < e1; ++c) u += Sl[a * e1 + c] * gp[i * e1 + c];
+        for (int32_t c = 0; c < d; ++c) r += Tl[a * e1 + c] * (double)V[i * d + c];
+        de += feature(Q[i * d + a], feature_map) * u + feature(K[i * d + a], feature_map) * r;
+    }
+    free(Sl); free(Tl);
+    return de;
 }

@@ -20,7 +20,7 @@ _SRC = os.path.join(_HERE, "grf_oracle.c")
 _LIB_PATH = os.path.join(_HERE, "libgrf_oracle.so")
 _lib = None
 
-RELU, IDENTITY = 0, 1
+RELU, IDENTITY, ELU1 = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
@@ -36,6 +36,7 @@ def _load():
         build()
         _lib = ctypes.CDLL(_LIB_PATH)
         _lib.grf_ref_sample.restype = ctypes.c_int64
+        _lib.grf_ref_dphi_entry_direct.restype = ctypes.c_double
     return _lib
 
 
@@ -135,7 +136,11 @@ def exact_mask(W: np.ndarray, f: np.ndarray) -> np.ndarray:
 
 def _feature(x: np.ndarray, feature_map: int) -> np.ndarray:
     x = x.astype(np.float64)
-    return np.maximum(x, 0.0) if feature_map == RELU else x
+    if feature_map == RELU:
+        return np.maximum(x, 0.0)
+    if feature_map == ELU1:          # elu(x) + 1
+        return np.where(x > 0.0, x + 1.0, np.exp(np.minimum(x, 0.0)))
+    return x
 
 
 def attention_bruteforce(Q, K, V, M, feature_map: int = RELU):
@@ -264,3 +269,97 @@ def conditioning_floor(Q, row_ptr, col, val, z, feature_map: int = RELU) -> np.n
     rows = np.repeat(np.arange(n), np.diff(row_ptr))
     dots = np.abs(np.einsum("ea,ea->e", fq[rows], z[col]))
     return np.bincount(rows, weights=np.abs(val.astype(np.float64)) * dots, minlength=n)
+
+
+# --------------------------------------------------------------------------- gradients (training with learnable f)
+
+def backward_seed(out, den, dout) -> np.ndarray:
+    """g' = dL/d[num, den] per row, [n, d+1] fp64, from the saved forward results of one slice:
+    g'_i = [dout_i / den_i, -(dout_i . out_i) / den_i]  (chain rule through out = num / den)."""
+    out = np.asarray(out, dtype=np.float64)
+    den = np.asarray(den, dtype=np.float64)
+    dout = np.asarray(dout, dtype=np.float64)
+    return np.concatenate([dout / den[:, None], -(dout * out).sum(axis=1, keepdims=True) / den[:, None]], axis=1)
+
+
+def attention_backward(Q, K, V, row_ptr, col, val, out, den, dout, feature_map: int = RELU):
+    """Gradients of L = sum(dout * out) for one (b,h) slice: (dQ [n,d], dK, dV, dphi [nnz]) in fp64.
+
+    ``out`` [n,d] and ``den`` [n] are the saved forward results (any float dtype; used in fp64)."""
+    Q, K, V = _f32(Q), _f32(K), _f32(V)
+    n, d = Q.shape
+    rp, c, v = _i32(row_ptr), _i32(col), _f32(val)
+    out = np.ascontiguousarray(out, dtype=np.float64)
+    den = np.ascontiguousarray(den, dtype=np.float64)
+    dout = np.ascontiguousarray(dout, dtype=np.float64)
+    dQ = np.empty((n, d), dtype=np.float64)
+    dK = np.empty((n, d), dtype=np.float64)
+    dV = np.empty((n, d), dtype=np.float64)
+    dphi = np.empty(c.shape[0], dtype=np.float64)
+    _load().grf_ref_attention_backward(
+        ctypes.c_int64(n), ctypes.c_int32(d), _p(Q, ctypes.c_float), _p(K, ctypes.c_float), _p(V, ctypes.c_float),
+        _p(rp, ctypes.c_int32), _p(c, ctypes.c_int32), _p(v, ctypes.c_float), ctypes.c_int32(feature_map),
+        _p(out, ctypes.c_double), _p(den, ctypes.c_double), _p(dout, ctypes.c_double),
+        _p(dQ, ctypes.c_double), _p(dK, ctypes.c_double), _p(dV, ctypes.c_double), _p(dphi, ctypes.c_double))
+    return dQ, dK, dV, dphi
+
+
+def masked_linear_attention_backward(Q, K, V, row_ptr, col, val, out, den, dout, feature_map: int = RELU):
+    """All slices of [B,H,n,d] tensors.  Returns dQ, dK, dV [B,H,n,d] and dphi [n_f, nnz]
+    (summed over the slices that share a value plane), fp64."""
+    Q, K, V = (np.asarray(x, dtype=np.float32) for x in (Q, K, V))
+    B, H, n, d = Q.shape
+    val = np.atleast_2d(val)
+    n_f = val.shape[0]
+    assert n_f in (1, H)
+    dQ, dK, dV = (np.empty((B, H, n, d), dtype=np.float64) for _ in range(3))
+    dphi = np.zeros((n_f, val.shape[1]), dtype=np.float64)
+    for b in range(B):
+        for h in range(H):
+            p = h if n_f > 1 else 0
+            dQ[b, h], dK[b, h], dV[b, h], de = attention_backward(
+                Q[b, h], K[b, h], V[b, h], row_ptr, col, val[p], out[b, h], den[b, h], dout[b, h], feature_map)
+            dphi[p] += de
+    return dQ, dK, dV, dphi
+
+
+def sample_backward(g, f_len: int, p_halt: float, n_walks: int, seed: int, row_ptr, col, dphi) -> np.ndarray:
+    """df [n_f, f_len] fp64 from dphi [n_f, nnz] (CSR order of the pattern sampled with the same arguments)."""
+    dphi = np.ascontiguousarray(np.atleast_2d(dphi), dtype=np.float64)
+    n_f, nnz = dphi.shape
+    rp, c, w = _i32(g.row_ptr), _i32(g.col), _f32(g.w)
+    prp, pc = _i32(row_ptr), _i32(col)
+    df = np.empty((n_f, f_len), dtype=np.float64)
+    _load().grf_ref_sample_backward(
+        ctypes.c_int64(g.n), _p(rp, ctypes.c_int32), _p(c, ctypes.c_int32), _p(w, ctypes.c_float),
+        ctypes.c_int32(f_len), ctypes.c_int32(n_f), ctypes.c_double(p_halt), ctypes.c_int32(n_walks), ctypes.c_uint64(seed),
+        _p(prp, ctypes.c_int32), _p(pc, ctypes.c_int32), ctypes.c_int64(nnz), _p(dphi, ctypes.c_double), _p(df, ctypes.c_double))
+    return df
+
+
+def row_direct_backward(i: int, Q, K, V, row_ptr, col, val, gp, feature_map: int = RELU):
+    """(dq_i, dk_i, dv_i) [d] each for one node of one slice, from Eq. (2) directly; gp = backward_seed(...)."""
+    Q, K, V = _f32(Q), _f32(K), _f32(V)
+    n, d = Q.shape
+    rp, c, v = _i32(row_ptr), _i32(col), _f32(val)
+    gp = np.ascontiguousarray(gp, dtype=np.float64)
+    res = [np.empty(d, dtype=np.float64) for _ in range(3)]
+    _load().grf_ref_row_direct_backward(
+        ctypes.c_int64(n), ctypes.c_int32(d), ctypes.c_int64(i),
+        _p(Q, ctypes.c_float), _p(K, ctypes.c_float), _p(V, ctypes.c_float),
+        _p(rp, ctypes.c_int32), _p(c, ctypes.c_int32), _p(v, ctypes.c_float), ctypes.c_int32(feature_map),
+        _p(gp, ctypes.c_double), *[_p(r, ctypes.c_double) for r in res])
+    return tuple(res)
+
+
+def dphi_entry_direct(i: int, l: int, Q, K, V, row_ptr, col, val, gp, feature_map: int = RELU) -> float:
+    """dL/dPhi_hat[i, l] for one stored entry of one slice, its two buckets formed by a scan of column l."""
+    Q, K, V = _f32(Q), _f32(K), _f32(V)
+    n, d = Q.shape
+    rp, c, v = _i32(row_ptr), _i32(col), _f32(val)
+    gp = np.ascontiguousarray(gp, dtype=np.float64)
+    return float(_load().grf_ref_dphi_entry_direct(
+        ctypes.c_int64(n), ctypes.c_int32(d), ctypes.c_int64(i), ctypes.c_int64(l),
+        _p(Q, ctypes.c_float), _p(K, ctypes.c_float), _p(V, ctypes.c_float),
+        _p(rp, ctypes.c_int32), _p(c, ctypes.c_int32), _p(v, ctypes.c_float), ctypes.c_int32(feature_map),
+        _p(gp, ctypes.c_double)))

@@ -1,0 +1,210 @@
+"""Pins of the CPU checker's gradients (no GPU).
+
+The checker's backward routines are hand-derived formulas; they are pinned here against
+mechanisms that share nothing with them: reverse-mode automatic differentiation (PyTorch, fp64)
+of the dense O(N^2) definition of masked attention with M_hat = Phi_hat Phi_hat^T and
+Phi_hat = sum_t f_t P_t; central finite differences of the checker's own (separately pinned)
+forward pass; and Euler's identity for the homogeneities of the output.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_03462_amd import synth
+
+
+def torch_feature(x, feature_map):
+    if feature_map == 0:
+        return torch.relu(x)
+    if feature_map == 2:
+        return torch.nn.functional.elu(x) + 1.0
+    return x
+
+
+def hop_matrices(oracle, g, f_len, p_halt, n_walks, seed):
+    """P_t dense [f_len, n, n] with Phi_hat(f) = sum_t f_t P_t: the checker's sampler run with one-hot f."""
+    rp, col, planes = oracle.sample(g, np.eye(f_len, dtype=np.float32), p_halt, n_walks, seed)
+    return rp, col, np.stack([oracle.phi_dense(g.n, rp, col, planes[t]) for t in range(f_len)])
+
+
+def dense_autograd(P_t, f, Q, K, V, dout, feature_map):
+    """Gradients of L = sum(dout * out) by autograd through the dense definition (Eq. 1-2, Eq. 4-5)."""
+    P_t = torch.from_numpy(P_t)
+    f = torch.tensor(np.asarray(f, dtype=np.float64), requires_grad=True)
+    Q, K, V = (torch.tensor(np.asarray(x, dtype=np.float64), requires_grad=True) for x in (Q, K, V))
+    Phi = torch.einsum("t,tij->ij", f, P_t)
+    Phi.retain_grad()
+    M = Phi @ Phi.T
+    A = torch_feature(Q, feature_map) @ torch_feature(K, feature_map).T
+    AM = M * A
+    out = (AM @ V) / AM.sum(dim=1, keepdim=True)
+    (out * torch.from_numpy(np.asarray(dout, dtype=np.float64))).sum().backward()
+    return {"dQ": Q.grad.numpy(), "dK": K.grad.numpy(), "dV": V.grad.numpy(), "df": f.grad.numpy(),
+            "dPhi": Phi.grad.numpy(), "out": out.detach().numpy()}
+
+
+def case(oracle, seed, feature_map, positive_f=False, n_side=9, d=8, f_len=5):
+    rng = np.random.default_rng(seed)
+    g = synth.with_weights(synth.grid_graph(n_side, n_side + 2, 8), "sym_norm")
+    f = synth.modulation(f_len, rng, "decay")[0].astype(np.float64)
+    if positive_f:
+        f = np.abs(f) + 0.05
+    f = f.astype(np.float32)
+    p_halt, n_walks = 0.35, 4
+    rp, col, P_t = hop_matrices(oracle, g, f_len, p_halt, n_walks, seed)
+    _, _, val = oracle.sample(g, f, p_halt, n_walks, seed)
+    Q, K, V = synth.qkv(1, 1, g.n, d, rng)
+    dout = rng.standard_normal((g.n, d))
+    return g, f, p_halt, n_walks, rp, col, val, P_t, Q[0, 0], K[0, 0], V[0, 0], dout
+
+
+def close(a, b, tol=1e-9):
+    scale = np.abs(b).max()
+    return np.abs(a - b).max() <= tol * scale
+
+
+@pytest.mark.parametrize("feature_map", [0, 1, 2])
+@pytest.mark.parametrize("positive_f", [True, False])
+def test_backward_equals_autograd_of_dense_definition(oracle, feature_map, positive_f):
+    g, f, p, nw, rp, col, val, P_t, Q, K, V, dout = case(oracle, 3 + feature_map, feature_map, positive_f)
+    # the sampler's values are the fp32 rounding of sum_t f_t P_t: hand autograd the same matrix
+    Phi = oracle.phi_dense(g.n, rp, col, val[0])
+    assert np.allclose(Phi, np.einsum("t,tij->ij", f.astype(np.float64), P_t), rtol=1e-6, atol=1e-7)
+    P_used = P_t.copy()
+    # make sum_t f_t P_used_t equal Phi exactly by absorbing the rounding into the first hop matrix with f_t != 0
+    t0 = int(np.flatnonzero(f)[0])
+    P_used[t0] += (Phi - np.einsum("t,tij->ij", f.astype(np.float64), P_t)) / float(f[t0])
+    ref = dense_autograd(P_used, f, Q, K, V, dout, feature_map)
+
+    fwd = oracle.masked_linear_attention(Q[None, None], K[None, None], V[None, None], rp, col, val, feature_map)
+    assert close(fwd["out"][0, 0], ref["out"])
+    dQ, dK, dV, dphi = oracle.attention_backward(Q, K, V, rp, col, val[0], fwd["out"][0, 0], fwd["den"][0, 0], dout, feature_map)
+    assert close(dQ, ref["dQ"]) and close(dK, ref["dK"]) and close(dV, ref["dV"])
+    rows = np.repeat(np.arange(g.n), np.diff(rp))
+    assert close(dphi, ref["dPhi"][rows, col])
+    df = oracle.sample_backward(g, len(f), p, nw, 3 + feature_map, rp, col, dphi)
+    # the hop matrices handed to autograd are fp32-rounded planes: df agrees to that rounding
+    assert close(df[0], ref["df"], tol=2e-6)
+    # and exactly with the contraction of dphi against the unrounded per-hop loads
+    traj, loads = oracle.sample_walks(g, p, nw, len(f), 3 + feature_map, with_loads=True)
+    dense_d = np.zeros((g.n, g.n)); dense_d[rows, col] = dphi
+    want = np.zeros(len(f))
+    for t in range(len(f)):
+        ok = traj[:, :, t] >= 0
+        i_idx = np.broadcast_to(np.arange(g.n)[:, None], ok.shape)[ok]
+        want[t] = (loads[:, :, t][ok] * dense_d[i_idx, traj[:, :, t][ok]]).sum() / nw
+    assert close(df[0], want, tol=1e-12)
+
+
+def test_backward_equals_finite_differences_of_the_forward(oracle):
+    """Central differences of the checker's forward pass on inputs quantised so that x +- h is exact in fp32."""
+    fm = 2   # smooth map
+    g, f, p, nw, rp, col, val, P_t, Q, K, V, dout = case(oracle, 11, fm, positive_f=True, n_side=6, d=4)
+    q = lambda x: (np.round(np.asarray(x, np.float64) * 256) / 256).astype(np.float32)
+    Q, K, V, val, f = q(Q), q(K), q(V), q(val * 16) / 16, q(f)
+
+    def loss(Q_, K_, V_, val_):
+        r = oracle.masked_linear_attention(Q_[None, None], K_[None, None], V_[None, None], rp, col, val_, fm)
+        return float((r["out"][0, 0] * dout).sum()), r
+
+    _, fwd = loss(Q, K, V, val)
+    dQ, dK, dV, dphi = oracle.attention_backward(Q, K, V, rp, col, val[0], fwd["out"][0, 0], fwd["den"][0, 0], dout, fm)
+    h = 2.0 ** -9
+    rng = np.random.default_rng(0)
+    for name, X, dX in (("Q", Q, dQ), ("K", K, dK), ("V", V, dV)):
+        for _ in range(6):
+            i, a = int(rng.integers(X.shape[0])), int(rng.integers(X.shape[1]))
+            Xp, Xm = X.copy(), X.copy()
+            Xp[i, a] += h; Xm[i, a] -= h
+            args_p = {"Q": (Xp, K, V), "K": (Q, Xp, V), "V": (Q, K, Xp)}[name]
+            args_m = {"Q": (Xm, K, V), "K": (Q, Xm, V), "V": (Q, K, Xm)}[name]
+            fd = (loss(*args_p, val)[0] - loss(*args_m, val)[0]) / (2 * h)
+            assert abs(fd - dX[i, a]) <= 2e-4 * np.abs(dX).max() + 1e-9, (name, i, a, fd, dX[i, a])
+    for _ in range(8):
+        e = int(rng.integers(val.shape[1]))
+        vp, vm = val.copy(), val.copy()
+        vp[0, e] += h; vm[0, e] -= h
+        fd = (loss(Q, K, V, vp)[0] - loss(Q, K, V, vm)[0]) / (2 * h)
+        assert abs(fd - dphi[e]) <= 2e-4 * np.abs(dphi).max() + 1e-9
+    # f: through the sampler (same walks, linear in f) and the attention
+    df = oracle.sample_backward(g, len(f), p, nw, 11, rp, col, dphi)[0]
+    f = q(f)
+    _, _, val0 = oracle.sample(g, f, p, nw, 11)
+    _, fwd0 = loss(Q, K, V, val0)
+    dQ0, dK0, dV0, dphi0 = oracle.attention_backward(Q, K, V, rp, col, val0[0], fwd0["out"][0, 0], fwd0["den"][0, 0], dout, fm)
+    df0 = oracle.sample_backward(g, len(f), p, nw, 11, rp, col, dphi0)[0]
+    for t in range(len(f)):
+        fp_, fm_ = f.copy(), f.copy()
+        fp_[t] += 2.0 ** -7; fm_[t] -= 2.0 ** -7
+        lp = loss(Q, K, V, oracle.sample(g, fp_, p, nw, 11)[2])[0]
+        lm = loss(Q, K, V, oracle.sample(g, fm_, p, nw, 11)[2])[0]
+        fd = (lp - lm) / 2.0 ** -6
+        assert abs(fd - df0[t]) <= 2e-3 * np.abs(df0).max() + 1e-9, (t, fd, df0[t])
+    assert df.shape == df0.shape
+
+
+@pytest.mark.parametrize("feature_map", [0, 1])
+def test_euler_identities(oracle, feature_map):
+    """out is homogeneous of degree 0 in Phi_hat (hence in f), in phi(Q) and in phi(K) (ReLU and the identity are
+    positively homogeneous), and linear in V:  <x, dL/dx> = 0 for x in {Phi_hat, f, Q, K},  <V, dL/dV> = L."""
+    g, f, p, nw, rp, col, val, P_t, Q, K, V, dout = case(oracle, 21, feature_map)
+    fwd = oracle.masked_linear_attention(Q[None, None], K[None, None], V[None, None], rp, col, val, feature_map)
+    out, den = fwd["out"][0, 0], fwd["den"][0, 0]
+    dQ, dK, dV, dphi = oracle.attention_backward(Q, K, V, rp, col, val[0], out, den, dout, feature_map)
+    df = oracle.sample_backward(g, len(f), p, nw, 21, rp, col, dphi)[0]
+    L = float((dout * out).sum())
+    scale = lambda x, dx: np.abs(x.astype(np.float64) * dx).sum()
+    assert abs((val[0].astype(np.float64) * dphi).sum()) <= 1e-10 * scale(val[0], dphi)
+    assert abs((Q.astype(np.float64) * dQ).sum()) <= 1e-10 * scale(Q, dQ)
+    assert abs((K.astype(np.float64) * dK).sum()) <= 1e-10 * scale(K, dK)
+    assert abs((V.astype(np.float64) * dV).sum() - L) <= 1e-10 * scale(V, dV)
+    # f: val is the fp32 rounding of sum_t f_t loads, so the identity holds to that rounding
+    assert abs((f.astype(np.float64) * df).sum()) <= 1e-6 * np.abs(f * df).sum()
+
+
+def test_single_row_and_single_entry_routines_match_the_full_backward(oracle):
+    g, f, p, nw, rp, col, val, P_t, Q, K, V, dout = case(oracle, 31, 0, n_side=10, d=8)
+    fwd = oracle.masked_linear_attention(Q[None, None], K[None, None], V[None, None], rp, col, val)
+    out, den = fwd["out"][0, 0], fwd["den"][0, 0]
+    dQ, dK, dV, dphi = oracle.attention_backward(Q, K, V, rp, col, val[0], out, den, dout)
+    gp = oracle.backward_seed(out, den, dout)
+    for i in (0, 7, g.n - 1, g.n // 2):
+        dq_i, dk_i, dv_i = oracle.row_direct_backward(i, Q, K, V, rp, col, val[0], gp)
+        assert close(dq_i, dQ[i], 1e-10) or np.abs(dq_i - dQ[i]).max() <= 1e-10 * np.abs(dQ).max()
+        assert np.abs(dk_i - dK[i]).max() <= 1e-10 * np.abs(dK).max()
+        assert np.abs(dv_i - dV[i]).max() <= 1e-10 * np.abs(dV).max()
+    rows = np.repeat(np.arange(g.n), np.diff(rp))
+    for e in (0, 5, len(col) // 2, len(col) - 1):
+        got = oracle.dphi_entry_direct(int(rows[e]), int(col[e]), Q, K, V, rp, col, val[0], gp)
+        assert abs(got - dphi[e]) <= 1e-10 * np.abs(dphi).max()
+
+
+def test_elu_plus_one_feature_map_is_the_library_routine(oracle):
+    """phi = elu(x) + 1 of the checker equals torch's elu + 1 inside the dense definition."""
+    g, f, p, nw, rp, col, val, P_t, Q, K, V, dout = case(oracle, 41, 2)
+    fwd = oracle.masked_linear_attention(Q[None, None], K[None, None], V[None, None], rp, col, val, 2)
+    Phi = torch.from_numpy(oracle.phi_dense(g.n, rp, col, val[0]))
+    Qt, Kt, Vt = (torch.from_numpy(x.astype(np.float64)) for x in (Q, K, V))
+    AM = (Phi @ Phi.T) * ((torch.nn.functional.elu(Qt) + 1) @ (torch.nn.functional.elu(Kt) + 1).T)
+    assert close(fwd["num"][0, 0], (AM @ Vt).numpy(), 1e-12)
+    assert close(fwd["den"][0, 0], AM.sum(1).numpy(), 1e-12)
+    assert np.all(fwd["den"][0, 0] != 0)
+
+
+def test_per_plane_accumulation_over_slices(oracle):
+    """dphi of a plane is the sum over the slices that use it (shared plane: all; per-head planes: one head each)."""
+    rng = np.random.default_rng(5)
+    g = synth.grid_graph(7, 7, 4)
+    f = synth.modulation(4, rng, "decay", n_f=2)
+    rp, col, val = oracle.sample(g, f, 0.4, 3, 2)
+    Q, K, V = synth.qkv(2, 2, g.n, 4, rng)
+    fwd = oracle.masked_linear_attention(Q, K, V, rp, col, val, 2)      # elu + 1: no zero denominators
+    dout = rng.standard_normal(Q.shape)
+    dQ, dK, dV, dphi = oracle.masked_linear_attention_backward(Q, K, V, rp, col, val, fwd["out"], fwd["den"], dout, 2)
+    assert dphi.shape == val.shape
+    for h in range(2):
+        want = sum(oracle.attention_backward(Q[b, h], K[b, h], V[b, h], rp, col, val[h], fwd["out"][b, h], fwd["den"][b, h], dout[b, h], 2)[3]
+                   for b in range(2))
+        assert np.allclose(dphi[h], want, rtol=1e-12, atol=1e-12 * np.abs(want).max())
+    shared = oracle.masked_linear_attention_backward(Q, K, V, rp, col, val[:1], *[oracle.masked_linear_attention(Q, K, V, rp, col, val[:1], 2)[k] for k in ("out", "den")], dout, 2)[3]
+    assert shared.shape == (1, val.shape[1])
