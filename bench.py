@@ -178,6 +178,36 @@ def main() -> int:
                      "note": "K and V of one head (16.8 MB) are re-read from L2 / Infinity Cache, so the algorithmic rate may exceed the HBM peak"},
     }
 
+    # gradients (training with learnable f): backward of the attention call and of the sampler, on the fused
+    # forward's saved out and den; six MFMA contractions of 2*nnz*d*d flops per slice
+    _, _, fden = grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, workspace=fws, return_num_den=True, out=fout)
+    d_out = torch.randn((B, H, N, d), dtype=torch.float32, device=dev, generator=torch.Generator(device=dev).manual_seed(0))
+    bws = torch.empty(grf.grf_attention_backward_workspace_bytes(B, H, N, d, nnz, phi.n_f), dtype=torch.uint8, device=dev)
+
+    def backward_step():
+        grads = grf.grf_masked_linear_attention_backward(Qd, Kd, Vd, phi, fout, fden, d_out, workspace=bws)
+        return grf.grf_sample_backward(g, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, phi, grads[3])
+
+    for _ in range(args.warmup):
+        backward_step()
+    torch.cuda.synchronize()
+    b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    b0.record(stream)
+    for _ in range(args.steps):
+        backward_step()
+    b1.record(stream)
+    torch.cuda.synchronize()
+    bwd_ms = b0.elapsed_time(b1) / args.steps
+    bwd_flops = 12.0 * nnz * d * d * B * H
+    backward = {
+        "entry_points": "grf_masked_linear_attention_backward + grf_sample_backward",
+        "ms": round(bwd_ms, 4),
+        "tokens_per_s_per_head": round(tokens / (bwd_ms * 1e-3), 1),
+        "roofline": {"bound": "mfma", "unit": "TFLOP/s", "peak": 157.3,
+                     "achieved_whole_call": round(bwd_flops / (bwd_ms * 1e-3) / 1e12, 2), "flops_per_call": bwd_flops,
+                     "note": "whole backward (seed, column lists, three bucket passes with their row reductions, dphi, df)"},
+    }
+
     result = {
         "metric": "GRF-masked linear attention tokens/s/head at N=%d" % N,
         "value": round(value, 1), "unit": "tokens/s/head",
@@ -192,6 +222,7 @@ def main() -> int:
         "roofline": roofline,
         "fused_variant": fused,
         "asymmetric_variant": asymmetric,
+        "backward": backward,
     }
 
     if not args.no_cpu_baseline:

@@ -45,6 +45,8 @@ typedef int32_t grf_status;
 /* Query/key feature map phi (Alg. 1 step 3).  m = d for both. */
 #define GRF_PHI_RELU      0     /* phi(x) = max(x, 0) elementwise: the map used in the paper's experiments */
 #define GRF_PHI_IDENTITY  1     /* phi(x) = x: for tests */
+#define GRF_PHI_ELU1      2     /* phi(x) = elu(x) + 1 (x + 1 for x > 0, exp(x) otherwise): the deterministic map of
+                                   the linear transformer that Sec. 2 and Alg. 1 step 3 name as an alternative */
 
 /* Message describing the last error returned on this thread.  Static storage; never free it. */
 const char* grf_last_error(void);
@@ -202,6 +204,55 @@ grf_status grf_asymmetric_masked_attention(const void* Q, const void* K, const v
                                            int64_t B, int64_t H, int64_t n, int32_t d,
                                            const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
                                            void* hip_stream, float* out, float* num_opt, float* den_opt);
+
+/* ---------------------------------------------------------------------------------------------
+ * Gradients, for training with the learnable modulation f of Alg. 1 (and through Q, K, V).
+ *
+ * The forward pass is out = attention(Q, K, V, Phi_hat) with Phi_hat = sample(f), linear in f.  Given
+ * d_out = dL/dout, grf_masked_linear_attention_backward returns dL/dQ, dL/dK, dL/dV and dL/dPhi_hat on the
+ * stored entries; grf_sample_backward then contracts dL/dPhi_hat with the per-hop walk loads to give dL/df.
+ *
+ * With v'_j = [v_j, 1] and g'_i = [d_out_i / den_i, -(d_out_i . out_i) / den_i] (chain rule through the division
+ * of Eq. 7), S'_l = sum_j Phi[j,l] phi(k_j) v'_j^T and T'_l = sum_i Phi[i,l] phi(q_i) g'_i^T,
+ *     dL/dphi(q_i) = sum_l Phi[i,l] S'_l g'_i          dL/dphi(k_j) = sum_l Phi[j,l] T'_l v'_j
+ *     dL/dv_j      = sum_l Phi[j,l] T_l^T phi(k_j)     dL/dPhi[i,l] = phi(q_i)^T S'_l g'_i + phi(k_i)^T T'_l v'_i
+ * and dL/dq = dL/dphi(q) * phi'(q) elementwise, likewise k.  Evaluated bucket by bucket like the fused forward
+ * pass (the rows that consume bucket l are its contributors), in three passes of two MFMA contractions each;
+ * per-entry partial rows are summed per output row in ascending-l order (deterministic, no float atomics).
+ *
+ * Q, K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map, bh_chunk: as in the forward call.
+ * out, den   device fp32 [B][H][n][d] and [B][H][n]: the forward results (out and den_opt of either variant).
+ * d_out      device fp32 [B][H][n][d].
+ * dQ, dK, dV device fp32 [B][H][n][d], overwritten.
+ * dphi_val   device fp32 [n_f][phi->capacity] or NULL: plane h receives the sum over the (batch, head) slices
+ *            that use plane h of dL/dPhi_hat; entries [nnz, capacity) are not touched.
+ * A row with den_i = 0 propagates IEEE inf/NaN into every gradient it touches (no epsilon, as in the forward).
+ * --------------------------------------------------------------------------------------------- */
+size_t grf_attention_backward_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t n_f, int32_t bh_chunk);
+
+grf_status grf_masked_linear_attention_backward(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                int64_t B, int64_t H, int64_t n, int32_t d,
+                                                const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                const float* out, const float* den, const float* d_out,
+                                                int32_t bh_chunk,
+                                                void* workspace, size_t workspace_bytes, void* hip_stream,
+                                                float* dQ, float* dK, float* dV, float* dphi_val);
+
+/* Gradient of the sampled features with respect to the modulation (Eq. GRF definition is linear in f):
+ *     df[h][t] = (1 / n_walks) * sum over nodes i, walks k with at least t hops of
+ *                load_{k,t} * dphi_val[h][entry (i, node visited by walk k after t hops)]
+ * over the same walks as grf_sample with the same (g, p_halt, n_walks, seed, f_len).
+ * phi        the pattern sampled with those arguments (row_ptr, col; val is not read), nnz its entries.
+ * dphi_val   device fp32 [n_f][phi->capacity].
+ * df         device fp32 [n_f][f_len], overwritten.  Sums run in a fixed order (bitwise reproducible).
+ * Workspace: n * n_f * f_len floats of per-node partial sums. */
+size_t grf_sample_backward_workspace_bytes(int64_t n, int32_t f_len, int32_t n_f);
+
+grf_status grf_sample_backward(const grf_graph* g, int32_t f_len, int32_t n_f,
+                               double p_halt, int32_t n_walks, uint64_t seed,
+                               const grf_phi* phi, int64_t nnz, const float* dphi_val,
+                               void* workspace, size_t workspace_bytes, void* hip_stream,
+                               float* df);
 
 #ifdef __cplusplus
 }

@@ -19,8 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libgrf_hip.so")
 
 GRF_OK, GRF_EINVAL, GRF_ECAPACITY, GRF_EUNSUPPORTED, GRF_EHIP, GRF_EWORKSPACE = 0, -1, -2, -3, -4, -5
 GRF_DTYPE_F32, GRF_DTYPE_BF16 = 0, 1
-GRF_PHI_RELU, GRF_PHI_IDENTITY = 0, 1
-_FEATURE_MAPS = {"relu": GRF_PHI_RELU, "identity": GRF_PHI_IDENTITY}
+GRF_PHI_RELU, GRF_PHI_IDENTITY, GRF_PHI_ELU1 = 0, 1, 2
+_FEATURE_MAPS = {"relu": GRF_PHI_RELU, "identity": GRF_PHI_IDENTITY, "elu1": GRF_PHI_ELU1}
 _STATUS_NAMES = {GRF_EINVAL: "GRF_EINVAL", GRF_ECAPACITY: "GRF_ECAPACITY", GRF_EUNSUPPORTED: "GRF_EUNSUPPORTED",
                  GRF_EHIP: "GRF_EHIP", GRF_EWORKSPACE: "GRF_EWORKSPACE"}
 
@@ -91,6 +91,19 @@ def lib() -> ctypes.CDLL:
         L.grf_asymmetric_masked_attention.restype = ctypes.c_int32
         L.grf_asymmetric_masked_attention.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, *common,
                                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.grf_attention_backward_workspace_bytes.restype = ctypes.c_size_t
+        L.grf_attention_backward_workspace_bytes.argtypes = L.grf_attention_workspace_bytes.argtypes
+        L.grf_masked_linear_attention_backward.restype = ctypes.c_int32
+        L.grf_masked_linear_attention_backward.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, *common,
+                                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                                           ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.grf_sample_backward_workspace_bytes.restype = ctypes.c_size_t
+        L.grf_sample_backward_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
+        L.grf_sample_backward.restype = ctypes.c_int32
+        L.grf_sample_backward.argtypes = [ctypes.POINTER(_Graph), ctypes.c_int32, ctypes.c_int32, ctypes.c_double,
+                                          ctypes.c_int32, ctypes.c_uint64, ctypes.POINTER(_Phi), ctypes.c_int64,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -361,3 +374,54 @@ def grf_asymmetric_masked_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.T
                                              phi.nnz, phi.n_f, _FEATURE_MAPS[feature_map], _stream_ptr(stream),
                                              _ptr(out), _ptr(num), _ptr(den)))
     return (out, num, den) if return_num_den else out
+
+
+# --------------------------------------------------------------------------- gradients
+
+def grf_attention_backward_workspace_bytes(B: int, H: int, n: int, d: int, nnz: int, n_f: int = 1, bh_chunk: int = 0) -> int:
+    return int(lib().grf_attention_backward_workspace_bytes(B, H, n, d, nnz, n_f, bh_chunk))
+
+
+def grf_masked_linear_attention_backward(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, phi: Phi,
+                                         out: torch.Tensor, den: torch.Tensor, d_out: torch.Tensor,
+                                         feature_map: str = "relu", bh_chunk: int = 0, want_dphi: bool = True,
+                                         workspace: Optional[torch.Tensor] = None, stream=None):
+    """(dQ, dK, dV, dphi_val) for d_out = dL/dout; ``out`` and ``den`` are the saved forward results (fp32).
+
+    dphi_val is [n_f, capacity] fp32 (entries beyond nnz untouched), or None when ``want_dphi`` is False."""
+    _require_gpu()
+    L = lib()
+    B, H, n, d = _check_qkv(Q, K, V)
+    for t, shape in ((out, (B, H, n, d)), (d_out, (B, H, n, d)), (den, (B, H, n))):
+        if tuple(t.shape) != shape or t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda:
+            raise ValueError("out, den, d_out must be contiguous fp32 CUDA tensors of shapes [B,H,n,d], [B,H,n], [B,H,n,d]")
+    need = L.grf_attention_backward_workspace_bytes(B, H, n, d, phi.nnz, phi.n_f, bh_chunk)
+    if need == 0:
+        raise GrfError(GRF_EUNSUPPORTED, f"unsupported problem (d={d})")
+    if workspace is None:
+        workspace = _workspace(need, Q.device)
+    dQ, dK, dV = (torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device) for _ in range(3))
+    dphi = torch.empty((phi.n_f, phi.capacity), dtype=torch.float32, device=Q.device) if want_dphi else None
+    ps = phi._struct()
+    _check(L.grf_masked_linear_attention_backward(
+        _ptr(Q), _ptr(K), _ptr(V), _dtype_code(Q), B, H, n, d, ctypes.byref(ps), phi.nnz, phi.n_f,
+        _FEATURE_MAPS[feature_map], _ptr(out), _ptr(den), _ptr(d_out), int(bh_chunk),
+        _ptr(workspace), workspace.numel(), _stream_ptr(stream), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dphi)))
+    return dQ, dK, dV, dphi
+
+
+def grf_sample_backward(graph: DeviceGraph, f_len: int, p_halt: float, n_walks: int, seed: int, phi: Phi,
+                        dphi_val: torch.Tensor, stream=None) -> torch.Tensor:
+    """df [n_f, f_len] fp32 on the GPU from dphi_val [n_f, capacity]; same walk arguments as the grf_sample call."""
+    _require_gpu()
+    L = lib()
+    if tuple(dphi_val.shape) != (phi.n_f, phi.capacity) or dphi_val.dtype != torch.float32 or not dphi_val.is_contiguous():
+        raise ValueError("dphi_val must be a contiguous fp32 tensor [n_f, capacity]")
+    dev = graph.row_ptr.device
+    ws = _workspace(L.grf_sample_backward_workspace_bytes(graph.n, f_len, phi.n_f), dev)
+    df = torch.empty((phi.n_f, f_len), dtype=torch.float32, device=dev)
+    gs, ps = graph._struct(), phi._struct()
+    _check(L.grf_sample_backward(ctypes.byref(gs), int(f_len), phi.n_f, float(p_halt), int(n_walks),
+                                 int(seed) & 0xFFFFFFFFFFFFFFFF, ctypes.byref(ps), phi.nnz, _ptr(dphi_val),
+                                 _ptr(ws), ws.numel(), _stream_ptr(stream), _ptr(df)))
+    return df

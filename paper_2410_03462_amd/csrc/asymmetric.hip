@@ -30,7 +30,7 @@ template <int D, typename T>
 __global__ __launch_bounds__(256) void asymmetric_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
                                                          long long n, int H, int n_f, long long val_stride,
                                                          const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
-                                                         const float* __restrict__ phi_val, int relu, long long n_waves, int32_t nnz,
+                                                         const float* __restrict__ phi_val, int fmap, long long n_waves, int32_t nnz,
                                                          float* __restrict__ out, float* __restrict__ num_opt, float* __restrict__ den_opt)
 {
     constexpr int LPE = D / 4;            // lanes per entry
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void asymmetric_kernel(const T* __restrict__ Q
     const int cg = lane % LPE;
 
     float4 q4 = load4(Q + (bh * n + i) * D + 4 * cg);
-    q4.x = feature(q4.x, relu); q4.y = feature(q4.y, relu); q4.z = feature(q4.z, relu); q4.w = feature(q4.w, relu);
+    q4.x = feature(q4.x, fmap); q4.y = feature(q4.y, fmap); q4.z = feature(q4.z, fmap); q4.w = feature(q4.w, fmap);
 
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float dacc = 0.0f;
@@ -80,10 +80,10 @@ __global__ __launch_bounds__(256) void asymmetric_kernel(const T* __restrict__ Q
             }
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
-                float p = q4.x * feature(k4[u].x, relu);
-                p = fmaf(q4.y, feature(k4[u].y, relu), p);
-                p = fmaf(q4.z, feature(k4[u].z, relu), p);
-                p = fmaf(q4.w, feature(k4[u].w, relu), p);
+                float p = q4.x * feature(k4[u].x, fmap);
+                p = fmaf(q4.y, feature(k4[u].y, fmap), p);
+                p = fmaf(q4.z, feature(k4[u].z, fmap), p);
+                p = fmaf(q4.w, feature(k4[u].w, fmap), p);
 #pragma unroll
                 for (int off = 1; off < LPE; off <<= 1) p += __shfl_xor(p, off, kWave);
                 const float a = w[u] * p;
@@ -124,14 +124,14 @@ extern "C" grf_status grf_asymmetric_masked_attention(const void* Q, const void*
     if (B * H * n > 0 && (Q == nullptr || out == nullptr)) return fail(GRF_EINVAL, "Q / out is NULL");
     if (B * H * n == 0) return GRF_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const int relu = feature_map == GRF_PHI_RELU ? 1 : 0;
+    const int fmap = feature_map;
     const long long waves = static_cast<long long>(B) * H * n;
     GRF_DISPATCH(d, dtype,
                  hipLaunchKernelGGL((asymmetric_kernel<D_, T_>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream,
                                     static_cast<const T_*>(Q), static_cast<const T_*>(K), static_cast<const T_*>(V),
                                     static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
                                     static_cast<long long>(phi->capacity), static_cast<const int32_t*>(phi->row_ptr),
-                                    static_cast<const int32_t*>(phi->col), static_cast<const float*>(phi->val), relu, waves,
+                                    static_cast<const int32_t*>(phi->col), static_cast<const float*>(phi->val), fmap, waves,
                                     static_cast<int32_t>(nnz), out, num_opt, den_opt));
     GRF_LAUNCH_CHECK("asymmetric_kernel");
     return GRF_OK;

@@ -91,7 +91,7 @@ __global__ __launch_bounds__(64) void buckets_kernel(const T* __restrict__ K, co
                                                       long long n, int H, int n_f,
                                                       const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
                                                       const float* __restrict__ csc_val,
-                                                      int relu, long long bh_first, long long n_waves, int32_t nnz,
+                                                      int fmap, long long bh_first, long long n_waves, int32_t nnz,
                                                       float* __restrict__ buckets)
 {
     constexpr int T2 = D / 32;
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(64) void buckets_kernel(const T* __restrict__ K, co
 
     floatx16 acc[T2][T2];
     float zacc[T2];
-    bucket_first_contraction<D, T, false>(Kb, Vb, csc_row, vals, col_ptr[l], col_ptr[l + 1], relu, acc, zacc);
+    bucket_first_contraction<D, T, T, false, true, kExtraSumA>(Kb, Vb, csc_row, vals, nullptr, col_ptr[l], col_ptr[l + 1], fmap, acc, zacc);
 
     float* rec = buckets + (slice * n + l) * REC;
 #pragma unroll
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(64) void buckets_kernel(const T* __restrict__ K, co
 template <int D, typename T>
 __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ Q, long long n, int H, int n_f, long long val_stride,
                                                      const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
-                                                     const float* __restrict__ phi_val, int relu,
+                                                     const float* __restrict__ phi_val, int fmap,
                                                      const float* __restrict__ buckets, long long bh_first, long long n_waves,
                                                      int32_t nnz, float* __restrict__ out, float* __restrict__ num_opt, float* __restrict__ den_opt)
 {
@@ -163,8 +163,8 @@ __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ Q, lo
 
     float fq[NL];
 #pragma unroll
-    for (int j = 0; j < NL; ++j) fq[j] = feature(to_float(q[j * RPL + sub]), relu);
-    const float fq_lane = lane < D ? feature(to_float(q[lane < D ? lane : 0]), relu) : 0.0f;
+    for (int j = 0; j < NL; ++j) fq[j] = feature(to_float(q[j * RPL + sub]), fmap);
+    const float fq_lane = lane < D ? feature(to_float(q[lane < D ? lane : 0]), fmap) : 0.0f;
 
     float acc0 = 0.0f, acc1 = 0.0f, acc2 = 0.0f, acc3 = 0.0f, zacc = 0.0f;
 
@@ -274,7 +274,7 @@ grf_status check_problem(const void* a, const void* b, int32_t dtype, int64_t B,
 {
     if (B < 0 || H < 0 || n < 0) return fail(GRF_EINVAL, "B=%lld, H=%lld, n=%lld must be >= 0", (long long)B, (long long)H, (long long)n);
     if (dtype != GRF_DTYPE_F32 && dtype != GRF_DTYPE_BF16) return fail(GRF_EINVAL, "dtype=%d is neither GRF_DTYPE_F32 nor GRF_DTYPE_BF16", dtype);
-    if (feature_map != GRF_PHI_RELU && feature_map != GRF_PHI_IDENTITY) return fail(GRF_EINVAL, "feature_map=%d is unknown", feature_map);
+    if (feature_map != GRF_PHI_RELU && feature_map != GRF_PHI_IDENTITY && feature_map != GRF_PHI_ELU1) return fail(GRF_EINVAL, "feature_map=%d is unknown", feature_map);
     if (d != 32 && d != 64) return fail(GRF_EUNSUPPORTED, "head dimension d=%d is not supported (32 or 64)", d);
     if (phi == nullptr) return fail(GRF_EINVAL, "phi is NULL");
     if (phi->n != n) return fail(GRF_EINVAL, "phi->n=%lld differs from n=%lld", (long long)phi->n, (long long)n);
@@ -298,7 +298,7 @@ namespace {
 
 template <int D, typename T>
 grf_status launch_buckets(const void* K, const void* V, int64_t n, int64_t H, int32_t n_f, const grf_phi* phi,
-                          int64_t nnz, const Transposed& t, int relu, int64_t bh_first, int64_t n_slices, float* buckets,
+                          int64_t nnz, const Transposed& t, int fmap, int64_t bh_first, int64_t n_slices, float* buckets,
                           hipStream_t stream)
 {
     const long long waves = static_cast<long long>(n_slices) * n;
@@ -307,14 +307,14 @@ grf_status launch_buckets(const void* K, const void* V, int64_t n, int64_t H, in
                        static_cast<const T*>(K), static_cast<const T*>(V), static_cast<long long>(n), static_cast<int>(H),
                        static_cast<int>(n_f),
                        static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
-                       static_cast<const float*>(t.s_val), relu,
+                       static_cast<const float*>(t.s_val), fmap,
                        static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), buckets);
     GRF_LAUNCH_CHECK("buckets_kernel");
     return GRF_OK;
 }
 
 template <int D, typename T>
-grf_status launch_gather(const void* Q, int64_t n, int64_t H, int32_t n_f, const grf_phi* phi, int64_t nnz, int relu,
+grf_status launch_gather(const void* Q, int64_t n, int64_t H, int32_t n_f, const grf_phi* phi, int64_t nnz, int fmap,
                          const float* buckets, int64_t bh_first, int64_t n_slices,
                          float* out, float* num_opt, float* den_opt, hipStream_t stream)
 {
@@ -323,7 +323,7 @@ grf_status launch_gather(const void* Q, int64_t n, int64_t H, int32_t n_f, const
     hipLaunchKernelGGL((gather_kernel<D, T>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream,
                        static_cast<const T*>(Q), static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
                        static_cast<long long>(phi->capacity), static_cast<const int32_t*>(phi->row_ptr),
-                       static_cast<const int32_t*>(phi->col), static_cast<const float*>(phi->val), relu, buckets,
+                       static_cast<const int32_t*>(phi->col), static_cast<const float*>(phi->val), fmap, buckets,
                        static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), out, num_opt, den_opt);
     GRF_LAUNCH_CHECK("gather_kernel");
     return GRF_OK;
@@ -367,9 +367,9 @@ extern "C" grf_status grf_form_buckets(const void* K, const void* V, int32_t dty
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const Transposed t = carve_transposed(static_cast<unsigned char*>(workspace), n, nnz, n_f);
     if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
-    const int relu = feature_map == GRF_PHI_RELU ? 1 : 0;
+    const int fmap = feature_map;
     grf_status st = GRF_OK;
-    GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, phi, nnz, t, relu, 0, B * H, buckets, stream)));
+    GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, phi, nnz, t, fmap, 0, B * H, buckets, stream)));
     return st;
 }
 
@@ -383,9 +383,9 @@ extern "C" grf_status grf_gather_buckets(const void* Q, int32_t dtype,
     if (B * H * n > 0 && out == nullptr) return fail(GRF_EINVAL, "out is NULL");
     if (B * H * n == 0) return GRF_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const int relu = feature_map == GRF_PHI_RELU ? 1 : 0;
+    const int fmap = feature_map;
     grf_status st = GRF_OK;
-    GRF_DISPATCH(d, dtype, (st = launch_gather<D_, T_>(Q, n, H, n_f, phi, nnz, relu, buckets, 0, B * H, out, num_opt, den_opt, stream)));
+    GRF_DISPATCH(d, dtype, (st = launch_gather<D_, T_>(Q, n, H, n_f, phi, nnz, fmap, buckets, 0, B * H, out, num_opt, den_opt, stream)));
     return st;
 }
 
@@ -404,15 +404,15 @@ extern "C" grf_status grf_masked_linear_attention(const void* Q, const void* K, 
     const Transposed t = carve_transposed(static_cast<unsigned char*>(workspace), n, nnz, n_f);
     float* buckets = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + t.bytes);
     if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
-    const int relu = feature_map == GRF_PHI_RELU ? 1 : 0;
+    const int fmap = feature_map;
     const int64_t slices = B * H;
     const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;
     for (int64_t first = 0; first < slices; first += step) {
         const int64_t count = (slices - first < step) ? (slices - first) : step;
         grf_status st = GRF_OK;
-        GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, phi, nnz, t, relu, first, count, buckets, stream)));
+        GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, phi, nnz, t, fmap, first, count, buckets, stream)));
         if (st != GRF_OK) return st;
-        GRF_DISPATCH(d, dtype, (st = launch_gather<D_, T_>(Q, n, H, n_f, phi, nnz, relu, buckets, first, count, out, num_opt, den_opt, stream)));
+        GRF_DISPATCH(d, dtype, (st = launch_gather<D_, T_>(Q, n, H, n_f, phi, nnz, fmap, buckets, first, count, out, num_opt, den_opt, stream)));
         if (st != GRF_OK) return st;
     }
     return GRF_OK;

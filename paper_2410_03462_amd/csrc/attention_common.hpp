@@ -13,8 +13,22 @@ struct bf16_t { uint16_t bits; };
 __device__ __forceinline__ float to_float(float x) { return x; }
 __device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(static_cast<uint32_t>(x.bits) << 16); }
 
-// phi(x): max(x, 0) as one v_med3_f32 (median of x, 0, +inf), or the identity.
-__device__ __forceinline__ float feature(float x, int relu) { return relu ? __builtin_amdgcn_fmed3f(x, 0.0f, __builtin_inff()) : x; }
+// phi(x) for the feature-map codes of grf.h: max(x, 0) as one v_med3_f32 (median of x, 0, +inf),
+// the identity, or elu(x) + 1 (x + 1 for x > 0, exp(x) otherwise).  `fmap` is wave-uniform.
+__device__ __forceinline__ float feature(float x, int fmap)
+{
+    const float relu = __builtin_amdgcn_fmed3f(x, 0.0f, __builtin_inff());
+    const float elu1 = x > 0.0f ? x + 1.0f : __expf(x);
+    return fmap == GRF_PHI_RELU ? relu : (fmap == GRF_PHI_ELU1 ? elu1 : x);
+}
+
+// d phi(x) / dx (ReLU: 0 at x = 0).
+__device__ __forceinline__ float feature_grad(float x, int fmap)
+{
+    const float relu = x > 0.0f ? 1.0f : 0.0f;
+    const float elu1 = x > 0.0f ? 1.0f : __expf(x);
+    return fmap == GRF_PHI_RELU ? relu : (fmap == GRF_PHI_ELU1 ? elu1 : 1.0f);
+}
 
 // Column lists of Phi_hat, carved out of the caller's workspace.
 struct Transposed {
@@ -48,11 +62,43 @@ __device__ __forceinline__ long long xcd_contiguous_block(unsigned block, unsign
     return static_cast<long long>(x) * q + (x < rem ? x : rem) + k;
 }
 
-// First contraction of a bucket, shared by the bucket-forming and the bucket-fused kernels:
-//     acc[a][c] (32x32 tiles) += A^T V over the column list [beg, end) of bucket l,   zacc[a] += column sums of A,
-// A = weight * phi(K row).  The two half-waves carry the two contributors of a pair (the k index
-// of v_mfma_f32_32x32x2_f32).  MFMA row/column x of tile t stands for element 32*t + x of the K/V
-// row, or, INTERLEAVED, element T2*x + t, so that a lane's operands are adjacent in memory.
+// The T2 = D/32 elements of row j that MFMA row/column `li` of the tiles stands for, widened to
+// fp32: element 32*t + li of the row, or, INTERLEAVED, element T2*li + t, so that a lane's
+// operands are adjacent in memory (one 8-byte load at d = 64 in fp32).
+template <int D, typename T, bool INTERLEAVED>
+__device__ __forceinline__ void load_operand_elems(const T* __restrict__ base, uint32_t j, int li, float (&x)[D / 32])
+{
+    constexpr int T2 = D / 32;
+    if constexpr (INTERLEAVED) {
+        const uint32_t off = j * D + T2 * li;
+        if constexpr (sizeof(T) == 4 && T2 == 2) {
+            const float2 v = *reinterpret_cast<const float2*>(base + off);
+            x[0] = v.x; x[1] = v.y;
+        } else if constexpr (sizeof(T) == 2 && T2 == 2) {
+            const uint32_t v = *reinterpret_cast<const uint32_t*>(base + off);
+            x[0] = __uint_as_float(v << 16); x[1] = __uint_as_float(v & 0xffff0000u);
+        } else {
+            x[0] = to_float(base[off]);
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < T2; ++t) x[t] = to_float(base[j * D + 32 * t + li]);
+    }
+}
+
+// What the first contraction accumulates besides the D x D tile.
+enum : int {
+    kExtraSumA = 0,        // column sums of the A operands        (z_l of the forward pass)
+    kExtraSumB = 1,        // column sums of the B operands
+    kExtraScaledSumB = 2,  // sum over contributors of escale[row] * (B operands)
+    kExtraNone = 3,
+};
+
+// First contraction of a bucket, shared by the bucket-forming, the bucket-fused and the backward kernels:
+//     acc[a][c] (32x32 tiles) += A^T B over the column list [beg, end) of bucket l,   extra[...] += see above,
+// where one of the two operands of a contributor is weight * phi(row) (A if WEIGHT_ON_A, else B) and the other
+// its row as stored.  The two half-waves carry the two contributors of a pair (the k index of
+// v_mfma_f32_32x32x2_f32); see load_operand_elems for which element a lane holds.
 //
 // The column list is walked in blocks of 128 entries (64 contributor pairs; most lists fit in one):
 //   - the (row, weight) of a block's entries are fetched up front, one entry per lane in two
@@ -60,20 +106,22 @@ __device__ __forceinline__ long long xcd_contiguous_block(unsigned block, unsign
 //     that inside the block the only memory instructions are the row loads: the load counter
 //     retires in order, and any wait on a recently issued index load would drain every row load
 //     issued before it;
-//   - a pair's rows of K and V are fetched RING pairs ahead into a ring of RING register slots,
-//     the slot that the current pair has just vacated;
+//   - a pair's rows are fetched RING pairs ahead into a ring of RING register slots, the slot
+//     that the current pair has just vacated;
 //   - row loads are unconditional (pairs past the end re-read the last entry with weight 0), since
 //     a load skipped on one control path would force a full wait where the paths join;
 //   - a scheduling barrier per pair keeps each pair's fetch work next to the previous pair's MFMAs:
 //     an MFMA holds the matrix pipe for 64 cycles, in which the fetch instructions issue for free.
-template <int D, typename T, bool INTERLEAVED>
-__device__ __forceinline__ void bucket_first_contraction(const T* __restrict__ Kb, const T* __restrict__ Vb,
+template <int D, typename TA, typename TB, bool INTERLEAVED, bool WEIGHT_ON_A, int EXTRA>
+__device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ Ab, const TB* __restrict__ Bb,
                                                          const int32_t* __restrict__ csc_row, const float* __restrict__ vals,
-                                                         int32_t beg_in, int32_t end_in, int relu,
+                                                         const float* __restrict__ escale,
+                                                         int32_t beg_in, int32_t end_in, int fmap,
                                                          floatx16 (&acc)[D / 32][D / 32], float (&zacc)[D / 32])
 {
     constexpr int T2 = D / 32;
     constexpr int RING = 16;
+    constexpr bool SCALED = EXTRA == kExtraScaledSumB;
     const int32_t beg = beg_in, end = end_in;
     const int lane = lane_id();
     const bool upper = lane >= 32;
@@ -88,34 +136,20 @@ __device__ __forceinline__ void bucket_first_contraction(const T* __restrict__ K
     }
     if (beg >= end) return;
 
-    // rows of the pair held in lanes (s, s + 1) of (jv, gv): lower half-wave takes s, upper s + 1
-    auto row_load = [&](int32_t jv, float gv, int s, float (&kk)[T2], float (&vv)[T2], float& gg) {
+    // rows of the pair held in lanes (s, s + 1) of (jv, gv, ev): lower half-wave takes s, upper s + 1
+    auto row_load = [&](int32_t jv, float gv, float ev, int s, float (&aa)[T2], float (&bb)[T2], float& gg, float& ee) {
         const int32_t j0 = __builtin_amdgcn_readlane(jv, s), j1 = __builtin_amdgcn_readlane(jv, s + 1);
         const float g0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), s));
         const float g1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), s + 1));
         const uint32_t j = static_cast<uint32_t>(upper ? j1 : j0);
         gg = upper ? g1 : g0;
-        if constexpr (INTERLEAVED) {
-            const uint32_t off = j * D + T2 * li;
-            if constexpr (sizeof(T) == 4 && T2 == 2) {
-                const float2 kx = *reinterpret_cast<const float2*>(Kb + off);
-                const float2 vx = *reinterpret_cast<const float2*>(Vb + off);
-                kk[0] = kx.x; kk[1] = kx.y; vv[0] = vx.x; vv[1] = vx.y;
-            } else if constexpr (sizeof(T) == 2 && T2 == 2) {
-                const uint32_t kx = *reinterpret_cast<const uint32_t*>(Kb + off);
-                const uint32_t vx = *reinterpret_cast<const uint32_t*>(Vb + off);
-                kk[0] = __uint_as_float(kx << 16); kk[1] = __uint_as_float(kx & 0xffff0000u);
-                vv[0] = __uint_as_float(vx << 16); vv[1] = __uint_as_float(vx & 0xffff0000u);
-            } else {
-                kk[0] = to_float(Kb[off]); vv[0] = to_float(Vb[off]);
-            }
-        } else {
-#pragma unroll
-            for (int t = 0; t < T2; ++t) {
-                kk[t] = to_float(Kb[j * D + 32 * t + li]);
-                vv[t] = to_float(Vb[j * D + 32 * t + li]);
-            }
+        if constexpr (SCALED) {
+            const float e0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ev), s));
+            const float e1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ev), s + 1));
+            ee = upper ? e1 : e0;
         }
+        load_operand_elems<D, TA, INTERLEAVED>(Ab, j, li, aa);
+        load_operand_elems<D, TB, INTERLEAVED>(Bb, j, li, bb);
     };
 
     for (int32_t block = beg; block < end; block += 2 * kWave) {
@@ -125,11 +159,13 @@ __device__ __forceinline__ void bucket_first_contraction(const T* __restrict__ K
         const float va = vals[ea], vb_ = vals[eb];
         const float g_a = block + lane < end ? va : 0.0f;
         const float g_b = block + kWave + lane < end ? vb_ : 0.0f;
+        float e_a = 0.0f, e_b = 0.0f;
+        if constexpr (SCALED) { e_a = escale[j_a]; e_b = escale[j_b]; }
         const int pairs = min((end - block + 1) >> 1, kWave);      // pairs of this block
 
-        float kb[RING][T2], vb[RING][T2], gb[RING];
+        float ab[RING][T2], bb[RING][T2], gb[RING], eb_[RING];
 #pragma unroll
-        for (int u = 0; u < RING; ++u) row_load(j_a, g_a, 2 * u, kb[u], vb[u], gb[u]);
+        for (int u = 0; u < RING; ++u) row_load(j_a, g_a, e_a, 2 * u, ab[u], bb[u], gb[u], eb_[u]);
         for (int q0 = 0; q0 < pairs; q0 += RING) {
             // this round fetches pairs q0 + RING .. q0 + 2 RING - 1 of the block: lanes of j_a for pairs
             // below 32, of j_b above (past pair 63 the fetch is redundant and re-reads j_b's tail)
@@ -137,23 +173,27 @@ __device__ __forceinline__ void bucket_first_contraction(const T* __restrict__ K
             const bool second = ahead >= 32;
             const int32_t j_sel = second ? j_b : j_a;
             const float g_sel = second ? g_b : g_a;
+            const float e_sel = second ? e_b : e_a;
             const int lane0 = (2 * ahead) & (kWave - 1);
 #pragma unroll
             for (int u = 0; u < RING; ++u) {
                 if (q0 + u < pairs) {
-                    float a_op[T2];
+                    float a_op[T2], b_op[T2];
 #pragma unroll
                     for (int t = 0; t < T2; ++t) {
-                        a_op[t] = gb[u] * feature(kb[u][t], relu);
-                        zacc[t] += a_op[t];
+                        a_op[t] = WEIGHT_ON_A ? gb[u] * feature(ab[u][t], fmap) : ab[u][t];
+                        b_op[t] = WEIGHT_ON_A ? bb[u][t] : gb[u] * feature(bb[u][t], fmap);
+                        if constexpr (EXTRA == kExtraSumA) zacc[t] += a_op[t];
+                        if constexpr (EXTRA == kExtraSumB) zacc[t] += b_op[t];
+                        if constexpr (SCALED) zacc[t] = fmaf(eb_[u], b_op[t], zacc[t]);
                     }
 #pragma unroll
                     for (int a = 0; a < T2; ++a)
 #pragma unroll
                         for (int c = 0; c < T2; ++c)
-                            acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_op[a], vb[u][c], acc[a][c], 0, 0, 0);
+                            acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_op[a], b_op[c], acc[a][c], 0, 0, 0);
                 }
-                row_load(j_sel, g_sel, lane0 + 2 * u, kb[u], vb[u], gb[u]);     // into the slot just vacated
+                row_load(j_sel, g_sel, e_sel, lane0 + 2 * u, ab[u], bb[u], gb[u], eb_[u]);     // into the slot just vacated
                 __builtin_amdgcn_sched_barrier(0);
             }
         }

@@ -1,0 +1,457 @@
+// Gradients of GRF-masked linear attention (Eq. 7; Alg. 1 with learnable f) on gfx950.
+//
+// With v'_j = [v_j, 1], g'_i = [d_out_i / den_i, -(d_out_i . out_i) / den_i] and, per bucket l with
+// contributor list C_l and weights w_i = Phi_hat[i, l],
+//     S'_l = sum_j w_j phi(k_j) v'_j^T        T'_l = sum_i w_i phi(q_i) g'_i^T
+// the gradients are
+//     dphi(q_i) += w_i S'_l g'_i      dphi(k_i) += w_i T'_l v'_i      dv_i += w_i T_l^T phi(k_i)
+//     dPhi[i,l]  = phi(q_i) . (S'_l g'_i) + phi(k_i) . (T'_l v'_i)
+// for every i in C_l: as in the fused forward pass, the rows that consume a bucket are its contributors.
+//
+// Three passes, each one wavefront per (slice, bucket) running two MFMA contractions
+// (v_mfma_f32_32x32x2_f32) like the forward kernel; a pass differs in which rows feed which operand:
+//
+//   pass           first contraction ACC = A^T B            second contraction, per consumer i     streams out
+//   kQuerySide     A = V,        B = w phi(K), +sum B (z)    U_i = g_i ACC + gd_i z                 w_i U_i, phi(q_i).U_i
+//   kKeySide       A = G,        B = w phi(Q), +sum gd B (y) R_i = v_i ACC + y                      w_i R_i, phi(k_i).R_i
+//   kValueSide     A = w phi(Q), B = G                       X_i = (w_i phi(k_i)) ACC               X_i
+//
+// (ACC is S^T, T^T and T respectively: the second contraction always runs over the row index of ACC,
+// which is the index the accumulator registers of a lane enumerate.)  The streamed rows are summed per
+// output row in ascending-l order by a second kernel, so results are bitwise reproducible.
+#include "attention_common.hpp"
+
+namespace grf {
+
+enum : int { kQuerySide = 0, kKeySide = 1, kValueSide = 2 };
+
+// N consecutive elements starting at p (p aligned to N elements), widened to fp32.
+template <typename T, int N>
+__device__ __forceinline__ void load_elems(const T* __restrict__ p, float (&out)[N])
+{
+    if constexpr (sizeof(T) == 4) {
+        if constexpr (N == 1) {
+            out[0] = *reinterpret_cast<const float*>(p);
+        } else if constexpr (N == 2) {
+            const float2 v = *reinterpret_cast<const float2*>(p);
+            out[0] = v.x; out[1] = v.y;
+        } else {
+#pragma unroll
+            for (int k = 0; k < N / 4; ++k) {
+                const float4 v = reinterpret_cast<const float4*>(p)[k];
+                out[4 * k] = v.x; out[4 * k + 1] = v.y; out[4 * k + 2] = v.z; out[4 * k + 3] = v.w;
+            }
+        }
+    } else {
+        if constexpr (N == 1) {
+            out[0] = __uint_as_float(static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(p)) << 16);
+        } else {
+            uint32_t w[N / 2];
+            if constexpr (N == 2) {
+                w[0] = *reinterpret_cast<const uint32_t*>(p);
+            } else if constexpr (N == 4) {
+                const uint2 v = *reinterpret_cast<const uint2*>(p);
+                w[0] = v.x; w[1] = v.y;
+            } else {
+                const uint4 v = *reinterpret_cast<const uint4*>(p);
+                w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+            }
+#pragma unroll
+            for (int k = 0; k < N / 2; ++k) {
+                out[2 * k] = __uint_as_float(w[k] << 16);
+                out[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u);
+            }
+        }
+    }
+}
+
+// g' per row of a chunk of slices: G[s][i][:] = d_out / den, gd[s][i] = -(d_out . out) / den.
+template <int D>
+__global__ __launch_bounds__(256) void backward_seed_kernel(const float* __restrict__ out, const float* __restrict__ den,
+                                                            const float* __restrict__ d_out, long long first_row, long long n_rows,
+                                                            float* __restrict__ G, float* __restrict__ gd)
+{
+    constexpr int RPW = kWave / D;        // rows per wavefront
+    const long long wave = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const int lane = lane_id();
+    const long long r = wave * RPW + lane / D;      // row inside the chunk
+    const int c = lane % D;
+    const bool ok = r < n_rows;
+    const long long src = (first_row + (ok ? r : 0)) * D + c;
+    const float dn = den[first_row + (ok ? r : 0)];
+    const float go = d_out[src];
+    float dot = go * out[src];
+#pragma unroll
+    for (int off = 1; off < D; off <<= 1) dot += __shfl_xor(dot, off, kWave);
+    if (ok) {
+        G[r * D + c] = go / dn;
+        if (c == 0) gd[r] = -dot / dn;
+    }
+}
+
+// One wavefront per (slice, bucket l), one wavefront per workgroup.  Every global load is
+// unconditional (lanes past the end of the column list re-read its last entry with weight 0).
+template <int D, typename T, int MODE>
+__global__ __launch_bounds__(64) void backward_bucket_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+                                                              const float* __restrict__ G, const float* __restrict__ gd,
+                                                              long long n, int H, int n_f,
+                                                              const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
+                                                              const float* __restrict__ csc_val,
+                                                              int fmap, long long bh_first, long long n_waves, int32_t nnz,
+                                                              float* __restrict__ partial, float* __restrict__ dphi_csc)
+{
+    constexpr int T2 = D / 32;
+    constexpr int QN = 4 * T2;     // operand elements a lane holds per group of four accumulator registers
+    const long long wave = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    if (wave >= n_waves) return;
+    const long long slice = wave / n;
+    const long long l = wave - slice * n;
+    const long long bh = bh_first + slice;
+    const long long plane = n_f > 1 ? (bh % H) : 0;
+    const T* Qb = Q + bh * n * D;
+    const T* Kb = K + bh * n * D;
+    const T* Vb = V + bh * n * D;
+    const float* Gb = G + slice * n * D;
+    const float* gdb = gd + slice * n;
+    const float* vals = csc_val + plane * nnz;
+
+    const int lane = lane_id();
+    const int half = lane >> 5;
+    const int li = lane & 31;
+
+    const int32_t beg = __builtin_amdgcn_readfirstlane(col_ptr[l]);
+    const int32_t end = __builtin_amdgcn_readfirstlane(col_ptr[l + 1]);
+    if (beg >= end) return;
+
+    // ---- first contraction
+    floatx16 acc[T2][T2];
+    float xacc[T2];
+    if constexpr (MODE == kQuerySide)
+        bucket_first_contraction<D, T, T, true, false, kExtraSumB>(Vb, Kb, csc_row, vals, nullptr, beg, end, fmap, acc, xacc);
+    else if constexpr (MODE == kKeySide)
+        bucket_first_contraction<D, float, T, true, false, kExtraScaledSumB>(Gb, Qb, csc_row, vals, gdb, beg, end, fmap, acc, xacc);
+    else
+        bucket_first_contraction<D, T, float, true, true, kExtraNone>(Qb, Gb, csc_row, vals, nullptr, beg, end, fmap, acc, xacc);
+
+    // the extra row, complete in the lower half-wave and zero in the upper, so that one more MFMA step
+    // (k = 0: the consumer's coefficient, k = 1: nothing) adds coefficient_i * extra to the output tile
+    float extra[T2];
+#pragma unroll
+    for (int t = 0; t < T2; ++t) {
+        const float full = xacc[t] + __shfl_xor(xacc[t], 32, kWave);
+        extra[t] = half == 0 ? full : 0.0f;
+    }
+
+    // ---- second contraction, 32 consumers at a time
+    const long long pbase = slice * static_cast<long long>(nnz);
+    for (int32_t tile = beg; tile < end; tile += 32) {
+        // consumer li of this tile: row, weight; its operand elements for the accumulator rows this lane pairs with
+        const int32_t pos = min(tile + li, end - 1);
+        const int32_t row = csc_row[pos];
+        const float w = tile + li < end ? vals[pos] : 0.0f;
+        float cop[4][QN];
+        float coef = 0.0f;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const long long off = static_cast<long long>(row) * D + T2 * (8 * b + 4 * half);
+            if constexpr (MODE == kQuerySide) load_elems<float, QN>(Gb + off, cop[b]);
+            if constexpr (MODE == kKeySide) load_elems<T, QN>(Vb + off, cop[b]);
+            if constexpr (MODE == kValueSide) load_elems<T, QN>(Kb + off, cop[b]);
+        }
+        if constexpr (MODE == kQuerySide) coef = half == 0 ? gdb[row] : 0.0f;
+        if constexpr (MODE == kKeySide) coef = half == 0 ? 1.0f : 0.0f;
+        if constexpr (MODE == kValueSide) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int e2 = 0; e2 < QN; ++e2) cop[b][e2] = w * feature(cop[b][e2], fmap);
+        }
+
+        // rows and weights of the 16 consumers this lane holds output for, and (query / key side) the
+        // elements of phi(q) / phi(k) of those consumers at this lane's output columns
+        int32_t orow[16];
+        float ow[16];
+        float xr[16][T2];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int c = 8 * (r / 4) + 4 * half + (r % 4);
+            orow[r] = __shfl(row, c, kWave);
+            ow[r] = __shfl(w, c, kWave);
+            if constexpr (MODE == kQuerySide) load_elems<T, T2>(Qb + static_cast<long long>(orow[r]) * D + T2 * li, xr[r]);
+            if constexpr (MODE == kKeySide) load_elems<T, T2>(Kb + static_cast<long long>(orow[r]) * D + T2 * li, xr[r]);
+        }
+
+        __builtin_amdgcn_sched_barrier(0);
+
+        floatx16 pc[T2];
+#pragma unroll
+        for (int c = 0; c < T2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) pc[c][r] = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+#pragma unroll
+            for (int t = 0; t < T2; ++t)
+#pragma unroll
+                for (int c = 0; c < T2; ++c)
+                    pc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(cop[r / 4][T2 * (r % 4) + t], acc[t][c][r], pc[c], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (MODE != kValueSide) {
+#pragma unroll
+            for (int c = 0; c < T2; ++c)
+                pc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(coef, extra[c], pc[c], 0, 0, 0);
+        }
+
+        // ---- stream out: register r of pc[c] is consumer 8*(r/4) + 4*half + r%4, output column T2*li + c
+        float s[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int32_t ppos = tile + 8 * (r / 4) + 4 * half + (r % 4);
+            float o[T2];
+            s[r] = 0.0f;
+#pragma unroll
+            for (int c = 0; c < T2; ++c) {
+                if constexpr (MODE == kValueSide) {
+                    o[c] = pc[c][r];
+                } else {
+                    o[c] = ow[r] * pc[c][r];
+                    s[r] = fmaf(feature(xr[r][c], fmap), pc[c][r], s[r]);
+                }
+            }
+            if (ppos < end) {
+                float* dst = partial + (pbase + ppos) * D + T2 * li;
+                if constexpr (T2 == 2) {
+                    *reinterpret_cast<float2*>(dst) = make_float2(o[0], o[1]);
+                } else {
+                    dst[0] = o[0];
+                }
+            }
+        }
+        if constexpr (MODE != kValueSide) {
+            // sum s[r] over the 32 lanes of the half-wave: each step halves the number of values a lane
+            // keeps and exchanges the other half with the lane that keeps those
+#pragma unroll
+            for (int cnt = 8, bit = 16; cnt >= 1; cnt >>= 1, bit >>= 1) {
+                const bool up = (li & bit) != 0;
+#pragma unroll
+                for (int k = 0; k < cnt; ++k) {
+                    const float keep = up ? s[k + cnt] : s[k];
+                    const float send = up ? s[k] : s[k + cnt];
+                    s[k] = keep + __shfl_xor(send, bit, kWave);
+                }
+            }
+            s[0] += __shfl_xor(s[0], 1, kWave);
+            // this lane now holds register index r = li / 2 (bits 4..1 of li)
+            const int r = li >> 1;
+            const int32_t ppos = tile + 8 * (r / 4) + 4 * half + (r % 4);
+            if ((li & 1) == 0 && ppos < end) dphi_csc[pbase + ppos] = s[0];
+        }
+    }
+}
+
+// One wavefront per (slice, row i): sums the row's streamed partial rows in ascending-l order and,
+// for the gradients of Q and K, multiplies by phi'(x) of the row's own elements.
+template <int D, typename T, bool THROUGH_FEATURE_MAP>
+__global__ __launch_bounds__(256) void backward_reduce_kernel(long long n, const int32_t* __restrict__ row_ptr,
+                                                              const int32_t* __restrict__ csr_to_csc, int32_t nnz,
+                                                              const float* __restrict__ partial, const T* __restrict__ src, int fmap,
+                                                              long long bh_first, long long n_waves, float* __restrict__ dst)
+{
+    constexpr int EPW = kWave / D;     // entries per wavefront step (1 at d = 64, 2 at d = 32)
+    const long long wave = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (wave >= n_waves) return;
+    const long long slice = wave / n;
+    const long long i = wave - slice * n;
+    const long long bh = bh_first + slice;
+    const int lane = lane_id();
+    const int sub = lane / D;
+    const int c = lane % D;
+    const float* slice_partial = partial + slice * static_cast<long long>(nnz) * D;
+
+    const int32_t beg = max(row_ptr[i], 0);
+    const int32_t end = min(row_ptr[i + 1], nnz);
+    float acc = 0.0f;
+    for (int32_t chunk = beg; chunk < end; chunk += kWave) {
+        const int32_t e = chunk + lane;
+        const int32_t pos_reg = e < end ? csr_to_csc[e] : -1;
+        const int cnt = min(kWave, end - chunk);
+        for (int t0 = 0; t0 < cnt; t0 += 8 * EPW) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int t = t0 + u * EPW + sub;
+                const int32_t pos = __shfl(pos_reg, t & (kWave - 1), kWave);
+                const bool ok = t < cnt && pos >= 0;
+                v[u] = ok ? slice_partial[static_cast<long long>(pos) * D + c] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+    }
+    if constexpr (EPW == 2) acc += __shfl_xor(acc, 32, kWave);
+    if (sub == 0) {
+        const long long o = (bh * n + i) * D + c;
+        if constexpr (THROUGH_FEATURE_MAP) acc *= feature_grad(to_float(src[o]), fmap);
+        dst[o] = acc;
+    }
+}
+
+// dphi_val[h][e] (+)= sum over the slices of this chunk that use plane h of the two per-entry terms.
+__global__ __launch_bounds__(256) void dphi_accumulate_kernel(long long nnz, int n_f, int H, long long bh_first, long long n_slices,
+                                                              const int32_t* __restrict__ csr_to_csc,
+                                                              const float* __restrict__ d_query, const float* __restrict__ d_key,
+                                                              long long val_stride, int first_chunk, float* __restrict__ dphi_val)
+{
+    const long long e = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int h = blockIdx.y;
+    if (e >= nnz) return;
+    const int32_t pos = csr_to_csc[e];
+    float acc = first_chunk ? 0.0f : dphi_val[h * val_stride + e];
+    if (pos >= 0) {
+        for (long long s = 0; s < n_slices; ++s) {
+            const long long bh = bh_first + s;
+            if (n_f > 1 && bh % H != h) continue;
+            acc += d_query[s * nnz + pos] + d_key[s * nnz + pos];
+        }
+    }
+    dphi_val[h * val_stride + e] = acc;
+}
+
+namespace {
+
+struct BackwardScratch {
+    float* G;          // [chunk][n][d]
+    float* gd;         // [chunk][n]
+    float* partial;    // [chunk][nnz][d]
+    float* d_query;    // [chunk][nnz]
+    float* d_key;      // [chunk][nnz]
+    size_t bytes;
+};
+
+BackwardScratch carve_backward(unsigned char* ws, int64_t slices, int64_t n, int32_t d, int64_t nnz)
+{
+    BackwardScratch b;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { unsigned char* p = ws ? ws + off : nullptr; off += align_up(bytes); return reinterpret_cast<float*>(p); };
+    const size_t entries = static_cast<size_t>(nnz > 0 ? nnz : 1), rows = static_cast<size_t>(n > 0 ? n : 1), sl = static_cast<size_t>(slices > 0 ? slices : 1);
+    b.G = take(sizeof(float) * sl * rows * d);
+    b.gd = take(sizeof(float) * sl * rows);
+    b.partial = take(sizeof(float) * sl * entries * d);
+    b.d_query = take(sizeof(float) * sl * entries);
+    b.d_key = take(sizeof(float) * sl * entries);
+    b.bytes = off;
+    return b;
+}
+
+template <int D, typename T>
+grf_status launch_backward_chunk(const void* Qv, const void* Kv, const void* Vv, int64_t n, int64_t H, int32_t n_f,
+                                 const grf_phi* phi, int64_t nnz, const Transposed& t, const BackwardScratch& b, int fmap,
+                                 int64_t bh_first, int64_t n_slices, const float* out, const float* den, const float* d_out,
+                                 float* dQ, float* dK, float* dV, float* dphi_val, hipStream_t stream)
+{
+    const T* Q = static_cast<const T*>(Qv);
+    const T* K = static_cast<const T*>(Kv);
+    const T* V = static_cast<const T*>(Vv);
+    const long long waves = static_cast<long long>(n_slices) * n;
+    if (waves == 0) return GRF_OK;
+    const long long first_row = static_cast<long long>(bh_first) * n;
+    constexpr int RPW = kWave / D;
+    hipLaunchKernelGGL((backward_seed_kernel<D>), dim3(blocks_for((waves + RPW - 1) / RPW, 4)), dim3(256), 0, stream,
+                       out, den, d_out, first_row, waves, b.G, b.gd);
+    GRF_LAUNCH_CHECK("backward_seed_kernel");
+
+    const dim3 bucket_grid(blocks_for(waves, 1)), reduce_grid(blocks_for(waves, 4));
+    const int32_t* col_ptr = t.col_ptr;
+    const int32_t* s_row = t.s_row;
+    const float* s_val = t.s_val;
+    const int32_t* csr_to_csc = t.csr_to_csc;
+    const int32_t* row_ptr = phi->row_ptr;
+    const float* partial = b.partial;
+
+    hipLaunchKernelGGL((backward_bucket_kernel<D, T, kQuerySide>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
+                       static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n), static_cast<int>(H),
+                       static_cast<int>(n_f), col_ptr, s_row, s_val, fmap, static_cast<long long>(bh_first), waves,
+                       static_cast<int32_t>(nnz), b.partial, b.d_query);
+    GRF_LAUNCH_CHECK("backward_bucket_kernel<query side>");
+    hipLaunchKernelGGL((backward_reduce_kernel<D, T, true>), reduce_grid, dim3(256), 0, stream, static_cast<long long>(n), row_ptr,
+                       csr_to_csc, static_cast<int32_t>(nnz), partial, Q, fmap, static_cast<long long>(bh_first), waves, dQ);
+    GRF_LAUNCH_CHECK("backward_reduce_kernel<dQ>");
+
+    hipLaunchKernelGGL((backward_bucket_kernel<D, T, kKeySide>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
+                       static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n), static_cast<int>(H),
+                       static_cast<int>(n_f), col_ptr, s_row, s_val, fmap, static_cast<long long>(bh_first), waves,
+                       static_cast<int32_t>(nnz), b.partial, b.d_key);
+    GRF_LAUNCH_CHECK("backward_bucket_kernel<key side>");
+    hipLaunchKernelGGL((backward_reduce_kernel<D, T, true>), reduce_grid, dim3(256), 0, stream, static_cast<long long>(n), row_ptr,
+                       csr_to_csc, static_cast<int32_t>(nnz), partial, K, fmap, static_cast<long long>(bh_first), waves, dK);
+    GRF_LAUNCH_CHECK("backward_reduce_kernel<dK>");
+
+    hipLaunchKernelGGL((backward_bucket_kernel<D, T, kValueSide>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
+                       static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n), static_cast<int>(H),
+                       static_cast<int>(n_f), col_ptr, s_row, s_val, fmap, static_cast<long long>(bh_first), waves,
+                       static_cast<int32_t>(nnz), b.partial, static_cast<float*>(nullptr));
+    GRF_LAUNCH_CHECK("backward_bucket_kernel<value side>");
+    hipLaunchKernelGGL((backward_reduce_kernel<D, T, false>), reduce_grid, dim3(256), 0, stream, static_cast<long long>(n), row_ptr,
+                       csr_to_csc, static_cast<int32_t>(nnz), partial, V, fmap, static_cast<long long>(bh_first), waves, dV);
+    GRF_LAUNCH_CHECK("backward_reduce_kernel<dV>");
+
+    if (dphi_val != nullptr && nnz > 0) {
+        hipLaunchKernelGGL(dphi_accumulate_kernel, dim3(blocks_for(nnz, 256), static_cast<unsigned>(n_f)), dim3(256), 0, stream,
+                           static_cast<long long>(nnz), static_cast<int>(n_f), static_cast<int>(H), static_cast<long long>(bh_first),
+                           static_cast<long long>(n_slices), csr_to_csc, static_cast<const float*>(b.d_query),
+                           static_cast<const float*>(b.d_key), static_cast<long long>(phi->capacity), bh_first == 0 ? 1 : 0, dphi_val);
+        GRF_LAUNCH_CHECK("dphi_accumulate_kernel");
+    }
+    return GRF_OK;
+}
+
+}  // namespace
+}  // namespace grf
+
+using namespace grf;
+
+extern "C" size_t grf_attention_backward_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t n_f, int32_t bh_chunk)
+{
+    if (B < 0 || H < 0 || n < 0 || nnz < 0 || n_f < 1 || (d != 32 && d != 64)) return 0;
+    int64_t slices = B * H;
+    if (bh_chunk > 0 && bh_chunk < slices) slices = bh_chunk;
+    return carve_transposed(nullptr, n, nnz, n_f).bytes + carve_backward(nullptr, slices, n, d, nnz).bytes;
+}
+
+extern "C" grf_status grf_masked_linear_attention_backward(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                           int64_t B, int64_t H, int64_t n, int32_t d,
+                                                           const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                           const float* out, const float* den, const float* d_out,
+                                                           int32_t bh_chunk,
+                                                           void* workspace, size_t workspace_bytes, void* hip_stream,
+                                                           float* dQ, float* dK, float* dV, float* dphi_val)
+{
+    if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
+    if (B * H * n > 0 && (Q == nullptr || out == nullptr || den == nullptr || d_out == nullptr))
+        return fail(GRF_EINVAL, "Q / out / den / d_out is NULL");
+    if (B * H * n > 0 && (dQ == nullptr || dK == nullptr || dV == nullptr)) return fail(GRF_EINVAL, "dQ / dK / dV is NULL");
+    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_attention_backward_workspace_bytes(B, H, n, d, nnz, n_f, bh_chunk))) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (B * H * n == 0) {
+        // no slices: the gradient with respect to Phi_hat is zero
+        if (dphi_val != nullptr && nnz > 0)
+            for (int32_t h = 0; h < n_f; ++h)
+                if (grf_status st = fill_i32(reinterpret_cast<int32_t*>(dphi_val + static_cast<int64_t>(h) * phi->capacity), nnz, 0, stream)) return st;
+        return GRF_OK;
+    }
+    const int64_t slices = B * H;
+    const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    const Transposed t = carve_transposed(ws, n, nnz, n_f);
+    const BackwardScratch b = carve_backward(ws + t.bytes, step, n, d, nnz);
+    if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
+    for (int64_t first = 0; first < slices; first += step) {
+        const int64_t count = (slices - first < step) ? (slices - first) : step;
+        grf_status st = GRF_OK;
+        GRF_DISPATCH(d, dtype, (st = launch_backward_chunk<D_, T_>(Q, K, V, n, H, n_f, phi, nnz, t, b, feature_map, first, count,
+                                                                   out, den, d_out, dQ, dK, dV, dphi_val, stream)));
+        if (st != GRF_OK) return st;
+    }
+    return GRF_OK;
+}

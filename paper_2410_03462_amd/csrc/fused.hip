@@ -69,7 +69,7 @@ __global__ __launch_bounds__(64) void fused_bucket_kernel(const T* __restrict__ 
                                                            long long n, int H, int n_f,
                                                            const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
                                                            const float* __restrict__ csc_val,
-                                                           int relu, long long bh_first, long long n_waves, int32_t nnz,
+                                                           int fmap, long long bh_first, long long n_waves, int32_t nnz,
                                                            float* __restrict__ partial, float* __restrict__ pden)
 {
     constexpr int T2 = D / 32;
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(64) void fused_bucket_kernel(const T* __restrict__ 
     // ---- S_l = A^T V_l
     floatx16 acc[T2][T2];
     float zacc[T2];
-    bucket_first_contraction<D, T, true>(Kb, Vb, csc_row, vals, beg, end, relu, acc, zacc);
+    bucket_first_contraction<D, T, T, true, true, kExtraSumA>(Kb, Vb, csc_row, vals, nullptr, beg, end, fmap, acc, zacc);
 
     float zfull[T2];
 #pragma unroll
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(64) void fused_bucket_kernel(const T* __restrict__ 
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int e2 = 0; e2 < QN; ++e2) qv[b][e2] = gq_cur * feature(qn[b][e2], relu);
+            for (int e2 = 0; e2 < QN; ++e2) qv[b][e2] = gq_cur * feature(qn[b][e2], fmap);
         // next tile's rows of Q, and the indices of the tile after it
         fetch_q(qrow_next, qn);
         gq_cur = gq_next;
@@ -238,7 +238,7 @@ namespace {
 
 template <int D, typename T>
 grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, int64_t H, int32_t n_f, const grf_phi* phi,
-                        int64_t nnz, const Transposed& t, int relu, int64_t bh_first, int64_t n_slices,
+                        int64_t nnz, const Transposed& t, int fmap, int64_t bh_first, int64_t n_slices,
                         float* partial, float* pden, float* out, float* num_opt, float* den_opt, hipStream_t stream)
 {
     const long long waves = static_cast<long long>(n_slices) * n;
@@ -247,7 +247,7 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
                        static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                        static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
                        static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
-                       static_cast<const float*>(t.s_val), relu, static_cast<long long>(bh_first), waves,
+                       static_cast<const float*>(t.s_val), fmap, static_cast<long long>(bh_first), waves,
                        static_cast<int32_t>(nnz), partial, pden);
     GRF_LAUNCH_CHECK("fused_bucket_kernel");
     hipLaunchKernelGGL((fused_reduce_kernel<D>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream,
@@ -294,11 +294,11 @@ extern "C" grf_status grf_masked_linear_attention_fused(const void* Q, const voi
     float* partial = reinterpret_cast<float*>(ws + t.bytes);
     float* pden = reinterpret_cast<float*>(ws + t.bytes + partial_bytes(step, nnz, d));
     if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
-    const int relu = feature_map == GRF_PHI_RELU ? 1 : 0;
+    const int fmap = feature_map;
     for (int64_t first = 0; first < slices; first += step) {
         const int64_t count = (slices - first < step) ? (slices - first) : step;
         grf_status st = GRF_OK;
-        GRF_DISPATCH(d, dtype, (st = launch_fused<D_, T_>(Q, K, V, n, H, n_f, phi, nnz, t, relu, first, count, partial, pden,
+        GRF_DISPATCH(d, dtype, (st = launch_fused<D_, T_>(Q, K, V, n, H, n_f, phi, nnz, t, fmap, first, count, partial, pden,
                                                           out, num_opt, den_opt, stream)));
         if (st != GRF_OK) return st;
     }

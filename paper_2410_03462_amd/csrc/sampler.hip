@@ -96,12 +96,19 @@ __global__ __launch_bounds__(256) void walks_kernel(GraphView g, WalkLaw law, in
 // shop[cap] (2 B each) = 20 B per deposit.
 constexpr int kDepositBytes = 20;
 
-template <bool FILL>
+// MODE kCount: row_ptr[node] = number of entries of the row.  kFill: entries written at row_ptr[node].
+// kGrad: instead of values, the row's share of dL/df is written to df_part[node][n_f][f_len], where
+// dphi (read through val_out's slot, [n_f][val_stride]) holds dL/dPhi_hat per stored entry.
+enum : int { kCount = 0, kFill = 1, kGrad = 2 };
+
+template <int MODE>
 __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int n_walks, int f_len, int n_f,
                                                   const float* __restrict__ f, int cap,
                                                   int32_t* __restrict__ row_ptr, int32_t* __restrict__ col_out,
-                                                  float* __restrict__ val_out, long long val_stride)
+                                                  float* __restrict__ val_out, long long val_stride,
+                                                  const float* __restrict__ dphi, float* __restrict__ df_part)
 {
+    constexpr bool FILL = MODE == kFill;
     extern __shared__ __align__(16) unsigned char lds[];
     int32_t* dcol = reinterpret_cast<int32_t*>(lds);
     float* dload = reinterpret_cast<float*>(dcol + cap);
@@ -150,7 +157,7 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
     __syncthreads();
 
     // Runs of equal columns: the run head writes the merged entry.
-    const int32_t row_start = FILL ? row_ptr[node] : 0;
+    const int32_t row_start = MODE != kCount ? row_ptr[node] : 0;
     const float n_float = static_cast<float>(n_walks);
     int heads = 0;
     for (int r0 = 0; r0 < D; r0 += kWave) {
@@ -159,6 +166,11 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
         const int32_t c = valid ? scol[r] : -1;
         const bool head = valid && (r == 0 || scol[r - 1] != c);
         const unsigned long long mask = __ballot(head);
+        if (MODE == kGrad && valid) {
+            // entry of Phi_hat that deposit r belongs to: runs up to and including this lane, minus one
+            const int run = heads + prefix_popcount(mask) + (head ? 1 : 0) - 1;
+            dcol[r] = row_start + run;
+        }
         if (FILL && head) {
             const long long pos = static_cast<long long>(row_start) + heads + prefix_popcount(mask);
             col_out[pos] = c;
@@ -171,7 +183,42 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
         }
         heads += __popcll(mask);
     }
-    if (!FILL && lane == 0) row_ptr[node] = heads;
+    if (MODE == kCount && lane == 0) row_ptr[node] = heads;
+
+    if (MODE == kGrad) {
+        // dL/df[h][t] of this node = (1/n) sum over deposits with hop t of load * dphi[h][entry]; lane t walks
+        // the deposits in sorted order, so the sum has a fixed order
+        const int32_t row_end = row_ptr[node + 1];
+        for (int h = 0; h < n_f; ++h) {
+            __syncthreads();
+            for (int r = lane; r < D; r += kWave) {
+                const int32_t e = dcol[r];
+                dload[r] = (e >= 0 && e < row_end && e < val_stride) ? sload[r] * dphi[h * val_stride + e] : 0.0f;
+            }
+            __syncthreads();
+            for (int t = lane; t < f_len; t += kWave) {
+                float acc = 0.0f;
+                for (int r = 0; r < D; ++r) acc += shop[r] == t ? dload[r] : 0.0f;
+                df_part[(static_cast<long long>(node) * n_f + h) * f_len + t] = acc / n_float;
+            }
+        }
+    }
+}
+
+// df[x] = sum over nodes of df_part[node][x], x in [0, n_f * f_len): one workgroup per x, fixed order.
+__global__ __launch_bounds__(256) void df_reduce_kernel(const float* __restrict__ df_part, long long n, int width, float* __restrict__ df)
+{
+    __shared__ float part[256];
+    const int x = blockIdx.x;
+    float acc = 0.0f;
+    for (long long i = threadIdx.x; i < n; i += 256) acc += df_part[i * width + x];
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (static_cast<int>(threadIdx.x) < off) part[threadIdx.x] += part[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) df[x] = part[0];
 }
 
 // ------------------------------------------------------------------------------------ scan / fill
@@ -351,16 +398,16 @@ extern "C" grf_status grf_sample(const grf_graph* g, const float* f, int32_t f_l
     const int cap = static_cast<int>(cap_ll);
     const size_t lds = static_cast<size_t>(cap) * kDepositBytes;
     if (lds > 64 * 1024) {
-        GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
-        GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+        GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_kernel<kCount>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+        GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_kernel<kFill>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
     }
     const GraphView gv = view_of(g);
     const dim3 grid(static_cast<unsigned>(g->n));
 
     // pass 1: entries per row, then offsets
-    hipLaunchKernelGGL(rows_kernel<false>, grid, dim3(kWave), lds, stream, gv, law, n_walks, f_len, n_f,
+    hipLaunchKernelGGL(rows_kernel<kCount>, grid, dim3(kWave), lds, stream, gv, law, n_walks, f_len, n_f,
                        static_cast<const float*>(f_dev), cap, phi_out->row_ptr, static_cast<int32_t*>(nullptr),
-                       static_cast<float*>(nullptr), 0ll);
+                       static_cast<float*>(nullptr), 0ll, static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
     GRF_LAUNCH_CHECK("rows_kernel<count>");
     if (grf_status st = exclusive_scan_inplace(phi_out->row_ptr, g->n, total_dev, stream)) return st;
     long long total = 0;
@@ -372,9 +419,57 @@ extern "C" grf_status grf_sample(const grf_graph* g, const float* f, int32_t f_l
         return fail(GRF_ECAPACITY, "Phi_hat has %lld entries but phi_out->capacity is %lld", total, (long long)phi_out->capacity);
 
     // pass 2: same walks again, entries written at their offsets
-    hipLaunchKernelGGL(rows_kernel<true>, grid, dim3(kWave), lds, stream, gv, law, n_walks, f_len, n_f,
+    hipLaunchKernelGGL(rows_kernel<kFill>, grid, dim3(kWave), lds, stream, gv, law, n_walks, f_len, n_f,
                        static_cast<const float*>(f_dev), cap, phi_out->row_ptr, phi_out->col, phi_out->val,
-                       static_cast<long long>(phi_out->capacity));
+                       static_cast<long long>(phi_out->capacity), static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
     GRF_LAUNCH_CHECK("rows_kernel<fill>");
+    return GRF_OK;
+}
+
+extern "C" size_t grf_sample_backward_workspace_bytes(int64_t n, int32_t f_len, int32_t n_f)
+{
+    if (n < 0 || f_len < 1 || n_f < 1) return 0;
+    return align_up(sizeof(float) * static_cast<size_t>(n > 0 ? n : 1) * static_cast<size_t>(n_f) * static_cast<size_t>(f_len));
+}
+
+extern "C" grf_status grf_sample_backward(const grf_graph* g, int32_t f_len, int32_t n_f,
+                                          double p_halt, int32_t n_walks, uint64_t seed,
+                                          const grf_phi* phi, int64_t nnz, const float* dphi_val,
+                                          void* workspace, size_t workspace_bytes, void* hip_stream, float* df)
+{
+    if (grf_status st = check_graph(g)) return st;
+    if (f_len < 1 || n_f < 1 || n_walks < 1)
+        return fail(GRF_EINVAL, "f_len=%d, n_f=%d, n_walks=%d must all be >= 1", f_len, n_f, n_walks);
+    if (f_len > 65535) return fail(GRF_EUNSUPPORTED, "f_len=%d exceeds 65535", f_len);
+    WalkLaw law;
+    if (grf_status st = make_law(p_halt, seed, &law)) return st;
+    if (phi == nullptr || df == nullptr) return fail(GRF_EINVAL, "phi / df is NULL");
+    if (phi->n != g->n) return fail(GRF_EINVAL, "phi->n=%lld differs from graph n=%lld", (long long)phi->n, (long long)g->n);
+    if (nnz < 0 || nnz > phi->capacity || nnz >= 2147483647ll) return fail(GRF_EINVAL, "nnz=%lld must lie in [0, phi->capacity=%lld]", (long long)nnz, (long long)phi->capacity);
+    if (phi->row_ptr == nullptr || (nnz > 0 && dphi_val == nullptr)) return fail(GRF_EINVAL, "phi->row_ptr / dphi_val is NULL");
+    const long long cap_ll = 1 + static_cast<long long>(n_walks) * (f_len - 1);
+    if (cap_ll > kMaxDeposits)
+        return fail(GRF_EUNSUPPORTED, "1 + n_walks*(f_len-1) = %lld deposits per node exceed the %d that fit in LDS", cap_ll, kMaxDeposits);
+    const size_t need = grf_sample_backward_workspace_bytes(g->n, f_len, n_f);
+    if (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
+        return fail(GRF_EWORKSPACE, "workspace must be non-NULL, 256-byte aligned and >= %zu bytes (got %zu)", need, workspace_bytes);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int width = n_f * f_len;
+    if (g->n == 0) {
+        if (grf_status st = fill_i32(reinterpret_cast<int32_t*>(df), width, 0, stream)) return st;
+        return GRF_OK;
+    }
+    float* df_part = static_cast<float*>(workspace);
+    const int cap = static_cast<int>(cap_ll);
+    const size_t lds = static_cast<size_t>(cap) * kDepositBytes;
+    if (lds > 64 * 1024)
+        GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_kernel<kGrad>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+    hipLaunchKernelGGL(rows_kernel<kGrad>, dim3(static_cast<unsigned>(g->n)), dim3(kWave), lds, stream, view_of(g), law, n_walks, f_len, n_f,
+                       static_cast<const float*>(nullptr), cap, phi->row_ptr, static_cast<int32_t*>(nullptr),
+                       static_cast<float*>(nullptr), static_cast<long long>(phi->capacity), dphi_val, df_part);
+    GRF_LAUNCH_CHECK("rows_kernel<grad>");
+    hipLaunchKernelGGL(df_reduce_kernel, dim3(static_cast<unsigned>(width)), dim3(256), 0, stream,
+                       static_cast<const float*>(df_part), static_cast<long long>(g->n), width, df);
+    GRF_LAUNCH_CHECK("df_reduce_kernel");
     return GRF_OK;
 }

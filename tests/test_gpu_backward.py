@@ -1,0 +1,218 @@
+"""Gradients of the HIP library against the CPU checker on identical seeded inputs (needs the GPU).
+
+Both sides receive the same saved forward results (the checker's out and den rounded to fp32), so the
+comparison isolates the backward arithmetic.  Bars as for the forward pass: 1e-5 (fp32) / 2e-2 (bf16
+inputs) in the norm  max|x - ref| / max|ref|  per tensor.
+"""
+import numpy as np
+import pytest
+
+from paper_2410_03462_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-5
+TOL_BF16 = 2e-2
+FEATURE_MAP_CODE = {"relu": 0, "identity": 1, "elu1": 2}
+
+
+@pytest.fixture(scope="module")
+def grf():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2410_03462_amd import binding
+    binding.lib()
+    return binding
+
+
+def relerr(x, ref):
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    scale = np.abs(ref).max()
+    return float(np.abs(x - ref).max() / scale) if scale > 0 else float(np.abs(x).max())
+
+
+def to_dev(x, dtype="f32"):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def small_workloads():
+    rng = np.random.default_rng(321)
+    yield "tiny_grid", synth.workload("tiny_grid")
+    wl = synth.workload("vit_grid"); wl.B, wl.H = 1, 2
+    yield "vit_grid_b1h2", wl
+    g = synth.random_graph(777, 6.0, rng, weights="sym_norm", isolated=5)       # ragged size, isolated nodes
+    yield "random_777", synth.Workload("random_777", g, synth.modulation(9, rng), 0.3, 11, 2, 2, 64, "f32")
+    g = synth.star_graph(300)                                                   # one hub column of ~all rows: many consumer tiles
+    yield "star_300", synth.Workload("star_300", g, synth.modulation(6, rng), 0.35, 5, 1, 2, 32, "f32")
+    g = synth.knn_graph(synth.uniform_points(2000, rng), 8, "gauss")
+    yield "cloud_2k_perhead_bf16", synth.Workload("cloud_2k", g, synth.modulation(12, rng, n_f=3), 0.25, 16, 2, 3, 64, "bf16")
+
+
+SMALL = dict(small_workloads())
+
+
+def saved_forward(oracle, wl, rp, col, val, fm):
+    Q, K, V = wl.qkv()
+    fwd = oracle.masked_linear_attention(Q, K, V, rp, col, val, feature_map=fm)
+    with np.errstate(invalid="ignore", over="ignore"):
+        return Q, K, V, fwd["out"].astype(np.float32), fwd["den"].astype(np.float32)
+
+
+def compare_backward(grf, oracle, wl, feature_map="relu", bh_chunk=0):
+    import torch
+    fm = FEATURE_MAP_CODE[feature_map]
+    tol = TOL_BF16 if wl.dtype == "bf16" else TOL_F32
+    rp, col, val = oracle.sample(wl.graph, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+    Q, K, V, out32, den32 = saved_forward(oracle, wl, rp, col, val, fm)
+    ok_rows = np.isfinite(out32).all(axis=-1) & (den32 != 0)
+    assert ok_rows.all(), "workload has a zero denominator: pick another seed for this test"
+    d_out = np.random.default_rng(99).standard_normal(Q.shape).astype(np.float32)
+    ref = oracle.masked_linear_attention_backward(Q, K, V, rp, col, val, out32, den32, d_out, fm)
+
+    phi = grf.Phi.from_host(wl.graph.n, rp, col, val)
+    Qd, Kd, Vd = (to_dev(x, wl.dtype) for x in (Q, K, V))
+    got = grf.grf_masked_linear_attention_backward(Qd, Kd, Vd, phi, to_dev(out32), to_dev(den32), to_dev(d_out),
+                                                   feature_map, bh_chunk=bh_chunk)
+    names = ("dQ", "dK", "dV", "dphi")
+    host = [t.cpu().numpy() for t in got]
+    host[3] = host[3][:, : phi.nnz]
+    for name, x, r in zip(names, host, ref):
+        assert np.isfinite(x).all(), name
+        assert relerr(x, r) <= tol, (name, relerr(x, r))
+
+    # df through the sampler's backward, fed with the GPU's own dphi; reference: the checker's chain
+    g = grf.DeviceGraph.from_host(wl.graph)
+    df = grf.grf_sample_backward(g, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, phi, got[3]).cpu().numpy()
+    df_ref = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp, col, ref[3])
+    assert df.shape == df_ref.shape
+    for h in range(wl.n_f):
+        assert relerr(df[h], df_ref[h]) <= 10 * tol, (h, relerr(df[h], df_ref[h]))
+    return host, df
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_backward_parity(grf, oracle, name):
+    compare_backward(grf, oracle, SMALL[name])
+
+
+@pytest.mark.parametrize("feature_map", ["identity", "elu1"])
+def test_backward_other_feature_maps(grf, oracle, feature_map):
+    compare_backward(grf, oracle, SMALL["random_777"], feature_map)
+    compare_backward(grf, oracle, SMALL["cloud_2k_perhead_bf16"], feature_map)
+
+
+def test_backward_chunking_and_determinism(grf, oracle):
+    wl = SMALL["random_777"]
+    full, df = compare_backward(grf, oracle, wl, "elu1")
+    again, df2 = compare_backward(grf, oracle, wl, "elu1")
+    part, df3 = compare_backward(grf, oracle, wl, "elu1", bh_chunk=3)
+    for a, b, c in zip(full, again, part):
+        assert np.array_equal(a, b)
+        assert np.array_equal(a[..., :1], c[..., :1]) or relerr(c, a) <= 1e-6     # dphi sums slices chunk by chunk
+    assert np.array_equal(df, df2)
+    for a, c in zip(full[:3], part[:3]):
+        assert np.array_equal(a, c)
+
+
+def test_sample_backward_alone(grf, oracle):
+    """The sampler's backward on a synthetic dphi: several planes, ragged graph, f_len above the walk count."""
+    rng = np.random.default_rng(17)
+    g_host = synth.random_graph(513, 5.0, rng, weights="sym_norm", isolated=3)
+    f = synth.modulation(11, rng, n_f=4)
+    rp, col, val = oracle.sample(g_host, f, 0.2, 6, 5)
+    dphi = rng.standard_normal(val.shape).astype(np.float32)
+    want = oracle.sample_backward(g_host, 11, 0.2, 6, 5, rp, col, dphi)
+    g = grf.DeviceGraph.from_host(g_host)
+    phi = grf.Phi.from_host(g_host.n, rp, col, val)
+    got = grf.grf_sample_backward(g, 11, 0.2, 6, 5, phi, to_dev(dphi)).cpu().numpy()
+    assert relerr(got, want) <= TOL_F32
+    # linear in dphi and exact for a one-hot dphi on the diagonal entry of node 7: only hop-0 deposits reach it
+    # unless a walk returns, so df[0] >= 1 / 1 and the rest is the returning walks' loads
+    e = int(rp[7] + np.searchsorted(col[rp[7]:rp[7 + 1]], 7))
+    onehot = np.zeros_like(dphi); onehot[:, e] = 1.0
+    got1 = grf.grf_sample_backward(g, 11, 0.2, 6, 5, phi, to_dev(onehot)).cpu().numpy()
+    want1 = oracle.sample_backward(g_host, 11, 0.2, 6, 5, rp, col, onehot)
+    assert relerr(got1, want1) <= TOL_F32
+    assert abs(got1[0, 0] - 1.0) <= 1e-6
+
+
+def test_backward_argument_errors(grf):
+    import torch
+    n = 64
+    phi = grf.Phi.from_host(n, np.arange(n + 1), np.arange(n), np.ones((1, n), np.float32))
+    x = torch.ones((1, 2, n, 64), device="cuda:0")
+    den = torch.ones((1, 2, n), device="cuda:0")
+    with pytest.raises(grf.GrfError) as e:
+        grf.grf_masked_linear_attention_backward(x, x, x, phi, x, den, x, workspace=torch.empty(256, dtype=torch.uint8, device="cuda:0"))
+    assert e.value.status == grf.GRF_EWORKSPACE
+    with pytest.raises(ValueError):
+        grf.grf_masked_linear_attention_backward(x, x, x, phi, x, den[:, :1], x)
+    e0 = torch.zeros((0, 2, n, 64), device="cuda:0")
+    d0 = torch.zeros((0, 2, n), device="cuda:0")
+    dQ, dK, dV, dphi = grf.grf_masked_linear_attention_backward(e0, e0, e0, phi, e0, d0, e0)
+    assert dQ.shape == (0, 2, n, 64) and torch.all(dphi == 0)
+
+
+def test_backward_headline_workload_full_size(grf, oracle):
+    """cloud_32k in the launch configuration the benchmark times.
+
+    Part 1, against the checker: the backward call is a function of (Q, K, V, Phi_hat, out, den, d_out); with seeded
+    synthetic out and den (signed, spread over two decades) sampled rows of dQ, dK, dV are compared with Eq. (2)
+    differentiated directly and sampled entries of dphi with their two buckets.
+    Part 2, properties of the HIP results alone: with out and den from the HIP forward pass, Euler's identities
+    (out is of degree 0 in Phi_hat and linear in V) hold.
+    Part 3: the sampler's backward at full size on a synthetic dphi against the checker."""
+    import torch
+    wl = synth.workload("cloud_32k")
+    rp, col, val = oracle.sample(wl.graph, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+    Q, K, V = wl.qkv()
+    phi = grf.Phi.from_host(wl.graph.n, rp, col, val)
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    rng = np.random.default_rng(5)
+    d_out_h = rng.standard_normal(Q.shape).astype(np.float32)
+    out_s = rng.standard_normal(Q.shape).astype(np.float32)
+    den_s = (np.exp(rng.standard_normal(Q.shape[:3])) * rng.choice([-1.0, 1.0], size=Q.shape[:3])).astype(np.float32)
+    d_out = to_dev(d_out_h)
+    dQ, dK, dV, dphi = grf.grf_masked_linear_attention_backward(Qd, Kd, Vd, phi, to_dev(out_s), to_dev(den_s), d_out)
+    dQ_h, dK_h, dV_h, dphi_h = dQ.cpu().numpy(), dK.cpu().numpy(), dV.cpu().numpy(), dphi.cpu().numpy()[0, : phi.nnz]
+    rows = np.random.default_rng(6).choice(wl.graph.n, size=10, replace=False)
+    gps = [oracle.backward_seed(out_s[0, h], den_s[0, h], d_out_h[0, h]) for h in range(8)]
+    for h in (0, 4, 7):
+        scales = [np.abs(x[0, h]).max() for x in (dQ_h, dK_h, dV_h)]
+        for i in rows:
+            ref = oracle.row_direct_backward(int(i), Q[0, h], K[0, h], V[0, h], rp, col, val[0], gps[h])
+            for got, want, sc in zip((dQ_h, dK_h, dV_h), ref, scales):
+                assert np.abs(got[0, h, i] - want).max() <= TOL_F32 * sc
+    # entries of dphi: the plane is shared by the 8 heads, so the reference sums the heads
+    ents = np.random.default_rng(7).choice(phi.nnz, size=6, replace=False)
+    erow = np.searchsorted(rp, ents, side="right") - 1
+    for e, i in zip(ents, erow):
+        want = sum(oracle.dphi_entry_direct(int(i), int(col[e]), Q[0, h], K[0, h], V[0, h], rp, col, val[0], gps[h]) for h in range(8))
+        assert abs(dphi_h[e] - want) <= TOL_F32 * np.abs(dphi_h).max()
+    del dQ, dK, dV, dphi
+
+    out, _, den = grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, return_num_den=True)
+    dQ, dK, dV, dphi = grf.grf_masked_linear_attention_backward(Qd, Kd, Vd, phi, out, den, d_out)
+    dphi_p = dphi[0, : phi.nnz].double().cpu().numpy()
+    a = val[0].astype(np.float64) * dphi_p
+    assert abs(a.sum()) <= 1e-4 * np.abs(a).sum()
+    dV_p = dV.double().cpu().numpy()
+    lhs = (V.astype(np.float64) * dV_p).sum()
+    rhs = float((d_out.double() * out.double()).sum())
+    assert abs(lhs - rhs) <= 1e-4 * np.abs(V * dV_p).sum()
+    q = (Q.astype(np.float64) * dQ.double().cpu().numpy())          # ReLU is positively homogeneous: degree 0 in Q and in K
+    assert abs(q.sum()) <= 1e-4 * np.abs(q).sum()
+    k = (K.astype(np.float64) * dK.double().cpu().numpy())
+    assert abs(k.sum()) <= 1e-4 * np.abs(k).sum()
+
+    g = grf.DeviceGraph.from_host(wl.graph)
+    synth_dphi = np.random.default_rng(8).standard_normal((1, phi.nnz)).astype(np.float32)
+    df = grf.grf_sample_backward(g, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, phi, to_dev(synth_dphi)).cpu().numpy()
+    df_ref = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp, col, synth_dphi)
+    assert relerr(df, df_ref) <= TOL_F32
+    del out, den, dQ, dK, dV, dphi
+    torch.cuda.empty_cache()

@@ -16,6 +16,7 @@ TOL_BF16 = 2e-2
 # out = num/den amplifies the fp32 rounding of den by (sum of |terms|)/|den|; rows where that
 # factor exceeds 1/COND_MIN are compared through num and den only.
 COND_MIN = 0.05
+FEATURE_MAP_CODE = {"relu": 0, "identity": 1, "elu1": 2}      # the checker's codes
 
 
 @pytest.fixture(scope="module")
@@ -164,7 +165,7 @@ def _oracle_phi(oracle, wl):
 def _compare_attention(grf, oracle, wl, rp, col, val, feature_map="relu", bh_chunk=0):
     Q, K, V = wl.qkv()
     tol = TOL_BF16 if wl.dtype == "bf16" else TOL_F32
-    fm = oracle.RELU if feature_map == "relu" else oracle.IDENTITY
+    fm = FEATURE_MAP_CODE[feature_map]
     ref = oracle.masked_linear_attention(Q, K, V, rp, col, val, feature_map=fm, return_buckets=True)
     phi = grf.Phi.from_host(wl.graph.n, rp, col, val)
     Qd, Kd, Vd = (to_dev(x, wl.dtype) for x in (Q, K, V))
@@ -218,6 +219,24 @@ def test_attention_identity_feature_map_and_chunking(grf, oracle):
         part = _compare_attention(grf, oracle, wl, rp, col, val, feature_map="identity", bh_chunk=chunk)
         for a, b in zip(full, part):
             assert np.array_equal(np.nan_to_num(a), np.nan_to_num(b))
+
+
+@pytest.mark.parametrize("name", ["tiny_grid", "random_777", "cloud_2k_perhead_bf16"])
+def test_elu_plus_one_feature_map_all_variants(grf, oracle, name):
+    """phi = elu(x) + 1 (Alg. 1 step 3's other example) through the bucket + gather pair, the fused and the asymmetric kernels."""
+    wl = SMALL[name]
+    rp, col, val = _oracle_phi(oracle, wl)
+    _compare_attention(grf, oracle, wl, rp, col, val, feature_map="elu1")
+    _compare_fused(grf, oracle, wl, rp, col, val, feature_map="elu1")
+    tol = TOL_BF16 if wl.dtype == "bf16" else TOL_F32
+    g = grf.DeviceGraph.from_host(wl.graph)
+    phi = grf.grf_sample(g, wl.f[:1], wl.p_halt, wl.n_walks, wl.walk_seed)
+    Q, K, V = wl.qkv()
+    Qd, Kd, Vd = (to_dev(x, wl.dtype) for x in (Q, K, V))
+    _, num, den = grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi, "elu1", return_num_den=True)
+    ref = oracle.asymmetric_attention_walks(wl.graph, wl.f[0], wl.p_halt, wl.n_walks, wl.walk_seed, Q, K, V, feature_map=2)
+    assert relerr(num.cpu().numpy(), ref["num"]) <= tol
+    assert relerr(den.cpu().numpy(), ref["den"]) <= tol
 
 
 def test_attention_end_to_end_from_gpu_sample(grf, oracle):
@@ -370,7 +389,7 @@ def test_cloud_128k_bf16_per_head_full_size(grf, oracle):
 def _compare_fused(grf, oracle, wl, rp, col, val, feature_map="relu", bh_chunk=0):
     Q, K, V = wl.qkv()
     tol = TOL_BF16 if wl.dtype == "bf16" else TOL_F32
-    fm = oracle.RELU if feature_map == "relu" else oracle.IDENTITY
+    fm = FEATURE_MAP_CODE[feature_map]
     ref = oracle.masked_linear_attention(Q, K, V, rp, col, val, feature_map=fm)
     phi = grf.Phi.from_host(wl.graph.n, rp, col, val)
     Qd, Kd, Vd = (to_dev(x, wl.dtype) for x in (Q, K, V))
