@@ -112,7 +112,9 @@ __global__ __launch_bounds__(64) void buckets_kernel(const T* __restrict__ K, co
 
     floatx16 acc[T2][T2];
     float zacc[T2];
-    bucket_first_contraction<D, T, T, false, true, kExtraSumA>(Kb, Vb, csc_row, vals, nullptr, col_ptr[l], col_ptr[l + 1], fmap, acc, zacc);
+    with_feature_map(fmap, [&](auto fm) {
+        bucket_first_contraction<D, T, T, false, true, kExtraSumA, decltype(fm)::value>(Kb, Vb, csc_row, vals, nullptr, col_ptr[l], col_ptr[l + 1], acc, zacc);
+    });
 
     float* rec = buckets + (slice * n + l) * REC;
 #pragma unroll

@@ -2,6 +2,8 @@
 // Phi_hat (who contributes to / consumes bucket l) and host-side argument checks.
 #pragma once
 
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace grf {
@@ -20,6 +22,25 @@ __device__ __forceinline__ float feature(float x, int fmap)
     const float relu = __builtin_amdgcn_fmed3f(x, 0.0f, __builtin_inff());
     const float elu1 = x > 0.0f ? x + 1.0f : __expf(x);
     return fmap == GRF_PHI_RELU ? relu : (fmap == GRF_PHI_ELU1 ? elu1 : x);
+}
+
+// The same with the code known at compile time (the MFMA kernels' inner loops).
+template <int FM>
+__device__ __forceinline__ float feature_ct(float x)
+{
+    if constexpr (FM == GRF_PHI_RELU) return __builtin_amdgcn_fmed3f(x, 0.0f, __builtin_inff());
+    else if constexpr (FM == GRF_PHI_ELU1) return x > 0.0f ? x + 1.0f : __expf(x);
+    else return x;
+}
+
+// Runs body(std::integral_constant<int, code>) for the wave-uniform feature-map code `fmap`, so that
+// the body is compiled once per map and the map costs nothing inside it.
+template <typename Body>
+__device__ __forceinline__ void with_feature_map(int fmap, Body&& body)
+{
+    if (fmap == GRF_PHI_RELU) body(std::integral_constant<int, GRF_PHI_RELU>{});
+    else if (fmap == GRF_PHI_ELU1) body(std::integral_constant<int, GRF_PHI_ELU1>{});
+    else body(std::integral_constant<int, GRF_PHI_IDENTITY>{});
 }
 
 // d phi(x) / dx (ReLU: 0 at x = 0).
@@ -112,11 +133,11 @@ enum : int {
 //     a load skipped on one control path would force a full wait where the paths join;
 //   - a scheduling barrier per pair keeps each pair's fetch work next to the previous pair's MFMAs:
 //     an MFMA holds the matrix pipe for 64 cycles, in which the fetch instructions issue for free.
-template <int D, typename TA, typename TB, bool INTERLEAVED, bool WEIGHT_ON_A, int EXTRA>
+template <int D, typename TA, typename TB, bool INTERLEAVED, bool WEIGHT_ON_A, int EXTRA, int FM>
 __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ Ab, const TB* __restrict__ Bb,
                                                          const int32_t* __restrict__ csc_row, const float* __restrict__ vals,
                                                          const float* __restrict__ escale,
-                                                         int32_t beg_in, int32_t end_in, int fmap,
+                                                         int32_t beg_in, int32_t end_in,
                                                          floatx16 (&acc)[D / 32][D / 32], float (&zacc)[D / 32])
 {
     constexpr int T2 = D / 32;
@@ -181,8 +202,8 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
                     float a_op[T2], b_op[T2];
 #pragma unroll
                     for (int t = 0; t < T2; ++t) {
-                        a_op[t] = WEIGHT_ON_A ? gb[u] * feature(ab[u][t], fmap) : ab[u][t];
-                        b_op[t] = WEIGHT_ON_A ? bb[u][t] : gb[u] * feature(bb[u][t], fmap);
+                        a_op[t] = WEIGHT_ON_A ? gb[u] * feature_ct<FM>(ab[u][t]) : ab[u][t];
+                        b_op[t] = WEIGHT_ON_A ? bb[u][t] : gb[u] * feature_ct<FM>(bb[u][t]);
                         if constexpr (EXTRA == kExtraSumA) zacc[t] += a_op[t];
                         if constexpr (EXTRA == kExtraSumB) zacc[t] += b_op[t];
                         if constexpr (SCALED) zacc[t] = fmaf(eb_[u], b_op[t], zacc[t]);

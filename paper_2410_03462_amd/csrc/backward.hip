@@ -12,13 +12,17 @@
 // (v_mfma_f32_32x32x2_f32) like the forward kernel; a pass differs in which rows feed which operand:
 //
 //   pass           first contraction ACC = A^T B            second contraction, per consumer i     streams out
-//   kQuerySide     A = V,        B = w phi(K), +sum B (z)    U_i = g_i ACC + gd_i z                 w_i U_i, phi(q_i).U_i
-//   kKeySide       A = G,        B = w phi(Q), +sum gd B (y) R_i = v_i ACC + y                      w_i R_i, phi(k_i).R_i
+//   kQuerySide     A = V,        B = w phi(K), +sum B (z)    U_i = g_i ACC + gd_i z                 U_i
+//   kKeySide       A = G,        B = w phi(Q), +sum gd B (y) R_i = v_i ACC + y                      R_i
 //   kValueSide     A = w phi(Q), B = G                       X_i = (w_i phi(k_i)) ACC               X_i
 //
 // (ACC is S^T, T^T and T respectively: the second contraction always runs over the row index of ACC,
-// which is the index the accumulator registers of a lane enumerate.)  The streamed rows are summed per
-// output row in ascending-l order by a second kernel, so results are bitwise reproducible.
+// which is the index the accumulator registers of a lane enumerate.)  A second kernel, one wavefront per
+// output row, reads the row's streamed vectors in ascending-l order: it forms dphi(q_i) = sum_l w_il U_il
+// (likewise k; plain sum for v), and on the way the per-entry terms phi(q_i).U_il and phi(k_i).R_il of
+// dPhi.  Sums have a fixed order: results are bitwise reproducible and no float atomics are used.
+#include <type_traits>
+
 #include "attention_common.hpp"
 
 namespace grf {
@@ -98,7 +102,7 @@ __global__ __launch_bounds__(64) void backward_bucket_kernel(const T* __restrict
                                                               const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
                                                               const float* __restrict__ csc_val,
                                                               int fmap, long long bh_first, long long n_waves, int32_t nnz,
-                                                              float* __restrict__ partial, float* __restrict__ dphi_csc)
+                                                              float* __restrict__ partial)
 {
     constexpr int T2 = D / 32;
     constexpr int QN = 4 * T2;     // operand elements a lane holds per group of four accumulator registers
@@ -123,15 +127,46 @@ __global__ __launch_bounds__(64) void backward_bucket_kernel(const T* __restrict
     const int32_t end = __builtin_amdgcn_readfirstlane(col_ptr[l + 1]);
     if (beg >= end) return;
 
+    // consumers of tile `tile`: row index and weight of entry tile + li (clamped, weight 0 past the end)
+    auto fetch_index = [&](int32_t tile, int32_t& row, float& g) {
+        const int32_t pos = min(tile + li, end - 1);
+        row = csc_row[pos];
+        g = tile + li < end ? vals[pos] : 0.0f;
+    };
+    // consumer li's operand elements for the accumulator rows this lane pairs with, and its coefficient of the extra row
+    auto fetch_operand = [&](long long row, float (&cc)[4][QN], float& cf) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const long long off = row * D + T2 * (8 * b + 4 * half);
+            if constexpr (MODE == kQuerySide) load_elems<float, QN>(Gb + off, cc[b]);
+            if constexpr (MODE == kKeySide) load_elems<T, QN>(Vb + off, cc[b]);
+            if constexpr (MODE == kValueSide) load_elems<T, QN>(Kb + off, cc[b]);
+        }
+        if constexpr (MODE == kQuerySide) cf = gdb[row];
+    };
+
+    // the first two consumer tiles' indices and the first tile's operand rows go out before the first
+    // contraction starts, so that they have arrived when it ends
+    int32_t row_cur, row_next;
+    float w_cur, w_next;
+    fetch_index(beg, row_cur, w_cur);
+    fetch_index(beg + 32, row_next, w_next);
+    float cn[4][QN];
+    float cfn = 1.0f;
+    fetch_operand(row_cur, cn, cfn);
+
     // ---- first contraction
     floatx16 acc[T2][T2];
     float xacc[T2];
-    if constexpr (MODE == kQuerySide)
-        bucket_first_contraction<D, T, T, true, false, kExtraSumB>(Vb, Kb, csc_row, vals, nullptr, beg, end, fmap, acc, xacc);
-    else if constexpr (MODE == kKeySide)
-        bucket_first_contraction<D, float, T, true, false, kExtraScaledSumB>(Gb, Qb, csc_row, vals, gdb, beg, end, fmap, acc, xacc);
-    else
-        bucket_first_contraction<D, T, float, true, true, kExtraNone>(Qb, Gb, csc_row, vals, nullptr, beg, end, fmap, acc, xacc);
+    with_feature_map(fmap, [&](auto fm) {
+        constexpr int FM = decltype(fm)::value;
+        if constexpr (MODE == kQuerySide)
+            bucket_first_contraction<D, T, T, true, false, kExtraSumB, FM>(Vb, Kb, csc_row, vals, nullptr, beg, end, acc, xacc);
+        else if constexpr (MODE == kKeySide)
+            bucket_first_contraction<D, float, T, true, false, kExtraScaledSumB, FM>(Gb, Qb, csc_row, vals, gdb, beg, end, acc, xacc);
+        else
+            bucket_first_contraction<D, T, float, true, true, kExtraNone, FM>(Qb, Gb, csc_row, vals, nullptr, beg, end, acc, xacc);
+    });
 
     // the extra row, complete in the lower half-wave and zero in the upper, so that one more MFMA step
     // (k = 0: the consumer's coefficient, k = 1: nothing) adds coefficient_i * extra to the output tile
@@ -145,41 +180,17 @@ __global__ __launch_bounds__(64) void backward_bucket_kernel(const T* __restrict
     // ---- second contraction, 32 consumers at a time
     const long long pbase = slice * static_cast<long long>(nnz);
     for (int32_t tile = beg; tile < end; tile += 32) {
-        // consumer li of this tile: row, weight; its operand elements for the accumulator rows this lane pairs with
-        const int32_t pos = min(tile + li, end - 1);
-        const int32_t row = csc_row[pos];
-        const float w = tile + li < end ? vals[pos] : 0.0f;
         float cop[4][QN];
-        float coef = 0.0f;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const long long off = static_cast<long long>(row) * D + T2 * (8 * b + 4 * half);
-            if constexpr (MODE == kQuerySide) load_elems<float, QN>(Gb + off, cop[b]);
-            if constexpr (MODE == kKeySide) load_elems<T, QN>(Vb + off, cop[b]);
-            if constexpr (MODE == kValueSide) load_elems<T, QN>(Kb + off, cop[b]);
-        }
-        if constexpr (MODE == kQuerySide) coef = half == 0 ? gdb[row] : 0.0f;
-        if constexpr (MODE == kKeySide) coef = half == 0 ? 1.0f : 0.0f;
-        if constexpr (MODE == kValueSide) {
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-#pragma unroll
-                for (int e2 = 0; e2 < QN; ++e2) cop[b][e2] = w * feature(cop[b][e2], fmap);
-        }
-
-        // rows and weights of the 16 consumers this lane holds output for, and (query / key side) the
-        // elements of phi(q) / phi(k) of those consumers at this lane's output columns
-        int32_t orow[16];
-        float ow[16];
-        float xr[16][T2];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int c = 8 * (r / 4) + 4 * half + (r % 4);
-            orow[r] = __shfl(row, c, kWave);
-            ow[r] = __shfl(w, c, kWave);
-            if constexpr (MODE == kQuerySide) load_elems<T, T2>(Qb + static_cast<long long>(orow[r]) * D + T2 * li, xr[r]);
-            if constexpr (MODE == kKeySide) load_elems<T, T2>(Kb + static_cast<long long>(orow[r]) * D + T2 * li, xr[r]);
-        }
+            for (int e2 = 0; e2 < QN; ++e2)
+                cop[b][e2] = MODE == kValueSide ? w_cur * feature(cn[b][e2], fmap) : cn[b][e2];
+        const float coef = half == 0 ? cfn : 0.0f;
+        // next tile's operand rows, and the indices of the tile after it
+        fetch_operand(row_next, cn, cfn);
+        w_cur = w_next;
+        fetch_index(tile + 64, row_next, w_next);
 
         __builtin_amdgcn_sched_barrier(0);
 
@@ -204,59 +215,31 @@ __global__ __launch_bounds__(64) void backward_bucket_kernel(const T* __restrict
         }
 
         // ---- stream out: register r of pc[c] is consumer 8*(r/4) + 4*half + r%4, output column T2*li + c
-        float s[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int32_t ppos = tile + 8 * (r / 4) + 4 * half + (r % 4);
-            float o[T2];
-            s[r] = 0.0f;
-#pragma unroll
-            for (int c = 0; c < T2; ++c) {
-                if constexpr (MODE == kValueSide) {
-                    o[c] = pc[c][r];
-                } else {
-                    o[c] = ow[r] * pc[c][r];
-                    s[r] = fmaf(feature(xr[r][c], fmap), pc[c][r], s[r]);
-                }
-            }
             if (ppos < end) {
                 float* dst = partial + (pbase + ppos) * D + T2 * li;
                 if constexpr (T2 == 2) {
-                    *reinterpret_cast<float2*>(dst) = make_float2(o[0], o[1]);
+                    *reinterpret_cast<float2*>(dst) = make_float2(pc[0][r], pc[1][r]);
                 } else {
-                    dst[0] = o[0];
+                    dst[0] = pc[0][r];
                 }
             }
-        }
-        if constexpr (MODE != kValueSide) {
-            // sum s[r] over the 32 lanes of the half-wave: each step halves the number of values a lane
-            // keeps and exchanges the other half with the lane that keeps those
-#pragma unroll
-            for (int cnt = 8, bit = 16; cnt >= 1; cnt >>= 1, bit >>= 1) {
-                const bool up = (li & bit) != 0;
-#pragma unroll
-                for (int k = 0; k < cnt; ++k) {
-                    const float keep = up ? s[k + cnt] : s[k];
-                    const float send = up ? s[k] : s[k + cnt];
-                    s[k] = keep + __shfl_xor(send, bit, kWave);
-                }
-            }
-            s[0] += __shfl_xor(s[0], 1, kWave);
-            // this lane now holds register index r = li / 2 (bits 4..1 of li)
-            const int r = li >> 1;
-            const int32_t ppos = tile + 8 * (r / 4) + 4 * half + (r % 4);
-            if ((li & 1) == 0 && ppos < end) dphi_csc[pbase + ppos] = s[0];
         }
     }
 }
 
-// One wavefront per (slice, row i): sums the row's streamed partial rows in ascending-l order and,
-// for the gradients of Q and K, multiplies by phi'(x) of the row's own elements.
-template <int D, typename T, bool THROUGH_FEATURE_MAP>
-__global__ __launch_bounds__(256) void backward_reduce_kernel(long long n, const int32_t* __restrict__ row_ptr,
+// One wavefront per (slice, row i) over the vectors streamed out for the row's entries, in ascending-l order.
+// WEIGHTED (gradients of Q and K): dst_i = phi'(x_i) * sum_l w_il u_il, and the entry's term of dPhi,
+// phi(x_i) . u_il, goes to dphi_part[slice][e] (CSR order).  Otherwise (gradient of V): dst_i = sum_l u_il.
+template <int D, typename T, bool WEIGHTED>
+__global__ __launch_bounds__(256) void backward_reduce_kernel(long long n, int H, int n_f, long long val_stride,
+                                                              const int32_t* __restrict__ row_ptr, const float* __restrict__ phi_val,
                                                               const int32_t* __restrict__ csr_to_csc, int32_t nnz,
                                                               const float* __restrict__ partial, const T* __restrict__ src, int fmap,
-                                                              long long bh_first, long long n_waves, float* __restrict__ dst)
+                                                              long long bh_first, long long n_waves,
+                                                              float* __restrict__ dst, float* __restrict__ dphi_part)
 {
     constexpr int EPW = kWave / D;     // entries per wavefront step (1 at d = 64, 2 at d = 32)
     const long long wave = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
@@ -264,10 +247,15 @@ __global__ __launch_bounds__(256) void backward_reduce_kernel(long long n, const
     const long long slice = wave / n;
     const long long i = wave - slice * n;
     const long long bh = bh_first + slice;
+    const long long plane = n_f > 1 ? (bh % H) : 0;
+    const float* vals = phi_val + plane * val_stride;
     const int lane = lane_id();
     const int sub = lane / D;
     const int c = lane % D;
     const float* slice_partial = partial + slice * static_cast<long long>(nnz) * D;
+    const long long o = (bh * n + i) * D + c;
+    float x = 0.0f, fx = 0.0f;
+    if constexpr (WEIGHTED) { x = to_float(src[o]); fx = feature(x, fmap); }
 
     const int32_t beg = max(row_ptr[i], 0);
     const int32_t end = min(row_ptr[i + 1], nnz);
@@ -275,45 +263,71 @@ __global__ __launch_bounds__(256) void backward_reduce_kernel(long long n, const
     for (int32_t chunk = beg; chunk < end; chunk += kWave) {
         const int32_t e = chunk + lane;
         const int32_t pos_reg = e < end ? csr_to_csc[e] : -1;
+        float w_reg = 1.0f;
+        if constexpr (WEIGHTED) w_reg = e < end ? vals[e] : 0.0f;
         const int cnt = min(kWave, end - chunk);
+        // eight steps' loads are issued together; the shuffles are executed by every lane
         for (int t0 = 0; t0 < cnt; t0 += 8 * EPW) {
-            float v[8];
+            float v[8], w[8];
+            bool ok[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int t = t0 + u * EPW + sub;
                 const int32_t pos = __shfl(pos_reg, t & (kWave - 1), kWave);
-                const bool ok = t < cnt && pos >= 0;
-                v[u] = ok ? slice_partial[static_cast<long long>(pos) * D + c] : 0.0f;
+                w[u] = __shfl(w_reg, t & (kWave - 1), kWave);
+                ok[u] = t < cnt && pos >= 0;
+                v[u] = ok[u] ? slice_partial[static_cast<long long>(pos) * D + c] : 0.0f;
             }
+            if constexpr (WEIGHTED) {
+                float dot[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) acc += v[u];
+                for (int u = 0; u < 8; ++u) {
+                    acc = fmaf(w[u], v[u], acc);
+                    dot[u] = fx * v[u];
+                }
+                // sum each dot[u] over the D lanes of its entry: three steps that halve the values a lane keeps
+                // (exchanging the other half with the lane that keeps those), then plain butterfly steps
+#pragma unroll
+                for (int keep = 4, bit = D / 2; keep >= 1; keep >>= 1, bit >>= 1) {
+                    const bool up = (c & bit) != 0;
+#pragma unroll
+                    for (int k = 0; k < keep; ++k) {
+                        const float mine = up ? dot[k + keep] : dot[k];
+                        const float theirs = up ? dot[k] : dot[k + keep];
+                        dot[k] = mine + __shfl_xor(theirs, bit, kWave);
+                    }
+                }
+#pragma unroll
+                for (int bit = D / 16; bit >= 1; bit >>= 1) dot[0] += __shfl_xor(dot[0], bit, kWave);
+                // this lane now holds step u = c / (D / 8) of the eight
+                const int t = t0 + (c / (D / 8)) * EPW + sub;
+                if ((c & (D / 8 - 1)) == 0 && t < cnt) dphi_part[slice * static_cast<long long>(nnz) + chunk + t] = dot[0];
+            } else {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc += v[u];
+            }
         }
     }
     if constexpr (EPW == 2) acc += __shfl_xor(acc, 32, kWave);
     if (sub == 0) {
-        const long long o = (bh * n + i) * D + c;
-        if constexpr (THROUGH_FEATURE_MAP) acc *= feature_grad(to_float(src[o]), fmap);
+        if constexpr (WEIGHTED) acc *= feature_grad(x, fmap);
         dst[o] = acc;
     }
 }
 
 // dphi_val[h][e] (+)= sum over the slices of this chunk that use plane h of the two per-entry terms.
 __global__ __launch_bounds__(256) void dphi_accumulate_kernel(long long nnz, int n_f, int H, long long bh_first, long long n_slices,
-                                                              const int32_t* __restrict__ csr_to_csc,
                                                               const float* __restrict__ d_query, const float* __restrict__ d_key,
                                                               long long val_stride, int first_chunk, float* __restrict__ dphi_val)
 {
     const long long e = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
     const int h = blockIdx.y;
     if (e >= nnz) return;
-    const int32_t pos = csr_to_csc[e];
     float acc = first_chunk ? 0.0f : dphi_val[h * val_stride + e];
-    if (pos >= 0) {
-        for (long long s = 0; s < n_slices; ++s) {
-            const long long bh = bh_first + s;
-            if (n_f > 1 && bh % H != h) continue;
-            acc += d_query[s * nnz + pos] + d_key[s * nnz + pos];
-        }
+    for (long long s = 0; s < n_slices; ++s) {
+        const long long bh = bh_first + s;
+        if (n_f > 1 && bh % H != h) continue;
+        acc += d_query[s * nnz + e] + d_key[s * nnz + e];
     }
     dphi_val[h * val_stride + e] = acc;
 }
@@ -324,8 +338,8 @@ struct BackwardScratch {
     float* G;          // [chunk][n][d]
     float* gd;         // [chunk][n]
     float* partial;    // [chunk][nnz][d]
-    float* d_query;    // [chunk][nnz]
-    float* d_key;      // [chunk][nnz]
+    float* d_query;    // [chunk][nnz], CSR order: phi(q_i) . U_il
+    float* d_key;      // [chunk][nnz], CSR order: phi(k_i) . R_il
     size_t bytes;
 };
 
@@ -369,37 +383,37 @@ grf_status launch_backward_chunk(const void* Qv, const void* Kv, const void* Vv,
     const int32_t* row_ptr = phi->row_ptr;
     const float* partial = b.partial;
 
-    hipLaunchKernelGGL((backward_bucket_kernel<D, T, kQuerySide>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
-                       static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n), static_cast<int>(H),
-                       static_cast<int>(n_f), col_ptr, s_row, s_val, fmap, static_cast<long long>(bh_first), waves,
-                       static_cast<int32_t>(nnz), b.partial, b.d_query);
+    const float* phi_val = phi->val;
+    const long long val_stride = phi->capacity;
+    auto bucket_pass = [&](auto mode) {
+        hipLaunchKernelGGL((backward_bucket_kernel<D, T, decltype(mode)::value>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
+                           static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),
+                           static_cast<int>(H), static_cast<int>(n_f), col_ptr, s_row, s_val, fmap,
+                           static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), b.partial);
+    };
+    auto reduce_pass = [&](auto weighted, const T* src, float* dst, float* dphi_part) {
+        hipLaunchKernelGGL((backward_reduce_kernel<D, T, decltype(weighted)::value>), reduce_grid, dim3(256), 0, stream,
+                           static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f), val_stride, row_ptr, phi_val,
+                           csr_to_csc, static_cast<int32_t>(nnz), partial, src, fmap, static_cast<long long>(bh_first), waves,
+                           dst, dphi_part);
+    };
+    bucket_pass(std::integral_constant<int, kQuerySide>{});
     GRF_LAUNCH_CHECK("backward_bucket_kernel<query side>");
-    hipLaunchKernelGGL((backward_reduce_kernel<D, T, true>), reduce_grid, dim3(256), 0, stream, static_cast<long long>(n), row_ptr,
-                       csr_to_csc, static_cast<int32_t>(nnz), partial, Q, fmap, static_cast<long long>(bh_first), waves, dQ);
+    reduce_pass(std::true_type{}, Q, dQ, b.d_query);
     GRF_LAUNCH_CHECK("backward_reduce_kernel<dQ>");
-
-    hipLaunchKernelGGL((backward_bucket_kernel<D, T, kKeySide>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
-                       static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n), static_cast<int>(H),
-                       static_cast<int>(n_f), col_ptr, s_row, s_val, fmap, static_cast<long long>(bh_first), waves,
-                       static_cast<int32_t>(nnz), b.partial, b.d_key);
+    bucket_pass(std::integral_constant<int, kKeySide>{});
     GRF_LAUNCH_CHECK("backward_bucket_kernel<key side>");
-    hipLaunchKernelGGL((backward_reduce_kernel<D, T, true>), reduce_grid, dim3(256), 0, stream, static_cast<long long>(n), row_ptr,
-                       csr_to_csc, static_cast<int32_t>(nnz), partial, K, fmap, static_cast<long long>(bh_first), waves, dK);
+    reduce_pass(std::true_type{}, K, dK, b.d_key);
     GRF_LAUNCH_CHECK("backward_reduce_kernel<dK>");
-
-    hipLaunchKernelGGL((backward_bucket_kernel<D, T, kValueSide>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
-                       static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n), static_cast<int>(H),
-                       static_cast<int>(n_f), col_ptr, s_row, s_val, fmap, static_cast<long long>(bh_first), waves,
-                       static_cast<int32_t>(nnz), b.partial, static_cast<float*>(nullptr));
+    bucket_pass(std::integral_constant<int, kValueSide>{});
     GRF_LAUNCH_CHECK("backward_bucket_kernel<value side>");
-    hipLaunchKernelGGL((backward_reduce_kernel<D, T, false>), reduce_grid, dim3(256), 0, stream, static_cast<long long>(n), row_ptr,
-                       csr_to_csc, static_cast<int32_t>(nnz), partial, V, fmap, static_cast<long long>(bh_first), waves, dV);
+    reduce_pass(std::false_type{}, V, dV, static_cast<float*>(nullptr));
     GRF_LAUNCH_CHECK("backward_reduce_kernel<dV>");
 
     if (dphi_val != nullptr && nnz > 0) {
         hipLaunchKernelGGL(dphi_accumulate_kernel, dim3(blocks_for(nnz, 256), static_cast<unsigned>(n_f)), dim3(256), 0, stream,
                            static_cast<long long>(nnz), static_cast<int>(n_f), static_cast<int>(H), static_cast<long long>(bh_first),
-                           static_cast<long long>(n_slices), csr_to_csc, static_cast<const float*>(b.d_query),
+                           static_cast<long long>(n_slices), static_cast<const float*>(b.d_query),
                            static_cast<const float*>(b.d_key), static_cast<long long>(phi->capacity), bh_first == 0 ? 1 : 0, dphi_val);
         GRF_LAUNCH_CHECK("dphi_accumulate_kernel");
     }

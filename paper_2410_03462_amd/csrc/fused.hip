@@ -116,7 +116,9 @@ __global__ __launch_bounds__(64) void fused_bucket_kernel(const T* __restrict__ 
     // ---- S_l = A^T V_l
     floatx16 acc[T2][T2];
     float zacc[T2];
-    bucket_first_contraction<D, T, T, true, true, kExtraSumA>(Kb, Vb, csc_row, vals, nullptr, beg, end, fmap, acc, zacc);
+    with_feature_map(fmap, [&](auto fm) {
+        bucket_first_contraction<D, T, T, true, true, kExtraSumA, decltype(fm)::value>(Kb, Vb, csc_row, vals, nullptr, beg, end, acc, zacc);
+    });
 
     float zfull[T2];
 #pragma unroll
@@ -129,10 +131,12 @@ __global__ __launch_bounds__(64) void fused_bucket_kernel(const T* __restrict__ 
     const long long pbase = slice * static_cast<long long>(nnz);
     for (int32_t tile = beg; tile < end; tile += 32) {
         float qv[4][QN];
+        with_feature_map(fmap, [&](auto fm) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
+            for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int e2 = 0; e2 < QN; ++e2) qv[b][e2] = gq_cur * feature(qn[b][e2], fmap);
+                for (int e2 = 0; e2 < QN; ++e2) qv[b][e2] = gq_cur * feature_ct<decltype(fm)::value>(qn[b][e2]);
+        });
         // next tile's rows of Q, and the indices of the tile after it
         fetch_q(qrow_next, qn);
         gq_cur = gq_next;
