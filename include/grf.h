@@ -238,6 +238,22 @@ grf_status grf_masked_linear_attention_backward(const void* Q, const void* K, co
                                                 void* workspace, size_t workspace_bytes, void* hip_stream,
                                                 float* dQ, float* dK, float* dV, float* dphi_val);
 
+/* Backward of grf_asymmetric_masked_attention (App. D): with a_ij = phi(q_i).phi(k_j) and c_ij = v'_j . g'_i,
+ *     dL/dPhi[i,j] = a_ij c_ij                      dL/dphi(q_i) = sum_j Phi[i,j] c_ij phi(k_j)
+ *     dL/dphi(k_j) = sum_i Phi[i,j] c_ij phi(q_i)   dL/dv_j      = sum_i Phi[i,j] a_ij g_i
+ * (row sums in one kernel, column sums over the column lists in a second; fixed summation order).
+ * Arguments as for grf_masked_linear_attention_backward; dL/df follows from grf_sample_backward as before,
+ * since Phi_hat is the same sampled matrix (with f = alpha). */
+size_t grf_asymmetric_backward_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t n_f, int32_t bh_chunk);
+
+grf_status grf_asymmetric_masked_attention_backward(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                    int64_t B, int64_t H, int64_t n, int32_t d,
+                                                    const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                    const float* out, const float* den, const float* d_out,
+                                                    int32_t bh_chunk,
+                                                    void* workspace, size_t workspace_bytes, void* hip_stream,
+                                                    float* dQ, float* dK, float* dV, float* dphi_val);
+
 /* Gradient of the sampled features with respect to the modulation (Eq. GRF definition is linear in f):
  *     df[h][t] = (1 / n_walks) * sum over nodes i, walks k with at least t hops of
  *                load_{k,t} * dphi_val[h][entry (i, node visited by walk k after t hops)]

@@ -506,3 +506,45 @@ double grf_ref_dphi_entry_direct(int64_t n, int32_t d, int64_t i, int64_t l, con
     free(Sl); free(Tl);
     return de;
 }
+
+/* ------------------------------------------------------------------ gradients of asymmetric-GRF attention (App. D)
+ * Forward (the per-end-node form of Alg. 2):  num'_i = [num_i, den_i] = sum_j Phi_ij (phi(q_i) . phi(k_j)) v'_j,
+ * out_i = num_i / den_i, the sum running over the stored entries of row i.  With g'_i as for the symmetric case,
+ * L depends on the inputs through  sum_(i,j) Phi_ij a_ij c_ij,  a_ij = phi(q_i) . phi(k_j),  c_ij = v'_j . g'_i:
+ *     dL/dPhi_ij   = a_ij c_ij                     dL/dphi(q_i) = sum_j Phi_ij c_ij phi(k_j)
+ *     dL/dphi(k_j) = sum_i Phi_ij c_ij phi(q_i)    dL/dv_j      = sum_i Phi_ij a_ij g_i
+ * One slice, fp64; dphi in CSR order.
+ */
+void grf_ref_asymmetric_backward(int64_t n, int32_t d, const float* Q, const float* K, const float* V,
+                                 const int32_t* phi_row_ptr, const int32_t* phi_col, const float* phi_val,
+                                 int32_t feature_map, const double* out, const double* den, const double* dout,
+                                 double* dQ, double* dK, double* dV, double* dphi)
+{
+    double* g = (double*)malloc(sizeof(double) * (size_t)(d + 1));
+    for (int64_t x = 0; x < n * (int64_t)d; ++x) { dQ[x] = 0.0; dK[x] = 0.0; dV[x] = 0.0; }
+    for (int64_t i = 0; i < n; ++i) {
+        double dot = 0.0;
+        for (int32_t c = 0; c < d; ++c) { g[c] = dout[i * d + c] / den[i]; dot += dout[i * d + c] * out[i * d + c]; }
+        g[d] = -dot / den[i];
+        for (int64_t e = phi_row_ptr[i]; e < phi_row_ptr[i + 1]; ++e) {
+            const int64_t j = phi_col[e];
+            const double w = (double)phi_val[e];
+            double a = 0.0, c = g[d];
+            for (int32_t x = 0; x < d; ++x) {
+                a += feature(Q[i * d + x], feature_map) * feature(K[j * d + x], feature_map);
+                c += (double)V[j * d + x] * g[x];
+            }
+            dphi[e] = a * c;
+            for (int32_t x = 0; x < d; ++x) {
+                dQ[i * d + x] += w * c * feature(K[j * d + x], feature_map);
+                dK[j * d + x] += w * c * feature(Q[i * d + x], feature_map);
+                dV[j * d + x] += w * a * g[x];
+            }
+        }
+    }
+    for (int64_t x = 0; x < n * (int64_t)d; ++x) {
+        dQ[x] *= feature_grad(Q[x], feature_map);
+        dK[x] *= feature_grad(K[x], feature_map);
+    }
+    free(g);
+}

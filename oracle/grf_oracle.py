@@ -363,3 +363,32 @@ def dphi_entry_direct(i: int, l: int, Q, K, V, row_ptr, col, val, gp, feature_ma
         _p(Q, ctypes.c_float), _p(K, ctypes.c_float), _p(V, ctypes.c_float),
         _p(rp, ctypes.c_int32), _p(c, ctypes.c_int32), _p(v, ctypes.c_float), ctypes.c_int32(feature_map),
         _p(gp, ctypes.c_double)))
+
+
+def asymmetric_attention_backward(Q, K, V, row_ptr, col, val, out, den, dout, feature_map: int = RELU):
+    """Gradients of asymmetric-GRF attention (App. D) for [B,H,n,d] tensors: dQ, dK, dV [B,H,n,d] and
+    dphi [n_f, nnz] (summed over the slices that share a plane), fp64."""
+    Q, K, V = (np.ascontiguousarray(x, dtype=np.float32) for x in (Q, K, V))
+    B, H, n, d = Q.shape
+    val = np.ascontiguousarray(np.atleast_2d(val), dtype=np.float32)
+    n_f = val.shape[0]
+    assert n_f in (1, H)
+    rp, c = _i32(row_ptr), _i32(col)
+    out = np.ascontiguousarray(out, dtype=np.float64)
+    den = np.ascontiguousarray(den, dtype=np.float64)
+    dout = np.ascontiguousarray(dout, dtype=np.float64)
+    dQ, dK, dV = (np.empty((B, H, n, d), dtype=np.float64) for _ in range(3))
+    dphi = np.zeros((n_f, val.shape[1]), dtype=np.float64)
+    lib = _load()
+    for b in range(B):
+        for h in range(H):
+            p = h if n_f > 1 else 0
+            de = np.empty(val.shape[1], dtype=np.float64)
+            lib.grf_ref_asymmetric_backward(
+                ctypes.c_int64(n), ctypes.c_int32(d), _p(Q[b, h], ctypes.c_float), _p(K[b, h], ctypes.c_float),
+                _p(V[b, h], ctypes.c_float), _p(rp, ctypes.c_int32), _p(c, ctypes.c_int32), _p(val[p], ctypes.c_float),
+                ctypes.c_int32(feature_map), _p(out[b, h], ctypes.c_double), _p(den[b, h], ctypes.c_double),
+                _p(dout[b, h], ctypes.c_double), _p(dQ[b, h], ctypes.c_double), _p(dK[b, h], ctypes.c_double),
+                _p(dV[b, h], ctypes.c_double), _p(de, ctypes.c_double))
+            dphi[p] += de
+    return dQ, dK, dV, dphi

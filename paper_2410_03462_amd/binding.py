@@ -98,6 +98,10 @@ def lib() -> ctypes.CDLL:
                                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                                            ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.grf_asymmetric_backward_workspace_bytes.restype = ctypes.c_size_t
+        L.grf_asymmetric_backward_workspace_bytes.argtypes = L.grf_attention_workspace_bytes.argtypes
+        L.grf_asymmetric_masked_attention_backward.restype = ctypes.c_int32
+        L.grf_asymmetric_masked_attention_backward.argtypes = L.grf_masked_linear_attention_backward.argtypes
         L.grf_sample_backward_workspace_bytes.restype = ctypes.c_size_t
         L.grf_sample_backward_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
         L.grf_sample_backward.restype = ctypes.c_int32
@@ -382,6 +386,17 @@ def grf_attention_backward_workspace_bytes(B: int, H: int, n: int, d: int, nnz: 
     return int(lib().grf_attention_backward_workspace_bytes(B, H, n, d, nnz, n_f, bh_chunk))
 
 
+def grf_asymmetric_backward_workspace_bytes(B: int, H: int, n: int, d: int, nnz: int, n_f: int = 1, bh_chunk: int = 0) -> int:
+    return int(lib().grf_asymmetric_backward_workspace_bytes(B, H, n, d, nnz, n_f, bh_chunk))
+
+
+def grf_asymmetric_masked_attention_backward(Q, K, V, phi: Phi, out, den, d_out, feature_map: str = "relu", bh_chunk: int = 0,
+                                             want_dphi: bool = True, workspace: Optional[torch.Tensor] = None, stream=None):
+    """Backward of grf_asymmetric_masked_attention: (dQ, dK, dV, dphi_val), arguments as the symmetric backward."""
+    return _backward_call("grf_asymmetric_masked_attention_backward", "grf_asymmetric_backward_workspace_bytes",
+                          Q, K, V, phi, out, den, d_out, feature_map, bh_chunk, want_dphi, workspace, stream)
+
+
 def grf_masked_linear_attention_backward(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, phi: Phi,
                                          out: torch.Tensor, den: torch.Tensor, d_out: torch.Tensor,
                                          feature_map: str = "relu", bh_chunk: int = 0, want_dphi: bool = True,
@@ -389,13 +404,18 @@ def grf_masked_linear_attention_backward(Q: torch.Tensor, K: torch.Tensor, V: to
     """(dQ, dK, dV, dphi_val) for d_out = dL/dout; ``out`` and ``den`` are the saved forward results (fp32).
 
     dphi_val is [n_f, capacity] fp32 (entries beyond nnz untouched), or None when ``want_dphi`` is False."""
+    return _backward_call("grf_masked_linear_attention_backward", "grf_attention_backward_workspace_bytes",
+                          Q, K, V, phi, out, den, d_out, feature_map, bh_chunk, want_dphi, workspace, stream)
+
+
+def _backward_call(entry, ws_query, Q, K, V, phi, out, den, d_out, feature_map, bh_chunk, want_dphi, workspace, stream):
     _require_gpu()
     L = lib()
     B, H, n, d = _check_qkv(Q, K, V)
     for t, shape in ((out, (B, H, n, d)), (d_out, (B, H, n, d)), (den, (B, H, n))):
         if tuple(t.shape) != shape or t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda:
             raise ValueError("out, den, d_out must be contiguous fp32 CUDA tensors of shapes [B,H,n,d], [B,H,n], [B,H,n,d]")
-    need = L.grf_attention_backward_workspace_bytes(B, H, n, d, phi.nnz, phi.n_f, bh_chunk)
+    need = getattr(L, ws_query)(B, H, n, d, phi.nnz, phi.n_f, bh_chunk)
     if need == 0:
         raise GrfError(GRF_EUNSUPPORTED, f"unsupported problem (d={d})")
     if workspace is None:
@@ -403,7 +423,7 @@ def grf_masked_linear_attention_backward(Q: torch.Tensor, K: torch.Tensor, V: to
     dQ, dK, dV = (torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device) for _ in range(3))
     dphi = torch.empty((phi.n_f, phi.capacity), dtype=torch.float32, device=Q.device) if want_dphi else None
     ps = phi._struct()
-    _check(L.grf_masked_linear_attention_backward(
+    _check(getattr(L, entry)(
         _ptr(Q), _ptr(K), _ptr(V), _dtype_code(Q), B, H, n, d, ctypes.byref(ps), phi.nnz, phi.n_f,
         _FEATURE_MAPS[feature_map], _ptr(out), _ptr(den), _ptr(d_out), int(bh_chunk),
         _ptr(workspace), workspace.numel(), _stream_ptr(stream), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dphi)))

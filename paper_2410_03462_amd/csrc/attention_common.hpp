@@ -71,6 +71,15 @@ grf_status check_problem(const void* a, const void* b, int32_t dtype, int64_t B,
                          const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map);
 grf_status check_workspace(const void* workspace, size_t have, size_t need);
 
+// Shared by the backward entry points (defined with the symmetric backward pass).
+// g' per row: G[r][:] = d_out / den and gd[r] = -(d_out . out) / den for rows first_row .. first_row + n_rows - 1.
+grf_status launch_backward_seed(int32_t d, const float* out, const float* den, const float* d_out, long long first_row,
+                                long long n_rows, float* G, float* gd, hipStream_t stream);
+// dphi_val[h][e] (+)= sum over the slices of a chunk that use plane h of term_a[s][e] (+ term_b[s][e] unless NULL).
+grf_status launch_dphi_accumulate(int64_t nnz, int32_t n_f, int64_t H, int64_t bh_first, int64_t n_slices,
+                                  const float* term_a, const float* term_b, int64_t val_stride, float* dphi_val,
+                                  hipStream_t stream);
+
 // Workgroups are handed to the eight XCDs round-robin by id, and each XCD has an L2 of its own.
 // This maps a workgroup id to a logical index such that every XCD works through one contiguous
 // range of logical indices (ids congruent mod 8 become neighbours), so that work items that are

@@ -327,9 +327,36 @@ __global__ __launch_bounds__(256) void dphi_accumulate_kernel(long long nnz, int
     for (long long s = 0; s < n_slices; ++s) {
         const long long bh = bh_first + s;
         if (n_f > 1 && bh % H != h) continue;
-        acc += d_query[s * nnz + e] + d_key[s * nnz + e];
+        acc += d_query[s * nnz + e];
+        if (d_key != nullptr) acc += d_key[s * nnz + e];
     }
     dphi_val[h * val_stride + e] = acc;
+}
+
+grf_status launch_backward_seed(int32_t d, const float* out, const float* den, const float* d_out, long long first_row,
+                                long long n_rows, float* G, float* gd, hipStream_t stream)
+{
+    if (n_rows <= 0) return GRF_OK;
+    if (d == 64) {
+        hipLaunchKernelGGL((backward_seed_kernel<64>), dim3(blocks_for(n_rows, 4)), dim3(256), 0, stream, out, den, d_out, first_row, n_rows, G, gd);
+    } else {
+        hipLaunchKernelGGL((backward_seed_kernel<32>), dim3(blocks_for((n_rows + 1) / 2, 4)), dim3(256), 0, stream, out, den, d_out, first_row, n_rows, G, gd);
+    }
+    GRF_LAUNCH_CHECK("backward_seed_kernel");
+    return GRF_OK;
+}
+
+grf_status launch_dphi_accumulate(int64_t nnz, int32_t n_f, int64_t H, int64_t bh_first, int64_t n_slices,
+                                  const float* term_a, const float* term_b, int64_t val_stride, float* dphi_val,
+                                  hipStream_t stream)
+{
+    if (dphi_val == nullptr || nnz <= 0) return GRF_OK;
+    hipLaunchKernelGGL(dphi_accumulate_kernel, dim3(blocks_for(nnz, 256), static_cast<unsigned>(n_f)), dim3(256), 0, stream,
+                       static_cast<long long>(nnz), static_cast<int>(n_f), static_cast<int>(H), static_cast<long long>(bh_first),
+                       static_cast<long long>(n_slices), term_a, term_b, static_cast<long long>(val_stride), bh_first == 0 ? 1 : 0,
+                       dphi_val);
+    GRF_LAUNCH_CHECK("dphi_accumulate_kernel");
+    return GRF_OK;
 }
 
 namespace {
@@ -369,11 +396,7 @@ grf_status launch_backward_chunk(const void* Qv, const void* Kv, const void* Vv,
     const T* V = static_cast<const T*>(Vv);
     const long long waves = static_cast<long long>(n_slices) * n;
     if (waves == 0) return GRF_OK;
-    const long long first_row = static_cast<long long>(bh_first) * n;
-    constexpr int RPW = kWave / D;
-    hipLaunchKernelGGL((backward_seed_kernel<D>), dim3(blocks_for((waves + RPW - 1) / RPW, 4)), dim3(256), 0, stream,
-                       out, den, d_out, first_row, waves, b.G, b.gd);
-    GRF_LAUNCH_CHECK("backward_seed_kernel");
+    if (grf_status st = launch_backward_seed(D, out, den, d_out, static_cast<long long>(bh_first) * n, waves, b.G, b.gd, stream)) return st;
 
     const dim3 bucket_grid(blocks_for(waves, 1)), reduce_grid(blocks_for(waves, 4));
     const int32_t* col_ptr = t.col_ptr;
@@ -410,13 +433,7 @@ grf_status launch_backward_chunk(const void* Qv, const void* Kv, const void* Vv,
     reduce_pass(std::false_type{}, V, dV, static_cast<float*>(nullptr));
     GRF_LAUNCH_CHECK("backward_reduce_kernel<dV>");
 
-    if (dphi_val != nullptr && nnz > 0) {
-        hipLaunchKernelGGL(dphi_accumulate_kernel, dim3(blocks_for(nnz, 256), static_cast<unsigned>(n_f)), dim3(256), 0, stream,
-                           static_cast<long long>(nnz), static_cast<int>(n_f), static_cast<int>(H), static_cast<long long>(bh_first),
-                           static_cast<long long>(n_slices), static_cast<const float*>(b.d_query),
-                           static_cast<const float*>(b.d_key), static_cast<long long>(phi->capacity), bh_first == 0 ? 1 : 0, dphi_val);
-        GRF_LAUNCH_CHECK("dphi_accumulate_kernel");
-    }
+    if (grf_status st = launch_dphi_accumulate(nnz, n_f, H, bh_first, n_slices, b.d_query, b.d_key, phi->capacity, dphi_val, stream)) return st;
     return GRF_OK;
 }
 

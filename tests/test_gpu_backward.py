@@ -157,6 +157,53 @@ def test_backward_argument_errors(grf):
     assert dQ.shape == (0, 2, n, 64) and torch.all(dphi == 0)
 
 
+def compare_asymmetric_backward(grf, oracle, wl, feature_map="relu", bh_chunk=0):
+    fm = FEATURE_MAP_CODE[feature_map]
+    tol = TOL_BF16 if wl.dtype == "bf16" else TOL_F32
+    rp, col, val = oracle.sample(wl.graph, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+    Q, K, V = wl.qkv()
+    B, H, n, d = Q.shape
+    out = np.empty(Q.shape, np.float64); den = np.empty(Q.shape[:3], np.float64)
+    for h in range(H):       # the checker's forward is Alg. 2 walk by walk, one modulation vector at a time
+        r = oracle.asymmetric_attention_walks(wl.graph, wl.f[h if wl.n_f > 1 else 0], wl.p_halt, wl.n_walks, wl.walk_seed,
+                                              Q[:, h:h + 1], K[:, h:h + 1], V[:, h:h + 1], fm)
+        out[:, h], den[:, h] = r["out"][:, 0], r["den"][:, 0]
+    out32, den32 = out.astype(np.float32), den.astype(np.float32)
+    assert np.isfinite(out32).all() and (den32 != 0).all(), "workload has a zero denominator: pick another seed for this test"
+    d_out = np.random.default_rng(98).standard_normal(Q.shape).astype(np.float32)
+    ref = oracle.asymmetric_attention_backward(Q, K, V, rp, col, val, out32, den32, d_out, fm)
+    phi = grf.Phi.from_host(n, rp, col, val)
+    Qd, Kd, Vd = (to_dev(x, wl.dtype) for x in (Q, K, V))
+    got = grf.grf_asymmetric_masked_attention_backward(Qd, Kd, Vd, phi, to_dev(out32), to_dev(den32), to_dev(d_out),
+                                                       feature_map, bh_chunk=bh_chunk)
+    host = [t.cpu().numpy() for t in got]
+    host[3] = host[3][:, : phi.nnz]
+    for name, x, r in zip(("dQ", "dK", "dV", "dphi"), host, ref):
+        assert np.isfinite(x).all(), name
+        assert relerr(x, r) <= tol, (name, relerr(x, r))
+    g = grf.DeviceGraph.from_host(wl.graph)
+    df = grf.grf_sample_backward(g, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, phi, got[3]).cpu().numpy()
+    df_ref = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp, col, ref[3])
+    for h in range(wl.n_f):
+        assert relerr(df[h], df_ref[h]) <= 10 * tol
+    return host
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_asymmetric_backward_parity(grf, oracle, name):
+    compare_asymmetric_backward(grf, oracle, SMALL[name], "elu1" if name == "star_300" else "relu")
+
+
+def test_asymmetric_backward_chunking_and_determinism(grf, oracle):
+    wl = SMALL["random_777"]
+    full = compare_asymmetric_backward(grf, oracle, wl, "elu1")
+    again = compare_asymmetric_backward(grf, oracle, wl, "elu1")
+    part = compare_asymmetric_backward(grf, oracle, wl, "elu1", bh_chunk=3)
+    for a, b, c in zip(full[:3], again[:3], part[:3]):
+        assert np.array_equal(a, b) and np.array_equal(a, c)
+    assert np.array_equal(full[3], again[3]) and relerr(part[3], full[3]) <= 1e-6
+
+
 def test_backward_headline_workload_full_size(grf, oracle):
     """cloud_32k in the launch configuration the benchmark times.
 

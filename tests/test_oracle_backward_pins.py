@@ -208,3 +208,37 @@ def test_per_plane_accumulation_over_slices(oracle):
         assert np.allclose(dphi[h], want, rtol=1e-12, atol=1e-12 * np.abs(want).max())
     shared = oracle.masked_linear_attention_backward(Q, K, V, rp, col, val[:1], *[oracle.masked_linear_attention(Q, K, V, rp, col, val[:1], 2)[k] for k in ("out", "den")], dout, 2)[3]
     assert shared.shape == (1, val.shape[1])
+
+
+@pytest.mark.parametrize("feature_map", [0, 2])
+def test_asymmetric_backward_equals_autograd_of_dense_definition(oracle, feature_map):
+    """App. D: mask estimate = Phi_hat itself.  Autograd (fp64) through out = ((Phi .* A) V) / ((Phi .* A) 1) with
+    Phi = sum_t f_t P_t, against the checker's formulas and its sampler backward."""
+    g, f, p, nw, rp, col, val, P_t, Q, K, V, dout = case(oracle, 51 + feature_map, feature_map, positive_f=(feature_map == 2))
+    Phi = oracle.phi_dense(g.n, rp, col, val[0])
+    P_used = P_t.copy()
+    t0 = int(np.flatnonzero(f)[0])
+    P_used[t0] += (Phi - np.einsum("t,tij->ij", f.astype(np.float64), P_t)) / float(f[t0])
+    ft = torch.tensor(f.astype(np.float64), requires_grad=True)
+    Qt, Kt, Vt = (torch.tensor(x.astype(np.float64), requires_grad=True) for x in (Q, K, V))
+    Pt = torch.einsum("t,tij->ij", ft, torch.from_numpy(P_used))
+    Pt.retain_grad()
+    AM = Pt * (torch_feature(Qt, feature_map) @ torch_feature(Kt, feature_map).T)
+    den_t = AM.sum(dim=1)
+    out_t = (AM @ Vt) / den_t[:, None]
+    (out_t * torch.from_numpy(dout)).sum().backward()
+
+    # forward values: the checker's walk-by-walk Alg. 2 agrees with the dense form (pinned elsewhere); use it here
+    fwd = oracle.asymmetric_attention_walks(g, f, p, nw, 51 + feature_map, Q[None, None], K[None, None], V[None, None], feature_map)
+    assert close(fwd["out"][0, 0], out_t.detach().numpy(), 1e-4)      # fp32-rounded values against unrounded walk sums
+    out64, den64 = out_t.detach().numpy(), den_t.detach().numpy()
+    dQ, dK, dV, dphi = oracle.asymmetric_attention_backward(Q[None, None], K[None, None], V[None, None], rp, col, val,
+                                                            out64[None, None], den64[None, None], dout[None, None], feature_map)
+    assert close(dQ[0, 0], Qt.grad.numpy()) and close(dK[0, 0], Kt.grad.numpy()) and close(dV[0, 0], Vt.grad.numpy())
+    rows = np.repeat(np.arange(g.n), np.diff(rp))
+    assert close(dphi[0], Pt.grad.numpy()[rows, col])
+    df = oracle.sample_backward(g, len(f), p, nw, 51 + feature_map, rp, col, dphi)
+    assert close(df[0], ft.grad.numpy(), tol=2e-6)
+    # degree 0 in Phi_hat, linear in V
+    assert abs((val[0].astype(np.float64) * dphi[0]).sum()) <= 1e-10 * np.abs(val[0] * dphi[0]).sum()
+    assert abs((V.astype(np.float64) * dV[0, 0]).sum() - (dout * out64).sum()) <= 1e-10 * np.abs(V * dV[0, 0]).sum()
