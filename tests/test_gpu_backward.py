@@ -204,6 +204,56 @@ def test_asymmetric_backward_chunking_and_determinism(grf, oracle):
     assert np.array_equal(full[3], again[3]) and relerr(part[3], full[3]) <= 1e-6
 
 
+@pytest.mark.parametrize("asymmetric", [False, True])
+def test_autograd_wrapper_trains_the_modulation(grf, oracle, asymmetric):
+    """The torch.autograd wrapper: gradients equal the explicit backward calls, f.grad matches a central finite
+    difference of the fp32 forward, and a few steps of gradient descent on f lower the loss."""
+    import torch
+    from paper_2410_03462_amd.autograd import grf_attention
+    rng = np.random.default_rng(4)
+    g_host = synth.with_weights(synth.grid_graph(20, 20, 8), "sym_norm")
+    g = grf.DeviceGraph.from_host(g_host)
+    Q, K, V = (to_dev(x) for x in synth.qkv(1, 2, g_host.n, 64, rng))
+    target = to_dev(rng.standard_normal((1, 2, g_host.n, 64)).astype(np.float32))
+    f0 = np.abs(synth.modulation(6, rng)[0]) + 0.1          # positive: no cancelling denominators
+    f = torch.tensor(f0, dtype=torch.float32, requires_grad=True)
+    Qr, Kr, Vr = (x.clone().requires_grad_(True) for x in (Q, K, V))
+    args = (g, 0.3, 8, 3, "elu1", asymmetric)
+
+    def loss_of(fv):
+        with torch.no_grad():
+            return float(((grf_attention(Q, K, V, fv, *args) - target) ** 2).sum())
+
+    out = grf_attention(Qr, Kr, Vr, f, *args)
+    loss = ((out - target) ** 2).sum()
+    loss.backward()
+    assert f.grad is not None and f.grad.shape == f.shape and torch.isfinite(f.grad).all()
+    # against the explicit calls
+    phi = grf.grf_sample(g, f0, 0.3, 8, 3)
+    fwd = grf.grf_asymmetric_masked_attention if asymmetric else grf.grf_masked_linear_attention_fused
+    bwd = grf.grf_asymmetric_masked_attention_backward if asymmetric else grf.grf_masked_linear_attention_backward
+    o2, _, den = fwd(Q, K, V, phi, "elu1", return_num_den=True)
+    dQ, dK, dV, dphi = bwd(Q, K, V, phi, o2, den, (2 * (o2 - target)).contiguous(), "elu1")
+    assert torch.equal(dQ, Qr.grad) and torch.equal(dK, Kr.grad) and torch.equal(dV, Vr.grad)
+    # central differences of the fp32 forward in f
+    for t in range(len(f0)):
+        h = 1e-2
+        fp_, fm_ = f0.copy(), f0.copy()
+        fp_[t] += h; fm_[t] -= h
+        fd = (loss_of(torch.tensor(fp_)) - loss_of(torch.tensor(fm_))) / (2 * h)
+        assert abs(fd - float(f.grad[t])) <= 2e-2 * float(f.grad.abs().max()) + 1e-3 * abs(fd), (t, fd, float(f.grad[t]))
+    # descent
+    l0 = float(loss.detach())
+    lr = 0.05 / float(f.grad.abs().max())
+    fv = f.detach().clone()
+    for _ in range(5):
+        fv.requires_grad_(True)
+        l = ((grf_attention(Q, K, V, fv, *args) - target) ** 2).sum()
+        l.backward()
+        fv = (fv - lr * fv.grad).detach()
+    assert loss_of(fv) < l0
+
+
 def test_backward_headline_workload_full_size(grf, oracle):
     """cloud_32k in the launch configuration the benchmark times.
 
