@@ -75,6 +75,34 @@ typedef struct grf_phi {
 } grf_phi;
 
 /* ---------------------------------------------------------------------------------------------
+ * Graph construction for dynamic point clouds (Sec. 4, point-cloud experiment; App. C): there the graph
+ * changes at every step, walks cannot be precomputed, and the k-nearest-neighbour search is the stated
+ * bottleneck.  The paper's solver is approximate and unspecified; this one is exact.
+ *
+ * points     device fp32 [n][3].
+ * Neighbours of i: the k points j != i with the smallest squared distance, computed in fp32 as
+ *            fl(fl(fl(dx*dx) + fl(dy*dy)) + fl(dz*dz)), dx = fl(x_i - x_j) (no fused multiply-add), ties going
+ *            to the smaller index; fewer than k if n - 1 < k.  1 <= k <= 32.
+ * symmetrise 0: row i holds its own k neighbours;  1: i ~ j if either lists the other.
+ * weights    GRF_WEIGHT_INV_DEGREE: 1 / deg(i);  GRF_WEIGHT_EXP: exp(-dist / sigma);
+ *            GRF_WEIGHT_GAUSS: exp(-dist^2 / (2 sigma^2));  the last two divided by their row sum (evaluated
+ *            relative to the row's nearest neighbour, so a row far from everything is still finite).
+ * Output     CSR as grf_graph expects it (columns ascending): row_ptr [n+1] always written; col, w [capacity]
+ *            written when capacity >= nnz, else GRF_ECAPACITY with *nnz_out set.  grf_knn_graph_nnz_bound is
+ *            always enough.  nnz_out is a HOST pointer; the call blocks on the stream once to fill it.
+ * --------------------------------------------------------------------------------------------- */
+#define GRF_WEIGHT_INV_DEGREE 0
+#define GRF_WEIGHT_EXP        1
+#define GRF_WEIGHT_GAUSS      2
+
+int64_t grf_knn_graph_nnz_bound(int64_t n, int32_t k, int32_t symmetrise);     /* n*k or 2*n*k; -1 on bad arguments */
+size_t grf_knn_graph_workspace_bytes(int64_t n, int32_t k);                    /* 0 on bad arguments */
+
+grf_status grf_knn_graph(const float* points, int64_t n, int32_t k, int32_t symmetrise, int32_t weight_kind, float sigma,
+                         void* workspace, size_t workspace_bytes, void* hip_stream,
+                         int32_t* row_ptr, int32_t* col, float* w, int64_t capacity, int64_t* nnz_out);
+
+/* ---------------------------------------------------------------------------------------------
  * Sampling (Alg. 1 steps 1-2; Sec. 3.3).
  *
  * From every node i, n_walks independent simple random walks are simulated.  Before every hop a walk

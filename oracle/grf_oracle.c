@@ -548,3 +548,112 @@ void grf_ref_asymmetric_backward(int64_t n, int32_t d, const float* Q, const flo
     }
     free(g);
 }
+
+/* ------------------------------------------------------------------ k-nearest-neighbour graph of a point cloud
+ * For dynamic point clouds the paper builds the graph on the fly from each node's k nearest neighbours
+ * (Sec. 4, point-cloud experiment; App. C).  Brute force: every pair is examined.
+ *
+ * The squared distance is taken in fp32, each operation rounded on its own (build with -ffp-contract=off):
+ *     fl(fl(fl(dx*dx) + fl(dy*dy)) + fl(dz*dz)),  dx = fl(x_i - x_j);
+ * neighbours are ordered by (squared distance, index).  The fp32 arithmetic is part of the definition because it
+ * decides an integer (which points are neighbours); both the checker and the library take it in this precision.
+ *
+ * knn_idx [n][k] (-1 where fewer than k other points exist), knn_d2 [n][k].
+ */
+static float squared_distance_f32(const float* a, const float* b)
+{
+    const float dx = a[0] - b[0], dy = a[1] - b[1], dz = a[2] - b[2];
+    const float xx = dx * dx, yy = dy * dy, zz = dz * dz;
+    const float xy = xx + yy;
+    return xy + zz;
+}
+
+/* The same for the n_rows query points listed in rows[] only: knn_idx, knn_d2 are [n_rows][k]. */
+void grf_ref_knn_lists_rows(int64_t n, const float* pts, int32_t k, int64_t n_rows, const int64_t* rows,
+                            int32_t* knn_idx, float* knn_d2);
+
+void grf_ref_knn_lists(int64_t n, const float* pts, int32_t k, int32_t* knn_idx, float* knn_d2)
+{
+    int64_t* rows = (int64_t*)malloc(sizeof(int64_t) * (size_t)(n > 0 ? n : 1));
+    for (int64_t i = 0; i < n; ++i) rows[i] = i;
+    grf_ref_knn_lists_rows(n, pts, k, n, rows, knn_idx, knn_d2);
+    free(rows);
+}
+
+void grf_ref_knn_lists_rows(int64_t n, const float* pts, int32_t k, int64_t n_rows, const int64_t* rows,
+                            int32_t* knn_idx, float* knn_d2)
+{
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const int64_t i = rows[r];
+        int32_t* bi = knn_idx + (size_t)r * k;
+        float* bd = knn_d2 + (size_t)r * k;
+        int32_t cnt = 0;
+        for (int64_t j = 0; j < n; ++j) {
+            if (j == i) continue;
+            const float d = squared_distance_f32(pts + 3 * i, pts + 3 * j);
+            if (cnt == k && !(d < bd[k - 1])) continue;        /* j ascending: an equal distance never displaces */
+            int32_t s = cnt < k ? cnt : k - 1;
+            while (s > 0 && bd[s - 1] > d) { bd[s] = bd[s - 1]; bi[s] = bi[s - 1]; --s; }
+            bd[s] = d; bi[s] = (int32_t)j;
+            if (cnt < k) ++cnt;
+        }
+        for (int32_t s = cnt; s < k; ++s) { bi[s] = -1; bd[s] = INFINITY; }
+    }
+}
+
+/* CSR graph from the lists: directed (row i = its k neighbours) or symmetric closure (i ~ j if either lists the
+ * other); columns ascending; weights 1/deg(i) (kind 0), exp(-dist/sigma) (1) or exp(-dist^2/(2 sigma^2)) (2), the
+ * last two divided by their row sum; fp64.  Two calls: with col_out == NULL only row_ptr_out is written and nnz
+ * returned. */
+int64_t grf_ref_knn_graph(int64_t n, int32_t k, const int32_t* knn_idx, const float* knn_d2,
+                          int32_t symmetrise, int32_t weight_kind, double sigma,
+                          int32_t* row_ptr_out, int32_t* col_out, double* w_out)
+{
+    int64_t running = 0;
+    int32_t* cols = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    double* d2s = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t cnt = 0;
+        for (int32_t s = 0; s < k; ++s)
+            if (knn_idx[i * k + s] >= 0) { cols[cnt] = knn_idx[i * k + s]; d2s[cnt] = (double)knn_d2[i * k + s]; ++cnt; }
+        if (symmetrise)
+            for (int64_t j = 0; j < n; ++j) {
+                if (j == i) continue;
+                int lists_i = 0, listed = 0;
+                double d2 = 0.0;
+                for (int32_t s = 0; s < k; ++s) if (knn_idx[j * k + s] == (int32_t)i) { lists_i = 1; d2 = (double)knn_d2[j * k + s]; }
+                for (int32_t s = 0; s < k; ++s) if (knn_idx[i * k + s] == (int32_t)j) listed = 1;
+                if (lists_i && !listed) { cols[cnt] = (int32_t)j; d2s[cnt] = d2; ++cnt; }
+            }
+        row_ptr_out[i] = (int32_t)running;
+        if (col_out != NULL) {
+            for (int64_t a = 1; a < cnt; ++a) {
+                int64_t b = a;
+                while (b > 0 && cols[b - 1] > cols[b]) {
+                    int32_t tc = cols[b]; cols[b] = cols[b - 1]; cols[b - 1] = tc;
+                    double td = d2s[b]; d2s[b] = d2s[b - 1]; d2s[b - 1] = td;
+                    --b;
+                }
+            }
+            /* exp(-d/sigma) / sum exp(-d/sigma), with numerator and denominator both divided by the largest term
+             * (that of the nearest neighbour) so that a far-away row does not become 0 / 0 */
+            double total = 0.0, nearest = INFINITY;
+            for (int64_t a = 0; a < cnt; ++a) if (d2s[a] < nearest) nearest = d2s[a];
+            for (int64_t a = 0; a < cnt; ++a) {
+                double raw = 1.0;
+                if (weight_kind == 1) raw = exp(-(sqrt(d2s[a]) - sqrt(nearest)) / sigma);
+                if (weight_kind == 2) raw = exp(-(d2s[a] - nearest) / (2.0 * sigma * sigma));
+                d2s[a] = raw;
+                total += raw;
+            }
+            for (int64_t a = 0; a < cnt; ++a) {
+                col_out[running + a] = cols[a];
+                w_out[running + a] = d2s[a] / total;
+            }
+        }
+        running += cnt;
+    }
+    row_ptr_out[n] = (int32_t)running;
+    free(cols); free(d2s);
+    return running;
+}

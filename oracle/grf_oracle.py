@@ -26,7 +26,7 @@ RELU, IDENTITY, ELU1 = 0, 1, 2
 def build(force: bool = False) -> str:
     """Compile grf_oracle.c with gcc (-O2, no fast-math)."""
     if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-o", _LIB_PATH, _SRC, "-lm"])
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fPIC", "-shared", "-o", _LIB_PATH, _SRC, "-lm"])
     return _LIB_PATH
 
 
@@ -37,6 +37,7 @@ def _load():
         _lib = ctypes.CDLL(_LIB_PATH)
         _lib.grf_ref_sample.restype = ctypes.c_int64
         _lib.grf_ref_dphi_entry_direct.restype = ctypes.c_double
+        _lib.grf_ref_knn_graph.restype = ctypes.c_int64
     return _lib
 
 
@@ -392,3 +393,49 @@ def asymmetric_attention_backward(Q, K, V, row_ptr, col, val, out, den, dout, fe
                 _p(dV[b, h], ctypes.c_double), _p(de, ctypes.c_double))
             dphi[p] += de
     return dQ, dK, dV, dphi
+
+
+# --------------------------------------------------------------------------- graph construction for point clouds
+
+WEIGHT_INV_DEGREE, WEIGHT_EXP, WEIGHT_GAUSS = 0, 1, 2
+
+
+def knn_lists(points, k: int):
+    """Brute-force k nearest neighbours of fp32 points [n,3]: (idx int32 [n,k], squared distances fp32 [n,k]),
+    ordered by (fp32 squared distance, index); -1 / inf where fewer than k other points exist."""
+    pts = _f32(points)
+    n = pts.shape[0]
+    idx = np.empty((n, k), dtype=np.int32)
+    d2 = np.empty((n, k), dtype=np.float32)
+    _load().grf_ref_knn_lists(ctypes.c_int64(n), _p(pts, ctypes.c_float), ctypes.c_int32(k), _p(idx, ctypes.c_int32), _p(d2, ctypes.c_float))
+    return idx, d2
+
+
+def knn_lists_rows(points, k: int, rows):
+    """knn_lists for the query points ``rows`` only (brute force over all points for each)."""
+    pts = _f32(points)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    idx = np.empty((len(rows), k), dtype=np.int32)
+    d2 = np.empty((len(rows), k), dtype=np.float32)
+    _load().grf_ref_knn_lists_rows(ctypes.c_int64(pts.shape[0]), _p(pts, ctypes.c_float), ctypes.c_int32(k), ctypes.c_int64(len(rows)),
+                                   _p(rows, ctypes.c_int64), _p(idx, ctypes.c_int32), _p(d2, ctypes.c_float))
+    return idx, d2
+
+
+def knn_graph(points, k: int, symmetrise: bool = True, weight_kind: int = WEIGHT_GAUSS, sigma: float = 1.0):
+    """(row_ptr int32 [n+1], col int32 [nnz], w float64 [nnz]) of the (symmetrised) k-nearest-neighbour graph."""
+    idx, d2 = knn_lists(points, k)
+    n = idx.shape[0]
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    lib = _load()
+
+    def call(col, w):
+        return lib.grf_ref_knn_graph(ctypes.c_int64(n), ctypes.c_int32(k), _p(idx, ctypes.c_int32), _p(d2, ctypes.c_float),
+                                     ctypes.c_int32(1 if symmetrise else 0), ctypes.c_int32(weight_kind), ctypes.c_double(sigma),
+                                     _p(row_ptr, ctypes.c_int32), _p(col, ctypes.c_int32), _p(w, ctypes.c_double))
+
+    nnz = call(None, None)
+    col = np.empty(nnz, dtype=np.int32)
+    w = np.empty(nnz, dtype=np.float64)
+    call(col, w)
+    return row_ptr, col, w

@@ -98,6 +98,14 @@ def lib() -> ctypes.CDLL:
                                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                                            ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.grf_knn_graph_nnz_bound.restype = ctypes.c_int64
+        L.grf_knn_graph_nnz_bound.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
+        L.grf_knn_graph_workspace_bytes.restype = ctypes.c_size_t
+        L.grf_knn_graph_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32]
+        L.grf_knn_graph.restype = ctypes.c_int32
+        L.grf_knn_graph.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                    ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64)]
         L.grf_asymmetric_backward_workspace_bytes.restype = ctypes.c_size_t
         L.grf_asymmetric_backward_workspace_bytes.argtypes = L.grf_attention_workspace_bytes.argtypes
         L.grf_asymmetric_masked_attention_backward.restype = ctypes.c_int32
@@ -200,6 +208,42 @@ class Phi:
 
 
 # --------------------------------------------------------------------------- entry points (same names as the C ABI)
+
+GRF_WEIGHT_INV_DEGREE, GRF_WEIGHT_EXP, GRF_WEIGHT_GAUSS = 0, 1, 2
+_WEIGHT_KINDS = {"inv_degree": GRF_WEIGHT_INV_DEGREE, "exp": GRF_WEIGHT_EXP, "gauss": GRF_WEIGHT_GAUSS}
+
+
+def grf_knn_graph_nnz_bound(n: int, k: int, symmetrise: bool = True) -> int:
+    return int(lib().grf_knn_graph_nnz_bound(n, k, 1 if symmetrise else 0))
+
+
+def grf_knn_graph_workspace_bytes(n: int, k: int) -> int:
+    return int(lib().grf_knn_graph_workspace_bytes(n, k))
+
+
+def grf_knn_graph(points: torch.Tensor, k: int, symmetrise: bool = True, weights: str = "gauss", sigma: float = 1.0,
+                  workspace: Optional[torch.Tensor] = None, stream=None) -> DeviceGraph:
+    """Exact k-nearest-neighbour graph of ``points`` (CUDA fp32 [n, 3]) as a DeviceGraph."""
+    _require_gpu()
+    L = lib()
+    if points.dim() != 2 or points.shape[1] != 3 or points.dtype != torch.float32 or not points.is_cuda or not points.is_contiguous():
+        raise ValueError("points must be a contiguous CUDA fp32 tensor [n, 3]")
+    n = int(points.shape[0])
+    bound = L.grf_knn_graph_nnz_bound(n, k, 1 if symmetrise else 0)
+    if bound < 0:
+        raise GrfError(GRF_EUNSUPPORTED, f"unsupported k={k}")
+    dev = points.device
+    if workspace is None:
+        workspace = _workspace(L.grf_knn_graph_workspace_bytes(n, k), dev)
+    row_ptr = torch.empty(n + 1, dtype=torch.int32, device=dev)
+    col = torch.empty(max(bound, 1), dtype=torch.int32, device=dev)
+    w = torch.empty(max(bound, 1), dtype=torch.float32, device=dev)
+    nnz = ctypes.c_int64(0)
+    _check(L.grf_knn_graph(_ptr(points), n, int(k), 1 if symmetrise else 0, _WEIGHT_KINDS[weights], float(sigma),
+                           _ptr(workspace), workspace.numel(), _stream_ptr(stream),
+                           _ptr(row_ptr), _ptr(col), _ptr(w), int(col.numel()), ctypes.byref(nnz)))
+    return DeviceGraph(n, row_ptr, col[: nnz.value], w[: nnz.value])
+
 
 def grf_sample_nnz_bound(n: int, n_walks: int, f_len: int) -> int:
     return int(lib().grf_sample_nnz_bound(n, n_walks, f_len))

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgrf_hip.so")
-SOURCES = ("status.hip", "sampler.hip", "attention.hip", "fused.hip", "asymmetric.hip", "backward.hip")
+SOURCES = ("status.hip", "sampler.hip", "attention.hip", "fused.hip", "asymmetric.hip", "backward.hip", "knn.hip")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -288,14 +288,20 @@ def workload(name: str, data_seed: int = 0, walk_seed: int = 0) -> Workload:
         g = grid_graph(32, 32, 8)
         return Workload(name, g, modulation(10, rng, "normal", std=0.5), 0.5, 8, 32, 8, 64, "f32", walk_seed, data_seed)
     if name == "cloud_8k":
-        g = knn_graph(uniform_points(8192, rng), 8, "exp")
-        return Workload(name, g, modulation(12, rng, "decay"), 0.25, 16, 8, 8, 64, "f32", walk_seed, data_seed)
+        pts = uniform_points(8192, rng)
+        g = knn_graph(pts, 8, "exp")
+        return Workload(name, g, modulation(12, rng, "decay"), 0.25, 16, 8, 8, 64, "f32", walk_seed, data_seed,
+                        {"points": pts, "k": 8, "kernel": "exp"})
     if name == "cloud_32k":
-        g = knn_graph(cluster_points(32768, 16, 0.05, rng), 16, "gauss")
-        return Workload(name, g, modulation(16, rng, "decay"), 0.2, 32, 1, 8, 64, "f32", walk_seed, data_seed)
+        pts = cluster_points(32768, 16, 0.05, rng)
+        g = knn_graph(pts, 16, "gauss")
+        return Workload(name, g, modulation(16, rng, "decay"), 0.2, 32, 1, 8, 64, "f32", walk_seed, data_seed,
+                        {"points": pts, "k": 16, "kernel": "gauss"})
     if name == "cloud_128k":
-        g = knn_graph(uniform_points(131072, rng), 16, "gauss")
-        return Workload(name, g, modulation(16, rng, "decay", n_f=16), 0.2, 32, 1, 16, 64, "bf16", walk_seed, data_seed)
+        pts = uniform_points(131072, rng)
+        g = knn_graph(pts, 16, "gauss")
+        return Workload(name, g, modulation(16, rng, "decay", n_f=16), 0.2, 32, 1, 16, 64, "bf16", walk_seed, data_seed,
+                        {"points": pts, "k": 16, "kernel": "gauss"})
     raise ValueError(name)
 
 

@@ -1,0 +1,171 @@
+"""k-nearest-neighbour graph construction of the HIP library against the CPU checker (needs the GPU).
+
+Neighbour lists and the CSR pattern are integer work decided by fp32 distances that both sides compute with the
+same operation order: they must be bit-exact.  Weights: 1e-5 in max|x - ref| / max|ref|.
+"""
+import numpy as np
+import pytest
+
+from paper_2410_03462_amd import synth
+
+pytestmark = pytest.mark.gpu
+TOL_F32 = 1e-5
+
+
+@pytest.fixture(scope="module")
+def grf():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2410_03462_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(x):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to("cuda:0")
+
+
+def host(g):
+    return g.row_ptr.cpu().numpy(), g.col.cpu().numpy(), g.w.cpu().numpy()
+
+
+def relerr(x, ref):
+    assert np.isfinite(x).all() and np.isfinite(ref).all()
+    scale = np.abs(ref).max()
+    return float(np.abs(np.asarray(x, np.float64) - ref).max() / scale) if scale > 0 else 0.0
+
+
+def check_against_checker(grf, oracle, pts, k, sigma=0.05):
+    pts = np.ascontiguousarray(pts, dtype=np.float32)
+    idx, _ = oracle.knn_lists(pts, k)
+    n = len(pts)
+    # directed lists, uniform weights: the sorted lists themselves
+    rp, col, w = host(grf.grf_knn_graph(dev(pts), k, symmetrise=False, weights="inv_degree"))
+    rp0, col0, w0 = oracle.knn_graph(pts, k, False, oracle.WEIGHT_INV_DEGREE)
+    assert np.array_equal(rp, rp0) and np.array_equal(col, col0)
+    assert relerr(w, w0) <= TOL_F32
+    valid = idx >= 0
+    assert np.array_equal(np.diff(rp), valid.sum(axis=1))
+    # symmetric closure with both kernels
+    for name, kind in (("gauss", oracle.WEIGHT_GAUSS), ("exp", oracle.WEIGHT_EXP)):
+        rp, col, w = host(grf.grf_knn_graph(dev(pts), k, symmetrise=True, weights=name, sigma=sigma))
+        rp0, col0, w0 = oracle.knn_graph(pts, k, True, kind, sigma)
+        assert np.array_equal(rp, rp0) and np.array_equal(col, col0), name
+        assert relerr(w, w0) <= TOL_F32, (name, relerr(w, w0))
+    # a second run gives the same bits
+    again = host(grf.grf_knn_graph(dev(pts), k, symmetrise=True, weights="exp", sigma=sigma))
+    assert all(np.array_equal(a, b) for a, b in zip(again, (rp, col, w)))
+
+
+@pytest.mark.parametrize("n,k", [(3000, 9), (777, 3), (2049, 16), (500, 32), (64, 1)])
+def test_uniform_points(grf, oracle, n, k):
+    check_against_checker(grf, oracle, np.random.default_rng(n).random((n, 3)), k)
+
+
+def test_coordinates_where_rounding_decides(grf, oracle):
+    """Coordinates near 1000 with neighbour distances near 1: the fp32 rounding of every product and sum shows in
+    the squared distances (a fused multiply-add on either side would reorder near-ties and shift the weights)."""
+    rng = np.random.default_rng(8)
+    pts = rng.random((4000, 3)) * 16.0 + 1000.0
+    check_against_checker(grf, oracle, pts, 12, sigma=0.2)
+
+
+def test_clustered_points_and_outliers(grf, oracle):
+    rng = np.random.default_rng(3)
+    pts = synth.cluster_points(6000, 5, 0.03, rng)
+    pts[17] = [40.0, -3.0, 9.0]                # far outliers: many empty shells before the search may stop
+    pts[4000] = [-25.0, 0.5, 0.5]
+    check_against_checker(grf, oracle, pts, 8)
+
+
+def test_exact_ties_on_lattices(grf, oracle):
+    g = np.stack(np.meshgrid(np.arange(12), np.arange(12), np.arange(12), indexing="ij"), -1).reshape(-1, 3)
+    check_against_checker(grf, oracle, g, 6, sigma=1.0)        # every interior point: six neighbours at distance 1
+    check_against_checker(grf, oracle, g, 7, sigma=1.0)        # the seventh is a 12-fold tie broken by index
+    line = np.zeros((300, 3)); line[:, 0] = np.arange(300)
+    check_against_checker(grf, oracle, line, 2, sigma=1.0)
+
+
+def test_degenerate_clouds(grf, oracle):
+    rng = np.random.default_rng(4)
+    same = np.full((200, 3), 0.25)                              # all points identical: every distance ties at 0
+    check_against_checker(grf, oracle, same, 5)
+    flat = rng.random((1500, 3)); flat[:, 2] = 0.5              # planar
+    check_against_checker(grf, oracle, flat, 6)
+    rod = rng.random((1500, 3)) * [1.0, 1e-3, 1e-3]             # nearly one-dimensional
+    check_against_checker(grf, oracle, rod, 6)
+    few = rng.random((5, 3))                                    # fewer points than k
+    check_against_checker(grf, oracle, few, 8)
+    one = rng.random((1, 3))
+    rp, col, w = host(grf.grf_knn_graph(dev(one), 3))
+    assert rp.tolist() == [0, 0] and len(col) == 0
+    import torch
+    empty = grf.grf_knn_graph(torch.zeros((0, 3), device="cuda:0"), 3)
+    assert empty.n == 0 and empty.nnz == 0
+
+
+def test_argument_errors(grf):
+    import torch
+    pts = torch.rand((100, 3), device="cuda:0")
+    with pytest.raises(grf.GrfError) as e:
+        grf.grf_knn_graph(pts, 33)
+    assert e.value.status == grf.GRF_EUNSUPPORTED
+    with pytest.raises(grf.GrfError) as e:
+        grf.grf_knn_graph(pts, 4, weights="gauss", sigma=0.0)
+    assert e.value.status == grf.GRF_EINVAL
+    with pytest.raises(grf.GrfError) as e:
+        grf.grf_knn_graph(pts, 4, workspace=torch.empty(256, dtype=torch.uint8, device="cuda:0"))
+    assert e.value.status == grf.GRF_EWORKSPACE
+    with pytest.raises(ValueError):
+        grf.grf_knn_graph(pts.double(), 4)
+
+
+def test_headline_point_cloud_full_size(grf, oracle):
+    """The 32768 clustered points of the headline workload, k = 16, symmetrised, Gaussian kernel: the whole graph
+    against the brute-force checker (sigma as the workload generator defines it: the median neighbour distance)."""
+    wl = synth.workload("cloud_32k")
+    pts = wl.notes["points"].astype(np.float32)
+    from scipy.spatial import cKDTree
+    dist, _ = cKDTree(pts.astype(np.float64)).query(pts.astype(np.float64), k=17)
+    sigma = float(np.median(dist[:, 1:]))
+    rp, col, w = host(grf.grf_knn_graph(dev(pts), 16, symmetrise=True, weights="gauss", sigma=sigma))
+    rp0, col0, w0 = oracle.knn_graph(pts, 16, True, oracle.WEIGHT_GAUSS, sigma)
+    assert np.array_equal(rp, rp0) and np.array_equal(col, col0)
+    assert relerr(w, w0) <= TOL_F32
+
+
+def test_largest_point_cloud_sampled_rows(grf, oracle):
+    """131072 uniform points, k = 16: directed lists of sampled rows against brute force over all points."""
+    wl_pts = np.random.default_rng([0, 1]).random((131072, 3)).astype(np.float32)
+    g = grf.grf_knn_graph(dev(wl_pts), 16, symmetrise=False, weights="inv_degree")
+    rp, col, _ = host(g)
+    assert np.array_equal(rp, np.arange(131073) * 16)
+    rows = np.random.default_rng(9).choice(131072, size=300, replace=False)
+    idx, _ = oracle.knn_lists_rows(wl_pts, 16, rows)
+    assert np.array_equal(col.reshape(131072, 16)[rows], np.sort(idx, axis=1))
+
+
+def test_dynamic_point_cloud_pipeline(grf, oracle):
+    """The paper's dynamic setting end to end on the GPU: neighbour lists of length 3, 27 walks of exactly 3 hops
+    (no halting), asymmetric GRFs, one head -- against the checker's chain from the same points."""
+    rng = np.random.default_rng(12)
+    pts = synth.cluster_points(4096, 6, 0.05, rng).astype(np.float32)
+    k, n_walks, f = 3, 27, np.array([[1.0, 0.6, 0.3, 0.15]], dtype=np.float32)
+    g = grf.grf_knn_graph(dev(pts), k, symmetrise=False, weights="inv_degree")
+    phi = grf.grf_sample(g, f, 0.0, n_walks, 5)
+    Q, K, V = synth.qkv(1, 1, len(pts), 64, rng)
+    import torch
+    Qd, Kd, Vd = (torch.from_numpy(x).to("cuda:0") for x in (Q, K, V))
+    out, num, den = grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi, return_num_den=True)
+    rp0, col0, w0 = oracle.knn_graph(pts, k, False, oracle.WEIGHT_INV_DEGREE)
+    g0 = synth.Graph(len(pts), rp0, col0, w0.astype(np.float32))
+    prp, pcol, pval = oracle.sample(g0, f, 0.0, n_walks, 5)
+    assert np.array_equal(phi.row_ptr.cpu().numpy(), prp) and np.array_equal(phi.col[: phi.nnz].cpu().numpy(), pcol)
+    ref = oracle.asymmetric_attention_walks(g0, f[0], 0.0, n_walks, 5, Q, K, V)
+    assert relerr(num.cpu().numpy(), ref["num"]) <= TOL_F32
+    assert relerr(den.cpu().numpy(), ref["den"]) <= TOL_F32
+    # every walk has exactly 3 hops: 1 + 27 * 3 deposits per node
+    traj = grf.grf_sample_walks(g, 0.0, n_walks, 4, 5).cpu().numpy()
+    assert np.all(traj >= 0)
