@@ -4,9 +4,9 @@
 // the paper names the neighbour search as the bottleneck of that setting (Sec. 4, point-cloud
 // experiment; App. C).  The paper uses an unspecified approximate solver; this one is exact:
 //
-//   1. bounding box, then a uniform grid with about two points per cell (device-side, no host sync);
+//   1. bounding box, then a uniform grid with about one point per two cells (device-side, no host sync);
 //   2. counting sort of the points by cell (histogram, scan, scatter);
-//   3. one thread per query point, in cell order: cells are visited in shells of growing Chebyshev
+//   3. eight lanes per query point, queries in cell order: cells are visited in shells of growing Chebyshev
 //      radius around the query's cell and the k best (squared distance, index) pairs are kept in
 //      registers; the search stops when the k-th best distance is below the distance to anything
 //      outside the visited shells;
@@ -22,7 +22,7 @@ namespace grf {
 
 namespace {
 constexpr int kMaxGridDim = 256;
-constexpr float kTargetPerCell = 2.0f;
+constexpr float kTargetPerCell = 0.5f;      // mean points per cell: small cells keep the shells tight where the cloud is dense
 }  // namespace
 
 struct KnnGrid {
@@ -137,15 +137,24 @@ __global__ __launch_bounds__(256) void knn_cell_scatter_kernel(const float* __re
 }
 
 // ------------------------------------------------------------------------------------ search
-// One thread per query point, in cell order.  best[] is kept sorted ascending by (distance, index);
-// unused slots hold (+inf, INT_MAX).
+// Eight lanes per query point (eight queries per wavefront), queries in cell order.  The cells of a shell are
+// scanned as runs of consecutive points (a row of cells along x is one run in the sorted array); the eight
+// lanes take eight points of a run at a time, and those that beat the current k-th best are inserted one
+// after the other into the list, which every lane of the group holds (sorted ascending by (distance, index);
+// unused slots hold (+inf, INT_MAX)).
+constexpr int kLanesPerQuery = 8;
+
 template <int KMAX>
-__global__ __launch_bounds__(256) void knn_search_kernel(const float4* __restrict__ sorted, long long n, int k,
+__global__ __launch_bounds__(64) void knn_search_kernel(const float4* __restrict__ sorted, long long n, int k,
                                                          const KnnGrid* __restrict__ grid, const int32_t* __restrict__ cell_start,
                                                          int32_t* __restrict__ knn_idx, float* __restrict__ knn_d2)
 {
-    const long long t = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (t >= n) return;
+    constexpr int L = kLanesPerQuery;
+    const int lane = lane_id();
+    const int sub = lane % L;                         // lane inside the group
+    const int group_base = lane - sub;                // first lane of the group
+    const long long t = (static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x) / L;
+    if (t >= n) return;                               // whole groups leave together
     const KnnGrid g = *grid;
     const float4 me = sorted[t];
     const int my_index = __float_as_int(me.w);
@@ -160,62 +169,84 @@ __global__ __launch_bounds__(256) void knn_search_kernel(const float4* __restric
     float worst_d = __builtin_inff();       // slot k - 1
     int worst_i = 2147483647;
 
-    auto visit_cell = [&](int x, int y, int z) {
-        const int c = (z * g.dims[1] + y) * g.dims[0] + x;
-        const int beg = cell_start[c], end = cell_start[c + 1];
-        for (int p = beg; p < end; ++p) {
-            const float4 q = sorted[p];
+    // points [beg, end) of the sorted array
+    auto visit_run = [&](int beg, int end) {
+        for (int p0 = beg; p0 < end; p0 += L) {
+            const int p = p0 + sub;
+            const float4 q = sorted[min(p, end - 1)];
             const int j = __float_as_int(q.w);
-            if (j == my_index) continue;
             const float d = squared_distance(me.x, me.y, me.z, q.x, q.y, q.z);
-            if (!(d < worst_d || (d == worst_d && j < worst_i))) continue;
-            float cd = d;
-            int ci = j;
+            const bool pass = p < end && j != my_index && (d < worst_d || (d == worst_d && j < worst_i));
+            unsigned pending = static_cast<unsigned>(__ballot(pass) >> group_base) & ((1u << L) - 1u);
+            while (pending != 0u) {
+                const int src = group_base + __builtin_ctz(pending);
+                pending &= pending - 1u;
+                float cd = __shfl(d, src, kWave);
+                int ci = __shfl(j, src, kWave);
+                if (!(cd < worst_d || (cd == worst_d && ci < worst_i))) continue;      // the list has moved on
 #pragma unroll
-            for (int s = 0; s < KMAX; ++s) {
-                const bool less = (cd < bd[s]) || (cd == bd[s] && ci < bi[s]);
-                const float td = less ? bd[s] : cd;
-                const int ti = less ? bi[s] : ci;
-                bd[s] = less ? cd : bd[s];
-                bi[s] = less ? ci : bi[s];
-                cd = td; ci = ti;
+                for (int s = 0; s < KMAX; ++s) {
+                    const bool less = (cd < bd[s]) || (cd == bd[s] && ci < bi[s]);
+                    const float td = less ? bd[s] : cd;
+                    const int ti = less ? bi[s] : ci;
+                    bd[s] = less ? cd : bd[s];
+                    bi[s] = less ? ci : bi[s];
+                    cd = td; ci = ti;
+                }
+#pragma unroll
+                for (int s = 0; s < KMAX; ++s)
+                    if (s == k - 1) { worst_d = bd[s]; worst_i = bi[s]; }
             }
-#pragma unroll
-            for (int s = 0; s < KMAX; ++s)
-                if (s == k - 1) { worst_d = bd[s]; worst_i = bi[s]; }
         }
+    };
+    auto visit_cells = [&](int x0, int x1, int y, int z) {      // cells x0 .. x1 of row (y, z): one run
+        const int c0 = (z * g.dims[1] + y) * g.dims[0];
+        visit_run(cell_start[c0 + x0], cell_start[c0 + x1 + 1]);
     };
 
     const int max_ring = max(g.dims[0], max(g.dims[1], g.dims[2]));
+    const int cc[3] = {cx, cy, cz};
+    const float mp[3] = {me.x, me.y, me.z};
     for (int r = 0; r <= max_ring; ++r) {
         if (r > 0) {
-            // everything outside the visited shells is farther than (r - 1) cell edges plus the query's distance
-            // to its own cell's boundary; the margin of 0.01 cells covers the rounding of the cell coordinates
-            const float reach = (static_cast<float>(r) - 1.01f) * g.h;
+            // shells 0 .. r-1 cover the box of cells [c - (r-1), c + (r-1)] on every axis; whatever is outside is at
+            // least as far as the nearest face of that box that still has cells beyond it.  A margin of 0.01 cell
+            // edges covers the rounding of the cell coordinates.
+            float reach = __builtin_inff();
+#pragma unroll
+            for (int a = 0; a < 3; ++a) {
+                const float rel = (mp[a] - g.lo[a]) * g.inv_h;       // query position in cell units
+                if (cc[a] - (r - 1) > 0) reach = fminf(reach, rel - static_cast<float>(cc[a] - (r - 1)));
+                if (cc[a] + (r - 1) < g.dims[a] - 1) reach = fminf(reach, static_cast<float>(cc[a] + r) - rel);
+            }
+            if (reach == __builtin_inff()) break;                    // every cell has been visited
+            reach = (reach - 0.01f) * g.h;
             if (reach > 0.0f && worst_d <= reach * reach) break;
         }
         const int z0 = max(cz - r, 0), z1 = min(cz + r, g.dims[2] - 1);
         const int y0 = max(cy - r, 0), y1 = min(cy + r, g.dims[1] - 1);
+        const int x0 = max(cx - r, 0), x1 = min(cx + r, g.dims[0] - 1);
         for (int z = z0; z <= z1; ++z) {
             const bool zface = (z == cz - r) || (z == cz + r);
             for (int y = y0; y <= y1; ++y) {
                 const bool face = zface || (y == cy - r) || (y == cy + r);
                 if (face) {
-                    const int x0 = max(cx - r, 0), x1 = min(cx + r, g.dims[0] - 1);
-                    for (int x = x0; x <= x1; ++x) visit_cell(x, y, z);
+                    visit_cells(x0, x1, y, z);
                 } else {
-                    if (cx - r >= 0) visit_cell(cx - r, y, z);
-                    if (r > 0 && cx + r < g.dims[0]) visit_cell(cx + r, y, z);
+                    if (cx - r >= 0) visit_cells(cx - r, cx - r, y, z);
+                    if (cx + r < g.dims[0]) visit_cells(cx + r, cx + r, y, z);
                 }
             }
         }
     }
+    if (sub == 0) {
 #pragma unroll
-    for (int s = 0; s < KMAX; ++s)
-        if (s < k) {
-            knn_idx[static_cast<long long>(my_index) * k + s] = bi[s] == 2147483647 ? -1 : bi[s];
-            knn_d2[static_cast<long long>(my_index) * k + s] = bd[s];
-        }
+        for (int s = 0; s < KMAX; ++s)
+            if (s < k) {
+                knn_idx[static_cast<long long>(my_index) * k + s] = bi[s] == 2147483647 ? -1 : bi[s];
+                knn_d2[static_cast<long long>(my_index) * k + s] = bd[s];
+            }
+    }
 }
 
 // ------------------------------------------------------------------------------------ graph assembly
@@ -312,8 +343,8 @@ struct KnnScratch {
     KnnGrid* grid;
     long long* total;
     int32_t* cell_of_point;   // [n]
-    int32_t* cell_start;      // [n + 2]
-    int32_t* cursor;          // [n + 1]  (cells, then rows)
+    int32_t* cell_start;      // [cells + 2], cells <= 2 n
+    int32_t* cursor;          // [2 n + 1]  (cells, then rows)
     float4* sorted;           // [n]
     int32_t* knn_idx;         // [n][k]
     float* knn_d2;            // [n][k]
@@ -331,8 +362,8 @@ KnnScratch carve_knn(unsigned char* ws, int64_t n, int32_t k)
     s.grid = reinterpret_cast<KnnGrid*>(take(sizeof(KnnGrid)));
     s.total = reinterpret_cast<long long*>(take(sizeof(long long)));
     s.cell_of_point = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * rows));
-    s.cell_start = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (rows + 2)));
-    s.cursor = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (rows + 1)));
+    s.cell_start = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (2 * rows + 2)));
+    s.cursor = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (2 * rows + 1)));
     s.sorted = reinterpret_cast<float4*>(take(sizeof(float4) * rows));
     s.knn_idx = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * rows * kk));
     s.knn_d2 = reinterpret_cast<float*>(take(sizeof(float) * rows * kk));
@@ -387,15 +418,16 @@ extern "C" grf_status grf_knn_graph(const float* points, int64_t n, int32_t k, i
     const KnnScratch s = carve_knn(static_cast<unsigned char*>(workspace), n, k);
     const unsigned pblocks = static_cast<unsigned>((n + 255) / 256);
     const unsigned eblocks = static_cast<unsigned>((n * k + 255) / 256);
+    const unsigned sblocks = static_cast<unsigned>((n + 7) / 8);        // one wavefront = eight queries per workgroup: the searches differ in length
 
     hipLaunchKernelGGL(knn_grid_kernel, dim3(1), dim3(1024), 0, stream, points, static_cast<long long>(n), s.grid);
     GRF_LAUNCH_CHECK("knn_grid_kernel");
-    if (grf_status st = fill_i32(s.cell_start, n + 2, 0, stream)) return st;
-    if (grf_status st = fill_i32(s.cursor, n + 1, 0, stream)) return st;
+    if (grf_status st = fill_i32(s.cell_start, 2 * n + 2, 0, stream)) return st;
+    if (grf_status st = fill_i32(s.cursor, 2 * n + 1, 0, stream)) return st;
     hipLaunchKernelGGL(knn_cell_count_kernel, dim3(pblocks), dim3(256), 0, stream, points, static_cast<long long>(n),
                        static_cast<const KnnGrid*>(s.grid), s.cell_of_point, s.cell_start);
     GRF_LAUNCH_CHECK("knn_cell_count_kernel");
-    if (grf_status st = exclusive_scan_inplace(s.cell_start, n + 1, s.total, stream)) return st;     // cells <= n
+    if (grf_status st = exclusive_scan_inplace(s.cell_start, 2 * n + 1, s.total, stream)) return st;     // cells <= 2 n
     hipLaunchKernelGGL(knn_cell_scatter_kernel, dim3(pblocks), dim3(256), 0, stream, points, static_cast<long long>(n),
                        static_cast<const int32_t*>(s.cell_of_point), static_cast<const int32_t*>(s.cell_start), s.cursor, s.sorted);
     GRF_LAUNCH_CHECK("knn_cell_scatter_kernel");
@@ -404,13 +436,13 @@ extern "C" grf_status grf_knn_graph(const float* points, int64_t n, int32_t k, i
     const KnnGrid* grid = s.grid;
     const int32_t* cell_start = s.cell_start;
     if (k <= 4)
-        hipLaunchKernelGGL((knn_search_kernel<4>), dim3(pblocks), dim3(256), 0, stream, sorted, static_cast<long long>(n), k, grid, cell_start, s.knn_idx, s.knn_d2);
+        hipLaunchKernelGGL((knn_search_kernel<4>), dim3(sblocks), dim3(64), 0, stream, sorted, static_cast<long long>(n), k, grid, cell_start, s.knn_idx, s.knn_d2);
     else if (k <= 8)
-        hipLaunchKernelGGL((knn_search_kernel<8>), dim3(pblocks), dim3(256), 0, stream, sorted, static_cast<long long>(n), k, grid, cell_start, s.knn_idx, s.knn_d2);
+        hipLaunchKernelGGL((knn_search_kernel<8>), dim3(sblocks), dim3(64), 0, stream, sorted, static_cast<long long>(n), k, grid, cell_start, s.knn_idx, s.knn_d2);
     else if (k <= 16)
-        hipLaunchKernelGGL((knn_search_kernel<16>), dim3(pblocks), dim3(256), 0, stream, sorted, static_cast<long long>(n), k, grid, cell_start, s.knn_idx, s.knn_d2);
+        hipLaunchKernelGGL((knn_search_kernel<16>), dim3(sblocks), dim3(64), 0, stream, sorted, static_cast<long long>(n), k, grid, cell_start, s.knn_idx, s.knn_d2);
     else
-        hipLaunchKernelGGL((knn_search_kernel<32>), dim3(pblocks), dim3(256), 0, stream, sorted, static_cast<long long>(n), k, grid, cell_start, s.knn_idx, s.knn_d2);
+        hipLaunchKernelGGL((knn_search_kernel<32>), dim3(sblocks), dim3(64), 0, stream, sorted, static_cast<long long>(n), k, grid, cell_start, s.knn_idx, s.knn_d2);
     GRF_LAUNCH_CHECK("knn_search_kernel");
 
     // rows: degrees, offsets, edges, then ordered columns and weights
