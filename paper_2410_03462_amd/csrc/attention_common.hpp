@@ -100,7 +100,7 @@ __device__ __forceinline__ void load_operand_elems(const T* __restrict__ base, u
 {
     constexpr int T2 = D / 32;
     if constexpr (INTERLEAVED) {
-        const uint32_t off = j * D + T2 * li;
+        const size_t off = static_cast<size_t>(j) * D + T2 * li;
         if constexpr (sizeof(T) == 4 && T2 == 2) {
             const float2 v = *reinterpret_cast<const float2*>(base + off);
             x[0] = v.x; x[1] = v.y;
@@ -112,7 +112,7 @@ __device__ __forceinline__ void load_operand_elems(const T* __restrict__ base, u
         }
     } else {
 #pragma unroll
-        for (int t = 0; t < T2; ++t) x[t] = to_float(base[j * D + 32 * t + li]);
+        for (int t = 0; t < T2; ++t) x[t] = to_float(base[static_cast<size_t>(j) * D + 32 * t + li]);
     }
 }
 

@@ -50,6 +50,8 @@ def small_workloads():
     yield "star_300", synth.Workload("star_300", g, synth.modulation(6, rng), 0.35, 5, 1, 2, 32, "f32")
     g = synth.knn_graph(synth.uniform_points(2000, rng), 8, "gauss")
     yield "cloud_2k_perhead_bf16", synth.Workload("cloud_2k", g, synth.modulation(12, rng, n_f=3), 0.25, 16, 2, 3, 64, "bf16")
+    g = synth.grid_graph(13, 17, 8)
+    yield "grid_d32_bf16", synth.Workload("grid_d32_bf16", g, synth.modulation(7, rng), 0.4, 6, 2, 2, 32, "bf16")
 
 
 SMALL = dict(small_workloads())
