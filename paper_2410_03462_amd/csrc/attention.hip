@@ -112,8 +112,10 @@ __global__ __launch_bounds__(64) void buckets_kernel(const T* __restrict__ K, co
 
     floatx16 acc[T2][T2];
     float zacc[T2];
+    const int32_t beg = col_ptr[l], end = col_ptr[l + 1];
+    const ListBlock first = load_list_block<false>(csc_row, vals, nullptr, beg, end);
     with_feature_map(fmap, [&](auto fm) {
-        bucket_first_contraction<D, T, T, false, true, kExtraSumA, decltype(fm)::value>(Kb, Vb, csc_row, vals, nullptr, col_ptr[l], col_ptr[l + 1], acc, zacc);
+        bucket_first_contraction<D, T, T, false, true, kExtraSumA, decltype(fm)::value>(Kb, Vb, csc_row, vals, nullptr, beg, end, first, acc, zacc);
     });
 
     float* rec = buckets + (slice * n + l) * REC;
@@ -287,6 +289,17 @@ grf_status check_problem(const void* a, const void* b, int32_t dtype, int64_t B,
     if (B * H * n > 0 && (a == nullptr || b == nullptr)) return fail(GRF_EINVAL, "an input tensor is NULL");
     if (B * H > (1ll << 40) / (n > 0 ? n : 1)) return fail(GRF_EUNSUPPORTED, "B*H*n is too large");
     return GRF_OK;
+}
+
+unsigned resident_wave_grid(const void* kernel, long long items)
+{
+    int device = 0, units = 0, per_unit = 0;
+    if (hipGetDevice(&device) != hipSuccess || hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_unit, kernel, kWave, 0) != hipSuccess || units < 1 || per_unit < 1) {
+        units = 256; per_unit = 8;       // an MI355X with two wavefronts per SIMD
+    }
+    const long long resident = static_cast<long long>(units) * per_unit;
+    return static_cast<unsigned>(items < resident ? (items > 0 ? items : 1) : resident);
 }
 
 grf_status check_workspace(const void* workspace, size_t have, size_t need)

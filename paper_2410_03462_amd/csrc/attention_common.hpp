@@ -124,6 +124,29 @@ enum : int {
     kExtraNone = 3,
 };
 
+// (row, weight[, scale]) of up to 128 consecutive entries of a column list, one entry per lane in two register
+// sets: entries block + lane and block + 64 + lane, clamped to the last entry, with weight 0 past the end.
+struct ListBlock {
+    int32_t j_a, j_b;
+    float g_a, g_b, e_a, e_b;
+};
+
+template <bool SCALED>
+__device__ __forceinline__ ListBlock load_list_block(const int32_t* __restrict__ csc_row, const float* __restrict__ vals,
+                                                     const float* __restrict__ escale, int32_t block, int32_t end)
+{
+    ListBlock b = {0, 0, 0.0f, 0.0f, 0.0f, 0.0f};
+    if (block >= end) return b;       // wave-uniform
+    const int lane = lane_id();
+    const int32_t ea = min(block + lane, end - 1), eb = min(block + kWave + lane, end - 1);
+    b.j_a = csc_row[ea]; b.j_b = csc_row[eb];
+    const float va = vals[ea], vb = vals[eb];
+    b.g_a = block + lane < end ? va : 0.0f;
+    b.g_b = block + kWave + lane < end ? vb : 0.0f;
+    if constexpr (SCALED) { b.e_a = escale[b.j_a]; b.e_b = escale[b.j_b]; }
+    return b;
+}
+
 // First contraction of a bucket, shared by the bucket-forming, the bucket-fused and the backward kernels:
 //     acc[a][c] (32x32 tiles) += A^T B over the column list [beg, end) of bucket l,   extra[...] += see above,
 // where one of the two operands of a contributor is weight * phi(row) (A if WEIGHT_ON_A, else B) and the other
@@ -131,8 +154,9 @@ enum : int {
 // v_mfma_f32_32x32x2_f32); see load_operand_elems for which element a lane holds.
 //
 // The column list is walked in blocks of 128 entries (64 contributor pairs; most lists fit in one):
-//   - the (row, weight) of a block's entries are fetched up front, one entry per lane in two
-//     register pairs, and a pair's two entries (wave-uniform) are pulled out with v_readlane, so
+//   - the (row, weight) of a block's entries are fetched up front (load_list_block; the first block is handed
+//     in by the caller, who can fetch it while the previous bucket is still being worked on), one entry per lane
+//     in two register pairs, and a pair's two entries (wave-uniform) are pulled out with v_readlane, so
 //     that inside the block the only memory instructions are the row loads: the load counter
 //     retires in order, and any wait on a recently issued index load would drain every row load
 //     issued before it;
@@ -146,7 +170,7 @@ template <int D, typename TA, typename TB, bool INTERLEAVED, bool WEIGHT_ON_A, i
 __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ Ab, const TB* __restrict__ Bb,
                                                          const int32_t* __restrict__ csc_row, const float* __restrict__ vals,
                                                          const float* __restrict__ escale,
-                                                         int32_t beg_in, int32_t end_in,
+                                                         int32_t beg_in, int32_t end_in, const ListBlock& first,
                                                          floatx16 (&acc)[D / 32][D / 32], float (&zacc)[D / 32])
 {
     constexpr int T2 = D / 32;
@@ -183,14 +207,9 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
     };
 
     for (int32_t block = beg; block < end; block += 2 * kWave) {
-        // entries block + lane and block + 64 + lane (clamped to the last entry, weight 0 past the end)
-        const int32_t ea = min(block + lane, end - 1), eb = min(block + kWave + lane, end - 1);
-        const int32_t j_a = csc_row[ea], j_b = csc_row[eb];
-        const float va = vals[ea], vb_ = vals[eb];
-        const float g_a = block + lane < end ? va : 0.0f;
-        const float g_b = block + kWave + lane < end ? vb_ : 0.0f;
-        float e_a = 0.0f, e_b = 0.0f;
-        if constexpr (SCALED) { e_a = escale[j_a]; e_b = escale[j_b]; }
+        const ListBlock lb = block == beg ? first : load_list_block<SCALED>(csc_row, vals, escale, block, end);
+        const int32_t j_a = lb.j_a, j_b = lb.j_b;
+        const float g_a = lb.g_a, g_b = lb.g_b, e_a = lb.e_a, e_b = lb.e_b;
         const int pairs = min((end - block + 1) >> 1, kWave);      // pairs of this block
 
         float ab[RING][T2], bb[RING][T2], gb[RING], eb_[RING];
@@ -229,6 +248,11 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
         }
     }
 }
+
+// Number of one-wavefront workgroups that are resident at once for `kernel` on the current device (compute
+// units x workgroups per unit at the kernel's register use), capped by the number of work items: the grid of
+// the kernels that loop over their work items with a stride of the grid size.
+unsigned resident_wave_grid(const void* kernel, long long items);
 
 inline unsigned blocks_for(long long items, int per_block) { return static_cast<unsigned>((items + per_block - 1) / per_block); }
 

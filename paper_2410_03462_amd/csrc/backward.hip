@@ -158,14 +158,15 @@ __global__ __launch_bounds__(64) void backward_bucket_kernel(const T* __restrict
     // ---- first contraction
     floatx16 acc[T2][T2];
     float xacc[T2];
+    const ListBlock first = load_list_block<MODE == kKeySide>(csc_row, vals, gdb, beg, end);
     with_feature_map(fmap, [&](auto fm) {
         constexpr int FM = decltype(fm)::value;
         if constexpr (MODE == kQuerySide)
-            bucket_first_contraction<D, T, T, true, false, kExtraSumB, FM>(Vb, Kb, csc_row, vals, nullptr, beg, end, acc, xacc);
+            bucket_first_contraction<D, T, T, true, false, kExtraSumB, FM>(Vb, Kb, csc_row, vals, nullptr, beg, end, first, acc, xacc);
         else if constexpr (MODE == kKeySide)
-            bucket_first_contraction<D, float, T, true, false, kExtraScaledSumB, FM>(Gb, Qb, csc_row, vals, gdb, beg, end, acc, xacc);
+            bucket_first_contraction<D, float, T, true, false, kExtraScaledSumB, FM>(Gb, Qb, csc_row, vals, gdb, beg, end, first, acc, xacc);
         else
-            bucket_first_contraction<D, T, float, true, true, kExtraNone, FM>(Qb, Gb, csc_row, vals, nullptr, beg, end, acc, xacc);
+            bucket_first_contraction<D, T, float, true, true, kExtraNone, FM>(Qb, Gb, csc_row, vals, nullptr, beg, end, first, acc, xacc);
     });
 
     // the extra row, complete in the lower half-wave and zero in the upper, so that one more MFMA step

@@ -57,8 +57,10 @@ __device__ __forceinline__ void load_run(const T* __restrict__ p, float (&out)[N
     }
 }
 
-// One wavefront per (slice, bucket l), one wavefront per workgroup: column lists differ in length,
-// and a workgroup's slots are only handed on when its slowest wavefront is done.
+// One wavefront per workgroup, each working through the (slice, bucket) pairs w, w + G, w + 2G, ... of a grid
+// of G resident wavefronts: column lists differ in length, and the next bucket's bounds and first list block
+// are fetched while the current bucket is still in its matrix work, so that a bucket does not start with a
+// chain of three dependent memory round trips (bounds, list, rows).
 //
 // Every global load below is unconditional: lanes past the end of the column list re-read its last
 // entry with weight 0, so there are no branches around loads and the loads of the next stage
@@ -74,111 +76,136 @@ __global__ __launch_bounds__(64) void fused_bucket_kernel(const T* __restrict__ 
 {
     constexpr int T2 = D / 32;
     constexpr int QN = 4 * T2;     // features a lane holds per group of four accumulator registers
-    const long long wave = xcd_contiguous_block(blockIdx.x, gridDim.x);     // one wavefront per workgroup
+    const long long stride = gridDim.x;
+    long long wave = xcd_contiguous_block(blockIdx.x, gridDim.x);
     if (wave >= n_waves) return;
-    const long long slice = wave / n;
-    const long long l = wave - slice * n;
-    const long long bh = bh_first + slice;
-    const long long plane = n_f > 1 ? (bh % H) : 0;
-    const T* Qb = Q + bh * n * D;
-    const T* Kb = K + bh * n * D;
-    const T* Vb = V + bh * n * D;
-    const float* vals = csc_val + plane * nnz;
 
     const int lane = lane_id();
     const int half = lane >> 5;
     const int li = lane & 31;
 
-    const int32_t beg = __builtin_amdgcn_readfirstlane(col_ptr[l]);
-    const int32_t end = __builtin_amdgcn_readfirstlane(col_ptr[l + 1]);
-    if (beg >= end) return;      // nobody visits node l: no partial rows belong to it
-
-    // consumers of tile `tile`: row index and weight of entry tile + li (clamped, weight 0 past the end)
-    auto fetch_index = [&](int32_t tile, int32_t& row, float& g) {
-        const int32_t pos = min(tile + li, end - 1);
-        row = csc_row[pos];
-        g = tile + li < end ? vals[pos] : 0.0f;
+    auto bounds_of = [&](long long w, int32_t& beg, int32_t& end) {
+        const long long l = w % n;
+        beg = __builtin_amdgcn_readfirstlane(col_ptr[l]);
+        end = __builtin_amdgcn_readfirstlane(col_ptr[l + 1]);
     };
-    auto fetch_q = [&](long long row, float (&qq)[4][QN]) {
-#pragma unroll
-        for (int b = 0; b < 4; ++b) load_run<T, QN>(Qb + row * D + T2 * (8 * b + 4 * half), qq[b]);
+    auto values_of = [&](long long w) {
+        const long long bh = bh_first + w / n;
+        return csc_val + (n_f > 1 ? (bh % H) : 0) * static_cast<long long>(nnz);
     };
 
-    // the first two consumer tiles' indices and the first tile's rows of Q go out before the first
-    // contraction starts, so that they have arrived when it ends
-    int32_t qrow_cur, qrow_next;
-    float gq_cur, gq_next;
-    fetch_index(beg, qrow_cur, gq_cur);
-    fetch_index(beg + 32, qrow_next, gq_next);
-    float qn[4][QN];
-    fetch_q(qrow_cur, qn);
+    int32_t beg, end;
+    bounds_of(wave, beg, end);
+    ListBlock first = load_list_block<false>(csc_row, values_of(wave), nullptr, beg, end);
 
-    // ---- S_l = A^T V_l
-    floatx16 acc[T2][T2];
-    float zacc[T2];
-    with_feature_map(fmap, [&](auto fm) {
-        bucket_first_contraction<D, T, T, true, true, kExtraSumA, decltype(fm)::value>(Kb, Vb, csc_row, vals, nullptr, beg, end, acc, zacc);
-    });
+    for (; wave < n_waves; wave += stride) {
+        const long long slice = wave / n;
+        const long long bh = bh_first + slice;
+        const T* Qb = Q + bh * n * D;
+        const T* Kb = K + bh * n * D;
+        const T* Vb = V + bh * n * D;
+        const float* vals = values_of(wave);
 
-    float zfull[T2];
-#pragma unroll
-    for (int t = 0; t < T2; ++t) zfull[t] = zacc[t] + __shfl_xor(zacc[t], 32, kWave);
+        // bounds of this wavefront's next bucket: asked for now, used after the first contraction
+        const long long wave_next = wave + stride;
+        int32_t beg_next = 0, end_next = 0;
+        if (wave_next < n_waves) bounds_of(wave_next, beg_next, end_next);
 
-    // ---- P_l = Qw S_l, 32 consumers at a time.  Accumulator register r of tile (t, c) holds
-    // S[T2*(8*(r/4) + 4*half + r%4) + t][T2*li + c]: fed back unchanged as the B operand, it pairs the
-    // feature held by the lower half-wave (k = 0) with the one held by the upper (k = 1); the A operand
-    // takes the same two features of consumer li's weighted phi(q).
-    const long long pbase = slice * static_cast<long long>(nnz);
-    for (int32_t tile = beg; tile < end; tile += 32) {
-        float qv[4][QN];
-        with_feature_map(fmap, [&](auto fm) {
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-#pragma unroll
-                for (int e2 = 0; e2 < QN; ++e2) qv[b][e2] = gq_cur * feature_ct<decltype(fm)::value>(qn[b][e2]);
-        });
-        // next tile's rows of Q, and the indices of the tile after it
-        fetch_q(qrow_next, qn);
-        gq_cur = gq_next;
-        fetch_index(tile + 64, qrow_next, gq_next);
-
-        __builtin_amdgcn_sched_barrier(0);
-
-        // 4*T2 MFMAs per accumulator register r of S; in their shadow, the two terms of the partial
-        // denominator that use the same features: weighted phi(q) against z_l, which sits in the lanes in
-        // the order of the first contraction's rows.
-        floatx16 pc[T2];
-#pragma unroll
-        for (int c = 0; c < T2; ++c)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) pc[c][r] = 0.0f;
-        float dl = 0.0f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-#pragma unroll
-            for (int t = 0; t < T2; ++t) {
-#pragma unroll
-                for (int c = 0; c < T2; ++c)
-                    pc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(qv[r / 4][T2 * (r % 4) + t], acc[t][c][r], pc[c], 0, 0, 0);
-                dl = fmaf(qv[r / 4][T2 * (r % 4) + t], __shfl(zfull[t], 8 * (r / 4) + 4 * half + (r % 4), kWave), dl);
-            }
-            __builtin_amdgcn_sched_barrier(0);
+        if (beg >= end) {      // nobody visits this node: no partial rows belong to it
+            beg = beg_next; end = end_next;
+            first = load_list_block<false>(csc_row, wave_next < n_waves ? values_of(wave_next) : vals, nullptr, beg, end);
+            continue;
         }
-        dl += __shfl_xor(dl, 32, kWave);
-        if (half == 0 && tile + li < end) pden[pbase + tile + li] = dl;
+
+        // consumers of tile `tile`: row index and weight of entry tile + li (clamped, weight 0 past the end)
+        auto fetch_index = [&](int32_t tile, int32_t& row, float& g) {
+            const int32_t pos = min(tile + li, end - 1);
+            row = csc_row[pos];
+            g = tile + li < end ? vals[pos] : 0.0f;
+        };
+        auto fetch_q = [&](long long row, float (&qq)[4][QN]) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) load_run<T, QN>(Qb + row * D + T2 * (8 * b + 4 * half), qq[b]);
+        };
+
+        // the first two consumer tiles are entries beg .. beg + 63 of the list, which the first block holds (one
+        // per lane); the first tile's rows of Q go out before the first contraction starts
+        int32_t qrow_cur = __shfl(first.j_a, li, kWave), qrow_next = __shfl(first.j_a, 32 + li, kWave);
+        float gq_cur = __shfl(first.g_a, li, kWave), gq_next = __shfl(first.g_a, 32 + li, kWave);
+        float qn[4][QN];
+        fetch_q(qrow_cur, qn);
+
+        // ---- S_l = A^T V_l
+        floatx16 acc[T2][T2];
+        float zacc[T2];
+        with_feature_map(fmap, [&](auto fm) {
+            bucket_first_contraction<D, T, T, true, true, kExtraSumA, decltype(fm)::value>(Kb, Vb, csc_row, vals, nullptr, beg, end, first, acc, zacc);
+        });
+
+        // the next bucket's first list block: in flight during the second contraction
+        const ListBlock first_next = load_list_block<false>(csc_row, wave_next < n_waves ? values_of(wave_next) : vals, nullptr, beg_next, end_next);
+
+        float zfull[T2];
+#pragma unroll
+        for (int t = 0; t < T2; ++t) zfull[t] = zacc[t] + __shfl_xor(zacc[t], 32, kWave);
+
+        // ---- P_l = Qw S_l, 32 consumers at a time.  Accumulator register r of tile (t, c) holds
+        // S[T2*(8*(r/4) + 4*half + r%4) + t][T2*li + c]: fed back unchanged as the B operand, it pairs the
+        // feature held by the lower half-wave (k = 0) with the one held by the upper (k = 1); the A operand
+        // takes the same two features of consumer li's weighted phi(q).
+        const long long pbase = slice * static_cast<long long>(nnz);
+        for (int32_t tile = beg; tile < end; tile += 32) {
+            float qv[4][QN];
+            with_feature_map(fmap, [&](auto fm) {
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+#pragma unroll
+                    for (int e2 = 0; e2 < QN; ++e2) qv[b][e2] = gq_cur * feature_ct<decltype(fm)::value>(qn[b][e2]);
+            });
+            // next tile's rows of Q, and the indices of the tile after it
+            fetch_q(qrow_next, qn);
+            gq_cur = gq_next;
+            fetch_index(tile + 64, qrow_next, gq_next);
+
+            __builtin_amdgcn_sched_barrier(0);
+
+            // 4*T2 MFMAs per accumulator register r of S; in their shadow, the two terms of the partial
+            // denominator that use the same features: weighted phi(q) against z_l, which sits in the lanes in
+            // the order of the first contraction's rows.
+            floatx16 pc[T2];
+#pragma unroll
+            for (int c = 0; c < T2; ++c)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) pc[c][r] = 0.0f;
+            float dl = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+#pragma unroll
+                for (int t = 0; t < T2; ++t) {
+#pragma unroll
+                    for (int c = 0; c < T2; ++c)
+                        pc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(qv[r / 4][T2 * (r % 4) + t], acc[t][c][r], pc[c], 0, 0, 0);
+                    dl = fmaf(qv[r / 4][T2 * (r % 4) + t], __shfl(zfull[t], 8 * (r / 4) + 4 * half + (r % 4), kWave), dl);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            dl += __shfl_xor(dl, 32, kWave);
+            if (half == 0 && tile + li < end) pden[pbase + tile + li] = dl;
 
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int32_t ppos = tile + 8 * (r / 4) + 4 * half + (r % 4);
-            if (ppos < end) {
-                float* dst = partial + (pbase + ppos) * D + T2 * li;
-                if constexpr (T2 == 2) {
-                    *reinterpret_cast<float2*>(dst) = make_float2(pc[0][r], pc[1][r]);
-                } else {
-                    dst[0] = pc[0][r];
+            for (int r = 0; r < 16; ++r) {
+                const int32_t ppos = tile + 8 * (r / 4) + 4 * half + (r % 4);
+                if (ppos < end) {
+                    float* dst = partial + (pbase + ppos) * D + T2 * li;
+                    if constexpr (T2 == 2) {
+                        *reinterpret_cast<float2*>(dst) = make_float2(pc[0][r], pc[1][r]);
+                    } else {
+                        dst[0] = pc[0][r];
+                    }
                 }
             }
         }
+        beg = beg_next; end = end_next; first = first_next;
     }
 }
 
@@ -247,7 +274,7 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
 {
     const long long waves = static_cast<long long>(n_slices) * n;
     if (waves == 0) return GRF_OK;
-    hipLaunchKernelGGL((fused_bucket_kernel<D, T>), dim3(blocks_for(waves, 1)), dim3(kWave), 0, stream,
+    hipLaunchKernelGGL((fused_bucket_kernel<D, T>), dim3(resident_wave_grid(reinterpret_cast<const void*>(&fused_bucket_kernel<D, T>), waves)), dim3(kWave), 0, stream,
                        static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                        static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
                        static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
