@@ -112,10 +112,24 @@ def main() -> int:
     # record and its (col, val) pair; Q is read and out written once
     gather_bytes = B * H * (nnz * (rec * 4 + 8) + 2 * N * d * 4)
     achieved = gather_bytes / (gather_ms * 1e-3) / 1e9
+    # what a plain device-to-device copy of 1 GiB sustains on this machine (read + write bytes), for scale
+    cp_src = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+    cp_dst = torch.empty_like(cp_src)
+    cp_dst.copy_(cp_src)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record(stream)
+    for _ in range(5):
+        cp_dst.copy_(cp_src)
+    c1.record(stream)
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * cp_src.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del cp_src, cp_dst
     roofline = {"kernel": "gather_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
-                "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": round(gather_ms, 4)}
+                "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": round(gather_ms, 4),
+                "copy_1GiB_GBs": round(copy_gbs, 1), "frac_of_copy": round(achieved / copy_gbs, 4)}
 
     # the bucket-fused variant of the attention call on the same inputs: its own numbers, never `value`
     fws = torch.empty(grf.grf_fused_attention_workspace_bytes(B, H, N, d, nnz, phi.n_f), dtype=torch.uint8, device=dev)
