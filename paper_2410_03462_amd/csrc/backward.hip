@@ -29,46 +29,6 @@ namespace grf {
 
 enum : int { kQuerySide = 0, kKeySide = 1, kValueSide = 2 };
 
-// N consecutive elements starting at p (p aligned to N elements), widened to fp32.
-template <typename T, int N>
-__device__ __forceinline__ void load_elems(const T* __restrict__ p, float (&out)[N])
-{
-    if constexpr (sizeof(T) == 4) {
-        if constexpr (N == 1) {
-            out[0] = *reinterpret_cast<const float*>(p);
-        } else if constexpr (N == 2) {
-            const float2 v = *reinterpret_cast<const float2*>(p);
-            out[0] = v.x; out[1] = v.y;
-        } else {
-#pragma unroll
-            for (int k = 0; k < N / 4; ++k) {
-                const float4 v = reinterpret_cast<const float4*>(p)[k];
-                out[4 * k] = v.x; out[4 * k + 1] = v.y; out[4 * k + 2] = v.z; out[4 * k + 3] = v.w;
-            }
-        }
-    } else {
-        if constexpr (N == 1) {
-            out[0] = __uint_as_float(static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(p)) << 16);
-        } else {
-            uint32_t w[N / 2];
-            if constexpr (N == 2) {
-                w[0] = *reinterpret_cast<const uint32_t*>(p);
-            } else if constexpr (N == 4) {
-                const uint2 v = *reinterpret_cast<const uint2*>(p);
-                w[0] = v.x; w[1] = v.y;
-            } else {
-                const uint4 v = *reinterpret_cast<const uint4*>(p);
-                w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
-            }
-#pragma unroll
-            for (int k = 0; k < N / 2; ++k) {
-                out[2 * k] = __uint_as_float(w[k] << 16);
-                out[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u);
-            }
-        }
-    }
-}
-
 // g' per row of a chunk of slices: G[s][i][:] = d_out / den, gd[s][i] = -(d_out . out) / den.
 template <int D>
 __global__ __launch_bounds__(256) void backward_seed_kernel(const float* __restrict__ out, const float* __restrict__ den,
@@ -138,9 +98,9 @@ __global__ __launch_bounds__(64) void backward_bucket_kernel(const T* __restrict
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             const long long off = row * D + T2 * (8 * b + 4 * half);
-            if constexpr (MODE == kQuerySide) load_elems<float, QN>(Gb + off, cc[b]);
-            if constexpr (MODE == kKeySide) load_elems<T, QN>(Vb + off, cc[b]);
-            if constexpr (MODE == kValueSide) load_elems<T, QN>(Kb + off, cc[b]);
+            if constexpr (MODE == kQuerySide) load_run<float, QN>(Gb + off, cc[b]);
+            if constexpr (MODE == kKeySide) load_run<T, QN>(Vb + off, cc[b]);
+            if constexpr (MODE == kValueSide) load_run<T, QN>(Kb + off, cc[b]);
         }
         if constexpr (MODE == kQuerySide) cf = gdb[row];
     };
