@@ -159,6 +159,10 @@ grf_status grf_sample_walks(const grf_graph* g, double p_halt, int32_t n_walks, 
  *   gather    num_i = sum_l Phi_hat[i,l] phi(q_i)^T S_l,   den_i = sum_l Phi_hat[i,l] phi(q_i)^T z_l
  *             out_i = num_i / den_i      (no epsilon: den_i = 0 gives IEEE inf/NaN, not an error)
  *
+ * Cost is linear in nnz(Phi_hat) except for the ordering of the column lists, which is quadratic in the length of a
+ * column (spread over the whole device); a bucket is summed by one wavefront, so a single column with very many
+ * entries (a hub node) is correct but serial in that part.
+ *
  * Q, K, V    contiguous [B][H][n][d], dtype GRF_DTYPE_F32 or GRF_DTYPE_BF16.  d in {32, 64}.
  * phi        Phi_hat with nnz entries (phi->row_ptr[n] == nnz) and n_f value planes: n_f == 1 is shared
  *            by all heads, n_f == H gives head h plane h.  One graph per call, shared over the batch.

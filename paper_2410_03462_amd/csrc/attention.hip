@@ -45,28 +45,36 @@ __global__ __launch_bounds__(256) void column_scatter_kernel(const int32_t* __re
     }
 }
 
-// One wavefront per column: order the segment by row index (rows are distinct within a column)
-// by counting, so that the buckets are summed in a fixed order.  Quadratic in the segment length.
+// One thread per position of the column lists: order each segment by row index (rows are distinct within a
+// column) by counting, so that the buckets are summed in a fixed order.  A position finds its column by
+// bisection of col_ptr and scans that column's segment; lanes of a wavefront mostly share the column, so the
+// scan reads are broadcasts.  The work is quadratic in a column's length but spread over as many wavefronts as
+// the column has blocks of 64 entries, so one very long column (a hub node) does not serialise the launch.
 __global__ __launch_bounds__(256) void column_sort_kernel(const int32_t* __restrict__ col_ptr, int32_t n, int32_t nnz,
                                                           const int32_t* __restrict__ u_row, const int32_t* __restrict__ u_src,
                                                           int32_t* __restrict__ s_row, int32_t* __restrict__ s_src,
                                                           int32_t* __restrict__ csr_to_csc)
 {
-    const long long c = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    if (c >= n) return;
-    const int32_t beg = col_ptr[c];
-    const int32_t len = col_ptr[c + 1] - beg;
-    for (int s = lane_id(); s < len; s += kWave) {
-        const int32_t key = u_row[beg + s];
-        int rank = 0;
-        for (int s2 = 0; s2 < len; ++s2) rank += static_cast<int>(u_row[beg + s2] < key);
-        const int32_t src = u_src[beg + s];
-        // Slots that a malformed Phi_hat (overlapping rows) left unset hold arbitrary bits: whatever is
-        // written downstream is a valid index, so the kernels that follow need no guards.
-        const bool ok = static_cast<uint32_t>(key) < static_cast<uint32_t>(n) && static_cast<uint32_t>(src) < static_cast<uint32_t>(nnz);
-        s_row[beg + rank] = ok ? key : 0;
-        s_src[beg + rank] = ok ? src : 0;
-        if (ok) csr_to_csc[src] = beg + rank;
+    const long long p = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (p >= nnz) return;
+    int32_t lo = 0, hi = n;                 // col_ptr[lo] <= p < col_ptr[hi]
+    while (hi - lo > 1) {
+        const int32_t mid = lo + (hi - lo) / 2;
+        if (col_ptr[mid] <= p) lo = mid; else hi = mid;
+    }
+    const int32_t beg = col_ptr[lo];
+    const int32_t len = col_ptr[lo + 1] - beg;
+    const int32_t key = u_row[p];
+    int rank = 0;
+    for (int s2 = 0; s2 < len; ++s2) rank += static_cast<int>(u_row[beg + s2] < key);
+    const int32_t src = u_src[p];
+    // Slots that a malformed Phi_hat (overlapping rows) left unset hold arbitrary bits: whatever is
+    // written downstream is a valid index, so the kernels that follow need no guards.
+    const bool ok = static_cast<uint32_t>(key) < static_cast<uint32_t>(n) && static_cast<uint32_t>(src) < static_cast<uint32_t>(nnz) && rank < len;
+    if (ok) {
+        s_row[beg + rank] = key;
+        s_src[beg + rank] = src;
+        csr_to_csc[src] = beg + rank;
     }
 }
 
@@ -260,7 +268,7 @@ grf_status transpose(const grf_phi* phi, int64_t nnz, int32_t n_f, const Transpo
                            static_cast<long long>(nnz), static_cast<int32_t>(n), static_cast<const int32_t*>(t.col_ptr),
                            t.cursor, t.u_row, t.u_src);
         GRF_LAUNCH_CHECK("column_scatter_kernel");
-        hipLaunchKernelGGL(column_sort_kernel, dim3(blocks_for(n, 4)), dim3(256), 0, stream,
+        hipLaunchKernelGGL(column_sort_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, stream,
                            static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n), static_cast<int32_t>(nnz),
                            static_cast<const int32_t*>(t.u_row), static_cast<const int32_t*>(t.u_src), t.s_row, t.s_src,
                            t.csr_to_csc);

@@ -287,6 +287,18 @@ def test_attention_special_feature_matrices(grf, oracle):
     assert torch.isnan(out[:, :, mask]).all()
 
 
+def test_hub_node_with_a_very_long_column(grf, oracle):
+    """A star with 20000 leaves: the hub's column of Phi_hat has an entry from almost every row (one bucket with ~20000
+    contributors and consumers, ~600 consumer tiles), all other columns are short."""
+    rng = np.random.default_rng(21)
+    g = synth.star_graph(20001)
+    wl = synth.Workload("star_20k", g, synth.modulation(4, rng), 0.3, 3, 1, 1, 32, "f32")
+    rp, col, val = _oracle_phi(oracle, wl)
+    assert np.bincount(col, minlength=g.n).max() > 15000
+    _compare_attention(grf, oracle, wl, rp, col, val)
+    _compare_fused(grf, oracle, wl, rp, col, val)
+
+
 def test_attention_argument_errors(grf):
     import torch
     n = 64
