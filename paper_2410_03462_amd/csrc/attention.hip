@@ -13,20 +13,22 @@
 namespace grf {
 
 // ------------------------------------------------------------------------------------ transpose
+// Entries per column; the arrival index of every entry within its column (what the atomic returns) is kept,
+// so that the scatter below needs no second round of atomics.
 __global__ __launch_bounds__(256) void column_histogram_kernel(const int32_t* __restrict__ col, long long nnz, int32_t n,
-                                                               int32_t* __restrict__ count)
+                                                               int32_t* __restrict__ count, int32_t* __restrict__ arrival)
 {
     const long long e = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (e >= nnz) return;
     const int32_t c = col[e];
-    if (static_cast<uint32_t>(c) < static_cast<uint32_t>(n)) atomicAdd(&count[c], 1);
+    arrival[e] = static_cast<uint32_t>(c) < static_cast<uint32_t>(n) ? atomicAdd(&count[c], 1) : -1;
 }
 
-// One wavefront per row: scatter (row, entry index) into the column segments.  The order inside
+// One wavefront per row: (row, entry index) of every entry goes to slot col_ptr[c] + arrival.  The order inside
 // a segment depends on atomic arrival and is fixed afterwards by column_sort_kernel.
 __global__ __launch_bounds__(256) void column_scatter_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
                                                              long long nnz, int32_t n, const int32_t* __restrict__ col_ptr,
-                                                             int32_t* __restrict__ cursor, int32_t* __restrict__ u_row,
+                                                             const int32_t* __restrict__ arrival, int32_t* __restrict__ u_row,
                                                              int32_t* __restrict__ u_src)
 {
     const long long row = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
@@ -37,8 +39,9 @@ __global__ __launch_bounds__(256) void column_scatter_kernel(const int32_t* __re
     for (long long e = beg + lane_id(); e < end; e += kWave) {
         if (e < 0) continue;
         const int32_t c = col[e];
-        if (static_cast<uint32_t>(c) >= static_cast<uint32_t>(n)) continue;
-        const int32_t slot = col_ptr[c] + atomicAdd(&cursor[c], 1);
+        const int32_t k = arrival[e];
+        if (static_cast<uint32_t>(c) >= static_cast<uint32_t>(n) || k < 0) continue;
+        const int32_t slot = col_ptr[c] + k;
         if (slot >= col_ptr[c + 1]) continue;   // only with overlapping rows in a malformed row_ptr
         u_row[slot] = static_cast<int32_t>(row);
         u_src[slot] = static_cast<int32_t>(e);
@@ -235,12 +238,12 @@ Transposed carve_transposed(unsigned char* ws, int64_t n, int64_t nnz, int32_t n
     auto take = [&](size_t bytes) { unsigned char* p = ws ? ws + off : nullptr; off += align_up(bytes); return p; };
     const size_t entries = static_cast<size_t>(nnz > 0 ? nnz : 1);
     t.col_ptr = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n + 1)));
-    t.cursor = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n > 0 ? n : 1)));
     t.u_row = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
     t.u_src = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
     t.s_row = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
     t.s_src = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
     t.csr_to_csc = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
+    t.arrival = t.csr_to_csc;      // the arrival indices are dead before the positions are written
     t.s_val = reinterpret_cast<float*>(take(sizeof(float) * entries * static_cast<size_t>(n_f > 0 ? n_f : 1)));
     t.total = reinterpret_cast<long long*>(take(sizeof(long long)));
     t.bytes = off;
@@ -251,14 +254,12 @@ grf_status transpose(const grf_phi* phi, int64_t nnz, int32_t n_f, const Transpo
 {
     const int64_t n = phi->n;
     if (grf_status st = fill_i32(t.col_ptr, n + 1, 0, stream)) return st;
-    if (grf_status st = fill_i32(t.cursor, n, 0, stream)) return st;
     if (nnz > 0) {
-        // entries that a malformed Phi_hat never reaches must not point anywhere
-        if (grf_status st = fill_i32(t.csr_to_csc, nnz, -1, stream)) return st;
         if (grf_status st = fill_i32(t.s_row, nnz, 0, stream)) return st;
         if (grf_status st = fill_i32(t.s_src, nnz, 0, stream)) return st;
         hipLaunchKernelGGL(column_histogram_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, stream,
-                           static_cast<const int32_t*>(phi->col), static_cast<long long>(nnz), static_cast<int32_t>(n), t.col_ptr);
+                           static_cast<const int32_t*>(phi->col), static_cast<long long>(nnz), static_cast<int32_t>(n), t.col_ptr,
+                           t.arrival);
         GRF_LAUNCH_CHECK("column_histogram_kernel");
     }
     if (grf_status st = exclusive_scan_inplace(t.col_ptr, n, t.total, stream)) return st;
@@ -266,8 +267,10 @@ grf_status transpose(const grf_phi* phi, int64_t nnz, int32_t n_f, const Transpo
         hipLaunchKernelGGL(column_scatter_kernel, dim3(blocks_for(n, 4)), dim3(256), 0, stream,
                            static_cast<const int32_t*>(phi->row_ptr), static_cast<const int32_t*>(phi->col),
                            static_cast<long long>(nnz), static_cast<int32_t>(n), static_cast<const int32_t*>(t.col_ptr),
-                           t.cursor, t.u_row, t.u_src);
+                           static_cast<const int32_t*>(t.arrival), t.u_row, t.u_src);
         GRF_LAUNCH_CHECK("column_scatter_kernel");
+        // entries that a malformed Phi_hat never reaches must not point anywhere
+        if (grf_status st = fill_i32(t.csr_to_csc, nnz, -1, stream)) return st;
         hipLaunchKernelGGL(column_sort_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, stream,
                            static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n), static_cast<int32_t>(nnz),
                            static_cast<const int32_t*>(t.u_row), static_cast<const int32_t*>(t.u_src), t.s_row, t.s_src,

@@ -94,12 +94,12 @@ __device__ __forceinline__ void load_run(const T* __restrict__ p, float (&out)[N
 // Column lists of Phi_hat, carved out of the caller's workspace.
 struct Transposed {
     int32_t* col_ptr;   // [n+1]
-    int32_t* cursor;    // [n]
     int32_t* u_row;     // [nnz] unsorted
     int32_t* u_src;
     int32_t* s_row;     // [nnz] rows ascending inside each column
     int32_t* s_src;     // index of the entry in CSR order (addresses every value plane)
     int32_t* csr_to_csc;  // [nnz] position in the column lists of CSR entry e
+    int32_t* arrival;     // [nnz] arrival index of entry e within its column while the lists are built (same memory)
     float* s_val;       // [n_f][nnz] value planes permuted into column-list order
     long long* total;
     size_t bytes;
