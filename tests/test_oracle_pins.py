@@ -485,3 +485,25 @@ def test_asymmetric_special_cases(oracle):
     num, den, _ = oracle.attention_bruteforce(Q[0, 0], K[0, 0], V[0, 0], M)
     assert np.allclose(res["num"][0, 0], num, rtol=1e-6, atol=1e-8)
     assert np.allclose(res["den"][0, 0], den, rtol=1e-6, atol=1e-8)
+
+
+def test_checker_results_are_frozen_for_the_tiny_workload():
+    """The checker still returns what tests/golden/oracle_tiny_grid.txt recorded (written by the script beside it,
+    which calls the checker only): integers bit for bit, reals to 1e-12 relative (libm may differ in the last bit)."""
+    import importlib.util
+    path = os.path.join(GOLDEN, "make_oracle_fixtures.py")
+    spec = importlib.util.spec_from_file_location("make_oracle_fixtures", path)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    want = [l.strip() for l in open(os.path.join(GOLDEN, "oracle_tiny_grid.txt")) if l.strip() and l[0] != "#"]
+    got = [l for l in mod.fixture_lines() if l[0] != "#"]
+    assert len(want) == len(got)
+    for w, g in zip(want, got):
+        kw, kg = w.split()[0], g.split()[0]
+        assert kw == kg
+        if kw.endswith("sha256") or kw == "nnz":
+            assert w == g, kw
+        else:
+            a = np.array([float.fromhex(x) for x in w.split()[1:]])
+            b = np.array([float.fromhex(x) for x in g.split()[1:]])
+            assert np.allclose(a, b, rtol=1e-12, atol=0), kw
