@@ -89,7 +89,9 @@ typedef struct grf_phi {
  *            relative to the row's nearest neighbour, so a row far from everything is still finite).
  * Output     CSR as grf_graph expects it (columns ascending): row_ptr [n+1] always written; col, w [capacity]
  *            written when capacity >= nnz, else GRF_ECAPACITY with *nnz_out set.  grf_knn_graph_nnz_bound is
- *            always enough.  nnz_out is a HOST pointer; the call blocks on the stream once to fill it.
+ *            always enough.  nnz_out is a HOST pointer; the call blocks on the stream once to fill it.  With
+ *            nnz_out == NULL the call does not synchronise; capacity must then be at least the bound, the count
+ *            stays on the device in row_ptr[n], and a grf_graph made from the result may carry nnz = capacity.
  * --------------------------------------------------------------------------------------------- */
 #define GRF_WEIGHT_INV_DEGREE 0
 #define GRF_WEIGHT_EXP        1
@@ -145,6 +147,17 @@ grf_status grf_sample(const grf_graph* g,
                       void* workspace, size_t workspace_bytes, void* hip_stream,
                       grf_phi* phi_out, int64_t* nnz_out);
 
+/* The same sampling as stream-ordered work only, for callers that must not touch the host (HIP graph capture,
+ * tight loops): f_device is a DEVICE pointer [n_f][f_len] read when the kernels run (so a training loop can update
+ * it in place), nothing is synchronised and no count comes back: phi_out->capacity must be at least
+ * grf_sample_nnz_bound() and the number of entries stays on the device in phi_out->row_ptr[n].  The attention
+ * calls accept phi_out with nnz = capacity (see there).  Workspace as for grf_sample. */
+grf_status grf_sample_async(const grf_graph* g,
+                            const float* f_device, int32_t f_len, int32_t n_f,
+                            double p_halt, int32_t n_walks, uint64_t seed,
+                            void* workspace, size_t workspace_bytes, void* hip_stream,
+                            grf_phi* phi_out);
+
 /* The walks alone, for inspection: traj is device [n][n_walks][max_nodes] int32; entry t of a walk is
  * the node visited after t hops, or -1 past its end.  Same stream as grf_sample with f_len = max_nodes. */
 grf_status grf_sample_walks(const grf_graph* g, double p_halt, int32_t n_walks, int32_t max_nodes,
@@ -164,7 +177,10 @@ grf_status grf_sample_walks(const grf_graph* g, double p_halt, int32_t n_walks, 
  * entries (a hub node) is correct but serial in that part.
  *
  * Q, K, V    contiguous [B][H][n][d], dtype GRF_DTYPE_F32 or GRF_DTYPE_BF16.  d in {32, 64}.
- * phi        Phi_hat with nnz entries (phi->row_ptr[n] == nnz) and n_f value planes: n_f == 1 is shared
+ * phi, nnz   Phi_hat and its number of entries.  nnz may also be any upper bound on phi->row_ptr[n] up to
+ *            phi->capacity (the kernels take the end of the rows from row_ptr[n]; nnz sizes the workspace and the
+ *            strides in it), which is what a caller has who sampled without waiting for the count (see grf_sample).
+ *            n_f value planes: n_f == 1 is shared
  *            by all heads, n_f == H gives head h plane h.  One graph per call, shared over the batch.
  * --------------------------------------------------------------------------------------------- */
 

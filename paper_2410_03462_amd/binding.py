@@ -62,6 +62,10 @@ def lib() -> ctypes.CDLL:
                                  ctypes.c_double, ctypes.c_int32, ctypes.c_uint64,
                                  ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                  ctypes.POINTER(_Phi), ctypes.POINTER(ctypes.c_int64)]
+        L.grf_sample_async.restype = ctypes.c_int32
+        L.grf_sample_async.argtypes = [ctypes.POINTER(_Graph), ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                       ctypes.c_double, ctypes.c_int32, ctypes.c_uint64,
+                                       ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(_Phi)]
         L.grf_sample_walks.restype = ctypes.c_int32
         L.grf_sample_walks.argtypes = [ctypes.POINTER(_Graph), ctypes.c_double, ctypes.c_int32, ctypes.c_int32,
                                        ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]
@@ -222,8 +226,13 @@ def grf_knn_graph_workspace_bytes(n: int, k: int) -> int:
 
 
 def grf_knn_graph(points: torch.Tensor, k: int, symmetrise: bool = True, weights: str = "gauss", sigma: float = 1.0,
-                  workspace: Optional[torch.Tensor] = None, stream=None) -> DeviceGraph:
-    """Exact k-nearest-neighbour graph of ``points`` (CUDA fp32 [n, 3]) as a DeviceGraph."""
+                  workspace: Optional[torch.Tensor] = None, stream=None, out: Optional[DeviceGraph] = None,
+                  sync: bool = True) -> DeviceGraph:
+    """Exact k-nearest-neighbour graph of ``points`` (CUDA fp32 [n, 3]) as a DeviceGraph.
+
+    ``sync=False``: no host synchronisation (capturable into a HIP graph); the result's ``col`` / ``w`` keep their full
+    bound-sized length and the entry count stays on the device in ``row_ptr[n]``.  ``out`` reuses a previous result's
+    buffers (they must have the bound's size)."""
     _require_gpu()
     L = lib()
     if points.dim() != 2 or points.shape[1] != 3 or points.dtype != torch.float32 or not points.is_cuda or not points.is_contiguous():
@@ -235,13 +244,20 @@ def grf_knn_graph(points: torch.Tensor, k: int, symmetrise: bool = True, weights
     dev = points.device
     if workspace is None:
         workspace = _workspace(L.grf_knn_graph_workspace_bytes(n, k), dev)
-    row_ptr = torch.empty(n + 1, dtype=torch.int32, device=dev)
-    col = torch.empty(max(bound, 1), dtype=torch.int32, device=dev)
-    w = torch.empty(max(bound, 1), dtype=torch.float32, device=dev)
+    if out is not None:
+        if out.n != n or out.col.numel() < bound:
+            raise ValueError("out does not match the point count or is smaller than the bound")
+        row_ptr, col, w = out.row_ptr, out.col, out.w
+    else:
+        row_ptr = torch.empty(n + 1, dtype=torch.int32, device=dev)
+        col = torch.empty(max(bound, 1), dtype=torch.int32, device=dev)
+        w = torch.empty(max(bound, 1), dtype=torch.float32, device=dev)
     nnz = ctypes.c_int64(0)
     _check(L.grf_knn_graph(_ptr(points), n, int(k), 1 if symmetrise else 0, _WEIGHT_KINDS[weights], float(sigma),
                            _ptr(workspace), workspace.numel(), _stream_ptr(stream),
-                           _ptr(row_ptr), _ptr(col), _ptr(w), int(col.numel()), ctypes.byref(nnz)))
+                           _ptr(row_ptr), _ptr(col), _ptr(w), int(col.numel()), ctypes.byref(nnz) if sync else None))
+    if not sync:
+        return DeviceGraph(n, row_ptr, col, w)
     return DeviceGraph(n, row_ptr, col[: nnz.value], w[: nnz.value])
 
 
@@ -250,7 +266,8 @@ def grf_sample_nnz_bound(n: int, n_walks: int, f_len: int) -> int:
 
 
 def grf_sample(graph: DeviceGraph, f, p_halt: float, n_walks: int, seed: int,
-               out: Optional[Phi] = None, capacity: Optional[int] = None, stream=None) -> Phi:
+               out: Optional[Phi] = None, capacity: Optional[int] = None, stream=None,
+               workspace: Optional[torch.Tensor] = None) -> Phi:
     """Sample Phi_hat.  ``f`` is a host array [n_f, f_len] (or [f_len]).
 
     With ``out`` the caller's buffers are reused (GrfError(GRF_ECAPACITY) if too small).  Otherwise the
@@ -261,7 +278,7 @@ def grf_sample(graph: DeviceGraph, f, p_halt: float, n_walks: int, seed: int,
     f = np.ascontiguousarray(np.atleast_2d(np.asarray(f, dtype=np.float32)))
     n_f, f_len = f.shape
     dev = graph.row_ptr.device
-    ws = _workspace(L.grf_sample_workspace_bytes(graph.n, n_walks, f_len, n_f), dev)
+    ws = workspace if workspace is not None else _workspace(L.grf_sample_workspace_bytes(graph.n, n_walks, f_len, n_f), dev)
     gs = graph._struct()
     nnz = ctypes.c_int64(0)
 
@@ -283,6 +300,31 @@ def grf_sample(graph: DeviceGraph, f, p_halt: float, n_walks: int, seed: int,
         raise ValueError("out does not match the graph / number of f sets")
     _check(call(out))
     out.nnz = int(nnz.value)
+    return out
+
+
+def grf_sample_async(graph: DeviceGraph, f: torch.Tensor, p_halt: float, n_walks: int, seed: int,
+                     out: Optional[Phi] = None, workspace: Optional[torch.Tensor] = None, stream=None) -> Phi:
+    """grf_sample without touching the host: ``f`` is a CUDA fp32 tensor [n_f, f_len] (or [f_len]) read on the stream,
+    nothing is synchronised, and the result's ``nnz`` is its capacity (grf_sample_nnz_bound), an upper bound that the
+    attention calls accept; the count stays on the device in ``row_ptr[n]``.  Capturable into a HIP graph when ``out``
+    and ``workspace`` are passed (no allocation inside the capture)."""
+    _require_gpu()
+    L = lib()
+    f2 = f.reshape(-1, f.shape[-1])
+    if not f2.is_cuda or f2.dtype != torch.float32 or not f2.is_contiguous():
+        raise ValueError("f must be a contiguous CUDA fp32 tensor")
+    n_f, f_len = int(f2.shape[0]), int(f2.shape[1])
+    dev = graph.row_ptr.device
+    if out is None:
+        out = Phi.empty(graph.n, int(L.grf_sample_nnz_bound(graph.n, n_walks, f_len)), n_f, dev)
+    elif out.n_f != n_f or out.n != graph.n:
+        raise ValueError("out does not match the graph / number of f sets")
+    ws = workspace if workspace is not None else _workspace(L.grf_sample_workspace_bytes(graph.n, n_walks, f_len, n_f), dev)
+    gs, ps = graph._struct(), out._struct()
+    _check(L.grf_sample_async(ctypes.byref(gs), _ptr(f2), f_len, n_f, float(p_halt), int(n_walks),
+                              int(seed) & 0xFFFFFFFFFFFFFFFF, _ptr(ws), ws.numel(), _stream_ptr(stream), ctypes.byref(ps)))
+    out.nnz = out.capacity
     return out
 
 

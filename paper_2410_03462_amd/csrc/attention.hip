@@ -15,11 +15,13 @@ namespace grf {
 // ------------------------------------------------------------------------------------ transpose
 // Entries per column; the arrival index of every entry within its column (what the atomic returns) is kept,
 // so that the scatter below needs no second round of atomics.
-__global__ __launch_bounds__(256) void column_histogram_kernel(const int32_t* __restrict__ col, long long nnz, int32_t n,
+__global__ __launch_bounds__(256) void column_histogram_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
+                                                               long long nnz, int32_t n,
                                                                int32_t* __restrict__ count, int32_t* __restrict__ arrival)
 {
     const long long e = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (e >= nnz) return;
+    if (e >= row_ptr[n]) { arrival[e] = -1; return; }      // nnz may be an upper bound: the rows end at row_ptr[n]
     const int32_t c = col[e];
     arrival[e] = static_cast<uint32_t>(c) < static_cast<uint32_t>(n) ? atomicAdd(&count[c], 1) : -1;
 }
@@ -59,7 +61,7 @@ __global__ __launch_bounds__(256) void column_sort_kernel(const int32_t* __restr
                                                           int32_t* __restrict__ csr_to_csc)
 {
     const long long p = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (p >= nnz) return;
+    if (p >= nnz || p >= col_ptr[n]) return;      // nnz may be an upper bound: the lists end at col_ptr[n]
     int32_t lo = 0, hi = n;                 // col_ptr[lo] <= p < col_ptr[hi]
     while (hi - lo > 1) {
         const int32_t mid = lo + (hi - lo) / 2;
@@ -82,12 +84,13 @@ __global__ __launch_bounds__(256) void column_sort_kernel(const int32_t* __restr
 }
 
 // Value planes in column-list order: s_val[h][pos] = val[h][s_src[pos]].
-__global__ __launch_bounds__(256) void column_values_kernel(const int32_t* __restrict__ s_src, long long nnz, int n_f,
+__global__ __launch_bounds__(256) void column_values_kernel(const int32_t* __restrict__ col_ptr, int32_t n,
+                                                            const int32_t* __restrict__ s_src, long long nnz, int n_f,
                                                             const float* __restrict__ val, long long val_stride,
                                                             float* __restrict__ s_val)
 {
     const long long pos = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (pos >= nnz) return;
+    if (pos >= nnz || pos >= col_ptr[n]) return;
     const int32_t src = s_src[pos];
     for (int h = 0; h < n_f; ++h) s_val[h * nnz + pos] = val[h * val_stride + src];
 }
@@ -258,8 +261,8 @@ grf_status transpose(const grf_phi* phi, int64_t nnz, int32_t n_f, const Transpo
         if (grf_status st = fill_i32(t.s_row, nnz, 0, stream)) return st;
         if (grf_status st = fill_i32(t.s_src, nnz, 0, stream)) return st;
         hipLaunchKernelGGL(column_histogram_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, stream,
-                           static_cast<const int32_t*>(phi->col), static_cast<long long>(nnz), static_cast<int32_t>(n), t.col_ptr,
-                           t.arrival);
+                           static_cast<const int32_t*>(phi->row_ptr), static_cast<const int32_t*>(phi->col),
+                           static_cast<long long>(nnz), static_cast<int32_t>(n), t.col_ptr, t.arrival);
         GRF_LAUNCH_CHECK("column_histogram_kernel");
     }
     if (grf_status st = exclusive_scan_inplace(t.col_ptr, n, t.total, stream)) return st;
@@ -277,6 +280,7 @@ grf_status transpose(const grf_phi* phi, int64_t nnz, int32_t n_f, const Transpo
                            t.csr_to_csc);
         GRF_LAUNCH_CHECK("column_sort_kernel");
         hipLaunchKernelGGL(column_values_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, stream,
+                           static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n),
                            static_cast<const int32_t*>(t.s_src), static_cast<long long>(nnz), static_cast<int>(n_f),
                            static_cast<const float*>(phi->val), static_cast<long long>(phi->capacity), t.s_val);
         GRF_LAUNCH_CHECK("column_values_kernel");

@@ -403,7 +403,10 @@ extern "C" grf_status grf_knn_graph(const float* points, int64_t n, int32_t k, i
     if (weight_kind != GRF_WEIGHT_INV_DEGREE && weight_kind != GRF_WEIGHT_EXP && weight_kind != GRF_WEIGHT_GAUSS)
         return fail(GRF_EINVAL, "weight_kind=%d is unknown", weight_kind);
     if (weight_kind != GRF_WEIGHT_INV_DEGREE && !(sigma > 0.0f)) return fail(GRF_EINVAL, "sigma=%g must be > 0", (double)sigma);
-    if (row_ptr == nullptr || nnz_out == nullptr) return fail(GRF_EINVAL, "row_ptr / nnz_out is NULL");
+    if (row_ptr == nullptr) return fail(GRF_EINVAL, "row_ptr is NULL");
+    if (nnz_out == nullptr && capacity < grf_knn_graph_nnz_bound(n, k, symmetrise))
+        return fail(GRF_ECAPACITY, "without nnz_out capacity must be at least grf_knn_graph_nnz_bound() = %lld (got %lld)",
+                    (long long)grf_knn_graph_nnz_bound(n, k, symmetrise), (long long)capacity);
     if (n > 0 && points == nullptr) return fail(GRF_EINVAL, "points is NULL");
     if (capacity < 0 || (capacity > 0 && (col == nullptr || w == nullptr))) return fail(GRF_EINVAL, "col / w is NULL or capacity < 0");
     const size_t need = grf_knn_graph_workspace_bytes(n, k);
@@ -412,7 +415,7 @@ extern "C" grf_status grf_knn_graph(const float* points, int64_t n, int32_t k, i
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (n == 0) {
         if (grf_status st = fill_i32(row_ptr, 1, 0, stream)) return st;
-        *nnz_out = 0;
+        if (nnz_out != nullptr) *nnz_out = 0;
         return GRF_OK;
     }
     const KnnScratch s = carve_knn(static_cast<unsigned char*>(workspace), n, k);
@@ -452,11 +455,13 @@ extern "C" grf_status grf_knn_graph(const float* points, int64_t n, int32_t k, i
                        static_cast<long long>(n), k, symmetrise ? 1 : 0, row_ptr);
     GRF_LAUNCH_CHECK("knn_degree_kernel");
     if (grf_status st = exclusive_scan_inplace(row_ptr, n, s.total, stream)) return st;
-    long long total = 0;
-    GRF_HIP_TRY(hipMemcpyAsync(&total, s.total, sizeof(long long), hipMemcpyDeviceToHost, stream));
-    GRF_HIP_TRY(hipStreamSynchronize(stream));
-    *nnz_out = total;
-    if (capacity < total) return fail(GRF_ECAPACITY, "the graph has %lld entries but capacity is %lld", total, (long long)capacity);
+    if (nnz_out != nullptr) {
+        long long total = 0;
+        GRF_HIP_TRY(hipMemcpyAsync(&total, s.total, sizeof(long long), hipMemcpyDeviceToHost, stream));
+        GRF_HIP_TRY(hipStreamSynchronize(stream));
+        *nnz_out = total;
+        if (capacity < total) return fail(GRF_ECAPACITY, "the graph has %lld entries but capacity is %lld", total, (long long)capacity);
+    }
     hipLaunchKernelGGL(knn_edges_kernel, dim3(eblocks), dim3(256), 0, stream, static_cast<const int32_t*>(s.knn_idx),
                        static_cast<const float*>(s.knn_d2), static_cast<long long>(n), k, symmetrise ? 1 : 0,
                        static_cast<const int32_t*>(row_ptr), s.cursor, s.u_col, s.u_d2);

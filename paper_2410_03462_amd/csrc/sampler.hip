@@ -357,19 +357,22 @@ extern "C" grf_status grf_sample_walks(const grf_graph* g, double p_halt, int32_
     return GRF_OK;
 }
 
-extern "C" grf_status grf_sample(const grf_graph* g, const float* f, int32_t f_len, int32_t n_f,
-                                 double p_halt, int32_t n_walks, uint64_t seed,
-                                 void* workspace, size_t workspace_bytes, void* hip_stream,
-                                 grf_phi* phi_out, int64_t* nnz_out)
+namespace {
+
+// Both sampling entry points.  f_host: copied to the workspace first (else f_device is used in place).
+// nnz_out: the stream is synchronised once to return the count (else capacity must cover the bound).
+grf_status sample_impl(const grf_graph* g, const float* f_host, const float* f_device, int32_t f_len, int32_t n_f,
+                       double p_halt, int32_t n_walks, uint64_t seed, void* workspace, size_t workspace_bytes,
+                       hipStream_t stream, grf_phi* phi_out, int64_t* nnz_out)
 {
     if (grf_status st = check_graph(g)) return st;
-    if (f == nullptr) return fail(GRF_EINVAL, "f is NULL");
+    if (f_host == nullptr && f_device == nullptr) return fail(GRF_EINVAL, "f is NULL");
     if (f_len < 1 || n_f < 1 || n_walks < 1)
         return fail(GRF_EINVAL, "f_len=%d, n_f=%d, n_walks=%d must all be >= 1", f_len, n_f, n_walks);
     if (f_len > 65535) return fail(GRF_EUNSUPPORTED, "f_len=%d exceeds 65535", f_len);
     WalkLaw law;
     if (grf_status st = make_law(p_halt, seed, &law)) return st;
-    if (phi_out == nullptr || nnz_out == nullptr) return fail(GRF_EINVAL, "phi_out / nnz_out is NULL");
+    if (phi_out == nullptr) return fail(GRF_EINVAL, "phi_out is NULL");
     if (phi_out->n != g->n) return fail(GRF_EINVAL, "phi_out->n=%lld differs from graph n=%lld", (long long)phi_out->n, (long long)g->n);
     if (phi_out->row_ptr == nullptr) return fail(GRF_EINVAL, "phi_out->row_ptr is NULL");
     if (phi_out->capacity < 0) return fail(GRF_EINVAL, "phi_out->capacity is negative");
@@ -381,19 +384,26 @@ extern "C" grf_status grf_sample(const grf_graph* g, const float* f, int32_t f_l
     const size_t need = grf_sample_workspace_bytes(g->n, n_walks, f_len, n_f);
     if (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
         return fail(GRF_EWORKSPACE, "workspace must be non-NULL, 256-byte aligned and >= %zu bytes (got %zu)", need, workspace_bytes);
-
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    unsigned char* ws = static_cast<unsigned char*>(workspace);
-    float* f_dev = reinterpret_cast<float*>(ws);
-    long long* total_dev = reinterpret_cast<long long*>(ws + align_up(sizeof(float) * static_cast<size_t>(n_f) * f_len));
-
-    if (g->n == 0) {
-        if (grf_status st = fill_i32(phi_out->row_ptr, 1, 0, stream)) return st;
-        *nnz_out = 0;
-        return GRF_OK;
+    if (nnz_out == nullptr) {
+        const int64_t bound = grf_sample_nnz_bound(g->n, n_walks, f_len);
+        if (bound >= 2147483647ll) return fail(GRF_EUNSUPPORTED, "the bound n*(1+n_walks*(f_len-1)) = %lld must fit int32", (long long)bound);
+        if (phi_out->capacity < bound)
+            return fail(GRF_ECAPACITY, "phi_out->capacity must be at least grf_sample_nnz_bound() = %lld (got %lld)",
+                        (long long)bound, (long long)phi_out->capacity);
     }
 
-    GRF_HIP_TRY(hipMemcpyAsync(f_dev, f, sizeof(float) * static_cast<size_t>(n_f) * f_len, hipMemcpyHostToDevice, stream));
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    long long* total_dev = reinterpret_cast<long long*>(ws + align_up(sizeof(float) * static_cast<size_t>(n_f) * f_len));
+    if (g->n == 0) {
+        if (grf_status st = fill_i32(phi_out->row_ptr, 1, 0, stream)) return st;
+        if (nnz_out != nullptr) *nnz_out = 0;
+        return GRF_OK;
+    }
+    const float* f_dev = f_device;
+    if (f_host != nullptr) {
+        GRF_HIP_TRY(hipMemcpyAsync(ws, f_host, sizeof(float) * static_cast<size_t>(n_f) * f_len, hipMemcpyHostToDevice, stream));
+        f_dev = reinterpret_cast<const float*>(ws);
+    }
 
     const int cap = static_cast<int>(cap_ll);
     const size_t lds = static_cast<size_t>(cap) * kDepositBytes;
@@ -406,24 +416,50 @@ extern "C" grf_status grf_sample(const grf_graph* g, const float* f, int32_t f_l
 
     // pass 1: entries per row, then offsets
     hipLaunchKernelGGL(rows_kernel<kCount>, grid, dim3(kWave), lds, stream, gv, law, n_walks, f_len, n_f,
-                       static_cast<const float*>(f_dev), cap, phi_out->row_ptr, static_cast<int32_t*>(nullptr),
+                       f_dev, cap, phi_out->row_ptr, static_cast<int32_t*>(nullptr),
                        static_cast<float*>(nullptr), 0ll, static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
     GRF_LAUNCH_CHECK("rows_kernel<count>");
     if (grf_status st = exclusive_scan_inplace(phi_out->row_ptr, g->n, total_dev, stream)) return st;
-    long long total = 0;
-    GRF_HIP_TRY(hipMemcpyAsync(&total, total_dev, sizeof(long long), hipMemcpyDeviceToHost, stream));
-    GRF_HIP_TRY(hipStreamSynchronize(stream));
-    *nnz_out = total;
-    if (total >= 2147483647ll) return fail(GRF_EUNSUPPORTED, "Phi_hat has %lld entries; int32 offsets cover < 2^31 - 1", total);
-    if (phi_out->capacity < total)
-        return fail(GRF_ECAPACITY, "Phi_hat has %lld entries but phi_out->capacity is %lld", total, (long long)phi_out->capacity);
+    if (nnz_out != nullptr) {
+        long long total = 0;
+        GRF_HIP_TRY(hipMemcpyAsync(&total, total_dev, sizeof(long long), hipMemcpyDeviceToHost, stream));
+        GRF_HIP_TRY(hipStreamSynchronize(stream));
+        *nnz_out = total;
+        if (total >= 2147483647ll) return fail(GRF_EUNSUPPORTED, "Phi_hat has %lld entries; int32 offsets cover < 2^31 - 1", total);
+        if (phi_out->capacity < total)
+            return fail(GRF_ECAPACITY, "Phi_hat has %lld entries but phi_out->capacity is %lld", total, (long long)phi_out->capacity);
+    }
 
     // pass 2: same walks again, entries written at their offsets
     hipLaunchKernelGGL(rows_kernel<kFill>, grid, dim3(kWave), lds, stream, gv, law, n_walks, f_len, n_f,
-                       static_cast<const float*>(f_dev), cap, phi_out->row_ptr, phi_out->col, phi_out->val,
+                       f_dev, cap, phi_out->row_ptr, phi_out->col, phi_out->val,
                        static_cast<long long>(phi_out->capacity), static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
     GRF_LAUNCH_CHECK("rows_kernel<fill>");
     return GRF_OK;
+}
+
+}  // namespace
+
+extern "C" grf_status grf_sample(const grf_graph* g, const float* f, int32_t f_len, int32_t n_f,
+                                 double p_halt, int32_t n_walks, uint64_t seed,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream,
+                                 grf_phi* phi_out, int64_t* nnz_out)
+{
+    if (grf_status st = check_graph(g)) return st;
+    if (f == nullptr) return fail(GRF_EINVAL, "f is NULL");
+    if (nnz_out == nullptr) return fail(GRF_EINVAL, "nnz_out is NULL");
+    return sample_impl(g, f, nullptr, f_len, n_f, p_halt, n_walks, seed, workspace, workspace_bytes,
+                       static_cast<hipStream_t>(hip_stream), phi_out, nnz_out);
+}
+
+extern "C" grf_status grf_sample_async(const grf_graph* g, const float* f_device, int32_t f_len, int32_t n_f,
+                                       double p_halt, int32_t n_walks, uint64_t seed,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream, grf_phi* phi_out)
+{
+    if (grf_status st = check_graph(g)) return st;
+    if (f_device == nullptr) return fail(GRF_EINVAL, "f_device is NULL");
+    return sample_impl(g, nullptr, f_device, f_len, n_f, p_halt, n_walks, seed, workspace, workspace_bytes,
+                       static_cast<hipStream_t>(hip_stream), phi_out, nullptr);
 }
 
 extern "C" size_t grf_sample_backward_workspace_bytes(int64_t n, int32_t f_len, int32_t n_f)

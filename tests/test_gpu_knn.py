@@ -169,3 +169,61 @@ def test_dynamic_point_cloud_pipeline(grf, oracle):
     # every walk has exactly 3 hops: 1 + 27 * 3 deposits per node
     traj = grf.grf_sample_walks(g, 0.0, n_walks, 4, 5).cpu().numpy()
     assert np.all(traj >= 0)
+
+
+def test_dynamic_step_without_host_synchronisation_replays_from_a_hip_graph(grf, oracle):
+    """grf_knn_graph (no count returned) -> grf_sample_async (device f) -> asymmetric attention and the fused symmetric
+    attention, with nnz given as the capacity bound: the same results as the synchronising calls, also when captured
+    once into a HIP graph and replayed on new points and a new f."""
+    import torch
+    rng = np.random.default_rng(31)
+    n, k, n_walks, seed = 3000, 3, 27, 5
+    pts_h = [synth.cluster_points(n, 4, 0.05, rng).astype(np.float32) for _ in range(3)]
+    f_h = [np.array([[1.0, 0.6, 0.3, 0.15]], np.float32), np.array([[0.5, -0.2, 0.4, 0.1]], np.float32), np.array([[1.0, 1.0, 1.0, 1.0]], np.float32)]
+    Q, K, V = (torch.from_numpy(x).to("cuda:0") for x in synth.qkv(1, 2, n, 64, rng))
+    pts = dev(pts_h[0]); f = torch.from_numpy(f_h[0]).to("cuda:0")
+
+    # buffers of the asynchronous pipeline, sized by the bounds
+    g_buf = grf.grf_knn_graph(pts, k, symmetrise=False, weights="inv_degree", sync=False)
+    assert g_buf.col.numel() == grf.grf_knn_graph_nnz_bound(n, k, False)
+    kws = torch.empty(grf.grf_knn_graph_workspace_bytes(n, k), dtype=torch.uint8, device="cuda:0")
+    phi_buf = grf.grf_sample_async(g_buf, f, 0.0, n_walks, seed)
+    assert phi_buf.nnz == phi_buf.capacity == grf.grf_sample_nnz_bound(n, n_walks, 4)
+    sws = torch.empty(1024, dtype=torch.uint8, device="cuda:0")
+    fws = torch.empty(grf.grf_fused_attention_workspace_bytes(1, 2, n, 64, phi_buf.nnz, 1), dtype=torch.uint8, device="cuda:0")
+    out_a, out_f = torch.empty((1, 2, n, 64), device="cuda:0"), torch.empty((1, 2, n, 64), device="cuda:0")
+
+    def step():
+        grf.grf_knn_graph(pts, k, symmetrise=False, weights="inv_degree", workspace=kws, out=g_buf, sync=False)
+        grf.grf_sample_async(g_buf, f, 0.0, n_walks, seed, out=phi_buf, workspace=sws)
+        grf.grf_asymmetric_masked_attention(Q, K, V, phi_buf, out=out_a)
+        grf.grf_masked_linear_attention_fused(Q, K, V, phi_buf, workspace=fws, out=out_f)
+
+    def reference(p_h, ff):
+        g = grf.grf_knn_graph(dev(p_h), k, symmetrise=False, weights="inv_degree")
+        phi = grf.grf_sample(g, ff, 0.0, n_walks, seed)
+        return phi, grf.grf_asymmetric_masked_attention(Q, K, V, phi), grf.grf_masked_linear_attention_fused(Q, K, V, phi)
+
+    step()
+    torch.cuda.synchronize()
+    phi0, ra, rf = reference(pts_h[0], f_h[0])
+    nnz0 = int(phi_buf.row_ptr[-1])
+    assert nnz0 == phi0.nnz
+    assert torch.equal(phi_buf.col[:nnz0], phi0.col[:nnz0]) and torch.equal(phi_buf.val[:, :nnz0], phi0.val[:, :nnz0])
+    assert torch.equal(torch.nan_to_num(out_a), torch.nan_to_num(ra)) and torch.equal(torch.nan_to_num(out_f), torch.nan_to_num(rf))
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for trial in (1, 2, 0):
+        pts.copy_(dev(pts_h[trial])); f.copy_(torch.from_numpy(f_h[trial]).to("cuda:0"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got_a, got_f = out_a.clone(), out_f.clone()
+        _, ra, rf = reference(pts_h[trial], f_h[trial])
+        assert torch.equal(torch.nan_to_num(got_a), torch.nan_to_num(ra)), trial
+        assert torch.equal(torch.nan_to_num(got_f), torch.nan_to_num(rf)), trial
