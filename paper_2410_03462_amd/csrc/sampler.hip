@@ -222,18 +222,36 @@ __global__ __launch_bounds__(256) void df_reduce_kernel(const float* __restrict_
 }
 
 // ------------------------------------------------------------------------------------ scan / fill
+// Exclusive prefix sum by one workgroup of 1024 threads over tiles of 4096 elements (the inputs are row or column
+// counts: a few hundred thousand elements at most in practice).  A thread's four elements are one 16-byte load
+// (data is 16-byte aligned), and the next tile is fetched before the current one is scanned.
 __global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ data, long long n, long long* __restrict__ total64)
 {
-    __shared__ long long wave_total[16];
+    __shared__ long long wave_total[2][16];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid >> 6;
+    const bool aligned = (reinterpret_cast<uintptr_t>(data) & 15u) == 0;
+    auto fetch = [&](long long tile, int32_t (&v)[4]) {
+        const long long idx = tile + static_cast<long long>(tid) * 4;
+        if (aligned && idx + 3 < n) {
+            const int4 q = *reinterpret_cast<const int4*>(data + idx);
+            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] = (idx + k < n) ? data[idx + k] : 0;
+        }
+    };
     long long carry = 0;
-    for (long long tile = 0; tile < n; tile += 4096) {
+    int32_t next[4];
+    fetch(0, next);
+    int parity = 0;
+    for (long long tile = 0; tile < n; tile += 4096, parity ^= 1) {
         const long long idx = tile + static_cast<long long>(tid) * 4;
         int32_t v[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = (idx + k < n) ? data[idx + k] : 0;
+        for (int k = 0; k < 4; ++k) v[k] = next[k];
+        if (tile + 4096 < n) fetch(tile + 4096, next);
         const long long local = static_cast<long long>(v[0]) + v[1] + v[2] + v[3];
         long long incl = local;
 #pragma unroll
@@ -241,12 +259,12 @@ __global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ data, 
             const long long up = __shfl_up(incl, off, kWave);
             if (lane >= off) incl += up;
         }
-        if (lane == kWave - 1) wave_total[wave] = incl;
-        __syncthreads();
+        if (lane == kWave - 1) wave_total[parity][wave] = incl;
+        __syncthreads();          // one barrier per tile: the two halves of wave_total alternate
         long long before = 0, tile_total = 0;
 #pragma unroll
         for (int w = 0; w < 16; ++w) {
-            const long long t = wave_total[w];
+            const long long t = wave_total[parity][w];
             if (w < wave) before += t;
             tile_total += t;
         }
@@ -257,11 +275,10 @@ __global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ data, 
             run += v[k];
         }
         carry += tile_total;
-        __syncthreads();
     }
     if (tid == 0) {
         data[n] = carry > 2147483647ll ? 2147483647 : static_cast<int32_t>(carry);
-        *total64 = carry;
+        if (total64 != nullptr) *total64 = carry;
     }
 }
 
