@@ -36,6 +36,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cloud_32k")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU checker timing (profiling runs)")
+    ap.add_argument("--dynamic-only", action="store_true",
+                    help="only the dynamic point-cloud section (graph construction + walks + asymmetric attention), for profiling")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device-to-device copy of 1 GiB three times (scale for the HBM byte counters)")
     args = ap.parse_args()
@@ -72,6 +74,85 @@ def main() -> int:
     Q, K, V = wl.qkv()
     to_dev = (lambda x: torch.from_numpy(x).to(dev).to(torch.bfloat16)) if wl.dtype == "bf16" else (lambda x: torch.from_numpy(x).to(dev))
     Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+
+    stream = torch.cuda.current_stream()
+
+    def dynamic_section(aout):
+        # dynamic point clouds (Sec. 4 / App. C): the graph is rebuilt every step, so graph construction is on the path.
+        # (i) the workload's own graph (symmetrised k-NN, kernel weights) rebuilt on the GPU;
+        # (ii) the paper's setting: neighbour lists of length 3, 27 walks of exactly 3 hops, asymmetric GRFs.
+        dynamic = None
+        tokens = N * B * H
+        if "points" in wl.notes:
+            pts = torch.from_numpy(wl.notes["points"].astype(np.float32)).to(dev)
+            kk, kern = wl.notes["k"], wl.notes["kernel"]
+            from scipy.spatial import cKDTree
+            sub = wl.notes["points"][:: max(1, N // 4096)]
+            sigma = float(np.median(cKDTree(wl.notes["points"]).query(sub, k=kk + 1)[0][:, 1:]))    # scale only; not timed
+            kws = torch.empty(grf.grf_knn_graph_workspace_bytes(N, max(kk, 3)), dtype=torch.uint8, device=dev)
+
+            def timed(fn):
+                for _ in range(args.warmup):
+                    fn()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(args.steps):
+                    fn()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / args.steps
+
+            knn_ms = timed(lambda: grf.grf_knn_graph(pts, kk, True, kern, sigma, workspace=kws))
+            f3 = np.array([[1.0, 0.6, 0.3, 0.15]], dtype=np.float32)
+            g3 = grf.grf_knn_graph(pts, 3, False, "inv_degree", workspace=kws)
+            phi3 = grf.grf_sample(g3, f3, 0.0, 27, wl.walk_seed)
+
+            def dynamic_step():
+                gg = grf.grf_knn_graph(pts, 3, False, "inv_degree", workspace=kws)
+                grf.grf_sample(gg, f3, 0.0, 27, wl.walk_seed, out=phi3)
+                grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi3, out=aout)
+
+            knn3_ms = timed(lambda: grf.grf_knn_graph(pts, 3, False, "inv_degree", workspace=kws))
+            dyn_ms = timed(dynamic_step)
+
+            # the same step without host synchronisation (counts stay on the device, buffers sized by their bounds),
+            # captured once into a HIP graph and replayed
+            f3_dev = torch.from_numpy(f3).to(dev)
+            g_buf = grf.grf_knn_graph(pts, 3, False, "inv_degree", workspace=kws, sync=False)
+            phi_buf = grf.grf_sample_async(g_buf, f3_dev, 0.0, 27, wl.walk_seed)
+            sws = torch.empty(1024, dtype=torch.uint8, device=dev)
+
+            def async_step():
+                grf.grf_knn_graph(pts, 3, False, "inv_degree", workspace=kws, out=g_buf, sync=False)
+                grf.grf_sample_async(g_buf, f3_dev, 0.0, 27, wl.walk_seed, out=phi_buf, workspace=sws)
+                grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi_buf, out=aout)
+
+            async_step()
+            torch.cuda.synchronize()
+            side = torch.cuda.Stream()
+            side.wait_stream(stream)
+            hip_graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(hip_graph, stream=side):
+                    async_step()
+            torch.cuda.synchronize()
+            replay_ms = timed(hip_graph.replay)
+            dynamic = {
+                "knn_graph_ms": round(knn_ms, 4), "knn_graph": "k=%d, symmetrised, %s kernel, row-normalised" % (kk, kern),
+                "knn_points_per_s": round(N / (knn_ms * 1e-3), 1),
+                "paper_setting": {"graph": "k=3 neighbour lists", "walks": "27 per node, 3 hops, no halting", "estimator": "asymmetric GRFs",
+                                  "knn_graph_ms": round(knn3_ms, 4), "step_ms": round(dyn_ms, 4), "phi_nnz": phi3.nnz,
+                                  "tokens_per_s_per_head": round(tokens / (dyn_ms * 1e-3), 1),
+                                  "hip_graph_replay_step_ms": round(replay_ms, 4),
+                                  "hip_graph_replay_tokens_per_s_per_head": round(tokens / (replay_ms * 1e-3), 1),
+                                  "step": "grf_knn_graph + grf_sample + grf_asymmetric_masked_attention"},
+            }
+        return dynamic
+
+    if args.dynamic_only:
+        print(json.dumps({"workload": wl.name, "dynamic_point_cloud": dynamic_section(torch.empty((B, H, N, d), dtype=torch.float32, device=dev))}))
+        return 0
 
     # buffers sized once, outside the timed region
     phi = grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
@@ -222,75 +303,7 @@ def main() -> int:
                      "note": "whole backward (seed, column lists, three bucket passes with their row reductions, dphi, df)"},
     }
 
-    # dynamic point clouds (Sec. 4 / App. C): the graph is rebuilt every step, so graph construction is on the path.
-    # (i) the workload's own graph (symmetrised k-NN, kernel weights) rebuilt on the GPU;
-    # (ii) the paper's setting: neighbour lists of length 3, 27 walks of exactly 3 hops, asymmetric GRFs.
-    dynamic = None
-    if "points" in wl.notes:
-        pts = torch.from_numpy(wl.notes["points"].astype(np.float32)).to(dev)
-        kk, kern = wl.notes["k"], wl.notes["kernel"]
-        from scipy.spatial import cKDTree
-        sub = wl.notes["points"][:: max(1, N // 4096)]
-        sigma = float(np.median(cKDTree(wl.notes["points"]).query(sub, k=kk + 1)[0][:, 1:]))    # scale only; not timed
-        kws = torch.empty(grf.grf_knn_graph_workspace_bytes(N, max(kk, 3)), dtype=torch.uint8, device=dev)
-
-        def timed(fn):
-            for _ in range(args.warmup):
-                fn()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for _ in range(args.steps):
-                fn()
-            e1.record(stream)
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / args.steps
-
-        knn_ms = timed(lambda: grf.grf_knn_graph(pts, kk, True, kern, sigma, workspace=kws))
-        f3 = np.array([[1.0, 0.6, 0.3, 0.15]], dtype=np.float32)
-        g3 = grf.grf_knn_graph(pts, 3, False, "inv_degree", workspace=kws)
-        phi3 = grf.grf_sample(g3, f3, 0.0, 27, wl.walk_seed)
-
-        def dynamic_step():
-            gg = grf.grf_knn_graph(pts, 3, False, "inv_degree", workspace=kws)
-            grf.grf_sample(gg, f3, 0.0, 27, wl.walk_seed, out=phi3)
-            grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi3, out=aout)
-
-        knn3_ms = timed(lambda: grf.grf_knn_graph(pts, 3, False, "inv_degree", workspace=kws))
-        dyn_ms = timed(dynamic_step)
-
-        # the same step without host synchronisation (counts stay on the device, buffers sized by their bounds),
-        # captured once into a HIP graph and replayed
-        f3_dev = torch.from_numpy(f3).to(dev)
-        g_buf = grf.grf_knn_graph(pts, 3, False, "inv_degree", workspace=kws, sync=False)
-        phi_buf = grf.grf_sample_async(g_buf, f3_dev, 0.0, 27, wl.walk_seed)
-        sws = torch.empty(1024, dtype=torch.uint8, device=dev)
-
-        def async_step():
-            grf.grf_knn_graph(pts, 3, False, "inv_degree", workspace=kws, out=g_buf, sync=False)
-            grf.grf_sample_async(g_buf, f3_dev, 0.0, 27, wl.walk_seed, out=phi_buf, workspace=sws)
-            grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi_buf, out=aout)
-
-        async_step()
-        torch.cuda.synchronize()
-        side = torch.cuda.Stream()
-        side.wait_stream(stream)
-        hip_graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(hip_graph, stream=side):
-                async_step()
-        torch.cuda.synchronize()
-        replay_ms = timed(hip_graph.replay)
-        dynamic = {
-            "knn_graph_ms": round(knn_ms, 4), "knn_graph": "k=%d, symmetrised, %s kernel, row-normalised" % (kk, kern),
-            "knn_points_per_s": round(N / (knn_ms * 1e-3), 1),
-            "paper_setting": {"graph": "k=3 neighbour lists", "walks": "27 per node, 3 hops, no halting", "estimator": "asymmetric GRFs",
-                              "knn_graph_ms": round(knn3_ms, 4), "step_ms": round(dyn_ms, 4), "phi_nnz": phi3.nnz,
-                              "tokens_per_s_per_head": round(tokens / (dyn_ms * 1e-3), 1),
-                              "hip_graph_replay_step_ms": round(replay_ms, 4),
-                              "hip_graph_replay_tokens_per_s_per_head": round(tokens / (replay_ms * 1e-3), 1),
-                              "step": "grf_knn_graph + grf_sample + grf_asymmetric_masked_attention"},
-        }
+    dynamic = dynamic_section(aout)
 
     result = {
         "metric": "GRF-masked linear attention tokens/s/head at N=%d" % N,
