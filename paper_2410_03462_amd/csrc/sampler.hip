@@ -92,13 +92,17 @@ __global__ __launch_bounds__(256) void walks_kernel(GraphView g, WalkLaw law, in
 }
 
 // ------------------------------------------------------------------------------------ rows of Phi_hat
-// LDS layout for `cap` deposits: dcol[cap] dload[cap] scol[cap] sload[cap] (4 B each), dhop[cap]
-// shop[cap] (2 B each) = 20 B per deposit.
-constexpr int kDepositBytes = 20;
+// LDS layout for `cap` deposits: dcol[cap] dload[cap] (4 B each), dhop[cap] perm[cap] (2 B each) = 12 B per
+// deposit, plus dent[cap] (4 B) in the gradient mode.  The deposits stay where the walks put them; the column
+// order is an index permutation (perm[r] = deposit at sorted position r), which keeps the footprint small: the
+// kernel is bound by the latency of the hops' dependent loads, so what matters is how many wavefronts fit a
+// compute unit.
+constexpr int kDepositBytes = 12;
+constexpr int kDepositBytesGrad = 16;
 
 // MODE kCount: row_ptr[node] = number of entries of the row.  kFill: entries written at row_ptr[node].
 // kGrad: instead of values, the row's share of dL/df is written to df_part[node][n_f][f_len], where
-// dphi (read through val_out's slot, [n_f][val_stride]) holds dL/dPhi_hat per stored entry.
+// dphi ([n_f][val_stride]) holds dL/dPhi_hat per stored entry.
 enum : int { kCount = 0, kFill = 1, kGrad = 2 };
 
 template <int MODE>
@@ -112,10 +116,9 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
     extern __shared__ __align__(16) unsigned char lds[];
     int32_t* dcol = reinterpret_cast<int32_t*>(lds);
     float* dload = reinterpret_cast<float*>(dcol + cap);
-    int32_t* scol = reinterpret_cast<int32_t*>(dload + cap);
-    float* sload = reinterpret_cast<float*>(scol + cap);
-    uint16_t* dhop = reinterpret_cast<uint16_t*>(sload + cap);
-    uint16_t* shop = dhop + cap;
+    uint16_t* dhop = reinterpret_cast<uint16_t*>(dload + cap);
+    uint16_t* perm = dhop + cap;
+    int32_t* dent = reinterpret_cast<int32_t*>(perm + cap);      // gradient mode only; byte offset 12 cap: 4-byte aligned
 
     const uint32_t node = blockIdx.x;
     const int lane = threadIdx.x;
@@ -152,7 +155,7 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
             const int32_t c2 = dcol[s2];
             rank += static_cast<int>((c2 < c) | ((c2 == c) & (s2 < s)));
         }
-        scol[rank] = c; sload[rank] = dload[s]; shop[rank] = dhop[s];
+        perm[rank] = static_cast<uint16_t>(s);
     }
     __syncthreads();
 
@@ -163,13 +166,12 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
     for (int r0 = 0; r0 < D; r0 += kWave) {
         const int r = r0 + lane;
         const bool valid = r < D;
-        const int32_t c = valid ? scol[r] : -1;
-        const bool head = valid && (r == 0 || scol[r - 1] != c);
+        const int32_t c = valid ? dcol[perm[r]] : -1;
+        const bool head = valid && (r == 0 || dcol[perm[r - 1]] != c);
         const unsigned long long mask = __ballot(head);
         if (MODE == kGrad && valid) {
-            // entry of Phi_hat that deposit r belongs to: runs up to and including this lane, minus one
-            const int run = heads + prefix_popcount(mask) + (head ? 1 : 0) - 1;
-            dcol[r] = row_start + run;
+            // entry of Phi_hat that sorted position r belongs to: runs up to and including this lane, minus one
+            dent[r] = row_start + heads + prefix_popcount(mask) + (head ? 1 : 0) - 1;
         }
         if (FILL && head) {
             const long long pos = static_cast<long long>(row_start) + heads + prefix_popcount(mask);
@@ -177,7 +179,11 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
             for (int h = 0; h < n_f; ++h) {
                 const float* fh = f + static_cast<long long>(h) * f_len;
                 float acc = 0.0f;
-                for (int e = r; e < D && scol[e] == c; ++e) acc = fmaf(sload[e], fh[shop[e]], acc);
+                for (int e = r; e < D; ++e) {
+                    const int s = perm[e];
+                    if (dcol[s] != c) break;
+                    acc = fmaf(dload[s], fh[dhop[s]], acc);
+                }
                 val_out[h * val_stride + pos] = acc / n_float;
             }
         }
@@ -187,18 +193,20 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
 
     if (MODE == kGrad) {
         // dL/df[h][t] of this node = (1/n) sum over deposits with hop t of load * dphi[h][entry]; lane t walks
-        // the deposits in sorted order, so the sum has a fixed order
+        // the deposits in sorted order, so the sum has a fixed order.  The columns are not needed any more:
+        // their array holds the staged products.
+        float* gval = reinterpret_cast<float*>(dcol);
         const int32_t row_end = row_ptr[node + 1];
         for (int h = 0; h < n_f; ++h) {
             __syncthreads();
             for (int r = lane; r < D; r += kWave) {
-                const int32_t e = dcol[r];
-                dload[r] = (e >= 0 && e < row_end && e < val_stride) ? sload[r] * dphi[h * val_stride + e] : 0.0f;
+                const int32_t e = dent[r];
+                gval[r] = (e >= 0 && e < row_end && e < val_stride) ? dload[perm[r]] * dphi[h * val_stride + e] : 0.0f;
             }
             __syncthreads();
             for (int t = lane; t < f_len; t += kWave) {
                 float acc = 0.0f;
-                for (int r = 0; r < D; ++r) acc += shop[r] == t ? dload[r] : 0.0f;
+                for (int r = 0; r < D; ++r) acc += dhop[perm[r]] == t ? gval[r] : 0.0f;
                 df_part[(static_cast<long long>(node) * n_f + h) * f_len + t] = acc / n_float;
             }
         }
@@ -307,7 +315,7 @@ grf_status fill_i32(int32_t* data, int64_t n, int32_t value, hipStream_t stream)
 // ------------------------------------------------------------------------------------ host side
 namespace {
 
-constexpr int kMaxDeposits = 8192;   // 8192 * 20 B = 160 KB, the LDS of one gfx950 compute unit
+constexpr int kMaxDeposits = 8192;   // 8192 * 16 B = 128 KB of the 160 KB of LDS of one gfx950 compute unit; also the range of a uint16 index
 
 grf_status check_graph(const grf_graph* g)
 {
@@ -514,7 +522,7 @@ extern "C" grf_status grf_sample_backward(const grf_graph* g, int32_t f_len, int
     }
     float* df_part = static_cast<float*>(workspace);
     const int cap = static_cast<int>(cap_ll);
-    const size_t lds = static_cast<size_t>(cap) * kDepositBytes;
+    const size_t lds = static_cast<size_t>(cap) * kDepositBytesGrad;
     if (lds > 64 * 1024)
         GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_kernel<kGrad>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
     hipLaunchKernelGGL(rows_kernel<kGrad>, dim3(static_cast<unsigned>(g->n)), dim3(kWave), lds, stream, view_of(g), law, n_walks, f_len, n_f,
