@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # Bytes moved between L2 and the fabric per gather launch, from rocprofv3 --pmc runs of this file
 # (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from --copy-calibration under the same
 # counters).  A stored measurement, not recomputed here; absent workloads report null.
-MEASURED_TRAFFIC_BYTES = {"cloud_32k": 322188156585}
+MEASURED_TRAFFIC_BYTES = {"cloud_32k": 322188156585, "vit_grid": 23538457990, "cloud_8k": 224494242686, "cloud_128k": 2542783367655}
 
 
 def main() -> int:
