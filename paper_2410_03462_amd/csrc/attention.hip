@@ -292,6 +292,10 @@ grf_status check_problem(const void* a, const void* b, int32_t dtype, int64_t B,
                          const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map)
 {
     if (B < 0 || H < 0 || n < 0) return fail(GRF_EINVAL, "B=%lld, H=%lld, n=%lld must be >= 0", (long long)B, (long long)H, (long long)n);
+    // one wavefront (or workgroup) per (slice, node) in the launches that follow; tensors of 2^31 rows would
+    // not fit the device anyway
+    if ((B > 0 && H > 2147483647ll / B) || (n > 0 && B * H > 2147483647ll / n))
+        return fail(GRF_EUNSUPPORTED, "B*H*n = %lld*%lld*%lld must be < 2^31", (long long)B, (long long)H, (long long)n);
     if (dtype != GRF_DTYPE_F32 && dtype != GRF_DTYPE_BF16) return fail(GRF_EINVAL, "dtype=%d is neither GRF_DTYPE_F32 nor GRF_DTYPE_BF16", dtype);
     if (feature_map != GRF_PHI_RELU && feature_map != GRF_PHI_IDENTITY && feature_map != GRF_PHI_ELU1) return fail(GRF_EINVAL, "feature_map=%d is unknown", feature_map);
     if (d != 32 && d != 64) return fail(GRF_EUNSUPPORTED, "head dimension d=%d is not supported (32 or 64)", d);
@@ -302,7 +306,6 @@ grf_status check_problem(const void* a, const void* b, int32_t dtype, int64_t B,
     if (n_f != 1 && n_f != H) return fail(GRF_EINVAL, "n_f=%d must be 1 or H=%lld", n_f, (long long)H);
     if (phi->row_ptr == nullptr || (nnz > 0 && (phi->col == nullptr || phi->val == nullptr))) return fail(GRF_EINVAL, "phi arrays are NULL");
     if (B * H * n > 0 && (a == nullptr || b == nullptr)) return fail(GRF_EINVAL, "an input tensor is NULL");
-    if (B * H > (1ll << 40) / (n > 0 ? n : 1)) return fail(GRF_EUNSUPPORTED, "B*H*n is too large");
     return GRF_OK;
 }
 

@@ -84,6 +84,12 @@ def test_argument_validation_precedes_device_work(binding):
     st = L.grf_masked_linear_attention(None, None, None, 7, 1, 1, 10, 64, ctypes.byref(phi), 0, 1, 0, 0,
                                        None, 0, None, None, None, None)
     assert st == binding.GRF_EINVAL
+    # B*H*n beyond what one launch (and the device) covers, including products that overflow 64 bits
+    for B, H in ((1 << 20, 1 << 20), (1 << 40, 1 << 40), (1 << 16, 1 << 12)):
+        st = L.grf_masked_linear_attention_fused(None, None, None, 0, B, H, 10, 64, ctypes.byref(phi), 0, 1, 0, 0,
+                                                 None, 0, None, None, None, None)
+        assert st == binding.GRF_EUNSUPPORTED, (B, H)
+        assert b"2^31" in L.grf_last_error()
 
 
 def test_product_path_has_no_cpu_fallback(binding):
