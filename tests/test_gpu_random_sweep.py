@@ -1,0 +1,155 @@
+"""Seeded sweep over small random problems: every entry point of the HIP library against the CPU checker
+(needs the GPU).
+
+The cases draw the graph family, the number of nodes (1 .. ~400, around the multiples of 32 and 64 that the
+kernels tile by), the walk law, the modulation, the slices, head dimension, input type and feature map at
+random from a fixed seed, so that ragged tails and degenerate shapes that no hand-picked case names are covered.
+Bars as everywhere: trajectories and pattern bit-exact, values 1e-5 (fp32) / 2e-2 (bf16 inputs) normwise.
+"""
+import numpy as np
+import pytest
+
+from paper_2410_03462_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+FEATURE_MAP_CODE = {"relu": 0, "identity": 1, "elu1": 2}
+N_CASES = 96
+
+
+@pytest.fixture(scope="module")
+def grf():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2410_03462_amd import binding
+    binding.lib()
+    return binding
+
+
+def relerr(x, ref):
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    scale = np.abs(ref).max()
+    return float(np.abs(x - ref).max() / scale) if scale > 0 else float(np.abs(x).max())
+
+
+def to_dev(x, dtype="f32"):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def check_gradients(got, ref, tol, label, diagonal):
+    """dQ, dK, dV, dphi against the checker.  `diagonal`: Phi_hat = f_0 I (one node, or a modulation of length one), where
+    out = v whatever q, k and f_0 are: every gradient but dV vanishes identically, the references are of rounding size
+    and what the GPU returns is the rounding of the cancelling terms, so only dV is compared there."""
+    for name, x, r in zip(("dQ", "dK", "dV", "dphi"), got, ref):
+        assert np.isfinite(x).all(), label + name
+        if r.size == 0 or (diagonal and name != "dV"):
+            continue
+        assert relerr(x, r) <= tol, (label + name, relerr(x, r))
+
+
+def draw_case(index):
+    rng = np.random.default_rng([2024, index])
+    sizes = [1, 2, 3, 31, 32, 33, 63, 64, 65, 95, 127, 128, 129, 191, 257, 389]
+    n = int(sizes[index % len(sizes)] if index < len(sizes) else rng.integers(1, 400))
+    family = ["random", "ring", "star", "path", "grid"][int(rng.integers(0, 5))]
+    if n < 4 and family in ("ring", "grid"):
+        family = "path"
+    if family == "random":
+        g = synth.random_graph(n, float(rng.uniform(1.0, 8.0)), rng, weights=["sym_norm", "inv_deg"][int(rng.integers(0, 2))],
+                               isolated=int(rng.integers(0, max(1, n // 8))))
+    elif family == "ring":
+        g = synth.ring_graph(n)
+    elif family == "star":
+        g = synth.star_graph(max(n, 2)) if n >= 2 else synth.path_graph(1)
+    elif family == "path":
+        g = synth.path_graph(n)
+    else:
+        h = max(2, int(np.sqrt(n)))
+        g = synth.grid_graph(h, max(2, n // h), [4, 8][int(rng.integers(0, 2))])
+    f_len = int(rng.integers(1, 13))
+    H = int(rng.integers(1, 4))
+    n_f = H if rng.random() < 0.4 else 1
+    f = synth.modulation(f_len, rng, n_f=n_f)
+    wl = synth.Workload(f"sweep_{index}_{family}_{g.n}", g, f, float(rng.choice([0.0, 0.1, 0.3, 0.5, 0.8])),
+                        int(rng.choice([1, 2, 5, 17, 63, 64, 65, 70])), int(rng.integers(1, 3)), H,
+                        int(rng.choice([32, 64])), str(rng.choice(["f32", "bf16"])),
+                        walk_seed=int(rng.integers(0, 2**62)), data_seed=index)
+    return wl, str(rng.choice(["relu", "identity", "elu1"]))
+
+
+@pytest.mark.parametrize("index", range(N_CASES))
+def test_random_case(grf, oracle, index):
+    wl, feature_map = draw_case(index)
+    print(wl.name, "f_len", wl.f_len, "n_f", wl.n_f, "p", wl.p_halt, "walks", wl.n_walks, "B", wl.B, "H", wl.H, "d", wl.d,
+          wl.dtype, feature_map, flush=True)
+    fm = FEATURE_MAP_CODE[feature_map]
+    tol = TOL[wl.dtype]
+    n = wl.graph.n
+    g = grf.DeviceGraph.from_host(wl.graph)
+
+    # ---- sampler
+    walks = grf.grf_sample_walks(g, wl.p_halt, wl.n_walks, wl.f_len, wl.walk_seed).cpu().numpy()
+    assert np.array_equal(walks, oracle.sample_walks(wl.graph, wl.p_halt, wl.n_walks, wl.f_len, wl.walk_seed))
+    phi = grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+    rp, col, val = phi.to_host()
+    rp0, col0, val0 = oracle.sample(wl.graph, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+    assert np.array_equal(rp, rp0) and np.array_equal(col, col0)
+    assert relerr(val, val0) <= TOL["f32"]
+
+    # ---- the three forward entry points, on the checker's Phi_hat
+    Q, K, V = wl.qkv()
+    Qd, Kd, Vd = (to_dev(x, wl.dtype) for x in (Q, K, V))
+    phi0 = grf.Phi.from_host(n, rp0, col0, val0)
+    ref = oracle.masked_linear_attention(Q, K, V, rp0, col0, val0, feature_map=fm)
+    chunk = int(index % 3)            # 0 = all slices at once
+    for call in (grf.grf_masked_linear_attention, grf.grf_masked_linear_attention_fused):
+        _, num, den = call(Qd, Kd, Vd, phi0, feature_map, bh_chunk=chunk, return_num_den=True)
+        assert relerr(num.cpu().numpy(), ref["num"]) <= tol, call.__name__
+        assert relerr(den.cpu().numpy(), ref["den"]) <= tol, call.__name__
+    phi1 = grf.Phi.from_host(n, rp0, col0, val0[:1])
+    _, num, den = grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi1, feature_map, return_num_den=True)
+    aref = oracle.asymmetric_attention_walks(wl.graph, wl.f[0], wl.p_halt, wl.n_walks, wl.walk_seed, Q, K, V, feature_map=fm)
+    assert relerr(num.cpu().numpy(), aref["num"]) <= tol
+    assert relerr(den.cpu().numpy(), aref["den"]) <= tol
+
+    # ---- gradients, with phi > 0 and a non-negative modulation so that no denominator vanishes
+    f_pos = np.abs(wl.f) + 0.01
+    diagonal = n == 1 or wl.f_len == 1
+    rp1, col1, val1 = oracle.sample(wl.graph, f_pos, wl.p_halt, wl.n_walks, wl.walk_seed)
+    fwd = oracle.masked_linear_attention(Q, K, V, rp1, col1, val1, feature_map=2)
+    out32, den32 = fwd["out"].astype(np.float32), fwd["den"].astype(np.float32)
+    assert np.isfinite(out32).all() and (den32 > 0).all()
+    d_out = np.random.default_rng([7, index]).standard_normal(Q.shape).astype(np.float32)
+    bref = oracle.masked_linear_attention_backward(Q, K, V, rp1, col1, val1, out32, den32, d_out, 2)
+    phi_pos = grf.Phi.from_host(n, rp1, col1, val1)
+    got = grf.grf_masked_linear_attention_backward(Qd, Kd, Vd, phi_pos, to_dev(out32), to_dev(den32), to_dev(d_out), "elu1",
+                                                   bh_chunk=chunk)
+    host = [t.cpu().numpy() for t in got]
+    host[3] = host[3][:, : phi_pos.nnz]
+    check_gradients(host, bref, tol, "", diagonal)
+    df = grf.grf_sample_backward(g, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, phi_pos, got[3]).cpu().numpy()
+    df_ref = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp1, col1, bref[3])
+    assert df.shape == df_ref.shape and np.isfinite(df).all()
+    if not diagonal:
+        for h in range(wl.n_f):
+            assert relerr(df[h], df_ref[h]) <= 10 * tol, (h, relerr(df[h], df_ref[h]))
+
+    # ---- the same for asymmetric features (per-head planes allowed)
+    afwd = {"out": np.empty(Q.shape), "den": np.empty(Q.shape[:3])}
+    for h in range(wl.H):
+        r = oracle.asymmetric_attention_walks(wl.graph, f_pos[h if wl.n_f > 1 else 0], wl.p_halt, wl.n_walks, wl.walk_seed,
+                                              Q[:, h:h + 1], K[:, h:h + 1], V[:, h:h + 1], feature_map=2)
+        afwd["out"][:, h], afwd["den"][:, h] = r["out"][:, 0], r["den"][:, 0]
+    aout32, aden32 = afwd["out"].astype(np.float32), afwd["den"].astype(np.float32)
+    assert np.isfinite(aout32).all() and (aden32 > 0).all()
+    abref = oracle.asymmetric_attention_backward(Q, K, V, rp1, col1, val1, aout32, aden32, d_out, 2)
+    got = grf.grf_asymmetric_masked_attention_backward(Qd, Kd, Vd, phi_pos, to_dev(aout32), to_dev(aden32), to_dev(d_out), "elu1",
+                                                       bh_chunk=chunk)
+    host = [t.cpu().numpy() for t in got]
+    host[3] = host[3][:, : phi_pos.nnz]
+    check_gradients(host, abref, tol, "asymmetric ", diagonal)
