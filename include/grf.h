@@ -318,6 +318,12 @@ grf_status grf_sample_backward(const grf_graph* g, int32_t f_len, int32_t n_f,
                                void* workspace, size_t workspace_bytes, void* hip_stream,
                                float* df);
 
+/* Testing aid, not part of the method.  The bucket kernels (grf_form_buckets, the fused call, the backward call)
+ * address rows of Q, K, V with 32-bit byte offsets when a [n][d] fp32 slice is below 4 GiB and with 64-bit offsets
+ * otherwise; on != 0 makes every later call in this process take the 64-bit form, so that it can be tested at small
+ * sizes.  Results are the same bits either way. */
+void grf_debug_force_wide_offsets(int32_t on);
+
 #ifdef __cplusplus
 }
 #endif

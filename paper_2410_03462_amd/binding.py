@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.grf_sample_walks.restype = ctypes.c_int32
         L.grf_sample_walks.argtypes = [ctypes.POINTER(_Graph), ctypes.c_double, ctypes.c_int32, ctypes.c_int32,
                                        ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]
+        L.grf_debug_force_wide_offsets.restype = None
+        L.grf_debug_force_wide_offsets.argtypes = [ctypes.c_int32]
         L.grf_bucket_record_floats.restype = ctypes.c_int64
         L.grf_bucket_record_floats.argtypes = [ctypes.c_int32]
         L.grf_attention_workspace_bytes.restype = ctypes.c_size_t
@@ -352,6 +354,10 @@ def _check_qkv(*ts):
         if not t.is_cuda or not t.is_contiguous() or t.shape != shape or t.dtype != dtype or t.dim() != 4:
             raise ValueError("Q, K, V must be contiguous CUDA tensors of one shape [B,H,n,d] and dtype")
     return shape
+
+
+def grf_debug_force_wide_offsets(on: bool) -> None:
+    lib().grf_debug_force_wide_offsets(1 if on else 0)
 
 
 def grf_bucket_record_floats(d: int) -> int:

@@ -8,6 +8,8 @@
 //
 // A bucket record is d*d floats of S_l (S_l[a][c] at a*d + c, a = feature index of phi(k)) followed
 // by d floats of z_l, so the gather reads one contiguous run per entry of Phi_hat.
+#include <atomic>
+
 #include "attention_common.hpp"
 
 namespace grf {
@@ -100,8 +102,8 @@ __global__ __launch_bounds__(256) void column_values_kernel(const int32_t* __res
 // B[L/32][L%32]; accumulator register r of lane L holds D[8*(r/4) + 4*(L/32) + r%4][L%32].
 // The two halves of the wavefront therefore carry two different contributors j (the k index),
 // lane%32 walks along a row of phi(K) (A operand) and of V (B operand): no transposes, no LDS.
-template <int D, typename T>
-__global__ __launch_bounds__(64) void buckets_kernel(const T* __restrict__ K, const T* __restrict__ V,
+template <int D, typename T, bool WIDE>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void buckets_kernel(const T* __restrict__ K, const T* __restrict__ V,
                                                       long long n, int H, int n_f,
                                                       const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
                                                       const float* __restrict__ csc_val,
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(64) void buckets_kernel(const T* __restrict__ K, co
     const int32_t beg = col_ptr[l], end = col_ptr[l + 1];
     const ListBlock first = load_list_block<false>(csc_row, vals, nullptr, beg, end);
     with_feature_map(fmap, [&](auto fm) {
-        bucket_first_contraction<D, T, T, false, true, kExtraSumA, decltype(fm)::value>(Kb, Vb, csc_row, vals, nullptr, beg, end, first, acc, zacc);
+        bucket_first_contraction<D, T, T, false, true, kExtraSumA, decltype(fm)::value, WIDE>(Kb, Vb, csc_row, vals, nullptr, beg, end, first, acc, zacc);
     });
 
     float* rec = buckets + (slice * n + l) * REC;
@@ -309,6 +311,15 @@ grf_status check_problem(const void* a, const void* b, int32_t dtype, int64_t B,
     return GRF_OK;
 }
 
+namespace {
+std::atomic<int> g_force_wide_offsets{0};
+}
+
+bool wide_offsets(int64_t n, int32_t d)
+{
+    return g_force_wide_offsets.load(std::memory_order_relaxed) != 0 || n * static_cast<int64_t>(d) * 4 > 0xffffffffll;
+}
+
 unsigned resident_wave_grid(const void* kernel, long long items)
 {
     int device = 0, units = 0, per_unit = 0;
@@ -336,12 +347,15 @@ grf_status launch_buckets(const void* K, const void* V, int64_t n, int64_t H, in
 {
     const long long waves = static_cast<long long>(n_slices) * n;
     if (waves == 0) return GRF_OK;
-    hipLaunchKernelGGL((buckets_kernel<D, T>), dim3(blocks_for(waves, 1)), dim3(kWave), 0, stream,
-                       static_cast<const T*>(K), static_cast<const T*>(V), static_cast<long long>(n), static_cast<int>(H),
-                       static_cast<int>(n_f),
-                       static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
-                       static_cast<const float*>(t.s_val), fmap,
-                       static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), buckets);
+    auto launch = [&](auto wide) {
+        hipLaunchKernelGGL((buckets_kernel<D, T, decltype(wide)::value>), dim3(blocks_for(waves, 1)), dim3(kWave), 0, stream,
+                           static_cast<const T*>(K), static_cast<const T*>(V), static_cast<long long>(n), static_cast<int>(H),
+                           static_cast<int>(n_f),
+                           static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
+                           static_cast<const float*>(t.s_val), fmap,
+                           static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), buckets);
+    };
+    if (wide_offsets(n, D)) launch(std::true_type{}); else launch(std::false_type{});
     GRF_LAUNCH_CHECK("buckets_kernel");
     return GRF_OK;
 }
@@ -366,6 +380,11 @@ grf_status launch_gather(const void* Q, int64_t n, int64_t H, int32_t n_f, const
 }  // namespace grf
 
 using namespace grf;
+
+extern "C" void grf_debug_force_wide_offsets(int32_t on)
+{
+    g_force_wide_offsets.store(on != 0 ? 1 : 0, std::memory_order_relaxed);
+}
 
 extern "C" int64_t grf_bucket_record_floats(int32_t d)
 {

@@ -132,27 +132,43 @@ __device__ __forceinline__ long long xcd_contiguous_block(unsigned block, unsign
     return static_cast<long long>(x) * q + (x < rem ? x : rem) + k;
 }
 
+// Address of element `elem` of row `row` of a [rows][D] tensor whose slice starts at `base` (wave-uniform).
+// Unless WIDE, the byte offset is formed in 32 bits, which lets the load take the slice base from scalar registers
+// and one vector register of offset (one vector instruction per row instead of three 64-bit ones); the host
+// selects WIDE when a slice spans 4 GiB or more.
+template <int D, typename T, bool WIDE>
+__device__ __forceinline__ const T* row_elem_ptr(const T* __restrict__ base, uint32_t row, int elem)
+{
+    if constexpr (WIDE) {
+        return base + (static_cast<size_t>(row) * D + elem);
+    } else {
+        const uint32_t off = row * static_cast<uint32_t>(D * sizeof(T)) + static_cast<uint32_t>(elem) * static_cast<uint32_t>(sizeof(T));
+        return reinterpret_cast<const T*>(reinterpret_cast<const char*>(base) + off);
+    }
+}
+
 // The T2 = D/32 elements of row j that MFMA row/column `li` of the tiles stands for, widened to
 // fp32: element 32*t + li of the row, or, INTERLEAVED, element T2*li + t, so that a lane's
 // operands are adjacent in memory (one 8-byte load at d = 64 in fp32).
-template <int D, typename T, bool INTERLEAVED>
+template <int D, typename T, bool INTERLEAVED, bool WIDE>
 __device__ __forceinline__ void load_operand_elems(const T* __restrict__ base, uint32_t j, int li, float (&x)[D / 32])
 {
     constexpr int T2 = D / 32;
     if constexpr (INTERLEAVED) {
-        const size_t off = static_cast<size_t>(j) * D + T2 * li;
+        const T* p = row_elem_ptr<D, T, WIDE>(base, j, T2 * li);
         if constexpr (sizeof(T) == 4 && T2 == 2) {
-            const float2 v = *reinterpret_cast<const float2*>(base + off);
+            const float2 v = *reinterpret_cast<const float2*>(p);
             x[0] = v.x; x[1] = v.y;
         } else if constexpr (sizeof(T) == 2 && T2 == 2) {
-            const uint32_t v = *reinterpret_cast<const uint32_t*>(base + off);
+            const uint32_t v = *reinterpret_cast<const uint32_t*>(p);
             x[0] = __uint_as_float(v << 16); x[1] = __uint_as_float(v & 0xffff0000u);
         } else {
-            x[0] = to_float(base[off]);
+            x[0] = to_float(*p);
         }
     } else {
+        const T* p = row_elem_ptr<D, T, WIDE>(base, j, li);
 #pragma unroll
-        for (int t = 0; t < T2; ++t) x[t] = to_float(base[static_cast<size_t>(j) * D + 32 * t + li]);
+        for (int t = 0; t < T2; ++t) x[t] = to_float(p[32 * t]);
     }
 }
 
@@ -193,20 +209,19 @@ __device__ __forceinline__ ListBlock load_list_block(const int32_t* __restrict__
 // its row as stored.  The two half-waves carry the two contributors of a pair (the k index of
 // v_mfma_f32_32x32x2_f32); see load_operand_elems for which element a lane holds.
 //
-// The column list is walked in blocks of 128 entries (64 contributor pairs; most lists fit in one):
-//   - the (row, weight) of a block's entries are fetched up front (load_list_block; the first block is handed
-//     in by the caller, who can fetch it while the previous bucket is still being worked on), one entry per lane
-//     in two register pairs, and a pair's two entries (wave-uniform) are pulled out with v_readlane, so
-//     that inside the block the only memory instructions are the row loads: the load counter
-//     retires in order, and any wait on a recently issued index load would drain every row load
-//     issued before it;
-//   - a pair's rows are fetched RING pairs ahead into a ring of RING register slots, the slot
-//     that the current pair has just vacated;
-//   - row loads are unconditional (pairs past the end re-read the last entry with weight 0), since
-//     a load skipped on one control path would force a full wait where the paths join;
-//   - a scheduling barrier per pair keeps each pair's fetch work next to the previous pair's MFMAs:
-//     an MFMA holds the matrix pipe for 64 cycles, in which the fetch instructions issue for free.
-template <int D, typename TA, typename TB, bool INTERLEAVED, bool WEIGHT_ON_A, int EXTRA, int FM>
+// On gfx950 an fp32 MFMA occupies the vector ALU: vector instructions do not issue in its shadow, so each one
+// between the MFMAs is paid in matrix time.  The loop is therefore written for few vector instructions per pair:
+//   - the column list is walked in blocks of 128 entries (64 contributor pairs; most lists fit in one) whose
+//     (row, weight) are fetched up front (load_list_block; the first block is handed in by the caller, who can
+//     fetch it while the previous bucket is still being worked on), one entry per lane in two register pairs;
+//   - a lane takes its contributor's entry from there with ds_bpermute (entry 2p for the lower half-wave, 2p + 1
+//     for the upper): an LDS-crossbar instruction, issued before the pair's MFMAs and complete when they are;
+//   - the row address is one 32-bit multiply-add on a scalar base (row_elem_ptr), shared by both operands' loads
+//     when they have the same element size;
+//   - a pair's rows are fetched RING pairs ahead into a ring of RING register slots, the slot that the current
+//     pair has just vacated; row loads are unconditional (pairs past the end re-read the last entry with weight
+//     0), since a load skipped on one control path would force a full wait where the paths join.
+template <int D, typename TA, typename TB, bool INTERLEAVED, bool WEIGHT_ON_A, int EXTRA, int FM, bool WIDE>
 __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ Ab, const TB* __restrict__ Bb,
                                                          const int32_t* __restrict__ csc_row, const float* __restrict__ vals,
                                                          const float* __restrict__ escale,
@@ -218,8 +233,8 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
     constexpr bool SCALED = EXTRA == kExtraScaledSumB;
     const int32_t beg = beg_in, end = end_in;
     const int lane = lane_id();
-    const bool upper = lane >= 32;
     const int li = lane & 31;
+    const int pick = (lane >> 5) << 2;      // ds_bpermute byte address of lane 0 (lower half-wave) or lane 1 (upper)
 #pragma unroll
     for (int a = 0; a < T2; ++a) {
         zacc[a] = 0.0f;
@@ -230,20 +245,14 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
     }
     if (beg >= end) return;
 
-    // rows of the pair held in lanes (s, s + 1) of (jv, gv, ev): lower half-wave takes s, upper s + 1
-    auto row_load = [&](int32_t jv, float gv, float ev, int s, float (&aa)[T2], float (&bb)[T2], float& gg, float& ee) {
-        const int32_t j0 = __builtin_amdgcn_readlane(jv, s), j1 = __builtin_amdgcn_readlane(jv, s + 1);
-        const float g0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), s));
-        const float g1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), s + 1));
-        const uint32_t j = static_cast<uint32_t>(upper ? j1 : j0);
-        gg = upper ? g1 : g0;
-        if constexpr (SCALED) {
-            const float e0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ev), s));
-            const float e1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ev), s + 1));
-            ee = upper ? e1 : e0;
-        }
-        load_operand_elems<D, TA, INTERLEAVED>(Ab, j, li, aa);
-        load_operand_elems<D, TB, INTERLEAVED>(Bb, j, li, bb);
+    // this lane's contributor of the pair held in lanes (s, s + 1) of (jv, gv, ev), and its two operand rows
+    auto row_load = [&](int32_t jv, float gv, float ev, int first_lane, int s, float (&aa)[T2], float (&bb)[T2], float& gg, float& ee) {
+        const int addr = first_lane + 4 * s;      // s is a compile-time constant at every call: one add of a literal
+        const uint32_t j = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(addr, jv));
+        gg = __int_as_float(__builtin_amdgcn_ds_bpermute(addr, __float_as_int(gv)));
+        if constexpr (SCALED) ee = __int_as_float(__builtin_amdgcn_ds_bpermute(addr, __float_as_int(ev)));
+        load_operand_elems<D, TA, INTERLEAVED, WIDE>(Ab, j, li, aa);
+        load_operand_elems<D, TB, INTERLEAVED, WIDE>(Bb, j, li, bb);
     };
 
     for (int32_t block = beg; block < end; block += 2 * kWave) {
@@ -254,7 +263,10 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
 
         float ab[RING][T2], bb[RING][T2], gb[RING], eb_[RING];
 #pragma unroll
-        for (int u = 0; u < RING; ++u) row_load(j_a, g_a, e_a, 2 * u, ab[u], bb[u], gb[u], eb_[u]);
+        for (int u = 0; u < RING; ++u) {
+            row_load(j_a, g_a, e_a, pick, 2 * u, ab[u], bb[u], gb[u], eb_[u]);
+            if ((u & 3) == 3) __builtin_amdgcn_sched_barrier(0);      // bounds the entries in flight between crossbar and loads
+        }
         for (int q0 = 0; q0 < pairs; q0 += RING) {
             // this round fetches pairs q0 + RING .. q0 + 2 RING - 1 of the block: lanes of j_a for pairs
             // below 32, of j_b above (past pair 63 the fetch is redundant and re-reads j_b's tail)
@@ -263,7 +275,10 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
             const int32_t j_sel = second ? j_b : j_a;
             const float g_sel = second ? g_b : g_a;
             const float e_sel = second ? e_b : e_a;
-            const int lane0 = (2 * ahead) & (kWave - 1);
+            // ds_bpermute address of the round's first pair; opaque to the optimiser, which would otherwise keep
+            // sixteen loop-invariant addresses in registers and lose a wavefront of occupancy
+            int lane0 = pick + 4 * ((2 * ahead) & (kWave - 1));
+            asm volatile("" : "+v"(lane0));
 #pragma unroll
             for (int u = 0; u < RING; ++u) {
                 if (q0 + u < pairs) {
@@ -282,7 +297,7 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
                         for (int c = 0; c < T2; ++c)
                             acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_op[a], b_op[c], acc[a][c], 0, 0, 0);
                 }
-                row_load(j_sel, g_sel, e_sel, lane0 + 2 * u, ab[u], bb[u], gb[u], eb_[u]);     // into the slot just vacated
+                row_load(j_sel, g_sel, e_sel, lane0, 2 * u, ab[u], bb[u], gb[u], eb_[u]);     // into the slot just vacated
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -295,6 +310,10 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
 unsigned resident_wave_grid(const void* kernel, long long items);
 
 inline unsigned blocks_for(long long items, int per_block) { return static_cast<unsigned>((items + per_block - 1) / per_block); }
+
+// True when a [n][d] slice may span 4 GiB or more (or the test hook forces it): the bucket kernels then use
+// 64-bit row offsets (row_elem_ptr).
+bool wide_offsets(int64_t n, int32_t d);
 
 // Dispatch on (d, dtype) to the compiled instances.
 #define GRF_DISPATCH(d, dtype, CALL)                                                     \

@@ -55,8 +55,8 @@ __global__ __launch_bounds__(256) void backward_seed_kernel(const float* __restr
 
 // One wavefront per (slice, bucket l), one wavefront per workgroup.  Every global load is
 // unconditional (lanes past the end of the column list re-read its last entry with weight 0).
-template <int D, typename T, int MODE>
-__global__ __launch_bounds__(64) void backward_bucket_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+template <int D, typename T, int MODE, bool WIDE>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void backward_bucket_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
                                                               const float* __restrict__ G, const float* __restrict__ gd,
                                                               long long n, int H, int n_f,
                                                               const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
@@ -122,11 +122,11 @@ __global__ __launch_bounds__(64) void backward_bucket_kernel(const T* __restrict
     with_feature_map(fmap, [&](auto fm) {
         constexpr int FM = decltype(fm)::value;
         if constexpr (MODE == kQuerySide)
-            bucket_first_contraction<D, T, T, true, false, kExtraSumB, FM>(Vb, Kb, csc_row, vals, nullptr, beg, end, first, acc, xacc);
+            bucket_first_contraction<D, T, T, true, false, kExtraSumB, FM, WIDE>(Vb, Kb, csc_row, vals, nullptr, beg, end, first, acc, xacc);
         else if constexpr (MODE == kKeySide)
-            bucket_first_contraction<D, float, T, true, false, kExtraScaledSumB, FM>(Gb, Qb, csc_row, vals, gdb, beg, end, first, acc, xacc);
+            bucket_first_contraction<D, float, T, true, false, kExtraScaledSumB, FM, WIDE>(Gb, Qb, csc_row, vals, gdb, beg, end, first, acc, xacc);
         else
-            bucket_first_contraction<D, T, float, true, true, kExtraNone, FM>(Qb, Gb, csc_row, vals, nullptr, beg, end, first, acc, xacc);
+            bucket_first_contraction<D, T, float, true, true, kExtraNone, FM, WIDE>(Qb, Gb, csc_row, vals, nullptr, beg, end, first, acc, xacc);
     });
 
     // the extra row, complete in the lower half-wave and zero in the upper, so that one more MFMA step
@@ -369,11 +369,15 @@ grf_status launch_backward_chunk(const void* Qv, const void* Kv, const void* Vv,
 
     const float* phi_val = phi->val;
     const long long val_stride = phi->capacity;
+    const bool wide = wide_offsets(n, D);
     auto bucket_pass = [&](auto mode) {
-        hipLaunchKernelGGL((backward_bucket_kernel<D, T, decltype(mode)::value>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
-                           static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),
-                           static_cast<int>(H), static_cast<int>(n_f), col_ptr, s_row, s_val, fmap,
-                           static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), b.partial);
+        auto launch = [&](auto w) {
+            hipLaunchKernelGGL((backward_bucket_kernel<D, T, decltype(mode)::value, decltype(w)::value>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
+                               static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),
+                               static_cast<int>(H), static_cast<int>(n_f), col_ptr, s_row, s_val, fmap,
+                               static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), b.partial);
+        };
+        if (wide) launch(std::true_type{}); else launch(std::false_type{});
     };
     auto reduce_pass = [&](auto weighted, const T* src, float* dst, float* dphi_part) {
         hipLaunchKernelGGL((backward_reduce_kernel<D, T, decltype(weighted)::value>), reduce_grid, dim3(256), 0, stream,

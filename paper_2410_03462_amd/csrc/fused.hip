@@ -26,8 +26,8 @@ namespace grf {
 // entry with weight 0, so there are no branches around loads and the loads of the next stage
 // (next group of K/V rows, next tile's Q rows, the indices after that) are issued before the
 // matrix work of the current stage and waited for only afterwards.
-template <int D, typename T>
-__global__ __launch_bounds__(64) void fused_bucket_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+template <int D, typename T, bool WIDE>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fused_bucket_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
                                                            long long n, int H, int n_f,
                                                            const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
                                                            const float* __restrict__ csc_val,
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(64) void fused_bucket_kernel(const T* __restrict__ 
         floatx16 acc[T2][T2];
         float zacc[T2];
         with_feature_map(fmap, [&](auto fm) {
-            bucket_first_contraction<D, T, T, true, true, kExtraSumA, decltype(fm)::value>(Kb, Vb, csc_row, vals, nullptr, beg, end, first, acc, zacc);
+            bucket_first_contraction<D, T, T, true, true, kExtraSumA, decltype(fm)::value, WIDE>(Kb, Vb, csc_row, vals, nullptr, beg, end, first, acc, zacc);
         });
 
         // the next bucket's first list block: in flight during the second contraction
@@ -234,12 +234,16 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
 {
     const long long waves = static_cast<long long>(n_slices) * n;
     if (waves == 0) return GRF_OK;
-    hipLaunchKernelGGL((fused_bucket_kernel<D, T>), dim3(resident_wave_grid(reinterpret_cast<const void*>(&fused_bucket_kernel<D, T>), waves)), dim3(kWave), 0, stream,
-                       static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
-                       static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
-                       static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
-                       static_cast<const float*>(t.s_val), fmap, static_cast<long long>(bh_first), waves,
-                       static_cast<int32_t>(nnz), partial, pden);
+    auto launch = [&](auto wide) {
+        constexpr bool W = decltype(wide)::value;
+        hipLaunchKernelGGL((fused_bucket_kernel<D, T, W>), dim3(resident_wave_grid(reinterpret_cast<const void*>(&fused_bucket_kernel<D, T, W>), waves)), dim3(kWave), 0, stream,
+                           static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+                           static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
+                           static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
+                           static_cast<const float*>(t.s_val), fmap, static_cast<long long>(bh_first), waves,
+                           static_cast<int32_t>(nnz), partial, pden);
+    };
+    if (wide_offsets(n, D)) launch(std::true_type{}); else launch(std::false_type{});
     GRF_LAUNCH_CHECK("fused_bucket_kernel");
     hipLaunchKernelGGL((fused_reduce_kernel<D>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream,
                        static_cast<long long>(n), static_cast<const int32_t*>(phi->row_ptr),

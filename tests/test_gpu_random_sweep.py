@@ -153,3 +153,34 @@ def test_random_case(grf, oracle, index):
     host = [t.cpu().numpy() for t in got]
     host[3] = host[3][:, : phi_pos.nnz]
     check_gradients(host, abref, tol, "asymmetric ", diagonal)
+
+
+@pytest.mark.parametrize("index", [5, 11, 14, 20, 37, 58])
+def test_wide_row_offsets_give_the_same_bits(grf, oracle, index):
+    """The bucket kernels' 64-bit row addressing (taken when a slice spans 4 GiB or more) forced at small sizes:
+    the same bits as the 32-bit form for the bucket records, the fused forward and the backward pass."""
+    wl, feature_map = draw_case(index)
+    n = wl.graph.n
+    rp, col, val = oracle.sample(wl.graph, np.abs(wl.f) + 0.01, wl.p_halt, wl.n_walks, wl.walk_seed)
+    phi = grf.Phi.from_host(n, rp, col, val)
+    Q, K, V = wl.qkv()
+    Qd, Kd, Vd = (to_dev(x, wl.dtype) for x in (Q, K, V))
+    d_out = to_dev(np.random.default_rng([9, index]).standard_normal(Q.shape).astype(np.float32))
+
+    def run():
+        rec = grf.grf_form_buckets(Kd, Vd, phi, feature_map)
+        out, num, den = grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, "elu1", return_num_den=True)
+        grads = grf.grf_masked_linear_attention_backward(Qd, Kd, Vd, phi, out, den, d_out, "elu1")
+        return [t.cpu().numpy() for t in (rec, out, num, den, *grads)]
+
+    narrow = run()
+    grf.grf_debug_force_wide_offsets(True)
+    try:
+        wide = run()
+    finally:
+        grf.grf_debug_force_wide_offsets(False)
+    for a, b in zip(narrow, wide):
+        assert np.array_equal(a, b, equal_nan=True)
+    # and the fused forward is right in the first place
+    ref = oracle.masked_linear_attention(Q, K, V, rp, col, val, feature_map=2)
+    assert relerr(narrow[2], ref["num"]) <= TOL[wl.dtype]
