@@ -15,20 +15,24 @@ struct bf16_t { uint16_t bits; };
 __device__ __forceinline__ float to_float(float x) { return x; }
 __device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(static_cast<uint32_t>(x.bits) << 16); }
 
-// phi(x) for the feature-map codes of grf.h: max(x, 0) as one v_med3_f32 (median of x, 0, +inf),
-// the identity, or elu(x) + 1 (x + 1 for x > 0, exp(x) otherwise).  `fmap` is wave-uniform.
+// max(x, 0) as one integer maximum of the bit pattern with 0: floats with the sign bit clear order like
+// integers, all others (negative values, -0) are negative integers.  (A floating-point maximum costs a second
+// instruction that quiets signalling NaNs first.)
+__device__ __forceinline__ float relu(float x) { return __int_as_float(max(__float_as_int(x), 0)); }
+
+// phi(x) for the feature-map codes of grf.h: max(x, 0), the identity, or elu(x) + 1 (x + 1 for x > 0,
+// exp(x) otherwise).  `fmap` is wave-uniform.
 __device__ __forceinline__ float feature(float x, int fmap)
 {
-    const float relu = __builtin_amdgcn_fmed3f(x, 0.0f, __builtin_inff());
     const float elu1 = x > 0.0f ? x + 1.0f : __expf(x);
-    return fmap == GRF_PHI_RELU ? relu : (fmap == GRF_PHI_ELU1 ? elu1 : x);
+    return fmap == GRF_PHI_RELU ? relu(x) : (fmap == GRF_PHI_ELU1 ? elu1 : x);
 }
 
 // The same with the code known at compile time (the MFMA kernels' inner loops).
 template <int FM>
 __device__ __forceinline__ float feature_ct(float x)
 {
-    if constexpr (FM == GRF_PHI_RELU) return __builtin_amdgcn_fmed3f(x, 0.0f, __builtin_inff());
+    if constexpr (FM == GRF_PHI_RELU) return relu(x);
     else if constexpr (FM == GRF_PHI_ELU1) return x > 0.0f ? x + 1.0f : __expf(x);
     else return x;
 }
@@ -170,6 +174,21 @@ __device__ __forceinline__ void load_operand_elems(const T* __restrict__ base, u
 #pragma unroll
         for (int t = 0; t < T2; ++t) x[t] = to_float(p[32 * t]);
     }
+}
+
+// Rows [row0, row0 + rows) of a [..][D] fp32 array as a raw buffer: stores through it at byte offsets at or
+// beyond rows * D * 4 are dropped by the hardware, so a tile's stores need neither predicates nor 64-bit
+// address arithmetic (vector instructions that an fp32 MFMA kernel pays for in matrix time).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t row_window(float* __restrict__ base, long long row0, int rows, int D)
+{
+    constexpr int kRawDword = 0x00020000;      // word 3 of a gfx9 buffer descriptor: 32-bit data format, no swizzling
+    // The arguments are the same in every lane; saying so keeps the descriptor in scalar registers (otherwise each
+    // store is wrapped in a loop over the distinct descriptors of the wavefront).
+    const unsigned long long addr = reinterpret_cast<unsigned long long>(base + row0 * D);
+    const unsigned lo = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(addr));
+    const unsigned hi = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(addr >> 32));
+    float* uniform_base = reinterpret_cast<float*>((static_cast<unsigned long long>(hi) << 32) | lo);
+    return __builtin_amdgcn_make_buffer_rsrc(uniform_base, 0, __builtin_amdgcn_readfirstlane(rows * D * 4), kRawDword);
 }
 
 // What the first contraction accumulates besides the D x D tile.

@@ -14,13 +14,12 @@
 //   pass           first contraction ACC = A^T B            second contraction, per consumer i     streams out
 //   kQuerySide     A = V,        B = w phi(K), +sum B (z)    U_i = g_i ACC + gd_i z                 U_i
 //   kKeySide       A = G,        B = w phi(Q), +sum gd B (y) R_i = v_i ACC + y                      R_i
-//   kValueSide     A = w phi(Q), B = G                       X_i = (w_i phi(k_i)) ACC               X_i
+//   kValueSide     A = w phi(Q), B = G                       X_i = phi(k_i) ACC                     X_i
 //
 // (ACC is S^T, T^T and T respectively: the second contraction always runs over the row index of ACC,
 // which is the index the accumulator registers of a lane enumerate.)  A second kernel, one wavefront per
 // output row, reads the row's streamed vectors in ascending-l order: it forms dphi(q_i) = sum_l w_il U_il
-// (likewise k; plain sum for v), and on the way the per-entry terms phi(q_i).U_il and phi(k_i).R_il of
-// dPhi.  Sums have a fixed order: results are bitwise reproducible and no float atomics are used.
+// (likewise k and v), and on the way the per-entry terms phi(q_i).U_il and phi(k_i).R_il of dPhi.  Sums have a fixed order: results are bitwise reproducible and no float atomics are used.
 #include <type_traits>
 
 #include "attention_common.hpp"
@@ -87,20 +86,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
     const int32_t end = __builtin_amdgcn_readfirstlane(col_ptr[l + 1]);
     if (beg >= end) return;
 
-    // consumers of tile `tile`: row index and weight of entry tile + li (clamped, weight 0 past the end)
-    auto fetch_index = [&](int32_t tile, int32_t& row, float& g) {
-        const int32_t pos = min(tile + li, end - 1);
-        row = csc_row[pos];
-        g = tile + li < end ? vals[pos] : 0.0f;
-    };
+    // consumers of tile `tile`: row index of entry tile + li (clamped to the last entry)
+    auto fetch_index = [&](int32_t tile, int32_t& row) { row = csc_row[min(tile + li, end - 1)]; };
     // consumer li's operand elements for the accumulator rows this lane pairs with, and its coefficient of the extra row
-    auto fetch_operand = [&](long long row, float (&cc)[4][QN], float& cf) {
+    auto fetch_operand = [&](int32_t row, float (&cc)[4][QN], float& cf) {
+        const uint32_t r = static_cast<uint32_t>(row);
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            const long long off = row * D + T2 * (8 * b + 4 * half);
-            if constexpr (MODE == kQuerySide) load_run<float, QN>(Gb + off, cc[b]);
-            if constexpr (MODE == kKeySide) load_run<T, QN>(Vb + off, cc[b]);
-            if constexpr (MODE == kValueSide) load_run<T, QN>(Kb + off, cc[b]);
+            const int elem = T2 * (8 * b + 4 * half);
+            if constexpr (MODE == kQuerySide) load_run<float, QN>(row_elem_ptr<D, float, WIDE>(Gb, r, elem), cc[b]);
+            if constexpr (MODE == kKeySide) load_run<T, QN>(row_elem_ptr<D, T, WIDE>(Vb, r, elem), cc[b]);
+            if constexpr (MODE == kValueSide) load_run<T, QN>(row_elem_ptr<D, T, WIDE>(Kb, r, elem), cc[b]);
         }
         if constexpr (MODE == kQuerySide) cf = gdb[row];
     };
@@ -108,9 +104,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
     // the first two consumer tiles' indices and the first tile's operand rows go out before the first
     // contraction starts, so that they have arrived when it ends
     int32_t row_cur, row_next;
-    float w_cur, w_next;
-    fetch_index(beg, row_cur, w_cur);
-    fetch_index(beg + 32, row_next, w_next);
+    fetch_index(beg, row_cur);
+    fetch_index(beg + 32, row_next);
     float cn[4][QN];
     float cfn = 1.0f;
     fetch_operand(row_cur, cn, cfn);
@@ -138,7 +133,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
         extra[t] = half == 0 ? full : 0.0f;
     }
 
-    // ---- second contraction, 32 consumers at a time
+    // ---- second contraction, 32 consumers at a time.  The consumer's own weight Phi_hat[i, l] is left to the
+    // reduce kernel, which is bound by memory, whereas vector instructions here are paid in matrix time.
     const long long pbase = slice * static_cast<long long>(nnz);
     for (int32_t tile = beg; tile < end; tile += 32) {
         float cop[4][QN];
@@ -146,12 +142,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
         for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int e2 = 0; e2 < QN; ++e2)
-                cop[b][e2] = MODE == kValueSide ? w_cur * feature(cn[b][e2], fmap) : cn[b][e2];
+                cop[b][e2] = MODE == kValueSide ? feature(cn[b][e2], fmap) : cn[b][e2];
         const float coef = half == 0 ? cfn : 0.0f;
         // next tile's operand rows, and the indices of the tile after it
         fetch_operand(row_next, cn, cfn);
-        w_cur = w_next;
-        fetch_index(tile + 64, row_next, w_next);
+        fetch_index(tile + 64, row_next);
 
         __builtin_amdgcn_sched_barrier(0);
 
@@ -175,25 +170,27 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
                 pc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(coef, extra[c], pc[c], 0, 0, 0);
         }
 
-        // ---- stream out: register r of pc[c] is consumer 8*(r/4) + 4*half + r%4, output column T2*li + c
+        // ---- stream out: register r of pc[c] is consumer tile + 8*(r/4) + 4*half + r%4, output column T2*li + c,
+        // through a window over the tile's rows, which drops the rows past the end of the list.  One column tile
+        // after the other, kept apart: merged into 8-byte stores, the two tiles' registers (never adjacent) would
+        // have to be copied next to each other first.
+        const __amdgpu_buffer_rsrc_t window = row_window(partial, pbase + tile, min(end - tile, 32), D);
+        int lane_off = (4 * half * D + T2 * li) * 4;
+        asm volatile("" : "+v"(lane_off));      // keeps the rows' constant offsets next to the stores, in their offset fields
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int32_t ppos = tile + 8 * (r / 4) + 4 * half + (r % 4);
-            if (ppos < end) {
-                float* dst = partial + (pbase + ppos) * D + T2 * li;
-                if constexpr (T2 == 2) {
-                    *reinterpret_cast<float2*>(dst) = make_float2(pc[0][r], pc[1][r]);
-                } else {
-                    dst[0] = pc[0][r];
-                }
-            }
+        for (int c = 0; c < T2; ++c) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(pc[c][r]), window, lane_off + (8 * (r / 4) + (r % 4)) * D * 4 + 4 * c, 0, 0);
+            asm volatile("" ::: "memory");
         }
     }
 }
 
-// One wavefront per (slice, row i) over the vectors streamed out for the row's entries, in ascending-l order.
-// WEIGHTED (gradients of Q and K): dst_i = phi'(x_i) * sum_l w_il u_il, and the entry's term of dPhi,
-// phi(x_i) . u_il, goes to dphi_part[slice][e] (CSR order).  Otherwise (gradient of V): dst_i = sum_l u_il.
+// One wavefront per (slice, row i) over the vectors streamed out for the row's entries, in ascending-l order:
+// sum_l w_il u_il with w_il = Phi_hat[i, l].  WEIGHTED (gradients of Q and K): dst_i = phi'(x_i) * that sum, and the
+// entry's term of dPhi, phi(x_i) . u_il, goes to dphi_part[slice][e] (CSR order).  Otherwise (gradient of V):
+// dst_i = the sum.
 template <int D, typename T, bool WEIGHTED>
 __global__ __launch_bounds__(256) void backward_reduce_kernel(long long n, int H, int n_f, long long val_stride,
                                                               const int32_t* __restrict__ row_ptr, const float* __restrict__ phi_val,
@@ -224,8 +221,7 @@ __global__ __launch_bounds__(256) void backward_reduce_kernel(long long n, int H
     for (int32_t chunk = beg; chunk < end; chunk += kWave) {
         const int32_t e = chunk + lane;
         const int32_t pos_reg = e < end ? csr_to_csc[e] : -1;
-        float w_reg = 1.0f;
-        if constexpr (WEIGHTED) w_reg = e < end ? vals[e] : 0.0f;
+        const float w_reg = e < end ? vals[e] : 0.0f;
         const int cnt = min(kWave, end - chunk);
         // eight steps' loads are issued together; the shuffles are executed by every lane
         for (int t0 = 0; t0 < cnt; t0 += 8 * EPW) {
@@ -265,7 +261,7 @@ __global__ __launch_bounds__(256) void backward_reduce_kernel(long long n, int H
                 if ((c & (D / 8 - 1)) == 0 && t < cnt) dphi_part[slice * static_cast<long long>(nnz) + chunk + t] = dot[0];
             } else {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) acc += v[u];
+                for (int u = 0; u < 8; ++u) acc = fmaf(w[u], v[u], acc);
             }
         }
     }

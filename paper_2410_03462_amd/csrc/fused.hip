@@ -3,13 +3,15 @@
 //
 // Queries and keys use the same graph features (Eq. 6), so the rows that consume bucket l are
 // exactly the rows that contribute to it: the column list C_l of Phi_hat.  Per bucket,
-//     S_l = A^T V_l,            A  = diag(Phi_hat[C_l, l]) phi(K[C_l])      (r_l x d)
-//     P_l = Qw S_l,             Qw = diag(Phi_hat[C_l, l]) phi(Q[C_l])      (r_l x d)
-//     pden_l = Qw z_l,          z_l = A^T 1
-// and then num_i = sum_l P_l[i], den_i = sum_l pden_l[i] over the entries of row i.  Both
-// contractions run on v_mfma_f32_32x32x2_f32; P_l and pden_l are streamed out in column-list
-// order (one d-float row per entry of Phi_hat) and a second kernel sums each row's entries in
-// ascending-l order, so the result is deterministic and no float atomics are used.
+//     S_l = A^T V_l,            A = diag(Phi_hat[C_l, l]) phi(K[C_l])      (r_l x d)
+//     P_l = phi(Q[C_l]) S_l                                                 (r_l x d)
+//     pden_l = phi(Q[C_l]) z_l,  z_l = A^T 1
+// and then num_i = sum_l Phi_hat[i,l] P_l[i], den_i = sum_l Phi_hat[i,l] pden_l[i] over the entries of
+// row i.  Both contractions run on v_mfma_f32_32x32x2_f32; P_l and pden_l are streamed out in
+// column-list order (one d-float row per entry of Phi_hat) and a second kernel forms each row's
+// weighted sums in ascending-l order, so the result is deterministic and no float atomics are used.
+// (The consumer's weight is applied there because the second kernel is bound by memory, whereas every
+// vector instruction of this one is paid in matrix time.)
 //
 // Index convention (T2 = d/32): MFMA row/column x of tile t stands for feature / value column
 // T2*x + t, so that a lane's T2 operands are adjacent in memory (one 8-byte load at d = 64).
@@ -77,21 +79,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
             continue;
         }
 
-        // consumers of tile `tile`: row index and weight of entry tile + li (clamped, weight 0 past the end)
-        auto fetch_index = [&](int32_t tile, int32_t& row, float& g) {
-            const int32_t pos = min(tile + li, end - 1);
-            row = csc_row[pos];
-            g = tile + li < end ? vals[pos] : 0.0f;
-        };
-        auto fetch_q = [&](long long row, float (&qq)[4][QN]) {
+        // consumers of tile `tile`: row index of entry tile + li (clamped to the last entry)
+        auto fetch_index = [&](int32_t tile, int32_t& row) { row = csc_row[min(tile + li, end - 1)]; };
+        auto fetch_q = [&](int32_t row, float (&qq)[4][QN]) {
+            const T* p = row_elem_ptr<D, T, WIDE>(Qb, static_cast<uint32_t>(row), T2 * 4 * half);
 #pragma unroll
-            for (int b = 0; b < 4; ++b) load_run<T, QN>(Qb + row * D + T2 * (8 * b + 4 * half), qq[b]);
+            for (int b = 0; b < 4; ++b) load_run<T, QN>(p + T2 * 8 * b, qq[b]);
         };
 
         // the first two consumer tiles are entries beg .. beg + 63 of the list, which the first block holds (one
         // per lane); the first tile's rows of Q go out before the first contraction starts
         int32_t qrow_cur = __shfl(first.j_a, li, kWave), qrow_next = __shfl(first.j_a, 32 + li, kWave);
-        float gq_cur = __shfl(first.g_a, li, kWave), gq_next = __shfl(first.g_a, 32 + li, kWave);
         float qn[4][QN];
         fetch_q(qrow_cur, qn);
 
@@ -109,10 +107,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
 #pragma unroll
         for (int t = 0; t < T2; ++t) zfull[t] = zacc[t] + __shfl_xor(zacc[t], 32, kWave);
 
-        // ---- P_l = Qw S_l, 32 consumers at a time.  Accumulator register r of tile (t, c) holds
+        // ---- P_l = phi(Q_l) S_l, 32 consumers at a time.  Accumulator register r of tile (t, c) holds
         // S[T2*(8*(r/4) + 4*half + r%4) + t][T2*li + c]: fed back unchanged as the B operand, it pairs the
         // feature held by the lower half-wave (k = 0) with the one held by the upper (k = 1); the A operand
-        // takes the same two features of consumer li's weighted phi(q).
+        // takes the same two features of consumer li's phi(q).
         const long long pbase = slice * static_cast<long long>(nnz);
         for (int32_t tile = beg; tile < end; tile += 32) {
             float qv[4][QN];
@@ -120,18 +118,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
 #pragma unroll
-                    for (int e2 = 0; e2 < QN; ++e2) qv[b][e2] = gq_cur * feature_ct<decltype(fm)::value>(qn[b][e2]);
+                    for (int e2 = 0; e2 < QN; ++e2) qv[b][e2] = feature_ct<decltype(fm)::value>(qn[b][e2]);
             });
             // next tile's rows of Q, and the indices of the tile after it
             fetch_q(qrow_next, qn);
-            gq_cur = gq_next;
-            fetch_index(tile + 64, qrow_next, gq_next);
+            fetch_index(tile + 64, qrow_next);
 
             __builtin_amdgcn_sched_barrier(0);
 
-            // 4*T2 MFMAs per accumulator register r of S; in their shadow, the two terms of the partial
-            // denominator that use the same features: weighted phi(q) against z_l, which sits in the lanes in
-            // the order of the first contraction's rows.
+            // 4*T2 MFMAs per accumulator register r of S, and the two terms of the partial denominator that use
+            // the same features: phi(q) against z_l, which sits in the lanes in the order of the first
+            // contraction's rows.
             floatx16 pc[T2];
 #pragma unroll
             for (int c = 0; c < T2; ++c)
@@ -152,27 +149,33 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
             dl += __shfl_xor(dl, 32, kWave);
             if (half == 0 && tile + li < end) pden[pbase + tile + li] = dl;
 
+            // register r of pc[c] is consumer tile + 8*(r/4) + 4*half + r%4, column T2*li + c: stored through a
+            // window over the tile's rows, which drops the rows past the end of the list
+            const __amdgpu_buffer_rsrc_t window = row_window(partial, pbase + tile, min(end - tile, 32), D);
+            // opaque here so that the rows' constant offsets are formed next to the stores, where they fold into the
+            // instructions' offset fields (hoisted out of the loop they would occupy 16*T2 registers)
+            int lane_off = (4 * half * D + T2 * li) * 4;
+            asm volatile("" : "+v"(lane_off));
+            // the whole offset goes through the vector offset and the instruction's offset field, the two terms that
+            // the range check covers.  One column tile after the other, kept apart: merged into 8-byte stores, the
+            // two tiles' registers (never adjacent) would have to be copied next to each other first
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int32_t ppos = tile + 8 * (r / 4) + 4 * half + (r % 4);
-                if (ppos < end) {
-                    float* dst = partial + (pbase + ppos) * D + T2 * li;
-                    if constexpr (T2 == 2) {
-                        *reinterpret_cast<float2*>(dst) = make_float2(pc[0][r], pc[1][r]);
-                    } else {
-                        dst[0] = pc[0][r];
-                    }
-                }
+            for (int c = 0; c < T2; ++c) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(pc[c][r]), window, lane_off + (8 * (r / 4) + (r % 4)) * D * 4 + 4 * c, 0, 0);
+                asm volatile("" ::: "memory");
             }
         }
         beg = beg_next; end = end_next; first = first_next;
     }
 }
 
-// One wavefront per (slice, row i): sums the row's partial numerators and denominators in
-// ascending-l order and divides.
+// One wavefront per (slice, row i): sums the row's partial numerators and denominators, each times its
+// entry Phi_hat[i, l], in ascending-l order and divides.
 template <int D>
-__global__ __launch_bounds__(256) void fused_reduce_kernel(long long n, const int32_t* __restrict__ row_ptr,
+__global__ __launch_bounds__(256) void fused_reduce_kernel(long long n, int H, int n_f, long long val_stride,
+                                                           const int32_t* __restrict__ row_ptr, const float* __restrict__ phi_val,
                                                            const int32_t* __restrict__ csr_to_csc, int32_t nnz,
                                                            const float* __restrict__ partial, const float* __restrict__ pden,
                                                            long long bh_first, long long n_waves,
@@ -189,6 +192,7 @@ __global__ __launch_bounds__(256) void fused_reduce_kernel(long long n, const in
     const int c = lane % D;
     const float* slice_partial = partial + slice * static_cast<long long>(nnz) * D;
     const float* slice_pden = pden + slice * static_cast<long long>(nnz);
+    const float* vals = phi_val + (n_f > 1 ? (bh % H) : 0) * val_stride;
 
     const int32_t beg = max(row_ptr[i], 0);
     const int32_t end = min(row_ptr[i + 1], nnz);
@@ -196,21 +200,23 @@ __global__ __launch_bounds__(256) void fused_reduce_kernel(long long n, const in
     for (int32_t chunk = beg; chunk < end; chunk += kWave) {
         const int32_t e = chunk + lane;
         const int32_t pos_reg = e < end ? csr_to_csc[e] : -1;
+        const float w_reg = e < end ? vals[e] : 0.0f;
         const int cnt = min(kWave, end - chunk);
         // eight entries' loads are issued together; the shuffles are executed by every lane (a
         // disabled source lane would read as 0)
         for (int t0 = 0; t0 < cnt; t0 += 8 * EPW) {
-            float v[8], dv[8];
+            float v[8], dv[8], w[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int t = t0 + u * EPW + sub;
                 const int32_t pos = __shfl(pos_reg, t & (kWave - 1), kWave);
+                w[u] = __shfl(w_reg, t & (kWave - 1), kWave);
                 const bool ok = t < cnt && pos >= 0;
                 v[u] = ok ? slice_partial[static_cast<long long>(pos) * D + c] : 0.0f;
                 dv[u] = ok ? slice_pden[pos] : 0.0f;
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) { acc += v[u]; dacc += dv[u]; }
+            for (int u = 0; u < 8; ++u) { acc = fmaf(w[u], v[u], acc); dacc = fmaf(w[u], dv[u], dacc); }
         }
     }
     if constexpr (EPW == 2) {
@@ -246,7 +252,8 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
     if (wide_offsets(n, D)) launch(std::true_type{}); else launch(std::false_type{});
     GRF_LAUNCH_CHECK("fused_bucket_kernel");
     hipLaunchKernelGGL((fused_reduce_kernel<D>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream,
-                       static_cast<long long>(n), static_cast<const int32_t*>(phi->row_ptr),
+                       static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f), static_cast<long long>(phi->capacity),
+                       static_cast<const int32_t*>(phi->row_ptr), static_cast<const float*>(phi->val),
                        static_cast<const int32_t*>(t.csr_to_csc), static_cast<int32_t>(nnz),
                        static_cast<const float*>(partial), static_cast<const float*>(pden),
                        static_cast<long long>(bh_first), waves, out, num_opt, den_opt);
