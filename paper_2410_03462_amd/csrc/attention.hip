@@ -112,12 +112,13 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void bu
 {
     constexpr int T2 = D / 32;
     constexpr long long REC = static_cast<long long>(D) * D + D;
-    const long long wave = blockIdx.x;         // one wavefront per workgroup: column lists differ in length
+    const uint32_t wave = blockIdx.x;          // one wavefront per workgroup: column lists differ in length
     if (wave >= n_waves) return;
-    const long long slice = wave / n;          // slice index inside this launch
-    const long long l = wave - slice * n;
+    const uint32_t slice32 = wave / static_cast<uint32_t>(n);      // slice index inside this launch; B*H*n < 2^31, and a
+    const long long slice = slice32;                               // 32-bit division is a fraction of a 64-bit one
+    const long long l = wave - slice32 * static_cast<uint32_t>(n);
     const long long bh = bh_first + slice;
-    const long long plane = n_f > 1 ? (bh % H) : 0;
+    const long long plane = n_f > 1 ? (static_cast<uint32_t>(bh) % static_cast<uint32_t>(H)) : 0u;
     const T* Kb = K + bh * n * D;
     const T* Vb = V + bh * n * D;
     const float* vals = csc_val + plane * nnz;

@@ -248,7 +248,7 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
                                                          floatx16 (&acc)[D / 32][D / 32], float (&zacc)[D / 32])
 {
     constexpr int T2 = D / 32;
-    constexpr int RING = 16;
+    constexpr int RING = 4;
     constexpr bool SCALED = EXTRA == kExtraScaledSumB;
     const int32_t beg = beg_in, end = end_in;
     const int lane = lane_id();

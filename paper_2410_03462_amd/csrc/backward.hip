@@ -67,10 +67,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
     constexpr int QN = 4 * T2;     // operand elements a lane holds per group of four accumulator registers
     const long long wave = xcd_contiguous_block(blockIdx.x, gridDim.x);
     if (wave >= n_waves) return;
-    const long long slice = wave / n;
-    const long long l = wave - slice * n;
+    const uint32_t slice32 = static_cast<uint32_t>(wave) / static_cast<uint32_t>(n);      // B*H*n < 2^31: a 32-bit division
+    const long long slice = slice32;
+    const long long l = static_cast<uint32_t>(wave) - slice32 * static_cast<uint32_t>(n);
     const long long bh = bh_first + slice;
-    const long long plane = n_f > 1 ? (bh % H) : 0;
+    const long long plane = n_f > 1 ? (static_cast<uint32_t>(bh) % static_cast<uint32_t>(H)) : 0u;
     const T* Qb = Q + bh * n * D;
     const T* Kb = K + bh * n * D;
     const T* Vb = V + bh * n * D;

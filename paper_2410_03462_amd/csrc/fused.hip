@@ -38,44 +38,54 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
 {
     constexpr int T2 = D / 32;
     constexpr int QN = 4 * T2;     // features a lane holds per group of four accumulator registers
-    const long long stride = gridDim.x;
-    long long wave = xcd_contiguous_block(blockIdx.x, gridDim.x);
-    if (wave >= n_waves) return;
+    // B*H*n < 2^31 (checked by the host), so the bucket counter fits 32 bits.  A wavefront divides once, for its first
+    // bucket, and then steps (slice, l) along by the grid size: a 64-bit division per bucket costs about a
+    // microsecond of dependent scalar instructions, which is a tenth of a short bucket's whole work.
+    const uint32_t n32 = static_cast<uint32_t>(n);
+    const uint32_t total = static_cast<uint32_t>(n_waves);
+    const uint32_t stride = gridDim.x;
+    uint32_t wave = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x, gridDim.x));
+    if (wave >= total) return;
+    uint32_t slice = wave / n32;
+    uint32_t l = wave - slice * n32;
 
     const int lane = lane_id();
     const int half = lane >> 5;
     const int li = lane & 31;
 
-    auto bounds_of = [&](long long w, int32_t& beg, int32_t& end) {
-        const long long l = w % n;
-        beg = __builtin_amdgcn_readfirstlane(col_ptr[l]);
-        end = __builtin_amdgcn_readfirstlane(col_ptr[l + 1]);
+    auto bounds_of = [&](uint32_t bucket, int32_t& beg, int32_t& end) {
+        beg = __builtin_amdgcn_readfirstlane(col_ptr[bucket]);
+        end = __builtin_amdgcn_readfirstlane(col_ptr[bucket + 1]);
     };
-    auto values_of = [&](long long w) {
-        const long long bh = bh_first + w / n;
-        return csc_val + (n_f > 1 ? (bh % H) : 0) * static_cast<long long>(nnz);
+    auto values_of = [&](uint32_t sl) {
+        const uint32_t bh = static_cast<uint32_t>(bh_first) + sl;
+        return csc_val + (n_f > 1 ? (bh % static_cast<uint32_t>(H)) : 0u) * static_cast<long long>(nnz);
     };
 
     int32_t beg, end;
-    bounds_of(wave, beg, end);
-    ListBlock first = load_list_block<false>(csc_row, values_of(wave), nullptr, beg, end);
+    bounds_of(l, beg, end);
+    ListBlock first = load_list_block<false>(csc_row, values_of(slice), nullptr, beg, end);
 
-    for (; wave < n_waves; wave += stride) {
-        const long long slice = wave / n;
+    for (;;) {
         const long long bh = bh_first + slice;
         const T* Qb = Q + bh * n * D;
         const T* Kb = K + bh * n * D;
         const T* Vb = V + bh * n * D;
-        const float* vals = values_of(wave);
+        const float* vals = values_of(slice);
 
-        // bounds of this wavefront's next bucket: asked for now, used after the first contraction
-        const long long wave_next = wave + stride;
+        // this wavefront's next bucket; its bounds are asked for now and used after the first contraction
+        const bool more = wave + stride < total;
+        uint32_t slice_next = slice, l_next = l + stride;
+        while (l_next >= n32) { l_next -= n32; ++slice_next; }
         int32_t beg_next = 0, end_next = 0;
-        if (wave_next < n_waves) bounds_of(wave_next, beg_next, end_next);
+        if (more) bounds_of(l_next, beg_next, end_next);
+        const float* vals_next = more ? values_of(slice_next) : vals;
 
         if (beg >= end) {      // nobody visits this node: no partial rows belong to it
+            if (!more) break;
+            wave += stride; slice = slice_next; l = l_next;
             beg = beg_next; end = end_next;
-            first = load_list_block<false>(csc_row, wave_next < n_waves ? values_of(wave_next) : vals, nullptr, beg, end);
+            first = load_list_block<false>(csc_row, vals_next, nullptr, beg, end);
             continue;
         }
 
@@ -101,7 +111,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
         });
 
         // the next bucket's first list block: in flight during the second contraction
-        const ListBlock first_next = load_list_block<false>(csc_row, wave_next < n_waves ? values_of(wave_next) : vals, nullptr, beg_next, end_next);
+        const ListBlock first_next = load_list_block<false>(csc_row, vals_next, nullptr, beg_next, end_next);
 
         float zfull[T2];
 #pragma unroll
@@ -111,7 +121,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
         // S[T2*(8*(r/4) + 4*half + r%4) + t][T2*li + c]: fed back unchanged as the B operand, it pairs the
         // feature held by the lower half-wave (k = 0) with the one held by the upper (k = 1); the A operand
         // takes the same two features of consumer li's phi(q).
-        const long long pbase = slice * static_cast<long long>(nnz);
+        const long long pbase = static_cast<long long>(slice) * nnz;
         for (int32_t tile = beg; tile < end; tile += 32) {
             float qv[4][QN];
             with_feature_map(fmap, [&](auto fm) {
@@ -167,6 +177,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
                 asm volatile("" ::: "memory");
             }
         }
+        if (!more) break;
+        wave += stride; slice = slice_next; l = l_next;
         beg = beg_next; end = end_next; first = first_next;
     }
 }
