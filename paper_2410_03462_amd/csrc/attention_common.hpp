@@ -274,8 +274,7 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
         load_operand_elems<D, TB, INTERLEAVED, WIDE>(Bb, j, li, bb);
     };
 
-    for (int32_t block = beg; block < end; block += 2 * kWave) {
-        const ListBlock lb = block == beg ? first : load_list_block<SCALED>(csc_row, vals, escale, block, end);
+    auto run_block = [&](const ListBlock& lb, int32_t block) {
         const int32_t j_a = lb.j_a, j_b = lb.j_b;
         const float g_a = lb.g_a, g_b = lb.g_b, e_a = lb.e_a, e_b = lb.e_b;
         const int pairs = min((end - block + 1) >> 1, kWave);      // pairs of this block
@@ -286,7 +285,8 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
             row_load(j_a, g_a, e_a, pick, 2 * u, ab[u], bb[u], gb[u], eb_[u]);
             if ((u & 3) == 3) __builtin_amdgcn_sched_barrier(0);      // bounds the entries in flight between crossbar and loads
         }
-        for (int q0 = 0; q0 < pairs; q0 += RING) {
+#pragma nounroll
+        for (int q0 = 0; q0 < pairs; q0 += RING) {      // kept a loop: unrolled over its at most 64 / RING rounds, the steps' waits degrade
             // this round fetches pairs q0 + RING .. q0 + 2 RING - 1 of the block: lanes of j_a for pairs
             // below 32, of j_b above (past pair 63 the fetch is redundant and re-reads j_b's tail)
             const int ahead = q0 + RING;
@@ -320,7 +320,14 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-    }
+    };
+    // The first block stands apart from the loop over the others: at a loop head the compiler's load-counter
+    // bookkeeping has to cover the back edge, where a list block has just been requested, and would wait for every
+    // outstanding load and store there, the caller's prefetches for its second stage and (in a kernel that walks
+    // over buckets) the previous bucket's stores included.
+    run_block(first, beg);
+    for (int32_t block = beg + 2 * kWave; block < end; block += 2 * kWave)
+        run_block(load_list_block<SCALED>(csc_row, vals, escale, block, end), block);
 }
 
 // Number of one-wavefront workgroups that are resident at once for `kernel` on the current device (compute

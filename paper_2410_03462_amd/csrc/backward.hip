@@ -61,15 +61,28 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
                                                               const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
                                                               const float* __restrict__ csc_val,
                                                               int fmap, long long bh_first, long long n_waves, int32_t nnz,
-                                                              float* __restrict__ partial)
+                                                              int spread_xcds, float* __restrict__ partial)
 {
     constexpr int T2 = D / 32;
     constexpr int QN = 4 * T2;     // operand elements a lane holds per group of four accumulator registers
-    const long long wave = xcd_contiguous_block(blockIdx.x, gridDim.x);
-    if (wave >= n_waves) return;
-    const uint32_t slice32 = static_cast<uint32_t>(wave) / static_cast<uint32_t>(n);      // B*H*n < 2^31: a 32-bit division
+    // Workgroups go to the eight XCDs round-robin by id and start in id order.  spread_xcds: each XCD takes one
+    // contiguous eighth of all buckets, so the XCDs work in different slices (right when eight slices' tensors fit
+    // the Infinity Cache with room to spare: their reads then spread over the memory side).  Otherwise the buckets
+    // of one slice after the other, each XCD a contiguous eighth of the slice: one slice's tensors hot at a time.
+    // B*H*n < 2^31, so 32-bit divisions do.
+    if (blockIdx.x >= n_waves) return;
+    const uint32_t n32 = static_cast<uint32_t>(n);
+    uint32_t slice32, l32;
+    if (spread_xcds) {
+        const uint32_t wave = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x, gridDim.x));
+        slice32 = wave / n32;
+        l32 = wave - slice32 * n32;
+    } else {
+        slice32 = blockIdx.x / n32;
+        l32 = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x - slice32 * n32, n32));
+    }
     const long long slice = slice32;
-    const long long l = static_cast<uint32_t>(wave) - slice32 * static_cast<uint32_t>(n);
+    const long long l = l32;
     const long long bh = bh_first + slice;
     const long long plane = n_f > 1 ? (static_cast<uint32_t>(bh) % static_cast<uint32_t>(H)) : 0u;
     const T* Qb = Q + bh * n * D;
@@ -367,12 +380,14 @@ grf_status launch_backward_chunk(const void* Qv, const void* Kv, const void* Vv,
     const float* phi_val = phi->val;
     const long long val_stride = phi->capacity;
     const bool wide = wide_offsets(n, D);
+    // eight slices' Q, K, V and G within a quarter of the 256 MB Infinity Cache: see the kernel
+    const int spread = 8ll * n * D * (3 * static_cast<long long>(sizeof(T)) + 4) <= (64ll << 20) ? 1 : 0;
     auto bucket_pass = [&](auto mode) {
         auto launch = [&](auto w) {
             hipLaunchKernelGGL((backward_bucket_kernel<D, T, decltype(mode)::value, decltype(w)::value>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
                                static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),
                                static_cast<int>(H), static_cast<int>(n_f), col_ptr, s_row, s_val, fmap,
-                               static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), b.partial);
+                               static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), spread, b.partial);
         };
         if (wide) launch(std::true_type{}); else launch(std::false_type{});
     };

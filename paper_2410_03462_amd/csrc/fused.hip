@@ -34,58 +34,90 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
                                                            const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
                                                            const float* __restrict__ csc_val,
                                                            int fmap, long long bh_first, long long n_waves, int32_t nnz,
-                                                           float* __restrict__ partial, float* __restrict__ pden)
+                                                           int spread_xcds, float* __restrict__ partial, float* __restrict__ pden)
 {
     constexpr int T2 = D / 32;
     constexpr int QN = 4 * T2;     // features a lane holds per group of four accumulator registers
     // B*H*n < 2^31 (checked by the host), so the bucket counter fits 32 bits.  A wavefront divides once, for its first
     // bucket, and then steps (slice, l) along by the grid size: a 64-bit division per bucket costs about a
     // microsecond of dependent scalar instructions, which is a tenth of a short bucket's whole work.
+    struct Position { uint32_t wave, slice, l; };
     const uint32_t n32 = static_cast<uint32_t>(n);
-    const uint32_t total = static_cast<uint32_t>(n_waves);
-    const uint32_t stride = gridDim.x;
-    uint32_t wave = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x, gridDim.x));
-    if (wave >= total) return;
-    uint32_t slice = wave / n32;
-    uint32_t l = wave - slice * n32;
+    // Workgroups go to the eight XCDs round-robin by id.  Two ways of sharing out the buckets, chosen by the host:
+    //   spread_xcds   each XCD takes one contiguous eighth of all buckets and its resident wavefronts stride through
+    //                 it, so the XCDs work in different slices: their row reads do not all land on the same lines of
+    //                 the memory side.  Right when eight slices' Q, K, V fit the Infinity Cache with room to spare.
+    //   otherwise     the grid strides through all buckets together, each XCD holding a contiguous run of the buckets
+    //                 in flight: one slice's Q, K, V are hot at a time.
+    const uint32_t all = static_cast<uint32_t>(n_waves);
+    uint32_t total = all, stride = gridDim.x;
+    Position cur;
+    if (spread_xcds) {
+        const uint32_t parts = min(8u, gridDim.x);      // XCDs that receive workgroups of this grid
+        const uint32_t xcd = blockIdx.x % parts;
+        const uint32_t share = all / parts, extra = all % parts;
+        const uint32_t first_bucket = xcd * share + min(xcd, extra);
+        total = first_bucket + share + (xcd < extra ? 1u : 0u);      // end of this XCD's range
+        stride = (gridDim.x - xcd + parts - 1) / parts;               // workgroups of this grid on this XCD
+        cur.wave = first_bucket + blockIdx.x / parts;
+    } else {
+        cur.wave = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x, gridDim.x));
+    }
+    if (cur.wave >= total) return;
+    cur.slice = cur.wave / n32;
+    cur.l = cur.wave - cur.slice * n32;
+    auto after = [&](Position p) {
+        p.wave += stride;
+        p.l += stride;
+        while (p.l >= n32) { p.l -= n32; ++p.slice; }
+        return p;
+    };
 
     const int lane = lane_id();
     const int half = lane >> 5;
     const int li = lane & 31;
 
-    auto bounds_of = [&](uint32_t bucket, int32_t& beg, int32_t& end) {
-        beg = __builtin_amdgcn_readfirstlane(col_ptr[bucket]);
-        end = __builtin_amdgcn_readfirstlane(col_ptr[bucket + 1]);
+    // bounds of a bucket's column list; an empty list past the wavefront's last bucket.  The index is the same in
+    // every lane, so these are scalar loads.
+    auto bounds_of = [&](const Position& p, int32_t& beg, int32_t& end) {
+        beg = 0; end = 0;
+        if (p.wave < total) { beg = col_ptr[p.l]; end = col_ptr[p.l + 1]; }
     };
     auto values_of = [&](uint32_t sl) {
         const uint32_t bh = static_cast<uint32_t>(bh_first) + sl;
         return csc_val + (n_f > 1 ? (bh % static_cast<uint32_t>(H)) : 0u) * static_cast<long long>(nnz);
     };
 
-    int32_t beg, end;
-    bounds_of(l, beg, end);
-    ListBlock first = load_list_block<false>(csc_row, values_of(slice), nullptr, beg, end);
+    // Three buckets are in flight per wavefront: the one being worked on, the next one, whose first list block is
+    // requested before the current bucket's own loads, and the one after, whose bounds are requested with it.  What
+    // was requested is taken into registers right after the first contraction, where the in-order load counter has
+    // long passed it: left until the next bucket starts, it would be waited for behind a run of stores whose length
+    // the compiler cannot know, that is, with a wait for every outstanding store.
+    Position nxt = after(cur);
+    int32_t beg, end, beg1, end1;
+    bounds_of(cur, beg, end);
+    bounds_of(nxt, beg1, end1);
+    ListBlock first = load_list_block<false>(csc_row, values_of(cur.slice), nullptr, beg, end);
 
     for (;;) {
+        const uint32_t slice = cur.slice;
         const long long bh = bh_first + slice;
         const T* Qb = Q + bh * n * D;
         const T* Kb = K + bh * n * D;
         const T* Vb = V + bh * n * D;
         const float* vals = values_of(slice);
 
-        // this wavefront's next bucket; its bounds are asked for now and used after the first contraction
-        const bool more = wave + stride < total;
-        uint32_t slice_next = slice, l_next = l + stride;
-        while (l_next >= n32) { l_next -= n32; ++slice_next; }
-        int32_t beg_next = 0, end_next = 0;
-        if (more) bounds_of(l_next, beg_next, end_next);
-        const float* vals_next = more ? values_of(slice_next) : vals;
+        const Position nn = after(nxt);
+        int32_t beg2, end2;
+        bounds_of(nn, beg2, end2);
+        ListBlock first_next = load_list_block<false>(csc_row, values_of(nxt.slice), nullptr, beg1, end1);
 
         if (beg >= end) {      // nobody visits this node: no partial rows belong to it
-            if (!more) break;
-            wave += stride; slice = slice_next; l = l_next;
-            beg = beg_next; end = end_next;
-            first = load_list_block<false>(csc_row, vals_next, nullptr, beg, end);
+            if (nxt.wave >= total) break;
+            asm volatile("" : "+v"(first_next.j_a), "+v"(first_next.j_b), "+v"(first_next.g_a), "+v"(first_next.g_b));
+            cur = nxt; nxt = nn;
+            beg = beg1; end = end1; beg1 = beg2; end1 = end2;
+            first = first_next;
             continue;
         }
 
@@ -110,8 +142,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
             bucket_first_contraction<D, T, T, true, true, kExtraSumA, decltype(fm)::value, WIDE>(Kb, Vb, csc_row, vals, nullptr, beg, end, first, acc, zacc);
         });
 
-        // the next bucket's first list block: in flight during the second contraction
-        const ListBlock first_next = load_list_block<false>(csc_row, vals_next, nullptr, beg_next, end_next);
+        // the next bucket's first list block and the bounds after it have arrived: into registers now (see above)
+        asm volatile("" : "+v"(first_next.j_a), "+v"(first_next.j_b), "+v"(first_next.g_a), "+v"(first_next.g_b));
+        beg2 = __builtin_amdgcn_readfirstlane(beg2);
+        end2 = __builtin_amdgcn_readfirstlane(end2);
 
         float zfull[T2];
 #pragma unroll
@@ -177,9 +211,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
                 asm volatile("" ::: "memory");
             }
         }
-        if (!more) break;
-        wave += stride; slice = slice_next; l = l_next;
-        beg = beg_next; end = end_next; first = first_next;
+        if (nxt.wave >= total) break;
+        cur = nxt; nxt = nn;
+        beg = beg1; end = end1; beg1 = beg2; end1 = end2;
+        first = first_next;
     }
 }
 
@@ -252,6 +287,8 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
 {
     const long long waves = static_cast<long long>(n_slices) * n;
     if (waves == 0) return GRF_OK;
+    // eight slices' Q, K, V within a quarter of the 256 MB Infinity Cache: see the kernel
+    const int spread = 8ll * 3 * n * D * static_cast<long long>(sizeof(T)) <= (64ll << 20) ? 1 : 0;
     auto launch = [&](auto wide) {
         constexpr bool W = decltype(wide)::value;
         hipLaunchKernelGGL((fused_bucket_kernel<D, T, W>), dim3(resident_wave_grid(reinterpret_cast<const void*>(&fused_bucket_kernel<D, T, W>), waves)), dim3(kWave), 0, stream,
@@ -259,7 +296,7 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
                            static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
                            static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
                            static_cast<const float*>(t.s_val), fmap, static_cast<long long>(bh_first), waves,
-                           static_cast<int32_t>(nnz), partial, pden);
+                           static_cast<int32_t>(nnz), spread, partial, pden);
     };
     if (wide_offsets(n, D)) launch(std::true_type{}); else launch(std::false_type{});
     GRF_LAUNCH_CHECK("fused_bucket_kernel");
