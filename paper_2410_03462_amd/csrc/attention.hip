@@ -162,13 +162,19 @@ __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ Q, lo
                                                      const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
                                                      const float* __restrict__ phi_val, int fmap,
                                                      const float* __restrict__ buckets, long long bh_first, long long n_waves,
-                                                     int32_t nnz, float* __restrict__ out, float* __restrict__ num_opt, float* __restrict__ den_opt)
+                                                     int32_t nnz, int spread_xcds,
+                                                     float* __restrict__ out, float* __restrict__ num_opt, float* __restrict__ den_opt)
 {
     constexpr int LPR = D / 4;            // lanes per record row
     constexpr int RPL = kWave / LPR;      // record rows per 1 KB load
     constexpr int NL = D / RPL;           // loads per record
     constexpr long long REC = static_cast<long long>(D) * D + D;
-    const long long wave = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    // Workgroups go to the eight XCDs round-robin by id.  spread_xcds: each XCD takes a contiguous eighth of all
+    // (slice, row) pairs, so that a slice's records pass through one L2 instead of all eight (right when eight
+    // slices' records fit the Infinity Cache; with larger slices the wider footprint in flight costs more in address
+    // translation than the L2 saves).
+    const long long block = spread_xcds ? xcd_contiguous_block(blockIdx.x, gridDim.x) : static_cast<long long>(blockIdx.x);
+    const long long wave = block * (blockDim.x / kWave) + (threadIdx.x / kWave);
     if (wave >= n_waves) return;
     const long long slice = wave / n;
     const long long i = wave - slice * n;
@@ -368,11 +374,12 @@ grf_status launch_gather(const void* Q, int64_t n, int64_t H, int32_t n_f, const
 {
     const long long waves = static_cast<long long>(n_slices) * n;
     if (waves == 0) return GRF_OK;
+    const int spread = 8ll * n * (D * D + D) * 4 <= (256ll << 20) ? 1 : 0;      // see the kernel
     hipLaunchKernelGGL((gather_kernel<D, T>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream,
                        static_cast<const T*>(Q), static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
                        static_cast<long long>(phi->capacity), static_cast<const int32_t*>(phi->row_ptr),
                        static_cast<const int32_t*>(phi->col), static_cast<const float*>(phi->val), fmap, buckets,
-                       static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), out, num_opt, den_opt);
+                       static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), spread, out, num_opt, den_opt);
     GRF_LAUNCH_CHECK("gather_kernel");
     return GRF_OK;
 }
