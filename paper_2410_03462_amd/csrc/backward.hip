@@ -286,22 +286,35 @@ __global__ __launch_bounds__(256) void backward_reduce_kernel(long long n, int H
     }
 }
 
-// dphi_val[h][e] (+)= sum over the slices of this chunk that use plane h of the two per-entry terms.
+// dphi_val[h][e] (+)= sum over the slices of this chunk that use plane h of the two per-entry terms.  A workgroup
+// covers 32 consecutive entries; its 8 groups of 32 threads take the slices s = g, g + 8, ... in order and the groups'
+// sums are added in group order, so the result has a fixed summation order for a given chunking.
 __global__ __launch_bounds__(256) void dphi_accumulate_kernel(long long nnz, int n_f, int H, long long bh_first, long long n_slices,
                                                               const float* __restrict__ d_query, const float* __restrict__ d_key,
                                                               long long val_stride, int first_chunk, float* __restrict__ dphi_val)
 {
-    const long long e = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    constexpr int kEntries = 32, kGroups = 8;
+    __shared__ float part[kGroups][kEntries];
+    const int lane = threadIdx.x % kEntries, group = threadIdx.x / kEntries;
+    const long long e = static_cast<long long>(blockIdx.x) * kEntries + lane;
     const int h = blockIdx.y;
-    if (e >= nnz) return;
-    float acc = first_chunk ? 0.0f : dphi_val[h * val_stride + e];
-    for (long long s = 0; s < n_slices; ++s) {
-        const long long bh = bh_first + s;
-        if (n_f > 1 && bh % H != h) continue;
-        acc += d_query[s * nnz + e];
-        if (d_key != nullptr) acc += d_key[s * nnz + e];
+    float acc = 0.0f;
+    if (e < nnz) {
+        for (long long s = group; s < n_slices; s += kGroups) {
+            const long long bh = bh_first + s;
+            if (n_f > 1 && bh % H != h) continue;
+            acc += d_query[s * nnz + e];
+            if (d_key != nullptr) acc += d_key[s * nnz + e];
+        }
     }
-    dphi_val[h * val_stride + e] = acc;
+    part[group][lane] = acc;
+    __syncthreads();
+    if (group == 0 && e < nnz) {
+        float total = first_chunk ? 0.0f : dphi_val[h * val_stride + e];
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) total += part[g][lane];
+        dphi_val[h * val_stride + e] = total;
+    }
 }
 
 grf_status launch_backward_seed(int32_t d, const float* out, const float* den, const float* d_out, long long first_row,
@@ -322,7 +335,7 @@ grf_status launch_dphi_accumulate(int64_t nnz, int32_t n_f, int64_t H, int64_t b
                                   hipStream_t stream)
 {
     if (dphi_val == nullptr || nnz <= 0) return GRF_OK;
-    hipLaunchKernelGGL(dphi_accumulate_kernel, dim3(blocks_for(nnz, 256), static_cast<unsigned>(n_f)), dim3(256), 0, stream,
+    hipLaunchKernelGGL(dphi_accumulate_kernel, dim3(blocks_for(nnz, 32), static_cast<unsigned>(n_f)), dim3(256), 0, stream,
                        static_cast<long long>(nnz), static_cast<int>(n_f), static_cast<int>(H), static_cast<long long>(bh_first),
                        static_cast<long long>(n_slices), term_a, term_b, static_cast<long long>(val_stride), bh_first == 0 ? 1 : 0,
                        dphi_val);
