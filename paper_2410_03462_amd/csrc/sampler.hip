@@ -290,6 +290,72 @@ __global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ data, 
     }
 }
 
+// The same for inputs of at most 1024 * PER elements, which one workgroup holds in registers: every thread requests its
+// PER consecutive elements at once (one memory round trip for the whole input instead of one per tile), scans them,
+// and the threads' totals are scanned across the wavefront and the workgroup.
+template <int PER>
+__global__ __launch_bounds__(1024) void scan_resident_kernel(int32_t* __restrict__ data, long long n, long long* __restrict__ total64)
+{
+    __shared__ long long wave_total[16];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+    const bool aligned = (reinterpret_cast<uintptr_t>(data) & 15u) == 0;
+    const long long base = static_cast<long long>(tid) * PER;
+    int32_t v[PER];
+#pragma unroll
+    for (int k = 0; k < PER; k += 4) {
+        const long long idx = base + k;
+        if (aligned && idx + 3 < n) {
+            const int4 q = *reinterpret_cast<const int4*>(data + idx);
+            v[k] = q.x; v[k + 1] = q.y; v[k + 2] = q.z; v[k + 3] = q.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[k + j] = (idx + j < n) ? data[idx + j] : 0;
+        }
+    }
+    long long local = 0;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) local += v[k];
+    long long incl = local;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const long long up = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += up;
+    }
+    if (lane == kWave - 1) wave_total[wave] = incl;
+    __syncthreads();
+    long long before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        const long long t = wave_total[w];
+        if (w < wave) before += t;
+        total += t;
+    }
+    long long run = before + incl - local;
+#pragma unroll
+    for (int k = 0; k < PER; k += 4) {
+        const long long idx = base + k;
+        int32_t o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            o[j] = run > 2147483647ll ? 2147483647 : static_cast<int32_t>(run);
+            run += v[k + j];
+        }
+        if (aligned && idx + 3 < n) {
+            *reinterpret_cast<int4*>(data + idx) = make_int4(o[0], o[1], o[2], o[3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (idx + j < n) data[idx + j] = o[j];
+        }
+    }
+    if (tid == 0) {
+        data[n] = total > 2147483647ll ? 2147483647 : static_cast<int32_t>(total);
+        if (total64 != nullptr) *total64 = total;
+    }
+}
+
 __global__ __launch_bounds__(256) void fill_kernel(int32_t* __restrict__ data, long long n, int32_t value)
 {
     const long long i = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -298,7 +364,13 @@ __global__ __launch_bounds__(256) void fill_kernel(int32_t* __restrict__ data, l
 
 grf_status exclusive_scan_inplace(int32_t* counts, int64_t n, long long* total64, hipStream_t stream)
 {
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, counts, static_cast<long long>(n), total64);
+    const long long count = static_cast<long long>(n);
+    if (count <= 1024 * 16)
+        hipLaunchKernelGGL(scan_resident_kernel<16>, dim3(1), dim3(1024), 0, stream, counts, count, total64);
+    else if (count <= 1024 * 32)
+        hipLaunchKernelGGL(scan_resident_kernel<32>, dim3(1), dim3(1024), 0, stream, counts, count, total64);
+    else
+        hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, counts, count, total64);
     GRF_LAUNCH_CHECK("scan_kernel");
     return GRF_OK;
 }
