@@ -358,3 +358,35 @@ def test_attention_calls_replay_from_a_hip_graph(grf, oracle):
         torch.cuda.synchronize()
         for a, b in zip(replayed, list(eager) + [out_g, out_a]):
             assert torch.equal(torch.nan_to_num(a), torch.nan_to_num(b)), trial
+
+
+def test_vit_grid_full_size_backward(grf, oracle):
+    """The image-shaped workload as benchmarked (256 slices of 1024 nodes; at this size the bucket kernels hand each XCD
+    its own share of the slices): dQ, dK, dV of sampled slices against the checker, with a positive modulation and
+    phi = elu + 1 so that no denominator vanishes; dPhi_hat, a sum over all slices, on the first two batch items."""
+    import torch
+    wl = synth.workload("vit_grid")
+    n = wl.graph.n
+    f_pos = np.abs(wl.f) + 0.01
+    rp, col, val = oracle.sample(wl.graph, f_pos, wl.p_halt, wl.n_walks, wl.walk_seed)
+    phi = grf.Phi.from_host(n, rp, col, val)
+    Q, K, V = wl.qkv()
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    out, _, den = grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, "elu1", return_num_den=True)
+    d_out = np.random.default_rng(41).standard_normal(Q.shape).astype(np.float32)
+    dQ, dK, dV, _ = grf.grf_masked_linear_attention_backward(Qd, Kd, Vd, phi, out, den, to_dev(d_out), "elu1")
+    out_h, den_h = out.cpu().numpy(), den.cpu().numpy()
+    assert np.isfinite(out_h).all() and (den_h > 0).all()
+    dQ, dK, dV = dQ.cpu().numpy(), dK.cpu().numpy(), dV.cpu().numpy()
+    for b, h in ((0, 0), (17, 3), (31, 7)):
+        sl = (slice(b, b + 1), slice(h, h + 1))
+        ref = oracle.masked_linear_attention_backward(Q[sl], K[sl], V[sl], rp, col, val, out_h[sl], den_h[sl], d_out[sl], 2)
+        for name, x, r in zip(("dQ", "dK", "dV"), (dQ[sl], dK[sl], dV[sl]), ref):
+            assert relerr(x, r) <= TOL_F32, (name, b, h, relerr(x, r))
+    sub = slice(0, 2)
+    got = grf.grf_masked_linear_attention_backward(Qd[sub].contiguous(), Kd[sub].contiguous(), Vd[sub].contiguous(), phi,
+                                                   out[sub].contiguous(), den[sub].contiguous(), to_dev(d_out[sub]), "elu1")
+    ref = oracle.masked_linear_attention_backward(Q[sub], K[sub], V[sub], rp, col, val, out_h[sub], den_h[sub], d_out[sub], 2)
+    assert relerr(got[3].cpu().numpy()[:, : phi.nnz], ref[3]) <= TOL_F32
+    assert relerr(got[0].cpu().numpy(), dQ[sub]) <= 1e-6        # the same slices, computed in a different launch
+    torch.cuda.empty_cache()

@@ -490,6 +490,57 @@ def test_fused_headline_workload_full_size(grf, oracle):
     torch.cuda.empty_cache()
 
 
+def test_fused_cloud_8k_full_size(grf, oracle):
+    """64 slices of 8192 nodes: the size range where the bucket kernels hand each XCD its own share of the slices."""
+    import torch
+    wl = synth.workload("cloud_8k")
+    rp0, col0, val0 = _oracle_phi(oracle, wl)
+    phi = grf.Phi.from_host(wl.graph.n, rp0, col0, val0)
+    Q, K, V = wl.qkv()
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    out, num, den = grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, return_num_den=True)
+    num_h, den_h = num.cpu().numpy(), den.cpu().numpy()
+    rows = np.random.default_rng(3).choice(wl.graph.n, size=12, replace=False)
+    for b, h in ((0, 0), (2, 7), (5, 3), (7, 7)):
+        num_scale = np.abs(num_h[b, h]).max(); den_scale = np.abs(den_h[b, h]).max()
+        for i in rows:
+            n_i, d_i, _ = oracle.row_direct(int(i), Q[b, h], K[b, h], V[b, h], rp0, col0, val0[0])
+            assert np.abs(num_h[b, h, i] - n_i).max() <= TOL_F32 * num_scale
+            assert abs(den_h[b, h, i] - d_i) <= TOL_F32 * den_scale
+    out2, num2, den2 = grf.grf_masked_linear_attention(Qd, Kd, Vd, phi, return_num_den=True)
+    assert relerr(num_h, num2.cpu().numpy()) <= TOL_F32
+    assert relerr(den_h, den2.cpu().numpy()) <= TOL_F32
+    del out, num, den, out2, num2, den2
+    torch.cuda.empty_cache()
+
+
+def test_vit_grid_full_size_all_forward_variants(grf, oracle):
+    """The image-shaped workload as benchmarked (256 slices of 1024 nodes): whole slices against the checker for the
+    bucket + gather pair (whose gather hands each XCD a contiguous share of the rows at this size), the fused and
+    the asymmetric call; every other slice through the agreement of the first two."""
+    import torch
+    wl = synth.workload("vit_grid")
+    rp0, col0, val0 = _oracle_phi(oracle, wl)
+    phi = grf.Phi.from_host(wl.graph.n, rp0, col0, val0)
+    Q, K, V = wl.qkv()
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    _, num, den = grf.grf_masked_linear_attention(Qd, Kd, Vd, phi, return_num_den=True)
+    _, fnum, fden = grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, return_num_den=True)
+    _, anum, aden = grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi, return_num_den=True)
+    num, den, fnum, fden, anum, aden = (t.cpu().numpy() for t in (num, den, fnum, fden, anum, aden))
+    assert relerr(fnum, num) <= TOL_F32 and relerr(fden, den) <= TOL_F32
+    for b, h in ((0, 0), (13, 5), (31, 7)):
+        sl = (slice(b, b + 1), slice(h, h + 1))
+        ref = oracle.masked_linear_attention(Q[sl], K[sl], V[sl], rp0, col0, val0)
+        assert relerr(num[sl], ref["num"]) <= TOL_F32
+        assert relerr(den[sl], ref["den"]) <= TOL_F32
+        assert relerr(fnum[sl], ref["num"]) <= TOL_F32
+        aref = oracle.asymmetric_attention_walks(wl.graph, wl.f[0], wl.p_halt, wl.n_walks, wl.walk_seed, Q[sl], K[sl], V[sl])
+        assert relerr(anum[sl], aref["num"]) <= TOL_F32
+        assert relerr(aden[sl], aref["den"]) <= TOL_F32
+    torch.cuda.empty_cache()
+
+
 # --------------------------------------------------------------------------- asymmetric GRFs (App. D, Alg. 2)
 
 @pytest.mark.parametrize("name", list(SMALL))
