@@ -6,6 +6,8 @@
 // after an exclusive scan, to write them at their final place, so no worst-case staging buffer
 // exists in HBM.  Walk decisions are integer-only (Philox words, a threshold compare and a
 // multiply-high), hence trajectories and the sparsity pattern do not depend on floating point.
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace grf {
@@ -105,7 +107,10 @@ constexpr int kDepositBytesGrad = 16;
 // dphi ([n_f][val_stride]) holds dL/dPhi_hat per stored entry.
 enum : int { kCount = 0, kFill = 1, kGrad = 2 };
 
-template <int MODE>
+// A wavefront serves 64 / W start nodes, W lanes each (W = the smallest of 8, 16, 32, 64 that covers n_walks, so
+// that few lanes idle: the kernel is bound by the latency of the hops' dependent loads, and a wavefront's hops
+// cost the same however many of its lanes walk).  `sub` is the node's slot in the wavefront, `sl` the lane in it.
+template <int MODE, int W>
 __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int n_walks, int f_len, int n_f,
                                                   const float* __restrict__ f, int cap,
                                                   int32_t* __restrict__ row_ptr, int32_t* __restrict__ col_out,
@@ -113,22 +118,36 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
                                                   const float* __restrict__ dphi, float* __restrict__ df_part)
 {
     constexpr bool FILL = MODE == kFill;
+    constexpr int P = kWave / W;
+    constexpr int kBytes = MODE == kGrad ? kDepositBytesGrad : kDepositBytes;
+    const int lane = threadIdx.x;
+    const int sub = lane / W;
+    const int sl = lane % W;
+    // this node's share of a wave-wide ballot, and the number of its set bits below this lane
+    auto share = [&](unsigned long long mask) -> unsigned long long {
+        if constexpr (W == kWave) return mask;
+        else return (mask >> (W * sub)) & ((1ull << W) - 1ull);
+    };
+    auto below = [&](unsigned long long mine) { return __popcll(mine & ((1ull << sl) - 1ull)); };
+
     extern __shared__ __align__(16) unsigned char lds[];
-    int32_t* dcol = reinterpret_cast<int32_t*>(lds);
+    unsigned char* region = lds + static_cast<size_t>(sub) * cap * kBytes;
+    int32_t* dcol = reinterpret_cast<int32_t*>(region);
     float* dload = reinterpret_cast<float*>(dcol + cap);
     uint16_t* dhop = reinterpret_cast<uint16_t*>(dload + cap);
     uint16_t* perm = dhop + cap;
     int32_t* dent = reinterpret_cast<int32_t*>(perm + cap);      // gradient mode only; byte offset 12 cap: 4-byte aligned
 
-    const uint32_t node = blockIdx.x;
-    const int lane = threadIdx.x;
+    const long long node_ll = static_cast<long long>(blockIdx.x) * P + sub;
+    const bool has_node = node_ll < g.n;
+    const uint32_t node = static_cast<uint32_t>(has_node ? node_ll : 0);
 
     // The n_walks zero-hop prefixes all deposit load 1 at the start node: one merged deposit.
-    if (lane == 0) { dcol[0] = static_cast<int32_t>(node); dload[0] = static_cast<float>(n_walks); dhop[0] = 0; }
-    int base = 1;
-    for (int first = 0; first < n_walks; first += kWave) {
-        const uint32_t walk = static_cast<uint32_t>(first + lane);
-        bool alive = static_cast<int>(walk) < n_walks;
+    if (sl == 0 && has_node) { dcol[0] = static_cast<int32_t>(node); dload[0] = static_cast<float>(n_walks); dhop[0] = 0; }
+    int base = has_node ? 1 : 0;
+    for (int first = 0; first < n_walks; first += W) {
+        const uint32_t walk = static_cast<uint32_t>(first + sl);
+        bool alive = has_node && static_cast<int>(walk) < n_walks;
         int32_t u = static_cast<int32_t>(node);
         float load = 1.0f;
         uint32_t x[4] = {0, 0, 0, 0};
@@ -137,18 +156,22 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
             if (alive) alive = walk_hop(g, law, t, x, u, load);
             const unsigned long long mask = __ballot(alive);
             if (mask == 0ull) break;
+            const unsigned long long mine = share(mask);
             if (alive) {
-                const int pos = base + prefix_popcount(mask);
+                const int pos = base + below(mine);
                 dcol[pos] = u; dload[pos] = load; dhop[pos] = static_cast<uint16_t>(t);
             }
-            base += __popcll(mask);
+            base += __popcll(mine);
         }
     }
-    const int D = base;   // <= 1 + n_walks * (f_len - 1) <= cap
+    const int D = base;   // <= 1 + n_walks * (f_len - 1) <= cap; 0 in a slot without a node
+    int d_max = D;        // the largest D of the wavefront: bound of the loops that hold a ballot
+#pragma unroll
+    for (int off = W; off < kWave; off <<= 1) d_max = max(d_max, __shfl_xor(d_max, off, kWave));
     __syncthreads();
 
     // Rank by counting: position of deposit s in the order (column, s).
-    for (int s = lane; s < D; s += kWave) {
+    for (int s = sl; s < D; s += W) {
         const int32_t c = dcol[s];
         int rank = 0;
         for (int s2 = 0; s2 < D; ++s2) {
@@ -160,21 +183,21 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
     __syncthreads();
 
     // Runs of equal columns: the run head writes the merged entry.
-    const int32_t row_start = MODE != kCount ? row_ptr[node] : 0;
+    const int32_t row_start = (MODE != kCount && has_node) ? row_ptr[node] : 0;
     const float n_float = static_cast<float>(n_walks);
     int heads = 0;
-    for (int r0 = 0; r0 < D; r0 += kWave) {
-        const int r = r0 + lane;
+    for (int r0 = 0; r0 < d_max; r0 += W) {
+        const int r = r0 + sl;
         const bool valid = r < D;
         const int32_t c = valid ? dcol[perm[r]] : -1;
         const bool head = valid && (r == 0 || dcol[perm[r - 1]] != c);
-        const unsigned long long mask = __ballot(head);
+        const unsigned long long mine = share(__ballot(head));
         if (MODE == kGrad && valid) {
             // entry of Phi_hat that sorted position r belongs to: runs up to and including this lane, minus one
-            dent[r] = row_start + heads + prefix_popcount(mask) + (head ? 1 : 0) - 1;
+            dent[r] = row_start + heads + below(mine) + (head ? 1 : 0) - 1;
         }
         if (FILL && head) {
-            const long long pos = static_cast<long long>(row_start) + heads + prefix_popcount(mask);
+            const long long pos = static_cast<long long>(row_start) + heads + below(mine);
             col_out[pos] = c;
             for (int h = 0; h < n_f; ++h) {
                 const float* fh = f + static_cast<long long>(h) * f_len;
@@ -187,30 +210,61 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
                 val_out[h * val_stride + pos] = acc / n_float;
             }
         }
-        heads += __popcll(mask);
+        heads += __popcll(mine);
     }
-    if (MODE == kCount && lane == 0) row_ptr[node] = heads;
+    if (MODE == kCount && sl == 0 && has_node) row_ptr[node] = heads;
 
     if (MODE == kGrad) {
         // dL/df[h][t] of this node = (1/n) sum over deposits with hop t of load * dphi[h][entry]; lane t walks
         // the deposits in sorted order, so the sum has a fixed order.  The columns are not needed any more:
         // their array holds the staged products.
         float* gval = reinterpret_cast<float*>(dcol);
-        const int32_t row_end = row_ptr[node + 1];
+        const int32_t row_end = has_node ? row_ptr[node + 1] : 0;
         for (int h = 0; h < n_f; ++h) {
             __syncthreads();
-            for (int r = lane; r < D; r += kWave) {
+            for (int r = sl; r < D; r += W) {
                 const int32_t e = dent[r];
                 gval[r] = (e >= 0 && e < row_end && e < val_stride) ? dload[perm[r]] * dphi[h * val_stride + e] : 0.0f;
             }
             __syncthreads();
-            for (int t = lane; t < f_len; t += kWave) {
-                float acc = 0.0f;
-                for (int r = 0; r < D; ++r) acc += dhop[perm[r]] == t ? gval[r] : 0.0f;
-                df_part[(static_cast<long long>(node) * n_f + h) * f_len + t] = acc / n_float;
+            if (has_node) {
+                for (int t = sl; t < f_len; t += W) {
+                    float acc = 0.0f;
+                    for (int r = 0; r < D; ++r) acc += dhop[perm[r]] == t ? gval[r] : 0.0f;
+                    df_part[(static_cast<long long>(node) * n_f + h) * f_len + t] = acc / n_float;
+                }
             }
         }
     }
+}
+
+// Launches rows_kernel<MODE, W> with the sub-wavefront width that fits n_walks.
+template <int MODE>
+grf_status launch_rows(const GraphView& gv, const WalkLaw& law, int n_walks, int f_len, int n_f, const float* f, int cap,
+                       int32_t* row_ptr, int32_t* col_out, float* val_out, long long val_stride, const float* dphi,
+                       float* df_part, hipStream_t stream)
+{
+    constexpr int kBytes = MODE == kGrad ? kDepositBytesGrad : kDepositBytes;
+    auto launch = [&](auto width) -> grf_status {
+        constexpr int W = decltype(width)::value;
+        constexpr int P = kWave / W;
+        const size_t lds = static_cast<size_t>(P) * cap * kBytes;
+        if (lds > 64 * 1024)
+            GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_kernel<MODE, W>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+        const unsigned blocks = static_cast<unsigned>((static_cast<long long>(gv.n) + P - 1) / P);
+        hipLaunchKernelGGL((rows_kernel<MODE, W>), dim3(blocks), dim3(kWave), lds, stream, gv, law, n_walks, f_len, n_f, f, cap,
+                           row_ptr, col_out, val_out, val_stride, dphi, df_part);
+        GRF_LAUNCH_CHECK("rows_kernel");
+        return GRF_OK;
+    };
+    // several nodes per wavefront only while their deposit areas together stay within 5 KB, a wavefront slot's share of
+    // a compute unit's 160 KB of LDS: beyond that the areas, not the slots, bound the nodes in flight, and sharing a
+    // wavefront only stretches each node's sort over fewer lanes (0.68 instead of 0.46 ms at the headline size)
+    auto fits = [&](int width) { return n_walks <= width && static_cast<size_t>(kWave / width) * cap * kBytes <= 5 * 1024; };
+    if (fits(8)) return launch(std::integral_constant<int, 8>{});
+    if (fits(16)) return launch(std::integral_constant<int, 16>{});
+    if (fits(32)) return launch(std::integral_constant<int, 32>{});
+    return launch(std::integral_constant<int, 64>{});
 }
 
 // df[x] = sum over nodes of df_part[node][x], x in [0, n_f * f_len): one workgroup per x, fixed order.
@@ -503,19 +557,11 @@ grf_status sample_impl(const grf_graph* g, const float* f_host, const float* f_d
     }
 
     const int cap = static_cast<int>(cap_ll);
-    const size_t lds = static_cast<size_t>(cap) * kDepositBytes;
-    if (lds > 64 * 1024) {
-        GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_kernel<kCount>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
-        GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_kernel<kFill>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
-    }
     const GraphView gv = view_of(g);
-    const dim3 grid(static_cast<unsigned>(g->n));
 
     // pass 1: entries per row, then offsets
-    hipLaunchKernelGGL(rows_kernel<kCount>, grid, dim3(kWave), lds, stream, gv, law, n_walks, f_len, n_f,
-                       f_dev, cap, phi_out->row_ptr, static_cast<int32_t*>(nullptr),
-                       static_cast<float*>(nullptr), 0ll, static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
-    GRF_LAUNCH_CHECK("rows_kernel<count>");
+    if (grf_status st = launch_rows<kCount>(gv, law, n_walks, f_len, n_f, f_dev, cap, phi_out->row_ptr, nullptr, nullptr, 0ll,
+                                            nullptr, nullptr, stream)) return st;
     if (grf_status st = exclusive_scan_inplace(phi_out->row_ptr, g->n, total_dev, stream)) return st;
     if (nnz_out != nullptr) {
         long long total = 0;
@@ -528,10 +574,8 @@ grf_status sample_impl(const grf_graph* g, const float* f_host, const float* f_d
     }
 
     // pass 2: same walks again, entries written at their offsets
-    hipLaunchKernelGGL(rows_kernel<kFill>, grid, dim3(kWave), lds, stream, gv, law, n_walks, f_len, n_f,
-                       f_dev, cap, phi_out->row_ptr, phi_out->col, phi_out->val,
-                       static_cast<long long>(phi_out->capacity), static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
-    GRF_LAUNCH_CHECK("rows_kernel<fill>");
+    if (grf_status st = launch_rows<kFill>(gv, law, n_walks, f_len, n_f, f_dev, cap, phi_out->row_ptr, phi_out->col, phi_out->val,
+                                           static_cast<long long>(phi_out->capacity), nullptr, nullptr, stream)) return st;
     return GRF_OK;
 }
 
@@ -594,13 +638,8 @@ extern "C" grf_status grf_sample_backward(const grf_graph* g, int32_t f_len, int
     }
     float* df_part = static_cast<float*>(workspace);
     const int cap = static_cast<int>(cap_ll);
-    const size_t lds = static_cast<size_t>(cap) * kDepositBytesGrad;
-    if (lds > 64 * 1024)
-        GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_kernel<kGrad>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
-    hipLaunchKernelGGL(rows_kernel<kGrad>, dim3(static_cast<unsigned>(g->n)), dim3(kWave), lds, stream, view_of(g), law, n_walks, f_len, n_f,
-                       static_cast<const float*>(nullptr), cap, phi->row_ptr, static_cast<int32_t*>(nullptr),
-                       static_cast<float*>(nullptr), static_cast<long long>(phi->capacity), dphi_val, df_part);
-    GRF_LAUNCH_CHECK("rows_kernel<grad>");
+    if (grf_status st = launch_rows<kGrad>(view_of(g), law, n_walks, f_len, n_f, nullptr, cap, phi->row_ptr, nullptr, nullptr,
+                                           static_cast<long long>(phi->capacity), dphi_val, df_part, stream)) return st;
     hipLaunchKernelGGL(df_reduce_kernel, dim3(static_cast<unsigned>(width)), dim3(256), 0, stream,
                        static_cast<const float*>(df_part), static_cast<long long>(g->n), width, df);
     GRF_LAUNCH_CHECK("df_reduce_kernel");
