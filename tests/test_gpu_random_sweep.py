@@ -76,7 +76,7 @@ def draw_case(index):
     n_f = H if rng.random() < 0.4 else 1
     f = synth.modulation(f_len, rng, n_f=n_f)
     wl = synth.Workload(f"sweep_{index}_{family}_{g.n}", g, f, float(rng.choice([0.0, 0.1, 0.3, 0.5, 0.8])),
-                        int(rng.choice([1, 2, 5, 17, 63, 64, 65, 70])), int(rng.integers(1, 3)), H,
+                        int(rng.choice([1, 2, 5, 8, 9, 16, 17, 27, 32, 33, 63, 64, 65, 70])), int(rng.integers(1, 3)), H,
                         int(rng.choice([32, 64])), str(rng.choice(["f32", "bf16"])),
                         walk_seed=int(rng.integers(0, 2**62)), data_seed=index)
     return wl, str(rng.choice(["relu", "identity", "elu1"]))
