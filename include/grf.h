@@ -53,7 +53,10 @@ const char* grf_last_error(void);
 
 /* Weighted adjacency matrix W of the graph G in CSR (Sec. 3.1).  Read-only.
  * Contract: row_ptr[0] = 0, row_ptr[n] = nnz, columns strictly ascending within a row, no self loops,
- * w finite.  deg(i) = row_ptr[i+1] - row_ptr[i] is the number of stored neighbours.  n, nnz < 2^31. */
+ * w finite.  deg(i) = row_ptr[i+1] - row_ptr[i] is the number of stored neighbours.  n, nnz < 2^31.
+ * Every index read from row_ptr and col (here and in grf_phi) is range-checked on the device before it is used
+ * as an address: an entry that breaks the contract ends the walk that meets it, respectively is skipped by the
+ * attention calls, and the values that depend on it are unspecified. */
 typedef struct grf_graph {
     int64_t        n;
     int64_t        nnz;

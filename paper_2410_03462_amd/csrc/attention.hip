@@ -37,11 +37,10 @@ __global__ __launch_bounds__(256) void column_scatter_kernel(const int32_t* __re
 {
     const long long row = static_cast<long long>(blockIdx.x) * (blockDim.x / kWave) + (threadIdx.x / kWave);
     if (row >= n) return;
-    const long long beg = row_ptr[row];
+    const long long beg = max(static_cast<long long>(row_ptr[row]), 0ll);      // a malformed row_ptr must not cost a long empty loop
     long long end = row_ptr[row + 1];
     if (end > nnz) end = nnz;
     for (long long e = beg + lane_id(); e < end; e += kWave) {
-        if (e < 0) continue;
         const int32_t c = col[e];
         const int32_t k = arrival[e];
         if (static_cast<uint32_t>(c) >= static_cast<uint32_t>(n) || k < 0) continue;

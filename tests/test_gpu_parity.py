@@ -603,3 +603,44 @@ def test_asymmetric_headline_workload_full_size(grf, oracle):
             a = w * (fk[js] @ fq[i])
             assert np.abs(num[0, h, i] - a @ V[0, h][js].astype(np.float64)).max() <= TOL_F32 * ns
             assert abs(den[0, h, i] - a.sum()) <= TOL_F32 * ds
+
+
+# --------------------------------------------------------------------------- inputs that break the contract
+
+def test_out_of_range_indices_are_skipped(grf, oracle):
+    """Column indices outside [0, n) in Phi_hat are skipped by every attention call (the result is that of Phi_hat
+    without those entries); a neighbour index outside [0, n) in the graph ends the walk that meets it."""
+    wl = SMALL["random_777"]
+    n = wl.graph.n
+    rp, col, val = _oracle_phi(oracle, wl)
+    rng = np.random.default_rng(77)
+    bad = rng.choice(col.shape[0], size=8, replace=False)
+    col_bad = col.copy()
+    col_bad[bad[:5]] = n
+    col_bad[bad[5:]] = -7
+    keep = np.ones(col.shape[0], bool); keep[bad] = False
+    rows = np.repeat(np.arange(n), np.diff(rp))
+    rp_clean = np.concatenate([[0], np.cumsum(np.bincount(rows[keep], minlength=n))]).astype(np.int32)
+    Q, K, V = wl.qkv()
+    ref = oracle.masked_linear_attention(Q, K, V, rp_clean, col[keep], val[:, keep])
+    Qd, Kd, Vd = to_dev(Q), to_dev(K), to_dev(V)
+    phi = grf.Phi.from_host(n, rp, col_bad, val)
+    for call in (grf.grf_masked_linear_attention, grf.grf_masked_linear_attention_fused):
+        _, num, den = call(Qd, Kd, Vd, phi, return_num_den=True)
+        assert relerr(num.cpu().numpy(), ref["num"]) <= TOL_F32, call.__name__
+        assert relerr(den.cpu().numpy(), ref["den"]) <= TOL_F32, call.__name__
+    _, anum, aden = grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi, return_num_den=True)
+    fq, fk = np.maximum(Q.astype(np.float64), 0), np.maximum(K.astype(np.float64), 0)
+    M = oracle.phi_dense(n, rp_clean, col[keep], val[0, keep])
+    A = M[None, None] * (fq @ np.swapaxes(fk, -1, -2))
+    assert relerr(anum.cpu().numpy(), A @ V.astype(np.float64)) <= TOL_F32
+    assert relerr(aden.cpu().numpy(), A.sum(-1)) <= TOL_F32
+
+    g_bad = synth.Graph(wl.graph.n, wl.graph.row_ptr.copy(), wl.graph.col.copy(), wl.graph.w.copy())
+    g_bad.col[[3, 400, 1999]] = [n + 5, -1, 2**30]
+    phi2 = grf.grf_sample(grf.DeviceGraph.from_host(g_bad), wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+    rp2, col2, val2 = phi2.to_host()
+    assert rp2[0] == 0 and rp2[-1] == phi2.nnz and np.all(np.diff(rp2) >= 1)
+    assert col2.min() >= 0 and col2.max() < n and np.isfinite(val2).all()
+    for i in range(n):
+        assert np.all(np.diff(col2[rp2[i]:rp2[i + 1]]) > 0)
