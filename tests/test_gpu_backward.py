@@ -390,3 +390,54 @@ def test_vit_grid_full_size_backward(grf, oracle):
     assert relerr(got[3].cpu().numpy()[:, : phi.nnz], ref[3]) <= TOL_F32
     assert relerr(got[0].cpu().numpy(), dQ[sub]) <= 1e-6        # the same slices, computed in a different launch
     torch.cuda.empty_cache()
+
+
+def test_largest_workload_fused_and_backward_full_size(grf, oracle):
+    """cloud_128k (131072 nodes, 16 heads with per-head modulation, bf16 inputs) through the fused forward and the
+    backward call as the benchmark runs them: the fused forward against the bucket + gather pair on every row and
+    against Eq. (2) evaluated directly on sampled rows; sampled rows of dQ, dK, dV against Eq. (2) differentiated
+    directly and sampled entries of dPhi_hat (one plane per head) against their two buckets, with seeded synthetic
+    out and den as in the headline test."""
+    import torch
+    wl = synth.workload("cloud_128k")
+    n = wl.graph.n
+    rp, col, val = oracle.sample(wl.graph, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+    Q, K, V = wl.qkv()
+    phi = grf.Phi.from_host(n, rp, col, val)
+    Qd, Kd, Vd = (to_dev(x, "bf16") for x in (Q, K, V))
+
+    _, fnum, fden = grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, return_num_den=True)
+    _, num, den = grf.grf_masked_linear_attention(Qd, Kd, Vd, phi, bh_chunk=4, return_num_den=True)
+    assert relerr(fnum.cpu().numpy(), num.cpu().numpy()) <= TOL_BF16
+    assert relerr(fden.cpu().numpy(), den.cpu().numpy()) <= TOL_BF16
+    fnum_h, fden_h = fnum.cpu().numpy(), fden.cpu().numpy()
+    rows = np.random.default_rng(16).choice(n, size=6, replace=False)
+    for h in (2, 11):
+        for i in rows:
+            n_i, d_i, _ = oracle.row_direct(int(i), Q[0, h], K[0, h], V[0, h], rp, col, val[h])
+            assert np.abs(fnum_h[0, h, i] - n_i).max() <= TOL_BF16 * np.abs(fnum_h[0, h]).max()
+            assert abs(fden_h[0, h, i] - d_i) <= TOL_BF16 * np.abs(fden_h[0, h]).max()
+    del fnum, fden, num, den
+    torch.cuda.empty_cache()
+
+    rng = np.random.default_rng(15)
+    d_out_h = rng.standard_normal(Q.shape).astype(np.float32)
+    out_s = rng.standard_normal(Q.shape).astype(np.float32)
+    den_s = (np.exp(rng.standard_normal(Q.shape[:3])) * rng.choice([-1.0, 1.0], size=Q.shape[:3])).astype(np.float32)
+    dQ, dK, dV, dphi = grf.grf_masked_linear_attention_backward(Qd, Kd, Vd, phi, to_dev(out_s), to_dev(den_s), to_dev(d_out_h))
+    dQ_h, dK_h, dV_h, dphi_h = dQ.cpu().numpy(), dK.cpu().numpy(), dV.cpu().numpy(), dphi.cpu().numpy()[:, : phi.nnz]
+    assert all(np.isfinite(x).all() for x in (dQ_h, dK_h, dV_h, dphi_h))
+    ents = np.random.default_rng(17).choice(phi.nnz, size=3, replace=False)
+    erow = np.searchsorted(rp, ents, side="right") - 1
+    for h in (2, 11):
+        gp = oracle.backward_seed(out_s[0, h], den_s[0, h], d_out_h[0, h])
+        scales = [np.abs(x[0, h]).max() for x in (dQ_h, dK_h, dV_h)]
+        for i in rows[:4]:
+            ref = oracle.row_direct_backward(int(i), Q[0, h], K[0, h], V[0, h], rp, col, val[h], gp)
+            for got, want, sc in zip((dQ_h, dK_h, dV_h), ref, scales):
+                assert np.abs(got[0, h, i] - want).max() <= TOL_BF16 * sc
+        for e, i in zip(ents, erow):      # one value plane per head: the entry's gradient comes from this head alone
+            want = oracle.dphi_entry_direct(int(i), int(col[e]), Q[0, h], K[0, h], V[0, h], rp, col, val[h], gp)
+            assert abs(dphi_h[h, e] - want) <= TOL_BF16 * np.abs(dphi_h[h]).max()
+    del dQ, dK, dV, dphi
+    torch.cuda.empty_cache()
