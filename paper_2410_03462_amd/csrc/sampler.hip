@@ -284,37 +284,38 @@ __global__ __launch_bounds__(256) void df_reduce_kernel(const float* __restrict_
 }
 
 // ------------------------------------------------------------------------------------ scan / fill
-// Exclusive prefix sum by one workgroup of 1024 threads over tiles of 4096 elements (the inputs are row or column
-// counts: a few hundred thousand elements at most in practice).  A thread's four elements are one 16-byte load
-// (data is 16-byte aligned), and the next tile is fetched before the current one is scanned.
-__global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ data, long long n, long long* __restrict__ total64)
+// Exclusive prefix sum by one workgroup of 1024 threads (the inputs are row, column or cell counts: a few hundred
+// thousand elements at most in practice) over tiles of 1024 * PER elements, which the workgroup holds in registers:
+// every thread requests its PER consecutive elements of the tile at once, as 16-byte loads (one memory round trip per
+// tile, and most inputs are one or two tiles), scans them, and the threads' totals are scanned across the wavefront
+// and the workgroup.
+template <int PER>
+__global__ __launch_bounds__(1024) void scan_resident_kernel(int32_t* __restrict__ data, long long n, long long* __restrict__ total64)
 {
     __shared__ long long wave_total[2][16];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid >> 6;
     const bool aligned = (reinterpret_cast<uintptr_t>(data) & 15u) == 0;
-    auto fetch = [&](long long tile, int32_t (&v)[4]) {
-        const long long idx = tile + static_cast<long long>(tid) * 4;
-        if (aligned && idx + 3 < n) {
-            const int4 q = *reinterpret_cast<const int4*>(data + idx);
-            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-        } else {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) v[k] = (idx + k < n) ? data[idx + k] : 0;
-        }
-    };
     long long carry = 0;
-    int32_t next[4];
-    fetch(0, next);
     int parity = 0;
-    for (long long tile = 0; tile < n; tile += 4096, parity ^= 1) {
-        const long long idx = tile + static_cast<long long>(tid) * 4;
-        int32_t v[4];
+    for (long long tile = 0; tile < n; tile += 1024ll * PER, parity ^= 1) {
+        const long long base = tile + static_cast<long long>(tid) * PER;
+        int32_t v[PER];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = next[k];
-        if (tile + 4096 < n) fetch(tile + 4096, next);
-        const long long local = static_cast<long long>(v[0]) + v[1] + v[2] + v[3];
+        for (int k = 0; k < PER; k += 4) {
+            const long long idx = base + k;
+            if (aligned && idx + 3 < n) {
+                const int4 q = *reinterpret_cast<const int4*>(data + idx);
+                v[k] = q.x; v[k + 1] = q.y; v[k + 2] = q.z; v[k + 3] = q.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[k + j] = (idx + j < n) ? data[idx + j] : 0;
+            }
+        }
+        long long local = 0;
+#pragma unroll
+        for (int k = 0; k < PER; ++k) local += v[k];
         long long incl = local;
 #pragma unroll
         for (int off = 1; off < kWave; off <<= 1) {
@@ -332,81 +333,27 @@ __global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ data, 
         }
         long long run = carry + before + incl - local;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if (idx + k < n) data[idx + k] = run > 2147483647ll ? 2147483647 : static_cast<int32_t>(run);
-            run += v[k];
+        for (int k = 0; k < PER; k += 4) {
+            const long long idx = base + k;
+            int32_t o[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                o[j] = run > 2147483647ll ? 2147483647 : static_cast<int32_t>(run);
+                run += v[k + j];
+            }
+            if (aligned && idx + 3 < n) {
+                *reinterpret_cast<int4*>(data + idx) = make_int4(o[0], o[1], o[2], o[3]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (idx + j < n) data[idx + j] = o[j];
+            }
         }
         carry += tile_total;
     }
     if (tid == 0) {
         data[n] = carry > 2147483647ll ? 2147483647 : static_cast<int32_t>(carry);
         if (total64 != nullptr) *total64 = carry;
-    }
-}
-
-// The same for inputs of at most 1024 * PER elements, which one workgroup holds in registers: every thread requests its
-// PER consecutive elements at once (one memory round trip for the whole input instead of one per tile), scans them,
-// and the threads' totals are scanned across the wavefront and the workgroup.
-template <int PER>
-__global__ __launch_bounds__(1024) void scan_resident_kernel(int32_t* __restrict__ data, long long n, long long* __restrict__ total64)
-{
-    __shared__ long long wave_total[16];
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1);
-    const int wave = tid >> 6;
-    const bool aligned = (reinterpret_cast<uintptr_t>(data) & 15u) == 0;
-    const long long base = static_cast<long long>(tid) * PER;
-    int32_t v[PER];
-#pragma unroll
-    for (int k = 0; k < PER; k += 4) {
-        const long long idx = base + k;
-        if (aligned && idx + 3 < n) {
-            const int4 q = *reinterpret_cast<const int4*>(data + idx);
-            v[k] = q.x; v[k + 1] = q.y; v[k + 2] = q.z; v[k + 3] = q.w;
-        } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[k + j] = (idx + j < n) ? data[idx + j] : 0;
-        }
-    }
-    long long local = 0;
-#pragma unroll
-    for (int k = 0; k < PER; ++k) local += v[k];
-    long long incl = local;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const long long up = __shfl_up(incl, off, kWave);
-        if (lane >= off) incl += up;
-    }
-    if (lane == kWave - 1) wave_total[wave] = incl;
-    __syncthreads();
-    long long before = 0, total = 0;
-#pragma unroll
-    for (int w = 0; w < 16; ++w) {
-        const long long t = wave_total[w];
-        if (w < wave) before += t;
-        total += t;
-    }
-    long long run = before + incl - local;
-#pragma unroll
-    for (int k = 0; k < PER; k += 4) {
-        const long long idx = base + k;
-        int32_t o[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            o[j] = run > 2147483647ll ? 2147483647 : static_cast<int32_t>(run);
-            run += v[k + j];
-        }
-        if (aligned && idx + 3 < n) {
-            *reinterpret_cast<int4*>(data + idx) = make_int4(o[0], o[1], o[2], o[3]);
-        } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (idx + j < n) data[idx + j] = o[j];
-        }
-    }
-    if (tid == 0) {
-        data[n] = total > 2147483647ll ? 2147483647 : static_cast<int32_t>(total);
-        if (total64 != nullptr) *total64 = total;
     }
 }
 
@@ -421,11 +368,9 @@ grf_status exclusive_scan_inplace(int32_t* counts, int64_t n, long long* total64
     const long long count = static_cast<long long>(n);
     if (count <= 1024 * 16)
         hipLaunchKernelGGL(scan_resident_kernel<16>, dim3(1), dim3(1024), 0, stream, counts, count, total64);
-    else if (count <= 1024 * 32)
-        hipLaunchKernelGGL(scan_resident_kernel<32>, dim3(1), dim3(1024), 0, stream, counts, count, total64);
     else
-        hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, stream, counts, count, total64);
-    GRF_LAUNCH_CHECK("scan_kernel");
+        hipLaunchKernelGGL(scan_resident_kernel<32>, dim3(1), dim3(1024), 0, stream, counts, count, total64);
+    GRF_LAUNCH_CHECK("scan_resident_kernel");
     return GRF_OK;
 }
 

@@ -102,6 +102,25 @@ def test_phi_pattern_bit_exact_values_close(grf, oracle, name):
     assert np.array_equal(rp2, rp) and np.array_equal(col2, col) and np.array_equal(val2, val)
 
 
+@pytest.mark.parametrize("n", [1023, 16383, 16384, 16385, 32767, 32769, 65536 + 77, 3 * 32768 + 1])
+def test_row_pointers_around_the_prefix_sum_tile_edges(grf, oracle, n):
+    """The row counts go through a prefix sum that works in tiles of 16384 (short inputs) or 32768 elements: node
+    counts on both sides of the tile edges, one tile with a ragged tail, several tiles."""
+    g_host = synth.ring_graph(n)
+    f = synth.modulation(4, np.random.default_rng(n))
+    g = grf.DeviceGraph.from_host(g_host)
+    rp, col, val = grf.grf_sample(g, f, 0.4, 3, 11 + n).to_host()
+    rp0, col0, val0 = oracle.sample(g_host, f, 0.4, 3, 11 + n)
+    assert np.array_equal(rp, rp0) and np.array_equal(col, col0)
+    assert relerr(val, val0) <= TOL_F32
+    # the column lists go through the same prefix sum, over the columns' entry counts
+    Q, K, V = (np.random.default_rng([n, i]).standard_normal((1, 1, n, 32)).astype(np.float32) for i in range(3))
+    ref = oracle.masked_linear_attention(Q, K, V, rp0, col0, val0, feature_map=0)
+    _, num, den = grf.grf_masked_linear_attention(to_dev(Q), to_dev(K), to_dev(V), grf.Phi.from_host(n, rp0, col0, val0),
+                                                  "relu", return_num_den=True)
+    assert relerr(num.cpu().numpy(), ref["num"]) <= TOL_F32 and relerr(den.cpu().numpy(), ref["den"]) <= TOL_F32
+
+
 def test_phi_special_cases(grf, oracle):
     wl = SMALL["random_777"]
     g = grf.DeviceGraph.from_host(wl.graph)
