@@ -347,7 +347,7 @@ grf_status check_workspace(const void* workspace, size_t have, size_t need)
 namespace {
 
 template <int D, typename T>
-grf_status launch_buckets(const void* K, const void* V, int64_t n, int64_t H, int32_t n_f, const grf_phi* phi,
+grf_status launch_buckets(const void* K, const void* V, int64_t n, int64_t H, int32_t n_f,
                           int64_t nnz, const Transposed& t, int fmap, int64_t bh_first, int64_t n_slices, float* buckets,
                           hipStream_t stream)
 {
@@ -428,7 +428,7 @@ extern "C" grf_status grf_form_buckets(const void* K, const void* V, int32_t dty
     if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
     const int fmap = feature_map;
     grf_status st = GRF_OK;
-    GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, phi, nnz, t, fmap, 0, B * H, buckets, stream)));
+    GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, nnz, t, fmap, 0, B * H, buckets, stream)));
     return st;
 }
 
@@ -469,7 +469,7 @@ extern "C" grf_status grf_masked_linear_attention(const void* Q, const void* K, 
     for (int64_t first = 0; first < slices; first += step) {
         const int64_t count = (slices - first < step) ? (slices - first) : step;
         grf_status st = GRF_OK;
-        GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, phi, nnz, t, fmap, first, count, buckets, stream)));
+        GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, nnz, t, fmap, first, count, buckets, stream)));
         if (st != GRF_OK) return st;
         GRF_DISPATCH(d, dtype, (st = launch_gather<D_, T_>(Q, n, H, n_f, phi, nnz, fmap, buckets, first, count, out, num_opt, den_opt, stream)));
         if (st != GRF_OK) return st;
