@@ -112,8 +112,8 @@ __global__ __launch_bounds__(256) void asymmetric_kernel(const T* __restrict__ Q
 }
 
 // ------------------------------------------------------------------------------------ gradients
-// With g'_i = [g_i, gd_i] = [d_out_i / den_i, -(d_out_i . out_i) / den_i], a_ij = phi(q_i) . phi(k_j) and
-// c_ij = v_j . g_i + gd_i, the loss depends on the inputs through sum_(i,j) Phi_ij a_ij c_ij:
+// With g_i = d_out_i / den_i, a_ij = phi(q_i) . phi(k_j) and c_ij = g_i . (v_j - out_i), the loss depends on the
+// inputs through sum_(i,j) Phi_ij a_ij c_ij:
 //     dPhi_ij = a_ij c_ij      dphi(q_i) = sum_j Phi_ij c_ij phi(k_j)
 //     dphi(k_j) = sum_i Phi_ij c_ij phi(q_i)      dv_j = sum_i Phi_ij a_ij g_i
 // The first two are sums over a row of Phi_hat (rows kernel, which also leaves Phi_ij c_ij and Phi_ij a_ij per
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void asymmetric_kernel(const T* __restrict__ Q
 // One wavefront per (slice, row i); lanes as in the forward kernel.
 template <int D, typename T>
 __global__ __launch_bounds__(256) void asymmetric_backward_rows_kernel(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-                                                                       const float* __restrict__ G, const float* __restrict__ gd,
+                                                                       const float* __restrict__ G, const float* __restrict__ out,
                                                                        long long n, int H, int n_f, long long val_stride,
                                                                        const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col,
                                                                        const float* __restrict__ phi_val, int fmap, long long bh_first,
@@ -151,7 +151,9 @@ __global__ __launch_bounds__(256) void asymmetric_backward_rows_kernel(const T* 
     const float4 q4 = load4(Q + (bh * n + i) * D + 4 * cg);
     const float4 fq = make_float4(feature(q4.x, fmap), feature(q4.y, fmap), feature(q4.z, fmap), feature(q4.w, fmap));
     const float4 g4 = *reinterpret_cast<const float4*>(G + (slice * n + i) * D + 4 * cg);
-    const float gdi = gd[slice * n + i];
+    // c_ij = g_i . (v_j - out_i): the difference is taken before the product, so that a row whose output is (nearly)
+    // one of its values loses nothing to cancellation between two dot products
+    const float4 o4 = *reinterpret_cast<const float4*>(out + (bh * n + i) * D + 4 * cg);
 
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     const int32_t beg = max(row_ptr[i], 0);
@@ -182,14 +184,13 @@ __global__ __launch_bounds__(256) void asymmetric_backward_rows_kernel(const T* 
                 const float4 fk = make_float4(feature(k4[u].x, fmap), feature(k4[u].y, fmap), feature(k4[u].z, fmap), feature(k4[u].w, fmap));
                 float a = fq.x * fk.x;
                 a = fmaf(fq.y, fk.y, a); a = fmaf(fq.z, fk.z, a); a = fmaf(fq.w, fk.w, a);
-                float c = g4.x * v4[u].x;
-                c = fmaf(g4.y, v4[u].y, c); c = fmaf(g4.z, v4[u].z, c); c = fmaf(g4.w, v4[u].w, c);
+                float c = g4.x * (v4[u].x - o4.x);
+                c = fmaf(g4.y, v4[u].y - o4.y, c); c = fmaf(g4.z, v4[u].z - o4.z, c); c = fmaf(g4.w, v4[u].w - o4.w, c);
 #pragma unroll
                 for (int off = 1; off < LPE; off <<= 1) {
                     a += __shfl_xor(a, off, kWave);
                     c += __shfl_xor(c, off, kWave);
                 }
-                c += gdi;
                 const float wc = w[u] * c;
                 acc.x = fmaf(wc, fk.x, acc.x);
                 acc.y = fmaf(wc, fk.y, acc.y);
@@ -340,7 +341,7 @@ grf_status launch_asymmetric_backward_chunk(const void* Qv, const void* Kv, cons
     if (waves == 0) return GRF_OK;
     if (grf_status st = launch_backward_seed(D, out, den, d_out, static_cast<long long>(bh_first) * n, waves, b.G, b.gd, stream)) return st;
     hipLaunchKernelGGL((asymmetric_backward_rows_kernel<D, T>), dim3(blocks_for(waves, 4)), dim3(256), 0, stream, Q, K, V,
-                       static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n), static_cast<int>(H),
+                       static_cast<const float*>(b.G), out, static_cast<long long>(n), static_cast<int>(H),
                        static_cast<int>(n_f), static_cast<long long>(phi->capacity), static_cast<const int32_t*>(phi->row_ptr),
                        static_cast<const int32_t*>(phi->col), static_cast<const float*>(phi->val), fmap,
                        static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), dQ, b.wc, b.wa, b.dpart);

@@ -16,6 +16,10 @@ pytestmark = pytest.mark.gpu
 TOL = {"f32": 1e-5, "bf16": 2e-2}
 FEATURE_MAP_CODE = {"relu": 0, "identity": 1, "elu1": 2}
 N_CASES = 96
+# further indices that once failed: 204 has rows of Phi_hat with one small entry, where the asymmetric gradients cancel;
+# 922 is a star graph whose Phi_hat spans 0.1 .. 374, where dphi is 1/230 of the absolute sum of its terms
+EXTRA_CASES = [204, 922]
+ILL_CONDITIONED = {922}
 
 
 @pytest.fixture(scope="module")
@@ -41,15 +45,38 @@ def to_dev(x, dtype="f32"):
     return t.to(torch.bfloat16) if dtype == "bf16" else t
 
 
-def check_gradients(got, ref, tol, label, diagonal):
+def check_gradients(got, ref, tol, label, diagonal, dphi_floor=0.0):
     """dQ, dK, dV, dphi against the checker.  `diagonal`: Phi_hat = f_0 I (one node, or a modulation of length one), where
     out = v whatever q, k and f_0 are: every gradient but dV vanishes identically, the references are of rounding size
-    and what the GPU returns is the rounding of the cancelling terms, so only dV is compared there."""
+    and what the GPU returns is the rounding of the cancelling terms, so only dV is compared there.  `dphi_floor`: an
+    absolute error allowed for dphi whatever its size (see dphi_term_scale)."""
     for name, x, r in zip(("dQ", "dK", "dV", "dphi"), got, ref):
         assert np.isfinite(x).all(), label + name
         if r.size == 0 or (diagonal and name != "dV"):
             continue
+        if name == "dphi" and np.abs(np.asarray(x, dtype=np.float64) - r).max() <= dphi_floor:
+            continue
         assert relerr(x, r) <= tol, (label + name, relerr(x, r))
+
+
+def dphi_term_scale(oracle, Q, K, V, rp, col, val, out, den, d_out):
+    """max over the stored entries of the sum of the absolute values of the terms of dL/dPhi_hat[i,l] =
+    sum_j (a_ij c_ij + a_ji c_ji) Phi_hat[j,l], a_ij = phi(q_i).phi(k_j) (phi = elu + 1), c_ij = g_i.v_j + gd_i with
+    the two parts of c_ij taken apart, summed over the slices of a value plane.  fp32 arithmetic in any order is good
+    to a few units in the last place of this, not of the (possibly much smaller) sum itself."""
+    B, H, n, _ = Q.shape
+    rows = np.repeat(np.arange(n), np.diff(rp))
+    scale = np.zeros(val.shape)
+    elu1 = lambda x: np.where(x > 0, x + 1.0, np.exp(np.minimum(x, 0.0)))
+    for b in range(B):
+        for h in range(H):
+            plane = h if val.shape[0] > 1 else 0
+            P = np.abs(oracle.phi_dense(n, rp, col, val[plane]))
+            gp = oracle.backward_seed(out[b, h], den[b, h], d_out[b, h])
+            A = np.abs(elu1(Q[b, h].astype(np.float64)) @ elu1(K[b, h].astype(np.float64)).T)
+            X = A * (np.abs(gp[:, :-1] @ V[b, h].astype(np.float64).T) + np.abs(gp[:, -1:]))
+            scale[plane] += ((X + X.T) @ P)[rows, col]
+    return float(scale.max())
 
 
 def draw_case(index):
@@ -82,7 +109,7 @@ def draw_case(index):
     return wl, str(rng.choice(["relu", "identity", "elu1"]))
 
 
-@pytest.mark.parametrize("index", range(N_CASES))
+@pytest.mark.parametrize("index", list(range(N_CASES)) + EXTRA_CASES)
 def test_random_case(grf, oracle, index):
     wl, feature_map = draw_case(index)
     print(wl.name, "f_len", wl.f_len, "n_f", wl.n_f, "p", wl.p_halt, "walks", wl.n_walks, "B", wl.B, "H", wl.H, "d", wl.d,
@@ -131,7 +158,12 @@ def test_random_case(grf, oracle, index):
                                                    bh_chunk=chunk)
     host = [t.cpu().numpy() for t in got]
     host[3] = host[3][:, : phi_pos.nnz]
-    check_gradients(host, bref, tol, "", diagonal)
+    floor = 0.0
+    if index in ILL_CONDITIONED:
+        scale = dphi_term_scale(oracle, Q, K, V, rp1, col1, val1, out32, den32, d_out)
+        assert scale > 100 * np.abs(bref[3]).max()          # the case is what its name says
+        floor = 2.0 ** -22 * scale                          # four units in the last place of the terms' size
+    check_gradients(host, bref, tol, "", diagonal, dphi_floor=floor)
     df = grf.grf_sample_backward(g, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, phi_pos, got[3]).cpu().numpy()
     df_ref = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp1, col1, bref[3])
     assert df.shape == df_ref.shape and np.isfinite(df).all()
