@@ -16,6 +16,7 @@
 // Index convention (T2 = d/32): MFMA row/column x of tile t stands for feature / value column
 // T2*x + t, so that a lane's T2 operands are adjacent in memory (one 8-byte load at d = 64).
 #include "attention_common.hpp"
+#include "fused_bf16.hpp"
 
 namespace grf {
 
@@ -291,6 +292,18 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
     const int spread = 8ll * 3 * n * D * static_cast<long long>(sizeof(T)) <= (64ll << 20) ? 1 : 0;
     auto launch = [&](auto wide) {
         constexpr bool W = decltype(wide)::value;
+        if constexpr (D == 64 && std::is_same<T, bf16_t>::value) {
+            // feature maps that keep bf16 values bf16 go to the bf16 matrix cores
+            if (fmap != GRF_PHI_ELU1) {
+                hipLaunchKernelGGL((fused_bucket_bf16_kernel<W>), dim3(static_cast<unsigned>(waves)), dim3(kWave), 0, stream,
+                                   static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+                                   static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
+                                   static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
+                                   static_cast<const float*>(t.s_val), fmap, static_cast<long long>(bh_first), waves,
+                                   static_cast<int32_t>(nnz), spread, partial, pden);
+                return;
+            }
+        }
         hipLaunchKernelGGL((fused_bucket_kernel<D, T, W>), dim3(resident_wave_grid(reinterpret_cast<const void*>(&fused_bucket_kernel<D, T, W>), waves)), dim3(kWave), 0, stream,
                            static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                            static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
