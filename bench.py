@@ -247,6 +247,17 @@ def main() -> int:
                      "flops_per_call": fused_flops,
                      "note": "whole attention call (column lists + fused buckets + row reduce); per-kernel times in profiles/"},
     }
+    if wl.dtype == "bf16" and d == 64:
+        # bf16 inputs at d = 64 run on the bf16 matrix instructions (fp32 operands as hi + lo) and are bound by the
+        # rows read and the partial rows written and read back, not by the matrix pipe
+        elem = 2
+        fused_bytes = float(nnz) * B * H * (3 * d * elem + 2 * (d + 1) * 4)
+        fused["roofline"] = {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
+                             "achieved_whole_call": round(fused_bytes / (fused_attn_ms * 1e-3) / 1e9, 1),
+                             "bytes_per_call": fused_bytes, "useful_flops_per_call": fused_flops,
+                             "note": "whole attention call; bytes = per entry of Phi_hat and slice three input rows, the partial "
+                                     "row written by the bucket kernel and read by the row reduce; re-read input rows are partly "
+                                     "served by L2 / Infinity Cache; per-kernel times in profiles/"}
 
     # asymmetric GRFs (App. D): the same sampled matrix used directly as the mask estimate
     aout = torch.empty_like(out)

@@ -244,10 +244,20 @@ __global__ __launch_bounds__(256) void backward_reduce_kernel(long long n, int H
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int t = t0 + u * EPW + sub;
-                const int32_t pos = __shfl(pos_reg, t & (kWave - 1), kWave);
-                w[u] = __shfl(w_reg, t & (kWave - 1), kWave);
-                ok[u] = t < cnt && pos >= 0;
-                v[u] = ok[u] ? slice_partial[static_cast<long long>(pos) * D + c] : 0.0f;
+                if constexpr (EPW == 1) {
+                    // the entry is the same in every lane: a scalar broadcast, and a row address in scalar registers
+                    // (the cross-lane unit is left to the dot products below); the load is unconditional
+                    const int32_t pos = __builtin_amdgcn_readlane(pos_reg, t & (kWave - 1));
+                    w[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_reg), t & (kWave - 1)));
+                    ok[u] = t < cnt && pos >= 0;
+                    const float x = slice_partial[static_cast<long long>(max(pos, 0)) * D + c];
+                    v[u] = ok[u] ? x : 0.0f;
+                } else {
+                    const int32_t pos = __shfl(pos_reg, t & (kWave - 1), kWave);
+                    w[u] = __shfl(w_reg, t & (kWave - 1), kWave);
+                    ok[u] = t < cnt && pos >= 0;
+                    v[u] = ok[u] ? slice_partial[static_cast<long long>(pos) * D + c] : 0.0f;
+                }
             }
             if constexpr (WEIGHTED) {
                 float dot[8];

@@ -257,11 +257,23 @@ __global__ __launch_bounds__(256) void fused_reduce_kernel(long long n, int H, i
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int t = t0 + u * EPW + sub;
-                const int32_t pos = __shfl(pos_reg, t & (kWave - 1), kWave);
-                w[u] = __shfl(w_reg, t & (kWave - 1), kWave);
-                const bool ok = t < cnt && pos >= 0;
-                v[u] = ok ? slice_partial[static_cast<long long>(pos) * D + c] : 0.0f;
-                dv[u] = ok ? slice_pden[pos] : 0.0f;
+                if constexpr (EPW == 1) {
+                    // the entry is the same in every lane: scalar broadcasts, a row address in scalar registers and a
+                    // scalar load of the partial denominator; the loads are unconditional
+                    const int32_t pos = __builtin_amdgcn_readlane(pos_reg, t & (kWave - 1));
+                    w[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_reg), t & (kWave - 1)));
+                    const bool ok = t < cnt && pos >= 0;
+                    const float x = slice_partial[static_cast<long long>(max(pos, 0)) * D + c];
+                    const float dx = slice_pden[max(pos, 0)];
+                    v[u] = ok ? x : 0.0f;
+                    dv[u] = ok ? dx : 0.0f;
+                } else {
+                    const int32_t pos = __shfl(pos_reg, t & (kWave - 1), kWave);
+                    w[u] = __shfl(w_reg, t & (kWave - 1), kWave);
+                    const bool ok = t < cnt && pos >= 0;
+                    v[u] = ok ? slice_partial[static_cast<long long>(pos) * D + c] : 0.0f;
+                    dv[u] = ok ? slice_pden[pos] : 0.0f;
+                }
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) { acc = fmaf(w[u], v[u], acc); dacc = fmaf(w[u], dv[u], dacc); }
