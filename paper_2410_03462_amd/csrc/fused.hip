@@ -17,6 +17,7 @@
 // T2*x + t, so that a lane's T2 operands are adjacent in memory (one 8-byte load at d = 64).
 #include "attention_common.hpp"
 #include "fused_bf16.hpp"
+#include "fused_split.hpp"
 
 namespace grf {
 
@@ -315,6 +316,15 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
                                    static_cast<int32_t>(nnz), spread, partial, pden);
                 return;
             }
+        }
+        if constexpr (D == 64 && std::is_same<T, float>::value) {
+            hipLaunchKernelGGL((fused_bucket_split_kernel<W>), dim3(static_cast<unsigned>(waves)), dim3(kWave), 0, stream,
+                               static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+                               static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
+                               static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
+                               static_cast<const float*>(t.s_val), fmap, static_cast<long long>(bh_first), waves,
+                               static_cast<int32_t>(nnz), spread, partial, pden);
+            return;
         }
         hipLaunchKernelGGL((fused_bucket_kernel<D, T, W>), dim3(resident_wave_grid(reinterpret_cast<const void*>(&fused_bucket_kernel<D, T, W>), waves)), dim3(kWave), 0, stream,
                            static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),

@@ -1,0 +1,251 @@
+// Bucket-fused evaluation (Eq. 7; Alg. 1 steps 3-5) for fp32 inputs at d = 64 on the bf16 matrix cores.
+//
+// v_mfma_f32_32x32x2_f32 shares the vector ALU and delivers 157 TFLOP/s; v_mfma_f32_32x32x16_bf16 runs beside
+// the vector ALU at sixteen times that rate.  An fp32 number is the sum of three bf16 numbers to within 2^-26
+// (h = nearest bf16 of x, m = nearest bf16 of x - h, l = nearest bf16 of x - h - m), products of bf16 numbers
+// are exact in fp32 and the matrix cores accumulate in fp32, so
+//     a b  =  a_h b_h + (a_h b_m + a_m b_h) + (a_h b_l + a_l b_h + a_m b_m)  +  O(2^-25 |a b|)
+// is an fp32 product from six bf16 MFMAs, at a third of the fp32 instruction's cost.  Both contractions of a
+// bucket are done this way; the vector ALU does the splitting meanwhile.
+//
+// Index convention as in the bf16-input kernel: MFMA row/column x of tile t stands for feature / value column
+// 2x + t (a lane's two tiles are the two floats of one 8-byte load).  Lane L = 32 g + f; in every operand the
+// lanes of group g carry depth slots (g, 0..7) of the instruction, two bf16 per register.
+#pragma once
+
+#include "fused_bf16.hpp"
+
+namespace grf {
+
+// (x, y) as h + m + l, two bf16 numbers each.
+__device__ __forceinline__ void split3_bf16(float x, float y, uint32_t& h, uint32_t& m, uint32_t& l)
+{
+    h = pack_bf16(x, y);
+    const float rx = x - low_bf16(h), ry = y - high_bf16(h);
+    m = pack_bf16(rx, ry);
+    l = pack_bf16(rx - low_bf16(m), ry - high_bf16(m));
+}
+
+// acc += a b for operands given as three pieces each: the six products that matter, small ones first.
+__device__ __forceinline__ void mfma_split3(const uint32_t (&a)[3][4], const uint32_t (&b)[3][4], floatx16& acc)
+{
+    const bf16x8 ah = as_operand(a[0]), am = as_operand(a[1]), al = as_operand(a[2]);
+    const bf16x8 bh = as_operand(b[0]), bm = as_operand(b[1]), bl = as_operand(b[2]);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bm, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bh, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bm, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc, 0, 0, 0);
+}
+
+// One wavefront per (slice, bucket l), one wavefront per workgroup; structure as fused_bucket_bf16_kernel:
+// 16 members of the column list per step of the first contraction (lane (g, f) takes members 8 g + 0..7 and
+// loads floats 2f, 2f + 1 of their rows of K and V), 32 consumers per step of the second, whose B operand is
+// the accumulators' registers 8 h + 0..7 split into pieces once per bucket.  z_l is summed on the vector ALU
+// beside the first contraction and handed to the lanes in the order of their depth slots with ds_bpermute; the
+// partial denominator phi(q) . z_l is 32 fused multiply-adds per lane and tile.
+template <bool WIDE>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fused_bucket_split_kernel(
+    const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V, long long n, int H, int n_f,
+    const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row, const float* __restrict__ csc_val, int fmap,
+    long long bh_first, long long n_waves, int32_t nnz, int spread_xcds, float* __restrict__ partial, float* __restrict__ pden)
+{
+    constexpr int D = 64;
+    // bucket of this workgroup: see fused_bucket_bf16_kernel
+    if (blockIdx.x >= n_waves) return;
+    const uint32_t n32 = static_cast<uint32_t>(n);
+    uint32_t slice32, l32;
+    if (spread_xcds) {
+        const uint32_t wave = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x, gridDim.x));
+        slice32 = wave / n32;
+        l32 = wave - slice32 * n32;
+    } else {
+        slice32 = blockIdx.x / n32;
+        l32 = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x - slice32 * n32, n32));
+    }
+    const long long slice = slice32;
+    const long long bh = bh_first + slice;
+    const long long plane = n_f > 1 ? (static_cast<uint32_t>(bh) % static_cast<uint32_t>(H)) : 0u;
+    const float* Qb = Q + bh * n * D;
+    const float* Kb = K + bh * n * D;
+    const float* Vb = V + bh * n * D;
+    const float* vals = csc_val + plane * nnz;
+
+    const int lane = lane_id();
+    const int g = lane >> 5;
+    const int f = lane & 31;
+
+    const int32_t beg = __builtin_amdgcn_readfirstlane(col_ptr[l32]);
+    const int32_t end = __builtin_amdgcn_readfirstlane(col_ptr[l32 + 1]);
+    if (beg >= end) return;      // nobody visits this node: no partial rows belong to it
+
+    // consumer f's q at the features of depth slots (g, .): floats 2 rho, 2 rho + 1 for rho = 8 hr + 4 g + 0..3
+    auto fetch_q = [&](int32_t row, float4 (&qw)[8]) {
+#pragma unroll
+        for (int hr = 0; hr < 4; ++hr) {
+            const float4* p = reinterpret_cast<const float4*>(row_elem_ptr<D, float, WIDE>(Qb, static_cast<uint32_t>(row), 2 * (8 * hr + 4 * g)));
+            qw[2 * hr] = p[0];
+            qw[2 * hr + 1] = p[1];
+        }
+    };
+    auto fetch_index = [&](int32_t tile, int32_t& row) { row = csc_row[min(tile + f, end - 1)]; };
+
+    // the first two consumer tiles' indices and the first tile's rows of Q go out before the first contraction
+    int32_t qrow_cur, qrow_next;
+    fetch_index(beg, qrow_cur);
+    fetch_index(beg + 32, qrow_next);
+    float4 qn[8];
+    fetch_q(qrow_cur, qn);
+
+    // ---- S_l = A^T V_l, z_l = A^T 1
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
+    float zacc[2] = {0.0f, 0.0f};
+
+    struct Members { float2 k[8], v[8]; float w[8]; };
+    auto fetch_members = [&](int32_t jv, float gv, int first, Members& m) {
+        int addr = 4 * ((first + 8 * g) & (kWave - 1));
+        asm volatile("" : "+v"(addr));      // one register, the members' offsets as literals
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t row = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(addr + 4 * j, jv));
+            m.w[j] = __int_as_float(__builtin_amdgcn_ds_bpermute(addr + 4 * j, __float_as_int(gv)));
+            m.k[j] = *reinterpret_cast<const float2*>(row_elem_ptr<D, float, WIDE>(Kb, row, 2 * f));
+            m.v[j] = *reinterpret_cast<const float2*>(row_elem_ptr<D, float, WIDE>(Vb, row, 2 * f));
+        }
+    };
+    auto contract_members = [&](const Members& m) {
+        uint32_t a_p[2][3][4], b_p[2][3][4];      // [tile][piece][register]
+        with_feature_map(fmap, [&](auto fm) {
+            constexpr int FM = decltype(fm)::value;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const float x0 = m.w[2 * p] * feature_ct<FM>(m.k[2 * p].x), x1 = m.w[2 * p + 1] * feature_ct<FM>(m.k[2 * p + 1].x);
+                const float y0 = m.w[2 * p] * feature_ct<FM>(m.k[2 * p].y), y1 = m.w[2 * p + 1] * feature_ct<FM>(m.k[2 * p + 1].y);
+                zacc[0] += x0 + x1;
+                zacc[1] += y0 + y1;
+                split3_bf16(x0, x1, a_p[0][0][p], a_p[0][1][p], a_p[0][2][p]);
+                split3_bf16(y0, y1, a_p[1][0][p], a_p[1][1][p], a_p[1][2][p]);
+            }
+        });
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            split3_bf16(m.v[2 * p].x, m.v[2 * p + 1].x, b_p[0][0][p], b_p[0][1][p], b_p[0][2][p]);
+            split3_bf16(m.v[2 * p].y, m.v[2 * p + 1].y, b_p[1][0][p], b_p[1][1][p], b_p[1][2][p]);
+        }
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) mfma_split3(a_p[a], b_p[c], acc[a][c]);
+    };
+
+    for (int32_t block = beg; block < end; block += 2 * kWave) {
+        ListBlock lb = load_list_block<false>(csc_row, vals, nullptr, block, end);
+        // all four of the block's loads are taken here, where the first two are needed anyway: requested later
+        // (the compiler sinks the second pair to its first use), they would return behind the rows' loads
+        asm volatile("" : "+v"(lb.j_a), "+v"(lb.j_b), "+v"(lb.g_a), "+v"(lb.g_b));
+        const int steps = min((end - block + 15) >> 4, 8);
+        // two register sets take turns: the next step's rows are requested before this step's arithmetic (past the
+        // block's last step the request is redundant and re-reads entries of the block)
+        Members even, odd;
+        __builtin_amdgcn_sched_barrier(0);
+        fetch_members(lb.j_a, lb.g_a, 0, even);
+#pragma nounroll
+        for (int s = 0; s < steps; s += 2) {
+            __builtin_amdgcn_sched_barrier(0);
+            fetch_members(s + 1 >= 4 ? lb.j_b : lb.j_a, s + 1 >= 4 ? lb.g_b : lb.g_a, 16 * (s + 1), odd);
+            __builtin_amdgcn_sched_barrier(0);
+            contract_members(even);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch_members(s + 2 >= 4 ? lb.j_b : lb.j_a, s + 2 >= 4 ? lb.g_b : lb.g_a, 16 * (s + 2), even);
+            __builtin_amdgcn_sched_barrier(0);
+            // also when step s + 1 lies past the end of the list (its members then have weight 0): were it skipped,
+            // the compiler would move the step's loads into the branch, next to their use
+            contract_members(odd);
+        }
+    }
+
+    // ---- z_l at the features of this lane's depth slots: lane rho of either group holds z[2 rho + a]
+    float zs[2][16];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        const float zfull = zacc[a] + __shfl_xor(zacc[a], 32, kWave);
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            zs[a][r] = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (8 * (r / 4) + 4 * g + (r % 4)), __float_as_int(zfull)));
+    }
+
+    // ---- the accumulators in pieces, in the registers' own order: [a][c][h] holds registers 8 h + 0..7
+    uint32_t s_p[2][2][2][3][4];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int p = 0; p < 4; ++p)
+                    split3_bf16(acc[a][c][8 * h + 2 * p], acc[a][c][8 * h + 2 * p + 1], s_p[a][c][h][0][p], s_p[a][c][h][1][p], s_p[a][c][h][2][p]);
+
+    // ---- P_l = phi(Q_l) S_l and pden_l = phi(Q_l) z_l, 32 consumers at a time
+    const long long pbase = slice * nnz;
+    for (int32_t tile = beg; tile < end; tile += 32) {
+        // phi(q) of this tile, register 8 h + j of depth slot (g, j): feature 2 (8 (2 h + j / 4) + 4 g + j % 4) + a
+        float fq[2][16];
+        with_feature_map(fmap, [&](auto fm) {
+            constexpr int FM = decltype(fm)::value;
+#pragma unroll
+            for (int hr = 0; hr < 4; ++hr) {
+                const float4 u = qn[2 * hr], v = qn[2 * hr + 1];
+                fq[0][4 * hr] = feature_ct<FM>(u.x); fq[1][4 * hr] = feature_ct<FM>(u.y);
+                fq[0][4 * hr + 1] = feature_ct<FM>(u.z); fq[1][4 * hr + 1] = feature_ct<FM>(u.w);
+                fq[0][4 * hr + 2] = feature_ct<FM>(v.x); fq[1][4 * hr + 2] = feature_ct<FM>(v.y);
+                fq[0][4 * hr + 3] = feature_ct<FM>(v.z); fq[1][4 * hr + 3] = feature_ct<FM>(v.w);
+            }
+        });
+        // next tile's rows of Q, and the indices of the tile after it
+        fetch_q(qrow_next, qn);
+        fetch_index(tile + 64, qrow_next);
+
+        float dl = 0.0f;
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dl = fmaf(fq[a][r], zs[a][r], dl);
+        dl += __shfl_xor(dl, 32, kWave);
+        if (g == 0 && tile + f < end) pden[pbase + tile + f] = dl;
+
+        floatx16 pc[2];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { pc[0][r] = 0.0f; pc[1][r] = 0.0f; }
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                uint32_t q_p[3][4];
+#pragma unroll
+                for (int p = 0; p < 4; ++p) split3_bf16(fq[a][8 * h + 2 * p], fq[a][8 * h + 2 * p + 1], q_p[0][p], q_p[1][p], q_p[2][p]);
+#pragma unroll
+                for (int c = 0; c < 2; ++c) mfma_split3(q_p, s_p[a][c][h], pc[c]);
+            }
+
+        // register r of pc[c] is consumer tile + 8 (r / 4) + 4 g + r % 4, column 2 f + c: one 8-byte store per
+        // register pair through a window over the tile's rows, which drops the rows past the end of the list
+        const __amdgpu_buffer_rsrc_t window = row_window(partial, pbase + tile, min(end - tile, 32), D);
+        int lane_off = (4 * g * D + 2 * f) * 4;
+        asm volatile("" : "+v"(lane_off));
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const uintx2 v = {__float_as_uint(pc[0][r]), __float_as_uint(pc[1][r])};
+            __builtin_amdgcn_raw_buffer_store_b64(v, window, lane_off + (8 * (r / 4) + (r % 4)) * D * 4, 0, 0);
+        }
+    }
+}
+
+}  // namespace grf
