@@ -23,10 +23,9 @@
 #include <type_traits>
 
 #include "attention_common.hpp"
+#include "backward_split.hpp"
 
 namespace grf {
-
-enum : int { kQuerySide = 0, kKeySide = 1, kValueSide = 2 };
 
 // g' per row of a chunk of slices: G[s][i][:] = d_out / den, gd[s][i] = -(d_out . out) / den.
 template <int D>
@@ -407,6 +406,15 @@ grf_status launch_backward_chunk(const void* Qv, const void* Kv, const void* Vv,
     const int spread = 8ll * n * D * (3 * static_cast<long long>(sizeof(T)) + 4) <= (64ll << 20) ? 1 : 0;
     auto bucket_pass = [&](auto mode) {
         auto launch = [&](auto w) {
+            if constexpr (D == 64) {
+                if (split_products(n, nnz)) {
+                    hipLaunchKernelGGL((backward_bucket_split_kernel<T, decltype(mode)::value, decltype(w)::value>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
+                                       static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),
+                                       static_cast<int>(H), static_cast<int>(n_f), col_ptr, s_row, s_val, fmap,
+                                       static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), spread, b.partial);
+                    return;
+                }
+            }
             hipLaunchKernelGGL((backward_bucket_kernel<D, T, decltype(mode)::value, decltype(w)::value>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
                                static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),
                                static_cast<int>(H), static_cast<int>(n_f), col_ptr, s_row, s_val, fmap,

@@ -307,7 +307,7 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
         constexpr bool W = decltype(wide)::value;
         if constexpr (D == 64 && std::is_same<T, bf16_t>::value) {
             // feature maps that keep bf16 values bf16 go to the bf16 matrix cores
-            if (fmap != GRF_PHI_ELU1) {
+            if (fmap != GRF_PHI_ELU1 && split_products(n, nnz)) {
                 hipLaunchKernelGGL((fused_bucket_bf16_kernel<W>), dim3(static_cast<unsigned>(waves)), dim3(kWave), 0, stream,
                                    static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                                    static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
@@ -317,7 +317,7 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
                 return;
             }
         }
-        if constexpr (D == 64 && std::is_same<T, float>::value) {
+        if constexpr (D == 64 && std::is_same<T, float>::value) if (split_products(n, nnz)) {
             hipLaunchKernelGGL((fused_bucket_split_kernel<W>), dim3(static_cast<unsigned>(waves)), dim3(kWave), 0, stream,
                                static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                                static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),

@@ -16,10 +16,10 @@ pytestmark = pytest.mark.gpu
 TOL = {"f32": 1e-5, "bf16": 2e-2}
 FEATURE_MAP_CODE = {"relu": 0, "identity": 1, "elu1": 2}
 N_CASES = 96
-# further indices that once failed: 204 has rows of Phi_hat with one small entry, where the asymmetric gradients cancel;
-# 922 is a star graph whose Phi_hat spans 0.1 .. 374, where dphi is 1/230 of the absolute sum of its terms
+# further indices that once failed: 204 has rows of Phi_hat with one small entry, where the gradients cancel (df is 1/28000
+# of the absolute sum of its terms); 922 is a star graph whose Phi_hat spans 0.1 .. 374, where dphi is 1/230 of that sum
 EXTRA_CASES = [204, 922]
-ILL_CONDITIONED = {922}
+ILL_CONDITIONED = {204, 922}
 
 
 @pytest.fixture(scope="module")
@@ -60,7 +60,7 @@ def check_gradients(got, ref, tol, label, diagonal, dphi_floor=0.0):
 
 
 def dphi_term_scale(oracle, Q, K, V, rp, col, val, out, den, d_out):
-    """max over the stored entries of the sum of the absolute values of the terms of dL/dPhi_hat[i,l] =
+    """Per stored entry, the sum of the absolute values of the terms of dL/dPhi_hat[i,l] =
     sum_j (a_ij c_ij + a_ji c_ji) Phi_hat[j,l], a_ij = phi(q_i).phi(k_j) (phi = elu + 1), c_ij = g_i.v_j + gd_i with
     the two parts of c_ij taken apart, summed over the slices of a value plane.  fp32 arithmetic in any order is good
     to a few units in the last place of this, not of the (possibly much smaller) sum itself."""
@@ -76,7 +76,7 @@ def dphi_term_scale(oracle, Q, K, V, rp, col, val, out, den, d_out):
             A = np.abs(elu1(Q[b, h].astype(np.float64)) @ elu1(K[b, h].astype(np.float64)).T)
             X = A * (np.abs(gp[:, :-1] @ V[b, h].astype(np.float64).T) + np.abs(gp[:, -1:]))
             scale[plane] += ((X + X.T) @ P)[rows, col]
-    return float(scale.max())
+    return scale
 
 
 def draw_case(index):
@@ -158,17 +158,24 @@ def test_random_case(grf, oracle, index):
                                                    bh_chunk=chunk)
     host = [t.cpu().numpy() for t in got]
     host[3] = host[3][:, : phi_pos.nnz]
-    floor = 0.0
+    floor, df_floor = 0.0, 0.0
     if index in ILL_CONDITIONED:
         scale = dphi_term_scale(oracle, Q, K, V, rp1, col1, val1, out32, den32, d_out)
-        assert scale > 100 * np.abs(bref[3]).max()          # the case is what its name says
-        floor = 2.0 ** -22 * scale                          # four units in the last place of the terms' size
+        # df is a sum of dphi's entries with non-negative coefficients (the walks' loads): the same sum of the scales
+        df_scale = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp1, col1, scale)
+        df_plain = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp1, col1, bref[3])
+        # the case is what its name says
+        assert scale.max() > 100 * np.abs(bref[3]).max() or df_scale.max() > 100 * np.abs(df_plain).max()
+        floor = 2.0 ** -22 * scale.max()                    # four units in the last place of the terms' size
+        df_floor = 2.0 ** -22 * df_scale.max()
     check_gradients(host, bref, tol, "", diagonal, dphi_floor=floor)
     df = grf.grf_sample_backward(g, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, phi_pos, got[3]).cpu().numpy()
     df_ref = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp1, col1, bref[3])
     assert df.shape == df_ref.shape and np.isfinite(df).all()
     if not diagonal:
         for h in range(wl.n_f):
+            if np.abs(df[h] - df_ref[h]).max() <= df_floor:
+                continue
             assert relerr(df[h], df_ref[h]) <= 10 * tol, (h, relerr(df[h], df_ref[h]))
 
     # ---- the same for asymmetric features (per-head planes allowed)
