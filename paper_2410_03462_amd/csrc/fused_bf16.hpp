@@ -33,11 +33,30 @@ __device__ __forceinline__ uint32_t pack_bf16(float x, float y)
 __device__ __forceinline__ float low_bf16(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float high_bf16(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
+// x minus the low (minus_low_bf16) or high (minus_high_bf16) bf16 of w, exactly: one v_dot2c_f32_bf16 each, x + w . (-1, 0)
+// or x + w . (0, -1), instead of a shift or mask and a subtraction.  (Every intermediate value is an fp32 number, so
+// the result does not depend on how the instruction orders its three terms.)
+// The selector pairs are handed over in registers: written as literals, the compiler encodes (-1, 0) as the inline
+// constant -1.0, which the instruction does not read as a bf16 pair.
+__device__ __forceinline__ uint32_t opaque_word(uint32_t w)
+{
+    asm("" : "+s"(w));      // not volatile: identical uses are merged into one scalar register
+    return w;
+}
+__device__ __forceinline__ float minus_low_bf16(float x, uint32_t w)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, opaque_word(0x0000bf80u)), x, false);
+}
+__device__ __forceinline__ float minus_high_bf16(float x, uint32_t w)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, opaque_word(0xbf800000u)), x, false);
+}
+
 // (x, y) as hi + lo, two bf16 numbers each.
 __device__ __forceinline__ void split_bf16(float x, float y, uint32_t& hi, uint32_t& lo)
 {
     hi = pack_bf16(x, y);
-    lo = pack_bf16(x - low_bf16(hi), y - high_bf16(hi));
+    lo = pack_bf16(minus_low_bf16(x, hi), minus_high_bf16(y, hi));
 }
 
 __device__ __forceinline__ uint32_t low_halves(uint32_t x, uint32_t y) { return (x & 0xffffu) | (y << 16); }

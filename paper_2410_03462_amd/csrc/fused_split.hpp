@@ -21,9 +21,9 @@ namespace grf {
 __device__ __forceinline__ void split3_bf16(float x, float y, uint32_t& h, uint32_t& m, uint32_t& l)
 {
     h = pack_bf16(x, y);
-    const float rx = x - low_bf16(h), ry = y - high_bf16(h);
+    const float rx = minus_low_bf16(x, h), ry = minus_high_bf16(y, h);
     m = pack_bf16(rx, ry);
-    l = pack_bf16(rx - low_bf16(m), ry - high_bf16(m));
+    l = pack_bf16(minus_low_bf16(rx, m), minus_high_bf16(ry, m));
 }
 
 // acc += a b for operands given as three pieces each: the six products that matter, small ones first.
