@@ -341,10 +341,6 @@ inline unsigned blocks_for(long long items, int per_block) { return static_cast<
 // 64-bit row offsets (row_elem_ptr).
 bool wide_offsets(int64_t n, int32_t d);
 
-// Whether the d = 64 bucket kernels run their contractions as bf16 MFMAs on operands split into pieces rather than
-// as fp32 MFMAs.
-inline bool split_products(int64_t, int64_t) { return true; }
-
 // Dispatch on (d, dtype) to the compiled instances.
 #define GRF_DISPATCH(d, dtype, CALL)                                                     \
     do {                                                                                 \

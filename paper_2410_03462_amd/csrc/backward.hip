@@ -406,19 +406,17 @@ grf_status launch_backward_chunk(const void* Qv, const void* Kv, const void* Vv,
     const int spread = 8ll * n * D * (3 * static_cast<long long>(sizeof(T)) + 4) <= (64ll << 20) ? 1 : 0;
     auto bucket_pass = [&](auto mode) {
         auto launch = [&](auto w) {
-            if constexpr (D == 64) {
-                if (split_products(n, nnz)) {
-                    hipLaunchKernelGGL((backward_bucket_split_kernel<T, decltype(mode)::value, decltype(w)::value>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
-                                       static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),
-                                       static_cast<int>(H), static_cast<int>(n_f), col_ptr, s_row, s_val, fmap,
-                                       static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), spread, b.partial);
-                    return;
-                }
+            if constexpr (D == 64) {      // on the bf16 matrix cores
+                hipLaunchKernelGGL((backward_bucket_split_kernel<T, decltype(mode)::value, decltype(w)::value>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
+                                   static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),
+                                   static_cast<int>(H), static_cast<int>(n_f), col_ptr, s_row, s_val, fmap,
+                                   static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), spread, b.partial);
+            } else {
+                hipLaunchKernelGGL((backward_bucket_kernel<D, T, decltype(mode)::value, decltype(w)::value>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
+                                   static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),
+                                   static_cast<int>(H), static_cast<int>(n_f), col_ptr, s_row, s_val, fmap,
+                                   static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), spread, b.partial);
             }
-            hipLaunchKernelGGL((backward_bucket_kernel<D, T, decltype(mode)::value, decltype(w)::value>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
-                               static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),
-                               static_cast<int>(H), static_cast<int>(n_f), col_ptr, s_row, s_val, fmap,
-                               static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), spread, b.partial);
         };
         if (wide) launch(std::true_type{}); else launch(std::false_type{});
     };

@@ -17,33 +17,6 @@ namespace grf {
 
 enum : int { kQuerySide = 0, kKeySide = 1, kValueSide = 2 };
 
-// Elements 2f, 2f + 1 of a row as loaded (one 8-byte or one 4-byte load), widened to fp32 only where they are used.
-template <typename T> struct RawPair { typedef float2 type; };
-template <> struct RawPair<bf16_t> { typedef uint32_t type; };
-
-template <typename T, bool WIDE>
-__device__ __forceinline__ typename RawPair<T>::type load_pair(const T* __restrict__ base, uint32_t row, int f)
-{
-    return *reinterpret_cast<const typename RawPair<T>::type*>(row_elem_ptr<64, T, WIDE>(base, row, 2 * f));
-}
-__device__ __forceinline__ float2 widen(float2 v) { return v; }
-__device__ __forceinline__ float2 widen(uint32_t w) { return make_float2(low_bf16(w), high_bf16(w)); }
-
-// Eight consecutive elements of a row starting at element `elem` (a multiple of 8), widened to fp32.
-template <typename T, bool WIDE>
-__device__ __forceinline__ void load_eight(const T* __restrict__ base, uint32_t row, int elem, float (&x)[8])
-{
-    if constexpr (sizeof(T) == 4) {
-        const float4* p = reinterpret_cast<const float4*>(row_elem_ptr<64, T, WIDE>(base, row, elem));
-        const float4 u = p[0], v = p[1];
-        x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w; x[4] = v.x; x[5] = v.y; x[6] = v.z; x[7] = v.w;
-    } else {
-        const uintx4 w = *reinterpret_cast<const uintx4*>(row_elem_ptr<64, T, WIDE>(base, row, elem));
-#pragma unroll
-        for (int k = 0; k < 4; ++k) { x[2 * k] = low_bf16(w[k]); x[2 * k + 1] = high_bf16(w[k]); }
-    }
-}
-
 // One wavefront per (slice, bucket l), one wavefront per workgroup; every global load is unconditional (members
 // past the end of the column list re-read its last entry with weight 0).  16 members of the list per step of the
 // first contraction (lane (g, f) takes members 8 g + 0..7 and loads elements 2f, 2f + 1 of their two rows), 32

@@ -305,33 +305,29 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
     const int spread = 8ll * 3 * n * D * static_cast<long long>(sizeof(T)) <= (64ll << 20) ? 1 : 0;
     auto launch = [&](auto wide) {
         constexpr bool W = decltype(wide)::value;
-        if constexpr (D == 64 && std::is_same<T, bf16_t>::value) {
-            // feature maps that keep bf16 values bf16 go to the bf16 matrix cores
-            if (fmap != GRF_PHI_ELU1 && split_products(n, nnz)) {
-                hipLaunchKernelGGL((fused_bucket_bf16_kernel<W>), dim3(static_cast<unsigned>(waves)), dim3(kWave), 0, stream,
+        if constexpr (D == 64) {
+            // d = 64 runs on the bf16 matrix cores: bf16 inputs under a feature map that keeps bf16 values bf16 with
+            // two-piece fp32 operands, everything else with three-piece operands and six products
+            auto go = [&](auto kernel) {
+                hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(waves)), dim3(kWave), 0, stream,
                                    static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                                    static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
                                    static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
                                    static_cast<const float*>(t.s_val), fmap, static_cast<long long>(bh_first), waves,
                                    static_cast<int32_t>(nnz), spread, partial, pden);
-                return;
+            };
+            if constexpr (std::is_same<T, bf16_t>::value) {
+                if (fmap != GRF_PHI_ELU1) { go(fused_bucket_bf16_kernel<W>); return; }
             }
-        }
-        if constexpr (D == 64 && std::is_same<T, float>::value) if (split_products(n, nnz)) {
-            hipLaunchKernelGGL((fused_bucket_split_kernel<W>), dim3(static_cast<unsigned>(waves)), dim3(kWave), 0, stream,
+            go(fused_bucket_split_kernel<T, W>);
+        } else {
+            hipLaunchKernelGGL((fused_bucket_kernel<D, T, W>), dim3(resident_wave_grid(reinterpret_cast<const void*>(&fused_bucket_kernel<D, T, W>), waves)), dim3(kWave), 0, stream,
                                static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                                static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
                                static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
                                static_cast<const float*>(t.s_val), fmap, static_cast<long long>(bh_first), waves,
                                static_cast<int32_t>(nnz), spread, partial, pden);
-            return;
         }
-        hipLaunchKernelGGL((fused_bucket_kernel<D, T, W>), dim3(resident_wave_grid(reinterpret_cast<const void*>(&fused_bucket_kernel<D, T, W>), waves)), dim3(kWave), 0, stream,
-                           static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
-                           static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
-                           static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
-                           static_cast<const float*>(t.s_val), fmap, static_cast<long long>(bh_first), waves,
-                           static_cast<int32_t>(nnz), spread, partial, pden);
     };
     if (wide_offsets(n, D)) launch(std::true_type{}); else launch(std::false_type{});
     GRF_LAUNCH_CHECK("fused_bucket_kernel");

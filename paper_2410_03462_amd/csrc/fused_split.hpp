@@ -1,4 +1,5 @@
-// Bucket-fused evaluation (Eq. 7; Alg. 1 steps 3-5) for fp32 inputs at d = 64 on the bf16 matrix cores.
+// Bucket-fused evaluation (Eq. 7; Alg. 1 steps 3-5) at d = 64 on the bf16 matrix cores with fp32-grade products
+// (fp32 inputs; bf16 inputs under a feature map whose values are not bf16 numbers).
 //
 // v_mfma_f32_32x32x2_f32 shares the vector ALU and delivers 157 TFLOP/s; v_mfma_f32_32x32x16_bf16 runs beside
 // the vector ALU at sixteen times that rate.  An fp32 number is the sum of three bf16 numbers to within 2^-26
@@ -39,15 +40,42 @@ __device__ __forceinline__ void mfma_split3(const uint32_t (&a)[3][4], const uin
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc, 0, 0, 0);
 }
 
+// Elements 2f, 2f + 1 of a row as loaded (one 8-byte or one 4-byte load), widened to fp32 only where they are used.
+template <typename T> struct RawPair { typedef float2 type; };
+template <> struct RawPair<bf16_t> { typedef uint32_t type; };
+
+template <typename T, bool WIDE>
+__device__ __forceinline__ typename RawPair<T>::type load_pair(const T* __restrict__ base, uint32_t row, int f)
+{
+    return *reinterpret_cast<const typename RawPair<T>::type*>(row_elem_ptr<64, T, WIDE>(base, row, 2 * f));
+}
+__device__ __forceinline__ float2 widen(float2 v) { return v; }
+__device__ __forceinline__ float2 widen(uint32_t w) { return make_float2(low_bf16(w), high_bf16(w)); }
+
+// Eight consecutive elements of a row starting at element `elem` (a multiple of 8), widened to fp32.
+template <typename T, bool WIDE>
+__device__ __forceinline__ void load_eight(const T* __restrict__ base, uint32_t row, int elem, float (&x)[8])
+{
+    if constexpr (sizeof(T) == 4) {
+        const float4* p = reinterpret_cast<const float4*>(row_elem_ptr<64, T, WIDE>(base, row, elem));
+        const float4 u = p[0], v = p[1];
+        x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w; x[4] = v.x; x[5] = v.y; x[6] = v.z; x[7] = v.w;
+    } else {
+        const uintx4 w = *reinterpret_cast<const uintx4*>(row_elem_ptr<64, T, WIDE>(base, row, elem));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { x[2 * k] = low_bf16(w[k]); x[2 * k + 1] = high_bf16(w[k]); }
+    }
+}
+
 // One wavefront per (slice, bucket l), one wavefront per workgroup; structure as fused_bucket_bf16_kernel:
 // 16 members of the column list per step of the first contraction (lane (g, f) takes members 8 g + 0..7 and
 // loads floats 2f, 2f + 1 of their rows of K and V), 32 consumers per step of the second, whose B operand is
 // the accumulators' registers 8 h + 0..7 split into pieces once per bucket.  z_l is summed on the vector ALU
 // beside the first contraction and handed to the lanes in the order of their depth slots with ds_bpermute; the
 // partial denominator phi(q) . z_l is 32 fused multiply-adds per lane and tile.
-template <bool WIDE>
+template <typename T, bool WIDE>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fused_bucket_split_kernel(
-    const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V, long long n, int H, int n_f,
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, long long n, int H, int n_f,
     const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row, const float* __restrict__ csc_val, int fmap,
     long long bh_first, long long n_waves, int32_t nnz, int spread_xcds, float* __restrict__ partial, float* __restrict__ pden)
 {
@@ -67,9 +95,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
     const long long slice = slice32;
     const long long bh = bh_first + slice;
     const long long plane = n_f > 1 ? (static_cast<uint32_t>(bh) % static_cast<uint32_t>(H)) : 0u;
-    const float* Qb = Q + bh * n * D;
-    const float* Kb = K + bh * n * D;
-    const float* Vb = V + bh * n * D;
+    const T* Qb = Q + bh * n * D;
+    const T* Kb = K + bh * n * D;
+    const T* Vb = V + bh * n * D;
     const float* vals = csc_val + plane * nnz;
 
     const int lane = lane_id();
@@ -80,14 +108,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
     const int32_t end = __builtin_amdgcn_readfirstlane(col_ptr[l32 + 1]);
     if (beg >= end) return;      // nobody visits this node: no partial rows belong to it
 
-    // consumer f's q at the features of depth slots (g, .): floats 2 rho, 2 rho + 1 for rho = 8 hr + 4 g + 0..3
-    auto fetch_q = [&](int32_t row, float4 (&qw)[8]) {
+    // consumer f's q at the features of depth slots (g, .): elements 2 rho, 2 rho + 1 for rho = 8 hr + 4 g + 0..3
+    auto fetch_q = [&](int32_t row, float (&qw)[4][8]) {
 #pragma unroll
-        for (int hr = 0; hr < 4; ++hr) {
-            const float4* p = reinterpret_cast<const float4*>(row_elem_ptr<D, float, WIDE>(Qb, static_cast<uint32_t>(row), 2 * (8 * hr + 4 * g)));
-            qw[2 * hr] = p[0];
-            qw[2 * hr + 1] = p[1];
-        }
+        for (int hr = 0; hr < 4; ++hr) load_eight<T, WIDE>(Qb, static_cast<uint32_t>(row), 2 * (8 * hr + 4 * g), qw[hr]);
     };
     auto fetch_index = [&](int32_t tile, int32_t& row) { row = csc_row[min(tile + f, end - 1)]; };
 
@@ -95,7 +119,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
     int32_t qrow_cur, qrow_next;
     fetch_index(beg, qrow_cur);
     fetch_index(beg + 32, qrow_next);
-    float4 qn[8];
+    float qn[4][8];
     fetch_q(qrow_cur, qn);
 
     // ---- S_l = A^T V_l, z_l = A^T 1
@@ -108,7 +132,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
             for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
     float zacc[2] = {0.0f, 0.0f};
 
-    struct Members { float2 k[8], v[8]; float w[8]; };
+    struct Members { typename RawPair<T>::type k[8], v[8]; float w[8]; };
     auto fetch_members = [&](int32_t jv, float gv, int first, Members& m) {
         int addr = 4 * ((first + 8 * g) & (kWave - 1));
         asm volatile("" : "+v"(addr));      // one register, the members' offsets as literals
@@ -116,8 +140,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
         for (int j = 0; j < 8; ++j) {
             const uint32_t row = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(addr + 4 * j, jv));
             m.w[j] = __int_as_float(__builtin_amdgcn_ds_bpermute(addr + 4 * j, __float_as_int(gv)));
-            m.k[j] = *reinterpret_cast<const float2*>(row_elem_ptr<D, float, WIDE>(Kb, row, 2 * f));
-            m.v[j] = *reinterpret_cast<const float2*>(row_elem_ptr<D, float, WIDE>(Vb, row, 2 * f));
+            m.k[j] = load_pair<T, WIDE>(Kb, row, f);
+            m.v[j] = load_pair<T, WIDE>(Vb, row, f);
         }
     };
     auto contract_members = [&](const Members& m) {
@@ -126,8 +150,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
             constexpr int FM = decltype(fm)::value;
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                const float x0 = m.w[2 * p] * feature_ct<FM>(m.k[2 * p].x), x1 = m.w[2 * p + 1] * feature_ct<FM>(m.k[2 * p + 1].x);
-                const float y0 = m.w[2 * p] * feature_ct<FM>(m.k[2 * p].y), y1 = m.w[2 * p + 1] * feature_ct<FM>(m.k[2 * p + 1].y);
+                const float2 k0 = widen(m.k[2 * p]), k1 = widen(m.k[2 * p + 1]);
+                const float x0 = m.w[2 * p] * feature_ct<FM>(k0.x), x1 = m.w[2 * p + 1] * feature_ct<FM>(k1.x);
+                const float y0 = m.w[2 * p] * feature_ct<FM>(k0.y), y1 = m.w[2 * p + 1] * feature_ct<FM>(k1.y);
                 zacc[0] += x0 + x1;
                 zacc[1] += y0 + y1;
                 split3_bf16(x0, x1, a_p[0][0][p], a_p[0][1][p], a_p[0][2][p]);
@@ -136,8 +161,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
         });
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
-            split3_bf16(m.v[2 * p].x, m.v[2 * p + 1].x, b_p[0][0][p], b_p[0][1][p], b_p[0][2][p]);
-            split3_bf16(m.v[2 * p].y, m.v[2 * p + 1].y, b_p[1][0][p], b_p[1][1][p], b_p[1][2][p]);
+            const float2 v0 = widen(m.v[2 * p]), v1 = widen(m.v[2 * p + 1]);
+            split3_bf16(v0.x, v1.x, b_p[0][0][p], b_p[0][1][p], b_p[0][2][p]);
+            split3_bf16(v0.y, v1.y, b_p[1][0][p], b_p[1][1][p], b_p[1][2][p]);
         }
 #pragma unroll
         for (int a = 0; a < 2; ++a)
@@ -201,13 +227,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
         with_feature_map(fmap, [&](auto fm) {
             constexpr int FM = decltype(fm)::value;
 #pragma unroll
-            for (int hr = 0; hr < 4; ++hr) {
-                const float4 u = qn[2 * hr], v = qn[2 * hr + 1];
-                fq[0][4 * hr] = feature_ct<FM>(u.x); fq[1][4 * hr] = feature_ct<FM>(u.y);
-                fq[0][4 * hr + 1] = feature_ct<FM>(u.z); fq[1][4 * hr + 1] = feature_ct<FM>(u.w);
-                fq[0][4 * hr + 2] = feature_ct<FM>(v.x); fq[1][4 * hr + 2] = feature_ct<FM>(v.y);
-                fq[0][4 * hr + 3] = feature_ct<FM>(v.z); fq[1][4 * hr + 3] = feature_ct<FM>(v.w);
-            }
+            for (int hr = 0; hr < 4; ++hr)
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int a = 0; a < 2; ++a) fq[a][4 * hr + k] = feature_ct<FM>(qn[hr][2 * k + a]);
         });
         // next tile's rows of Q, and the indices of the tile after it
         fetch_q(qrow_next, qn);
