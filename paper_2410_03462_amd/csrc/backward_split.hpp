@@ -32,6 +32,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
     float* __restrict__ partial)
 {
     constexpr int D = 64;
+    // pieces per operand: fp32-grade products for fp32 inputs; with bf16 inputs (bar 2e-2) two pieces, three products
+    constexpr int NP = sizeof(T) == 2 ? 2 : 3;
     // bucket of this workgroup: see backward_bucket_kernel
     if (blockIdx.x >= n_waves) return;
     const uint32_t n32 = static_cast<uint32_t>(n);
@@ -121,7 +123,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
             w[j] = __int_as_float(__builtin_amdgcn_ds_bpermute(addr + 4 * j, __float_as_int(gv)));
             if constexpr (MODE == kKeySide) e[j] = __int_as_float(__builtin_amdgcn_ds_bpermute(addr + 4 * j, __float_as_int(ev)));
         }
-        uint32_t a_p[2][3][4], b_p[2][3][4];      // [tile][piece][register]
+        uint32_t a_p[2][NP][4], b_p[2][NP][4];      // [tile][piece][register]
         with_feature_map(fmap, [&](auto fm) {
             constexpr int FM = decltype(fm)::value;
 #pragma unroll
@@ -140,16 +142,16 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
                     xacc[0] = fmaf(e[2 * p], b0.x, fmaf(e[2 * p + 1], b1.x, xacc[0]));
                     xacc[1] = fmaf(e[2 * p], b0.y, fmaf(e[2 * p + 1], b1.y, xacc[1]));
                 }
-                split3_bf16(a0.x, a1.x, a_p[0][0][p], a_p[0][1][p], a_p[0][2][p]);
-                split3_bf16(a0.y, a1.y, a_p[1][0][p], a_p[1][1][p], a_p[1][2][p]);
-                split3_bf16(b0.x, b1.x, b_p[0][0][p], b_p[0][1][p], b_p[0][2][p]);
-                split3_bf16(b0.y, b1.y, b_p[1][0][p], b_p[1][1][p], b_p[1][2][p]);
+                split_pieces<NP>(a0.x, a1.x, a_p[0], p);
+                split_pieces<NP>(a0.y, a1.y, a_p[1], p);
+                split_pieces<NP>(b0.x, b1.x, b_p[0], p);
+                split_pieces<NP>(b0.y, b1.y, b_p[1], p);
             }
         });
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int c = 0; c < 2; ++c) mfma_split3(a_p[a], b_p[c], acc[a][c]);
+            for (int c = 0; c < 2; ++c) mfma_pieces<NP>(a_p[a], b_p[c], acc[a][c]);
     };
 
     for (int32_t block = beg; block < end; block += 2 * kWave) {
@@ -190,7 +192,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
     for (int c = 0; c < 2; ++c) extra[c] = xacc[c] + __shfl_xor(xacc[c], 32, kWave);
 
     // ---- the accumulators in pieces, in the registers' own order: [a][c][h] holds registers 8 h + 0..7
-    uint32_t s_p[2][2][2][3][4];
+    uint32_t s_p[2][2][2][NP][4];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -199,7 +201,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
             for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int p = 0; p < 4; ++p)
-                    split3_bf16(acc[a][c][8 * h + 2 * p], acc[a][c][8 * h + 2 * p + 1], s_p[a][c][h][0][p], s_p[a][c][h][1][p], s_p[a][c][h][2][p]);
+                    split_pieces<NP>(acc[a][c][8 * h + 2 * p], acc[a][c][8 * h + 2 * p + 1], s_p[a][c][h], p);
 
     // ---- second contraction, 32 consumers at a time.  The consumer's own weight Phi_hat[i, l] is left to the
     // reduce kernel.
@@ -242,11 +244,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
         for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                uint32_t c_p[3][4];
+                uint32_t c_p[NP][4];
 #pragma unroll
-                for (int p = 0; p < 4; ++p) split3_bf16(co[a][8 * h + 2 * p], co[a][8 * h + 2 * p + 1], c_p[0][p], c_p[1][p], c_p[2][p]);
+                for (int p = 0; p < 4; ++p) split_pieces<NP>(co[a][8 * h + 2 * p], co[a][8 * h + 2 * p + 1], c_p, p);
 #pragma unroll
-                for (int c = 0; c < 2; ++c) mfma_split3(c_p, s_p[a][c][h], pc[c]);
+                for (int c = 0; c < 2; ++c) mfma_pieces<NP>(c_p, s_p[a][c][h], pc[c]);
             }
 
         // one 8-byte store per register pair through a window over the tile's rows, which drops the rows past the

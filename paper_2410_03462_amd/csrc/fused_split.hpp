@@ -40,6 +40,26 @@ __device__ __forceinline__ void mfma_split3(const uint32_t (&a)[3][4], const uin
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc, 0, 0, 0);
 }
 
+// The same for operands in NP pieces (3, or 2 where a relative error of 2^-18 per operand is within the bar: bf16 inputs).
+template <int NP>
+__device__ __forceinline__ void split_pieces(float x, float y, uint32_t (&dst)[NP][4], int p)
+{
+    if constexpr (NP == 3) split3_bf16(x, y, dst[0][p], dst[1][p], dst[2][p]);
+    else split_bf16(x, y, dst[0][p], dst[1][p]);
+}
+template <int NP>
+__device__ __forceinline__ void mfma_pieces(const uint32_t (&a)[NP][4], const uint32_t (&b)[NP][4], floatx16& acc)
+{
+    if constexpr (NP == 3) {
+        mfma_split3(a, b, acc);
+    } else {
+        const bf16x8 ah = as_operand(a[0]), al = as_operand(a[1]), bh = as_operand(b[0]), bl = as_operand(b[1]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc, 0, 0, 0);
+    }
+}
+
 // Elements 2f, 2f + 1 of a row as loaded (one 8-byte or one 4-byte load), widened to fp32 only where they are used.
 template <typename T> struct RawPair { typedef float2 type; };
 template <> struct RawPair<bf16_t> { typedef uint32_t type; };
