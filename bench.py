@@ -247,14 +247,15 @@ def main() -> int:
                      "flops_per_call": fused_flops,
                      "note": "whole attention call (column lists + fused buckets + row reduce); per-kernel times in profiles/"},
     }
-    if wl.dtype == "bf16" and d == 64:
-        # bf16 inputs at d = 64 run on the bf16 matrix instructions (fp32 operands as hi + lo) and are bound by the
-        # rows read and the partial rows written and read back, not by the matrix pipe
-        elem = 2
+    elem = 2 if wl.dtype == "bf16" else 4
+    if d == 64:
+        # at d = 64 the bucket kernels run on the bf16 matrix instructions (fp32 operands in two or three bf16 pieces) and
+        # are bound by the rows read and the partial rows written and read back, not by the matrix pipe
         fused_bytes = float(nnz) * B * H * (3 * d * elem + 2 * (d + 1) * 4)
         fused["roofline"] = {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
                              "achieved_whole_call": round(fused_bytes / (fused_attn_ms * 1e-3) / 1e9, 1),
                              "bytes_per_call": fused_bytes, "useful_flops_per_call": fused_flops,
+                             "useful_TFLOPs_whole_call": round(fused_flops / (fused_attn_ms * 1e-3) / 1e12, 2),
                              "note": "whole attention call; bytes = per entry of Phi_hat and slice three input rows, the partial "
                                      "row written by the bucket kernel and read by the row reduce; re-read input rows are partly "
                                      "served by L2 / Infinity Cache; per-kernel times in profiles/"}
@@ -313,6 +314,17 @@ def main() -> int:
                      "achieved_whole_call": round(bwd_flops / (bwd_ms * 1e-3) / 1e12, 2), "flops_per_call": bwd_flops,
                      "note": "whole backward (seed, column lists, three bucket passes with their row reductions, dphi, df)"},
     }
+    if d == 64:
+        # three passes, each reading two input rows and one fp32 seed row per entry of Phi_hat and slice, writing one
+        # fp32 partial row and reading it back in the row reduction
+        bwd_bytes = float(nnz) * B * H * 3 * (2 * d * elem + d * 4 + 2 * d * 4)
+        backward["roofline"] = {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
+                                "achieved_whole_call": round(bwd_bytes / (bwd_ms * 1e-3) / 1e9, 1),
+                                "bytes_per_call": bwd_bytes, "useful_flops_per_call": bwd_flops,
+                                "useful_TFLOPs_whole_call": round(bwd_flops / (bwd_ms * 1e-3) / 1e12, 2),
+                                "note": "whole backward (seed, column lists, three bucket passes on the bf16 matrix instructions "
+                                        "with their row reductions, dphi, df); re-read input rows are partly served by L2 / "
+                                        "Infinity Cache; per-kernel times in profiles/"}
 
     dynamic = dynamic_section(aout)
 
