@@ -232,10 +232,12 @@ grf_status grf_masked_linear_attention(const void* Q, const void* K, const void*
  * registers, multiplies them at once by the weighted phi(q) of the same rows, and streams out one
  * d-float partial numerator and one partial denominator per entry of Phi_hat; a second kernel sums
  * each row's partials in ascending-l order (deterministic; no float atomics).
- * With bf16 inputs at d = 64 and a feature map that keeps bf16 values bf16 (ReLU, identity) the two
- * contractions run on the bf16 matrix instructions: the operand that is not a bf16 number as stored
- * (Phi_hat[j,l] phi(k_j), then S_l) enters as the sum of two bf16 numbers, a relative error of at most
- * 2^-18 on that operand; products and sums are fp32 as everywhere else.
+ * At d = 64 the two contractions run on the bf16 matrix instructions with fp32 accumulation.  fp32 operands
+ * enter as the sum of three bf16 numbers (relative error at most 2^-26) and a product is formed from the six
+ * piece products that matter: fp32 accuracy.  With bf16 inputs and a feature map that keeps bf16 values bf16
+ * (ReLU, identity) the operand that is not a bf16 number as stored (Phi_hat[j,l] phi(k_j), then S_l) enters as
+ * the sum of two bf16 numbers, a relative error of at most 2^-18 on that operand.  d = 32 uses the fp32 matrix
+ * instructions.  Which of these runs depends on d, dtype and feature_map only.
  * Workspace: column lists plus (d + 1) floats per entry of Phi_hat per resident slice. */
 size_t grf_fused_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t n_f, int32_t bh_chunk);
 
@@ -274,6 +276,9 @@ grf_status grf_asymmetric_masked_attention(const void* Q, const void* K, const v
  * and dL/dq = dL/dphi(q) * phi'(q) elementwise, likewise k.  Evaluated bucket by bucket like the fused forward
  * pass (the rows that consume bucket l are its contributors), in three passes of two MFMA contractions each;
  * per-entry partial rows are summed per output row in ascending-l order (deterministic, no float atomics).
+ * At d = 64 the contractions run on the bf16 matrix instructions with fp32 accumulation, operands entering as
+ * sums of bf16 numbers: three pieces and six piece products per product with fp32 inputs (fp32 accuracy), two
+ * pieces and three piece products with bf16 inputs (relative error at most 2^-18 per operand).
  *
  * Q, K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map, bh_chunk: as in the forward call.
  * out, den   device fp32 [B][H][n][d] and [B][H][n]: the forward results (out and den_opt of either variant).
