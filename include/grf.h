@@ -237,7 +237,9 @@ grf_status grf_masked_linear_attention(const void* Q, const void* K, const void*
  * piece products that matter: fp32 accuracy.  With bf16 inputs and a feature map that keeps bf16 values bf16
  * (ReLU, identity) the operand that is not a bf16 number as stored (Phi_hat[j,l] phi(k_j), then S_l) enters as
  * the sum of two bf16 numbers, a relative error of at most 2^-18 on that operand.  d = 32 uses the fp32 matrix
- * instructions.  Which of these runs depends on d, dtype and feature_map only.
+ * instructions.  Which of these runs depends on d, dtype and feature_map only.  (A bf16 number has the exponent
+ * range of an fp32 number, so nothing overflows that would not in fp32, except magnitudes within one part in 256
+ * of the largest finite fp32 number, whose leading piece rounds to infinity.)
  * Workspace: column lists plus (d + 1) floats per entry of Phi_hat per resident slice. */
 size_t grf_fused_attention_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t n_f, int32_t bh_chunk);
 
