@@ -1,6 +1,6 @@
 // The three bucket passes of the backward pass (gradients of Eq. 7) at d = 64 on the bf16 matrix cores: fp32
-// operands enter as three bf16 pieces and every product is six bf16 MFMAs (see fused_split.hpp), which runs at a
-// third of the cost of v_mfma_f32_32x32x2_f32 and beside the vector ALU instead of on it.
+// operands enter as three bf16 pieces and every product is six bf16 MFMAs (see fused_split.hpp), which takes well
+// under half the matrix time of v_mfma_f32_32x32x2_f32 and runs beside the vector ALU instead of on it.
 //
 //   pass           first contraction ACC = A^T B            second contraction, per consumer i     streams out
 //   kQuerySide     A = V,        B = w phi(K), x = sum B     U_i = g_i ACC + gd_i x                 U_i

@@ -6,8 +6,8 @@
 // (h = nearest bf16 of x, m = nearest bf16 of x - h, l = nearest bf16 of x - h - m), products of bf16 numbers
 // are exact in fp32 and the matrix cores accumulate in fp32, so
 //     a b  =  a_h b_h + (a_h b_m + a_m b_h) + (a_h b_l + a_l b_h + a_m b_m)  +  O(2^-25 |a b|)
-// is an fp32 product from six bf16 MFMAs, at a third of the fp32 instruction's cost.  Both contractions of a
-// bucket are done this way; the vector ALU does the splitting meanwhile.
+// is an fp32 product from six bf16 MFMAs: for a depth of 16, 6 x 34 cycles against 8 x 60 of the fp32 instruction.
+// Both contractions of a bucket are done this way; the vector ALU does the splitting.
 //
 // Index convention as in the bf16-input kernel: MFMA row/column x of tile t stands for feature / value column
 // 2x + t (a lane's two tiles are the two floats of one 8-byte load).  Lane L = 32 g + f; in every operand the
