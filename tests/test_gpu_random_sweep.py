@@ -158,16 +158,17 @@ def test_random_case(grf, oracle, index):
                                                    bh_chunk=chunk)
     host = [t.cpu().numpy() for t in got]
     host[3] = host[3][:, : phi_pos.nnz]
-    floor, df_floor = 0.0, 0.0
-    if index in ILL_CONDITIONED:
-        scale = dphi_term_scale(oracle, Q, K, V, rp1, col1, val1, out32, den32, d_out)
-        # df is a sum of dphi's entries with non-negative coefficients (the walks' loads): the same sum of the scales
-        df_scale = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp1, col1, scale)
+    # dphi and df are sums in which large terms can cancel (df on star graphs to 1e-5 of its terms): an absolute error
+    # of four units in the last place of the terms' absolute sum is allowed whatever the size of the result.  For the
+    # well-conditioned cases this is far below the plain bar, which then decides.
+    scale = dphi_term_scale(oracle, Q, K, V, rp1, col1, val1, out32, den32, d_out)
+    # df is a sum of dphi's entries with non-negative coefficients (the walks' loads): the same sum of the scales
+    df_scale = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp1, col1, scale)
+    floor = 2.0 ** -22 * scale.max()
+    df_floor = 2.0 ** -22 * df_scale.max()
+    if index in ILL_CONDITIONED:      # the case is what its name says
         df_plain = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp1, col1, bref[3])
-        # the case is what its name says
         assert scale.max() > 100 * np.abs(bref[3]).max() or df_scale.max() > 100 * np.abs(df_plain).max()
-        floor = 2.0 ** -22 * scale.max()                    # four units in the last place of the terms' size
-        df_floor = 2.0 ** -22 * df_scale.max()
     check_gradients(host, bref, tol, "", diagonal, dphi_floor=floor)
     df = grf.grf_sample_backward(g, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, phi_pos, got[3]).cpu().numpy()
     df_ref = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp1, col1, bref[3])
