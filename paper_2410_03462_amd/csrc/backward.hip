@@ -249,8 +249,8 @@ __global__ __launch_bounds__(256) void backward_reduce_kernel(long long n, int H
                     const int32_t pos = __builtin_amdgcn_readlane(pos_reg, t & (kWave - 1));
                     w[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_reg), t & (kWave - 1)));
                     ok[u] = t < cnt && pos >= 0;
-                    const float x = slice_partial[static_cast<long long>(max(pos, 0)) * D + c];
-                    v[u] = ok[u] ? x : 0.0f;
+                    const float loaded = slice_partial[static_cast<long long>(max(pos, 0)) * D + c];
+                    v[u] = ok[u] ? loaded : 0.0f;
                 } else {
                     const int32_t pos = __shfl(pos_reg, t & (kWave - 1), kWave);
                     w[u] = __shfl(w_reg, t & (kWave - 1), kWave);
