@@ -199,6 +199,22 @@ def cluster_points(n: int, n_clusters: int, std: float, rng: np.random.Generator
 
 # --------------------------------------------------------------------------- tensors
 
+def one_long_column(length, rng):
+    """A hand-made feature matrix in CSR, for tests of list-length boundaries: n = length + 3 rows, a diagonal, and a
+    column 0 of `length` entries (rows 0 .. length-1); values uniform in 0.2 .. 1.  Returns (n, row_ptr, col, val[1, nnz])."""
+    n = length + 3
+    rows = np.concatenate([np.arange(n), np.arange(1, length)])
+    cols = np.concatenate([np.arange(n), np.zeros(length - 1, dtype=np.int64)])
+    order = np.lexsort((cols, rows))
+    rows, cols = rows[order], cols[order]
+    rp = np.zeros(n + 1, dtype=np.int32)
+    np.add.at(rp, rows + 1, 1)
+    rp = np.cumsum(rp).astype(np.int32)
+    val = rng.uniform(0.2, 1.0, size=(1, len(cols))).astype(np.float32)
+    return n, rp, cols.astype(np.int32), val
+
+
+
 def modulation(f_len: int, rng: np.random.Generator, kind: str = "decay", n_f: int = 1, std: float = 1.0) -> np.ndarray:
     """f of shape [n_f, f_len], float32.  ``decay``: N(0,1)/(k+1); ``normal``: N(0, std)."""
     g = rng.standard_normal((n_f, f_len))

@@ -96,6 +96,33 @@ def compare_backward(grf, oracle, wl, feature_map="relu", bh_chunk=0):
     return host, df
 
 
+@pytest.mark.parametrize("dtype,feature_map", [("f32", "elu1"), ("bf16", "relu")])
+def test_backward_column_lengths_at_step_tile_and_block_boundaries(grf, oracle, dtype, feature_map):
+    """d = 64: column lists that end just before, at and just after the boundaries of the bucket kernels' steps of 16
+    members, tiles of 32 consumers and blocks of 128 entries, and long ones."""
+    rng = np.random.default_rng(6)
+    tol = TOL_BF16 if dtype == "bf16" else TOL_F32
+    fm = FEATURE_MAP_CODE[feature_map]
+    # (a list of one entry would make Phi_hat diagonal, where every gradient but dV vanishes identically,
+    # and one of a thousand, where every query averages over a thousand keys, leaves dQ a sum that cancels to 1e-5)
+    for length in (2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 143, 144, 145, 255, 256, 257, 300):
+        n, rp, col, val = synth.one_long_column(length, rng)
+        Q, K, V = synth.qkv(1, 2, n, 64, np.random.default_rng([length, 3]), dtype)
+        fwd = oracle.masked_linear_attention(Q, K, V, rp, col, val, feature_map=fm)
+        out32, den32 = fwd["out"].astype(np.float32), fwd["den"].astype(np.float32)
+        assert np.isfinite(out32).all() and (den32 > 0).all()
+        d_out = np.random.default_rng([length, 4]).standard_normal(Q.shape).astype(np.float32)
+        ref = oracle.masked_linear_attention_backward(Q, K, V, rp, col, val, out32, den32, d_out, fm)
+        phi = grf.Phi.from_host(n, rp, col, val)
+        got = grf.grf_masked_linear_attention_backward(*(to_dev(x, dtype) for x in (Q, K, V)), phi, to_dev(out32), to_dev(den32),
+                                                       to_dev(d_out), feature_map)
+        host = [t.cpu().numpy() for t in got]
+        host[3] = host[3][:, : phi.nnz]
+        for name, x, r in zip(("dQ", "dK", "dV", "dphi"), host, ref):
+            assert np.isfinite(x).all(), (length, name)
+            assert relerr(x, r) <= tol, (length, name, relerr(x, r))
+
+
 @pytest.mark.parametrize("name", list(SMALL))
 def test_backward_parity(grf, oracle, name):
     compare_backward(grf, oracle, SMALL[name])

@@ -440,6 +440,18 @@ def _compare_fused(grf, oracle, wl, rp, col, val, feature_map="relu", bh_chunk=0
     return out, num, den
 
 
+@pytest.mark.parametrize("dtype,feature_map", [("f32", "relu"), ("bf16", "relu"), ("bf16", "elu1")])
+def test_fused_column_lengths_at_step_tile_and_block_boundaries(grf, oracle, dtype, feature_map):
+    """d = 64: the bucket kernels contract a column list 16 members at a time out of blocks of 128 entries and
+    consume it 32 rows at a time: lists that end just before, at and just after those boundaries, and long ones."""
+    rng = np.random.default_rng(5)
+    for length in (1, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 112, 113, 127, 128, 129, 143, 144, 145, 255, 256, 257, 1000):
+        n, rp, col, val = synth.one_long_column(length, rng)
+        wl = synth.Workload(f"column_{length}", synth.path_graph(n), np.ones((1, 1), np.float32), 0.5, 1, 1, 2, 64, dtype,
+                            data_seed=length)
+        _compare_fused(grf, oracle, wl, rp, col, val, feature_map)
+
+
 @pytest.mark.parametrize("name", list(SMALL))
 def test_fused_attention_parity(grf, oracle, name):
     wl = SMALL[name]
