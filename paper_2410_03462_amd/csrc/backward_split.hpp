@@ -154,6 +154,13 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
             for (int c = 0; c < 2; ++c) mfma_pieces<NP>(a_p[a], b_p[c], acc[a][c]);
     };
 
+    if (end - beg <= 16) {
+        // a list of one step (most lists of a grid graph): one request, one contraction
+        const ListBlock lb = load_list_block<MODE == kKeySide>(csc_row, vals, gdb, beg, end);
+        Members only;
+        fetch_members(lb.j_a, 0, only);
+        contract_members(only, lb.g_a, lb.e_a, 0);
+    } else
     for (int32_t block = beg; block < end; block += 2 * kWave) {
         ListBlock lb = load_list_block<MODE == kKeySide>(csc_row, vals, gdb, block, end);
         // all of the block's loads are taken here, where the first are needed anyway: requested later (the compiler

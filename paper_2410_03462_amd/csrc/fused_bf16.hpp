@@ -189,6 +189,13 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
         }
     };
 
+    if (end - beg <= 16) {
+        // a list of one step (most lists of a grid graph): one request, one contraction
+        const ListBlock lb = load_list_block<false>(csc_row, vals, nullptr, beg, end);
+        Members only;
+        fetch_members(lb.j_a, lb.g_a, 0, only);
+        contract_members(only);
+    } else
     for (int32_t block = beg; block < end; block += 2 * kWave) {
         ListBlock lb = load_list_block<false>(csc_row, vals, nullptr, block, end);
         // all four of the block's loads are taken here, where the first two are needed anyway: requested later
