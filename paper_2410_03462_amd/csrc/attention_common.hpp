@@ -191,6 +191,27 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t row_window(float* __restrict__
     return __builtin_amdgcn_make_buffer_rsrc(uniform_base, 0, __builtin_amdgcn_readfirstlane(rows * D * 4), kRawDword);
 }
 
+// (slice, bucket) of a one-wavefront workgroup in a grid of one workgroup per bucket.  Workgroups go to the eight
+// XCDs round-robin by id and start in id order.  spread_xcds: each XCD takes one contiguous eighth of all buckets,
+// so the XCDs work in different slices (right when eight slices' tensors fit the Infinity Cache with room to spare:
+// their reads then spread over the memory side).  Otherwise the buckets of one slice after the other, each XCD a
+// contiguous eighth of the slice: one slice's tensors hot at a time.  B*H*n < 2^31, so 32-bit divisions do.
+struct BucketId { uint32_t slice, l; };
+__device__ __forceinline__ BucketId bucket_of_workgroup(long long n, int spread_xcds)
+{
+    const uint32_t n32 = static_cast<uint32_t>(n);
+    BucketId b;
+    if (spread_xcds) {
+        const uint32_t wave = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x, gridDim.x));
+        b.slice = wave / n32;
+        b.l = wave - b.slice * n32;
+    } else {
+        b.slice = blockIdx.x / n32;
+        b.l = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x - b.slice * n32, n32));
+    }
+    return b;
+}
+
 // What the first contraction accumulates besides the D x D tile.
 enum : int {
     kExtraSumA = 0,        // column sums of the A operands        (z_l of the forward pass)

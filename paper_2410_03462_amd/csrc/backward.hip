@@ -64,23 +64,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
 {
     constexpr int T2 = D / 32;
     constexpr int QN = 4 * T2;     // operand elements a lane holds per group of four accumulator registers
-    // Workgroups go to the eight XCDs round-robin by id and start in id order.  spread_xcds: each XCD takes one
-    // contiguous eighth of all buckets, so the XCDs work in different slices (right when eight slices' tensors fit
-    // the Infinity Cache with room to spare: their reads then spread over the memory side).  Otherwise the buckets
-    // of one slice after the other, each XCD a contiguous eighth of the slice: one slice's tensors hot at a time.
-    // B*H*n < 2^31, so 32-bit divisions do.
     if (blockIdx.x >= n_waves) return;
-    const uint32_t n32 = static_cast<uint32_t>(n);
-    uint32_t slice32, l32;
-    if (spread_xcds) {
-        const uint32_t wave = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x, gridDim.x));
-        slice32 = wave / n32;
-        l32 = wave - slice32 * n32;
-    } else {
-        slice32 = blockIdx.x / n32;
-        l32 = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x - slice32 * n32, n32));
-    }
-    const long long slice = slice32;
+    const BucketId bucket = bucket_of_workgroup(n, spread_xcds);
+    const uint32_t l32 = bucket.l;
+    const long long slice = bucket.slice;
     const long long l = l32;
     const long long bh = bh_first + slice;
     const long long plane = n_f > 1 ? (static_cast<uint32_t>(bh) % static_cast<uint32_t>(H)) : 0u;

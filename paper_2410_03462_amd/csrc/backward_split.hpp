@@ -34,19 +34,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
     constexpr int D = 64;
     // pieces per operand: fp32-grade products for fp32 inputs; with bf16 inputs (bar 2e-2) two pieces, three products
     constexpr int NP = sizeof(T) == 2 ? 2 : 3;
-    // bucket of this workgroup: see backward_bucket_kernel
     if (blockIdx.x >= n_waves) return;
-    const uint32_t n32 = static_cast<uint32_t>(n);
-    uint32_t slice32, l32;
-    if (spread_xcds) {
-        const uint32_t wave = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x, gridDim.x));
-        slice32 = wave / n32;
-        l32 = wave - slice32 * n32;
-    } else {
-        slice32 = blockIdx.x / n32;
-        l32 = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x - slice32 * n32, n32));
-    }
-    const long long slice = slice32;
+    const BucketId bucket = bucket_of_workgroup(n, spread_xcds);
+    const uint32_t l32 = bucket.l;
+    const long long slice = bucket.slice;
     const long long bh = bh_first + slice;
     const long long plane = n_f > 1 ? (static_cast<uint32_t>(bh) % static_cast<uint32_t>(H)) : 0u;
     const T* Qb = Q + bh * n * D;
@@ -258,16 +249,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
                 for (int c = 0; c < 2; ++c) mfma_pieces<NP>(c_p, s_p[a][c][h], pc[c]);
             }
 
-        // one 8-byte store per register pair through a window over the tile's rows, which drops the rows past the
-        // end of the list
-        const __amdgpu_buffer_rsrc_t window = row_window(partial, pbase + tile, min(end - tile, 32), D);
-        int lane_off = (4 * g * D + 2 * f) * 4;
-        asm volatile("" : "+v"(lane_off));
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const uintx2 v = {__float_as_uint(pc[0][r]), __float_as_uint(pc[1][r])};
-            __builtin_amdgcn_raw_buffer_store_b64(v, window, lane_off + (8 * (r / 4) + (r % 4)) * D * 4, 0, 0);
-        }
+        store_consumer_tile(partial, pbase + tile, min(end - tile, 32), g, f, pc[0], pc[1]);
     }
 }
 

@@ -75,6 +75,25 @@ __device__ __forceinline__ bf16x8 as_operand(const uint32_t (&w)[4])
     return __builtin_bit_cast(bf16x8, v);
 }
 
+// A 32 x 64 output tile of the second contraction: register r of p0 / p1 in lane (g, f) is consumer row
+// 8 (r / 4) + 4 g + r % 4, column 2 f / 2 f + 1.  One 8-byte store per register pair through a window over the
+// tile's `rows` valid rows of the [..][64] fp32 array, which drops the rows past the end of the list; the rows'
+// constant offsets go into the instructions' offset fields (lane_off is made opaque so that they are not hoisted
+// into sixteen registers).
+__device__ __forceinline__ void store_consumer_tile(float* __restrict__ partial, long long row0, int rows, int g, int f,
+                                                    const floatx16& p0, const floatx16& p1)
+{
+    constexpr int D = 64;
+    const __amdgpu_buffer_rsrc_t window = row_window(partial, row0, rows, D);
+    int lane_off = (4 * g * D + 2 * f) * 4;
+    asm volatile("" : "+v"(lane_off));
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const uintx2 v = {__float_as_uint(p0[r]), __float_as_uint(p1[r])};
+        __builtin_amdgcn_raw_buffer_store_b64(v, window, lane_off + (8 * (r / 4) + (r % 4)) * D * 4, 0, 0);
+    }
+}
+
 // One wavefront per (slice, bucket l), one wavefront per workgroup.  Every global load is unconditional
 // (members past the end of the column list re-read its last entry with weight 0).
 //
@@ -95,21 +114,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
     long long bh_first, long long n_waves, int32_t nnz, int spread_xcds, float* __restrict__ partial, float* __restrict__ pden)
 {
     constexpr int D = 64;
-    // Workgroups go to the eight XCDs round-robin by id and start in id order.  spread_xcds: each XCD takes one
-    // contiguous eighth of all buckets; otherwise the buckets of one slice after the other, each XCD a contiguous
-    // eighth of the slice.  B*H*n < 2^31, so 32-bit divisions do.
     if (blockIdx.x >= n_waves) return;
-    const uint32_t n32 = static_cast<uint32_t>(n);
-    uint32_t slice32, l32;
-    if (spread_xcds) {
-        const uint32_t wave = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x, gridDim.x));
-        slice32 = wave / n32;
-        l32 = wave - slice32 * n32;
-    } else {
-        slice32 = blockIdx.x / n32;
-        l32 = static_cast<uint32_t>(xcd_contiguous_block(blockIdx.x - slice32 * n32, n32));
-    }
-    const long long slice = slice32;
+    const BucketId bucket = bucket_of_workgroup(n, spread_xcds);
+    const uint32_t l32 = bucket.l;
+    const long long slice = bucket.slice;
     const long long bh = bh_first + slice;
     const long long plane = n_f > 1 ? (static_cast<uint32_t>(bh) % static_cast<uint32_t>(H)) : 0u;
     const bf16_t* Qb = Q + bh * n * D;
@@ -272,16 +280,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
             }
         if (g == 0 && tile + f < end) pden[pbase + tile + f] = pd[0];
 
-        // register r of pc[c] is consumer tile + 8 (r / 4) + 4 g + r % 4, column 2 f + c: one 8-byte store per
-        // register pair through a window over the tile's rows, which drops the rows past the end of the list
-        const __amdgpu_buffer_rsrc_t window = row_window(partial, pbase + tile, min(end - tile, 32), D);
-        int lane_off = (4 * g * D + 2 * f) * 4;
-        asm volatile("" : "+v"(lane_off));
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const uintx2 v = {__float_as_uint(pc[0][r]), __float_as_uint(pc[1][r])};
-            __builtin_amdgcn_raw_buffer_store_b64(v, window, lane_off + (8 * (r / 4) + (r % 4)) * D * 4, 0, 0);
-        }
+        store_consumer_tile(partial, pbase + tile, min(end - tile, 32), g, f, pc[0], pc[1]);
     }
 }
 
