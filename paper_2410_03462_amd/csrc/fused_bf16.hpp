@@ -75,6 +75,50 @@ __device__ __forceinline__ bf16x8 as_operand(const uint32_t (&w)[4])
     return __builtin_bit_cast(bf16x8, v);
 }
 
+// Walks the column list [beg, end) in steps of 16 members, out of blocks of 128 entries held one per lane in two
+// register sets (load_list_block).  request(rows, weights, scales, first, set) issues the loads of the step whose
+// members are entries first .. first + 15 (mod 64) of the registers handed over, into `set`; contract(set, weights,
+// scales, first) does the step's arithmetic.  Two sets take turns, so that the next step's loads are in flight
+// under this step's arithmetic, with scheduling barriers between request and arithmetic (the compiler would
+// otherwise reorder them).  The steps come in pairs: the second one is contracted also when it lies past the end of
+// the list (its members then have weight 0), since a skipped step's loads would be moved into the branch, next to
+// their use; past a block's last step the request is redundant and re-reads entries of the block.  A list of one
+// step (most lists of a grid graph) takes one request and one contraction.
+template <typename Members, bool SCALED, typename Request, typename Contract>
+__device__ __forceinline__ void walk_column_list(const int32_t* __restrict__ csc_row, const float* __restrict__ vals,
+                                                 const float* __restrict__ escale, int32_t beg, int32_t end,
+                                                 Request&& request, Contract&& contract)
+{
+    if (end - beg <= 16) {
+        const ListBlock lb = load_list_block<SCALED>(csc_row, vals, escale, beg, end);
+        Members only;
+        request(lb.j_a, lb.g_a, lb.e_a, 0, only);
+        contract(only, lb.g_a, lb.e_a, 0);
+        return;
+    }
+    for (int32_t block = beg; block < end; block += 2 * kWave) {
+        ListBlock lb = load_list_block<SCALED>(csc_row, vals, escale, block, end);
+        // all of the block's loads are taken here, where the first are needed anyway: requested later (the compiler
+        // sinks the second set to its first use), they would return behind the rows' loads
+        asm volatile("" : "+v"(lb.j_a), "+v"(lb.j_b), "+v"(lb.g_a), "+v"(lb.g_b), "+v"(lb.e_a), "+v"(lb.e_b));
+        const int steps = min((end - block + 15) >> 4, 8);
+        Members even, odd;
+        __builtin_amdgcn_sched_barrier(0);
+        request(lb.j_a, lb.g_a, lb.e_a, 0, even);
+#pragma nounroll
+        for (int s = 0; s < steps; s += 2) {
+            __builtin_amdgcn_sched_barrier(0);
+            request(s + 1 >= 4 ? lb.j_b : lb.j_a, s + 1 >= 4 ? lb.g_b : lb.g_a, s + 1 >= 4 ? lb.e_b : lb.e_a, 16 * (s + 1), odd);
+            __builtin_amdgcn_sched_barrier(0);
+            contract(even, s >= 4 ? lb.g_b : lb.g_a, s >= 4 ? lb.e_b : lb.e_a, 16 * s);
+            __builtin_amdgcn_sched_barrier(0);
+            request(s + 2 >= 4 ? lb.j_b : lb.j_a, s + 2 >= 4 ? lb.g_b : lb.g_a, s + 2 >= 4 ? lb.e_b : lb.e_a, 16 * (s + 2), even);
+            __builtin_amdgcn_sched_barrier(0);
+            contract(odd, s + 1 >= 4 ? lb.g_b : lb.g_a, s + 1 >= 4 ? lb.e_b : lb.e_a, 16 * (s + 1));
+        }
+    }
+}
+
 // A 32 x 64 output tile of the second contraction: register r of p0 / p1 in lane (g, f) is consumer row
 // 8 (r / 4) + 4 g + r % 4, column 2 f / 2 f + 1.  One 8-byte store per register pair through a window over the
 // tile's `rows` valid rows of the [..][64] fp32 array, which drops the rows past the end of the list; the rows'
@@ -197,38 +241,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
         }
     };
 
-    if (end - beg <= 16) {
-        // a list of one step (most lists of a grid graph): one request, one contraction
-        const ListBlock lb = load_list_block<false>(csc_row, vals, nullptr, beg, end);
-        Members only;
-        fetch_members(lb.j_a, lb.g_a, 0, only);
-        contract_members(only);
-    } else
-    for (int32_t block = beg; block < end; block += 2 * kWave) {
-        ListBlock lb = load_list_block<false>(csc_row, vals, nullptr, block, end);
-        // all four of the block's loads are taken here, where the first two are needed anyway: requested later
-        // (the compiler sinks the second pair to its first use), they would return behind the rows' loads
-        asm volatile("" : "+v"(lb.j_a), "+v"(lb.j_b), "+v"(lb.g_a), "+v"(lb.g_b));
-        const int steps = min((end - block + 15) >> 4, 8);
-        // two register sets take turns: the next step's rows are requested before this step's arithmetic (past the
-        // block's last step the request is redundant and re-reads entries of the block)
-        Members even, odd;
-        __builtin_amdgcn_sched_barrier(0);      // the block's four loads before the rows' (loads return in order)
-        fetch_members(lb.j_a, lb.g_a, 0, even);
-#pragma nounroll
-        for (int s = 0; s < steps; s += 2) {
-            __builtin_amdgcn_sched_barrier(0);
-            fetch_members(s + 1 >= 4 ? lb.j_b : lb.j_a, s + 1 >= 4 ? lb.g_b : lb.g_a, 16 * (s + 1), odd);
-            __builtin_amdgcn_sched_barrier(0);
-            contract_members(even);
-            __builtin_amdgcn_sched_barrier(0);
-            fetch_members(s + 2 >= 4 ? lb.j_b : lb.j_a, s + 2 >= 4 ? lb.g_b : lb.g_a, 16 * (s + 2), even);
-            __builtin_amdgcn_sched_barrier(0);
-            // also when step s + 1 lies past the end of the list (its members then have weight 0): were it skipped,
-            // the compiler would move the step's loads into the branch, next to their use
-            contract_members(odd);
-        }
-    }
+    walk_column_list<Members, false>(csc_row, vals, nullptr, beg, end,
+                                     [&](int32_t jv, float gv, float, int first, Members& m) { fetch_members(jv, gv, first, m); },
+                                     [&](const Members& m, float, float, int) { contract_members(m); });
 
     // ---- the accumulators as hi + lo, in the registers' own order: [a][c][h] holds registers 8 h + 0..7
     uint32_t s_hi[2][3][2][4], s_lo[2][3][2][4];

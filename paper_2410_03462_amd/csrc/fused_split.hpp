@@ -182,38 +182,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
             for (int c = 0; c < 2; ++c) mfma_split3(a_p[a], b_p[c], acc[a][c]);
     };
 
-    if (end - beg <= 16) {
-        // a list of one step (most lists of a grid graph): one request, one contraction
-        const ListBlock lb = load_list_block<false>(csc_row, vals, nullptr, beg, end);
-        Members only;
-        fetch_members(lb.j_a, lb.g_a, 0, only);
-        contract_members(only);
-    } else
-    for (int32_t block = beg; block < end; block += 2 * kWave) {
-        ListBlock lb = load_list_block<false>(csc_row, vals, nullptr, block, end);
-        // all four of the block's loads are taken here, where the first two are needed anyway: requested later
-        // (the compiler sinks the second pair to its first use), they would return behind the rows' loads
-        asm volatile("" : "+v"(lb.j_a), "+v"(lb.j_b), "+v"(lb.g_a), "+v"(lb.g_b));
-        const int steps = min((end - block + 15) >> 4, 8);
-        // two register sets take turns: the next step's rows are requested before this step's arithmetic (past the
-        // block's last step the request is redundant and re-reads entries of the block)
-        Members even, odd;
-        __builtin_amdgcn_sched_barrier(0);
-        fetch_members(lb.j_a, lb.g_a, 0, even);
-#pragma nounroll
-        for (int s = 0; s < steps; s += 2) {
-            __builtin_amdgcn_sched_barrier(0);
-            fetch_members(s + 1 >= 4 ? lb.j_b : lb.j_a, s + 1 >= 4 ? lb.g_b : lb.g_a, 16 * (s + 1), odd);
-            __builtin_amdgcn_sched_barrier(0);
-            contract_members(even);
-            __builtin_amdgcn_sched_barrier(0);
-            fetch_members(s + 2 >= 4 ? lb.j_b : lb.j_a, s + 2 >= 4 ? lb.g_b : lb.g_a, 16 * (s + 2), even);
-            __builtin_amdgcn_sched_barrier(0);
-            // also when step s + 1 lies past the end of the list (its members then have weight 0): were it skipped,
-            // the compiler would move the step's loads into the branch, next to their use
-            contract_members(odd);
-        }
-    }
+    walk_column_list<Members, false>(csc_row, vals, nullptr, beg, end,
+                                     [&](int32_t jv, float gv, float, int first, Members& m) { fetch_members(jv, gv, first, m); },
+                                     [&](const Members& m, float, float, int) { contract_members(m); });
 
     // ---- z_l at the features of this lane's depth slots: lane rho of either group holds z[2 rho + a]
     float zs[2][16];
