@@ -87,6 +87,73 @@ __device__ __forceinline__ void load_eight(const T* __restrict__ base, uint32_t 
     }
 }
 
+// First contraction of a bucket at d = 64 with three-piece operands: acc[a][c] = A^T B over the column list
+// [beg, end) with A = Phi_hat[j,l] phi(k_j), B = v_j (MFMA row/column x of tile t stands for element 2x + t), and
+// zacc[a] = this lane's share of z_l = A^T 1: the sum over lanes f and 32 + f is z_l[2f + a].  16 members of the
+// list per step: lane (g, f) takes members 8 g + 0..7 of the step from the list block with ds_bpermute and loads
+// elements 2f, 2f + 1 of their rows of K and V.
+template <typename T, bool WIDE>
+__device__ __forceinline__ void bucket_first_contraction_split(const T* __restrict__ Kb, const T* __restrict__ Vb,
+                                                               const int32_t* __restrict__ csc_row, const float* __restrict__ vals,
+                                                               int fmap, int32_t beg, int32_t end,
+                                                               floatx16 (&acc)[2][2], float (&zacc)[2])
+{
+    const int lane = lane_id();
+    const int g = lane >> 5;
+    const int f = lane & 31;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        zacc[a] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
+    }
+    if (beg >= end) return;      // an empty list: zeros, and no row is read
+    struct Members { typename RawPair<T>::type k[8], v[8]; float w[8]; };
+    auto fetch_members = [&](int32_t jv, float gv, int first, Members& m) {
+        int addr = 4 * ((first + 8 * g) & (kWave - 1));
+        asm volatile("" : "+v"(addr));      // one register, the members' offsets as literals
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t row = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(addr + 4 * j, jv));
+            m.w[j] = __int_as_float(__builtin_amdgcn_ds_bpermute(addr + 4 * j, __float_as_int(gv)));
+            m.k[j] = load_pair<T, WIDE>(Kb, row, f);
+            m.v[j] = load_pair<T, WIDE>(Vb, row, f);
+        }
+    };
+    auto contract_members = [&](const Members& m) {
+        uint32_t a_p[2][3][4], b_p[2][3][4];      // [tile][piece][register]
+        with_feature_map(fmap, [&](auto fm) {
+            constexpr int FM = decltype(fm)::value;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const float2 k0 = widen(m.k[2 * p]), k1 = widen(m.k[2 * p + 1]);
+                const float x0 = m.w[2 * p] * feature_ct<FM>(k0.x), x1 = m.w[2 * p + 1] * feature_ct<FM>(k1.x);
+                const float y0 = m.w[2 * p] * feature_ct<FM>(k0.y), y1 = m.w[2 * p + 1] * feature_ct<FM>(k1.y);
+                zacc[0] += x0 + x1;
+                zacc[1] += y0 + y1;
+                split3_bf16(x0, x1, a_p[0][0][p], a_p[0][1][p], a_p[0][2][p]);
+                split3_bf16(y0, y1, a_p[1][0][p], a_p[1][1][p], a_p[1][2][p]);
+            }
+        });
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const float2 v0 = widen(m.v[2 * p]), v1 = widen(m.v[2 * p + 1]);
+            split3_bf16(v0.x, v1.x, b_p[0][0][p], b_p[0][1][p], b_p[0][2][p]);
+            split3_bf16(v0.y, v1.y, b_p[1][0][p], b_p[1][1][p], b_p[1][2][p]);
+        }
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) mfma_split3(a_p[a], b_p[c], acc[a][c]);
+    };
+
+    walk_column_list<Members, false>(csc_row, vals, nullptr, beg, end,
+                                     [&](int32_t jv, float gv, float, int first, Members& m) { fetch_members(jv, gv, first, m); },
+                                     [&](const Members& m, float, float, int) { contract_members(m); });
+}
+
 // One wavefront per (slice, bucket l), one wavefront per workgroup; structure as fused_bucket_bf16_kernel:
 // 16 members of the column list per step of the first contraction (lane (g, f) takes members 8 g + 0..7 and
 // loads floats 2f, 2f + 1 of their rows of K and V), 32 consumers per step of the second, whose B operand is
@@ -135,56 +202,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
 
     // ---- S_l = A^T V_l, z_l = A^T 1
     floatx16 acc[2][2];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
-    float zacc[2] = {0.0f, 0.0f};
-
-    struct Members { typename RawPair<T>::type k[8], v[8]; float w[8]; };
-    auto fetch_members = [&](int32_t jv, float gv, int first, Members& m) {
-        int addr = 4 * ((first + 8 * g) & (kWave - 1));
-        asm volatile("" : "+v"(addr));      // one register, the members' offsets as literals
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t row = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(addr + 4 * j, jv));
-            m.w[j] = __int_as_float(__builtin_amdgcn_ds_bpermute(addr + 4 * j, __float_as_int(gv)));
-            m.k[j] = load_pair<T, WIDE>(Kb, row, f);
-            m.v[j] = load_pair<T, WIDE>(Vb, row, f);
-        }
-    };
-    auto contract_members = [&](const Members& m) {
-        uint32_t a_p[2][3][4], b_p[2][3][4];      // [tile][piece][register]
-        with_feature_map(fmap, [&](auto fm) {
-            constexpr int FM = decltype(fm)::value;
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const float2 k0 = widen(m.k[2 * p]), k1 = widen(m.k[2 * p + 1]);
-                const float x0 = m.w[2 * p] * feature_ct<FM>(k0.x), x1 = m.w[2 * p + 1] * feature_ct<FM>(k1.x);
-                const float y0 = m.w[2 * p] * feature_ct<FM>(k0.y), y1 = m.w[2 * p + 1] * feature_ct<FM>(k1.y);
-                zacc[0] += x0 + x1;
-                zacc[1] += y0 + y1;
-                split3_bf16(x0, x1, a_p[0][0][p], a_p[0][1][p], a_p[0][2][p]);
-                split3_bf16(y0, y1, a_p[1][0][p], a_p[1][1][p], a_p[1][2][p]);
-            }
-        });
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const float2 v0 = widen(m.v[2 * p]), v1 = widen(m.v[2 * p + 1]);
-            split3_bf16(v0.x, v1.x, b_p[0][0][p], b_p[0][1][p], b_p[0][2][p]);
-            split3_bf16(v0.y, v1.y, b_p[1][0][p], b_p[1][1][p], b_p[1][2][p]);
-        }
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int c = 0; c < 2; ++c) mfma_split3(a_p[a], b_p[c], acc[a][c]);
-    };
-
-    walk_column_list<Members, false>(csc_row, vals, nullptr, beg, end,
-                                     [&](int32_t jv, float gv, float, int first, Members& m) { fetch_members(jv, gv, first, m); },
-                                     [&](const Members& m, float, float, int) { contract_members(m); });
+    float zacc[2];
+    bucket_first_contraction_split<T, WIDE>(Kb, Vb, csc_row, vals, fmap, beg, end, acc, zacc);
 
     // ---- z_l at the features of this lane's depth slots: lane rho of either group holds z[2 rho + a]
     float zs[2][16];
