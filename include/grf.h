@@ -233,10 +233,10 @@ grf_status grf_masked_linear_attention(const void* Q, const void* K, const void*
  * d-float partial numerator and one partial denominator per entry of Phi_hat; a second kernel sums
  * each row's partials in ascending-l order (deterministic; no float atomics).
  * At d = 64 the two contractions run on the bf16 matrix instructions with fp32 accumulation.  fp32 operands
- * enter as the sum of three bf16 numbers (relative error at most 2^-26) and a product is formed from the six
- * piece products that matter: fp32 accuracy.  With bf16 inputs and a feature map that keeps bf16 values bf16
+ * enter as the sum of three bf16 numbers (exact: 3 x 8 significant bits) and a product is formed from the six
+ * piece products that matter (what is dropped is at most 2^-23 of the product): fp32 accuracy.  With bf16 inputs and a feature map that keeps bf16 values bf16
  * (ReLU, identity) the operand that is not a bf16 number as stored (Phi_hat[j,l] phi(k_j), then S_l) enters as
- * the sum of two bf16 numbers, a relative error of at most 2^-18 on that operand.  d = 32 uses the fp32 matrix
+ * the sum of two bf16 numbers, a relative error of at most 2^-16 on that operand.  d = 32 uses the fp32 matrix
  * instructions.  Which of these runs depends on d, dtype and feature_map only.  (A bf16 number has the exponent
  * range of an fp32 number, so nothing overflows that would not in fp32, except magnitudes within one part in 256
  * of the largest finite fp32 number, whose leading piece rounds to infinity.)
@@ -280,7 +280,7 @@ grf_status grf_asymmetric_masked_attention(const void* Q, const void* K, const v
  * per-entry partial rows are summed per output row in ascending-l order (deterministic, no float atomics).
  * At d = 64 the contractions run on the bf16 matrix instructions with fp32 accumulation, operands entering as
  * sums of bf16 numbers: three pieces and six piece products per product with fp32 inputs (fp32 accuracy), two
- * pieces and three piece products with bf16 inputs (relative error at most 2^-18 per operand).
+ * pieces and three piece products with bf16 inputs (relative error at most 2^-16 per operand).
  *
  * Q, K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map, bh_chunk: as in the forward call.
  * out, den   device fp32 [B][H][n][d] and [B][H][n]: the forward results (out and den_opt of either variant).

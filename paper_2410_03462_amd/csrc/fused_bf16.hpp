@@ -5,8 +5,8 @@
 // stands (a row of V in the first contraction, a row of phi(Q) in the second: ReLU and the identity keep
 // bf16 values bf16), and the other one (Phi_hat[j,l] phi(k_j), then S_l itself) is an fp32 number that is
 // handed to the matrix cores as hi + lo, two bf16 numbers: hi the nearest bf16, lo the nearest bf16 of the
-// rest, |x - hi - lo| <= 2^-18 |x|.  Products of bf16 numbers are exact in fp32 and all sums are fp32, so
-// this is the fp32 kernel's arithmetic up to that 2^-18 on one operand.
+// rest, |x - hi - lo| <= 2^-16 |x|.  Products of bf16 numbers are exact in fp32 and all sums are fp32, so
+// this is the fp32 kernel's arithmetic up to that 2^-16 on one operand.
 //
 // Index convention: MFMA row/column x of tile t stands for feature / value column 2x + t (a lane's two
 // tiles are the two halves of one 32-bit word of a row).  Lane L = 32 g + f; in every operand the lanes of

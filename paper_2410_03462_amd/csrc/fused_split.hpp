@@ -2,10 +2,10 @@
 // (fp32 inputs; bf16 inputs under a feature map whose values are not bf16 numbers).
 //
 // v_mfma_f32_32x32x2_f32 shares the vector ALU and delivers 157 TFLOP/s; v_mfma_f32_32x32x16_bf16 runs beside
-// the vector ALU at sixteen times that rate.  An fp32 number is the sum of three bf16 numbers to within 2^-26
+// the vector ALU at sixteen times that rate.  An fp32 number is exactly the sum of three bf16 numbers
 // (h = nearest bf16 of x, m = nearest bf16 of x - h, l = nearest bf16 of x - h - m), products of bf16 numbers
 // are exact in fp32 and the matrix cores accumulate in fp32, so
-//     a b  =  a_h b_h + (a_h b_m + a_m b_h) + (a_h b_l + a_l b_h + a_m b_m)  +  O(2^-25 |a b|)
+//     a b  =  a_h b_h + (a_h b_m + a_m b_h) + (a_h b_l + a_l b_h + a_m b_m)  +  O(2^-23 |a b|)
 // is an fp32 product from six bf16 MFMAs: for a depth of 16, 6 x 34 cycles against 8 x 60 of the fp32 instruction.
 // Both contractions of a bucket are done this way; the vector ALU does the splitting.
 //
@@ -40,7 +40,7 @@ __device__ __forceinline__ void mfma_split3(const uint32_t (&a)[3][4], const uin
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc, 0, 0, 0);
 }
 
-// The same for operands in NP pieces (3, or 2 where a relative error of 2^-18 per operand is within the bar: bf16 inputs).
+// The same for operands in NP pieces (3, or 2 where a relative error of 2^-16 per operand is within the bar: bf16 inputs).
 template <int NP>
 __device__ __forceinline__ void split_pieces(float x, float y, uint32_t (&dst)[NP][4], int p)
 {
