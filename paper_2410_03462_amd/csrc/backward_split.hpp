@@ -11,7 +11,7 @@
 // Lane L = 32 g + f; in every operand the lanes of group g carry depth slots (g, 0..7), two bf16 per register.
 #pragma once
 
-#include "fused_split.hpp"
+#include "split_common.hpp"
 
 namespace grf {
 

@@ -13,130 +13,9 @@
 // group g carry depth slots (g, 0..7) of the instruction, as two bf16 per register.
 #pragma once
 
-#include "attention_common.hpp"
+#include "split_common.hpp"
 
 namespace grf {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-typedef short shortx2 __attribute__((ext_vector_type(2)));
-typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
-typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
-
-// Two fp32 numbers as one register of two bf16 (round to nearest even), x in the low half.
-__device__ __forceinline__ uint32_t pack_bf16(float x, float y)
-{
-    const floatx2 v = {x, y};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
-__device__ __forceinline__ float low_bf16(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float high_bf16(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-
-// x minus the low (minus_low_bf16) or high (minus_high_bf16) bf16 of w, exactly: one v_dot2c_f32_bf16 each, x + w . (-1, 0)
-// or x + w . (0, -1), instead of a shift or mask and a subtraction.  (Every intermediate value is an fp32 number, so
-// the result does not depend on how the instruction orders its three terms.)
-// The selector pairs are handed over in registers: written as literals, the compiler encodes (-1, 0) as the inline
-// constant -1.0, which the instruction does not read as a bf16 pair.
-__device__ __forceinline__ uint32_t opaque_word(uint32_t w)
-{
-    asm("" : "+s"(w));      // not volatile: identical uses are merged into one scalar register
-    return w;
-}
-__device__ __forceinline__ float minus_low_bf16(float x, uint32_t w)
-{
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, opaque_word(0x0000bf80u)), x, false);
-}
-__device__ __forceinline__ float minus_high_bf16(float x, uint32_t w)
-{
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, opaque_word(0xbf800000u)), x, false);
-}
-
-// (x, y) as hi + lo, two bf16 numbers each.
-__device__ __forceinline__ void split_bf16(float x, float y, uint32_t& hi, uint32_t& lo)
-{
-    hi = pack_bf16(x, y);
-    lo = pack_bf16(minus_low_bf16(x, hi), minus_high_bf16(y, hi));
-}
-
-__device__ __forceinline__ uint32_t low_halves(uint32_t x, uint32_t y) { return (x & 0xffffu) | (y << 16); }
-__device__ __forceinline__ uint32_t high_halves(uint32_t x, uint32_t y) { return (x >> 16) | (y & 0xffff0000u); }
-
-// max(., floor) of both 16-bit halves as signed integers: with floor = 0 this is ReLU of two bf16 numbers
-// (sign-magnitude floats order like integers where it matters, see relu()), with floor = -32768 the identity.
-__device__ __forceinline__ uint32_t max_i16x2(uint32_t x, uint32_t floor)
-{
-    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(shortx2, x), __builtin_bit_cast(shortx2, floor)));
-}
-
-__device__ __forceinline__ bf16x8 as_operand(const uint32_t (&w)[4])
-{
-    const uintx4 v = {w[0], w[1], w[2], w[3]};
-    return __builtin_bit_cast(bf16x8, v);
-}
-
-// Walks the column list [beg, end) in steps of 16 members, out of blocks of 128 entries held one per lane in two
-// register sets (load_list_block).  request(rows, weights, scales, first, set) issues the loads of the step whose
-// members are entries first .. first + 15 (mod 64) of the registers handed over, into `set`; contract(set, weights,
-// scales, first) does the step's arithmetic.  Two sets take turns, so that the next step's loads are in flight
-// under this step's arithmetic, with scheduling barriers between request and arithmetic (the compiler would
-// otherwise reorder them).  The steps come in pairs: the second one is contracted also when it lies past the end of
-// the list (its members then have weight 0), since a skipped step's loads would be moved into the branch, next to
-// their use; past a block's last step the request is redundant and re-reads entries of the block.  A list of one
-// step (most lists of a grid graph) takes one request and one contraction.
-template <typename Members, bool SCALED, typename Request, typename Contract>
-__device__ __forceinline__ void walk_column_list(const int32_t* __restrict__ csc_row, const float* __restrict__ vals,
-                                                 const float* __restrict__ escale, int32_t beg, int32_t end,
-                                                 Request&& request, Contract&& contract)
-{
-    if (end - beg <= 16) {
-        const ListBlock lb = load_list_block<SCALED>(csc_row, vals, escale, beg, end);
-        Members only;
-        request(lb.j_a, lb.g_a, lb.e_a, 0, only);
-        contract(only, lb.g_a, lb.e_a, 0);
-        return;
-    }
-    for (int32_t block = beg; block < end; block += 2 * kWave) {
-        ListBlock lb = load_list_block<SCALED>(csc_row, vals, escale, block, end);
-        // all of the block's loads are taken here, where the first are needed anyway: requested later (the compiler
-        // sinks the second set to its first use), they would return behind the rows' loads
-        asm volatile("" : "+v"(lb.j_a), "+v"(lb.j_b), "+v"(lb.g_a), "+v"(lb.g_b), "+v"(lb.e_a), "+v"(lb.e_b));
-        const int steps = min((end - block + 15) >> 4, 8);
-        Members even, odd;
-        __builtin_amdgcn_sched_barrier(0);
-        request(lb.j_a, lb.g_a, lb.e_a, 0, even);
-#pragma nounroll
-        for (int s = 0; s < steps; s += 2) {
-            __builtin_amdgcn_sched_barrier(0);
-            request(s + 1 >= 4 ? lb.j_b : lb.j_a, s + 1 >= 4 ? lb.g_b : lb.g_a, s + 1 >= 4 ? lb.e_b : lb.e_a, 16 * (s + 1), odd);
-            __builtin_amdgcn_sched_barrier(0);
-            contract(even, s >= 4 ? lb.g_b : lb.g_a, s >= 4 ? lb.e_b : lb.e_a, 16 * s);
-            __builtin_amdgcn_sched_barrier(0);
-            request(s + 2 >= 4 ? lb.j_b : lb.j_a, s + 2 >= 4 ? lb.g_b : lb.g_a, s + 2 >= 4 ? lb.e_b : lb.e_a, 16 * (s + 2), even);
-            __builtin_amdgcn_sched_barrier(0);
-            contract(odd, s + 1 >= 4 ? lb.g_b : lb.g_a, s + 1 >= 4 ? lb.e_b : lb.e_a, 16 * (s + 1));
-        }
-    }
-}
-
-// A 32 x 64 output tile of the second contraction: register r of p0 / p1 in lane (g, f) is consumer row
-// 8 (r / 4) + 4 g + r % 4, column 2 f / 2 f + 1.  One 8-byte store per register pair through a window over the
-// tile's `rows` valid rows of the [..][64] fp32 array, which drops the rows past the end of the list; the rows'
-// constant offsets go into the instructions' offset fields (lane_off is made opaque so that they are not hoisted
-// into sixteen registers).
-__device__ __forceinline__ void store_consumer_tile(float* __restrict__ partial, long long row0, int rows, int g, int f,
-                                                    const floatx16& p0, const floatx16& p1)
-{
-    constexpr int D = 64;
-    const __amdgpu_buffer_rsrc_t window = row_window(partial, row0, rows, D);
-    int lane_off = (4 * g * D + 2 * f) * 4;
-    asm volatile("" : "+v"(lane_off));
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const uintx2 v = {__float_as_uint(p0[r]), __float_as_uint(p1[r])};
-        __builtin_amdgcn_raw_buffer_store_b64(v, window, lane_off + (8 * (r / 4) + (r % 4)) * D * 4, 0, 0);
-    }
-}
 
 // One wavefront per (slice, bucket l), one wavefront per workgroup.  Every global load is unconditional
 // (members past the end of the column list re-read its last entry with weight 0).

@@ -14,78 +14,9 @@
 // lanes of group g carry depth slots (g, 0..7) of the instruction, two bf16 per register.
 #pragma once
 
-#include "fused_bf16.hpp"
+#include "split_common.hpp"
 
 namespace grf {
-
-// (x, y) as h + m + l, two bf16 numbers each.
-__device__ __forceinline__ void split3_bf16(float x, float y, uint32_t& h, uint32_t& m, uint32_t& l)
-{
-    h = pack_bf16(x, y);
-    const float rx = minus_low_bf16(x, h), ry = minus_high_bf16(y, h);
-    m = pack_bf16(rx, ry);
-    l = pack_bf16(minus_low_bf16(rx, m), minus_high_bf16(ry, m));
-}
-
-// acc += a b for operands given as three pieces each: the six products that matter, small ones first.
-__device__ __forceinline__ void mfma_split3(const uint32_t (&a)[3][4], const uint32_t (&b)[3][4], floatx16& acc)
-{
-    const bf16x8 ah = as_operand(a[0]), am = as_operand(a[1]), al = as_operand(a[2]);
-    const bf16x8 bh = as_operand(b[0]), bm = as_operand(b[1]), bl = as_operand(b[2]);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bm, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bh, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bm, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc, 0, 0, 0);
-}
-
-// The same for operands in NP pieces (3, or 2 where a relative error of 2^-16 per operand is within the bar: bf16 inputs).
-template <int NP>
-__device__ __forceinline__ void split_pieces(float x, float y, uint32_t (&dst)[NP][4], int p)
-{
-    if constexpr (NP == 3) split3_bf16(x, y, dst[0][p], dst[1][p], dst[2][p]);
-    else split_bf16(x, y, dst[0][p], dst[1][p]);
-}
-template <int NP>
-__device__ __forceinline__ void mfma_pieces(const uint32_t (&a)[NP][4], const uint32_t (&b)[NP][4], floatx16& acc)
-{
-    if constexpr (NP == 3) {
-        mfma_split3(a, b, acc);
-    } else {
-        const bf16x8 ah = as_operand(a[0]), al = as_operand(a[1]), bh = as_operand(b[0]), bl = as_operand(b[1]);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc, 0, 0, 0);
-    }
-}
-
-// Elements 2f, 2f + 1 of a row as loaded (one 8-byte or one 4-byte load), widened to fp32 only where they are used.
-template <typename T> struct RawPair { typedef float2 type; };
-template <> struct RawPair<bf16_t> { typedef uint32_t type; };
-
-template <typename T, bool WIDE>
-__device__ __forceinline__ typename RawPair<T>::type load_pair(const T* __restrict__ base, uint32_t row, int f)
-{
-    return *reinterpret_cast<const typename RawPair<T>::type*>(row_elem_ptr<64, T, WIDE>(base, row, 2 * f));
-}
-__device__ __forceinline__ float2 widen(float2 v) { return v; }
-__device__ __forceinline__ float2 widen(uint32_t w) { return make_float2(low_bf16(w), high_bf16(w)); }
-
-// Eight consecutive elements of a row starting at element `elem` (a multiple of 8), widened to fp32.
-template <typename T, bool WIDE>
-__device__ __forceinline__ void load_eight(const T* __restrict__ base, uint32_t row, int elem, float (&x)[8])
-{
-    if constexpr (sizeof(T) == 4) {
-        const float4* p = reinterpret_cast<const float4*>(row_elem_ptr<64, T, WIDE>(base, row, elem));
-        const float4 u = p[0], v = p[1];
-        x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w; x[4] = v.x; x[5] = v.y; x[6] = v.z; x[7] = v.w;
-    } else {
-        const uintx4 w = *reinterpret_cast<const uintx4*>(row_elem_ptr<64, T, WIDE>(base, row, elem));
-#pragma unroll
-        for (int k = 0; k < 4; ++k) { x[2 * k] = low_bf16(w[k]); x[2 * k + 1] = high_bf16(w[k]); }
-    }
-}
 
 // First contraction of a bucket at d = 64 with three-piece operands: acc[a][c] = A^T B over the column list
 // [beg, end) with A = Phi_hat[j,l] phi(k_j), B = v_j (MFMA row/column x of tile t stands for element 2x + t), and
