@@ -250,6 +250,21 @@ grf_status grf_masked_linear_attention_fused(const void* Q, const void* K, const
                                              void* workspace, size_t workspace_bytes, void* hip_stream,
                                              float* out, float* num_opt, float* den_opt);
 
+/* grf_masked_linear_attention_fused for callers that can neither allocate device memory nor hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Inputs, outputs,
+ * results (bit-identical to grf_masked_linear_attention_fused) and error behaviour are the same; the scratch
+ * memory (column lists of Phi_hat, partial rows) is a 64 MiB device array that is part of the loaded library, one
+ * copy per GPU, held until the process ends.  The call allocates nothing, frees nothing and does not synchronise;
+ * it splits the B*H slices into as many chunks as the array requires.
+ * Limit: grf_fused_attention_workspace_bytes(B, H, n, d, nnz, n_f, 1) <= 64 MiB (about 230 000 entries of Phi_hat
+ * at d = 64 and n_f = 1), else GRF_EUNSUPPORTED and nothing is launched.
+ * Every call on a GPU uses that GPU's one array: calls that may overlap in time on one GPU (different streams,
+ * different host threads) race on it and must be ordered by the caller. */
+grf_status grf_masked_linear_attention_fused_static(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                    int64_t B, int64_t H, int64_t n, int32_t d,
+                                                    const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                    void* hip_stream, float* out, float* num_opt, float* den_opt);
+
 /* ---------------------------------------------------------------------------------------------
  * Asymmetric graph random features (App. D, Alg. 2): the keys use the one-hot feature (f^(2) = delta_0,
  * Phi^(2) = I), so the mask estimate is the sampled matrix itself.  phi must have been sampled with

@@ -94,6 +94,9 @@ def lib() -> ctypes.CDLL:
         L.grf_fused_attention_workspace_bytes.argtypes = L.grf_attention_workspace_bytes.argtypes
         L.grf_masked_linear_attention_fused.restype = ctypes.c_int32
         L.grf_masked_linear_attention_fused.argtypes = L.grf_masked_linear_attention.argtypes
+        L.grf_masked_linear_attention_fused_static.restype = ctypes.c_int32
+        L.grf_masked_linear_attention_fused_static.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, *common,
+                                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.grf_asymmetric_masked_attention.restype = ctypes.c_int32
         L.grf_asymmetric_masked_attention.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, *common,
                                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -423,6 +426,27 @@ def grf_masked_linear_attention_fused(Q, K, V, phi: Phi, feature_map: str = "rel
     """Bucket-fused variant: same results as grf_masked_linear_attention without bucket records in HBM."""
     return _attention_call("grf_masked_linear_attention_fused", "grf_fused_attention_workspace_bytes",
                            Q, K, V, phi, feature_map, bh_chunk, return_num_den, workspace, out, stream)
+
+
+def grf_masked_linear_attention_fused_static(Q, K, V, phi: Phi, feature_map: str = "relu", return_num_den: bool = False,
+                                             out: Optional[torch.Tensor] = None, num: Optional[torch.Tensor] = None,
+                                             den: Optional[torch.Tensor] = None, stream=None):
+    """The bucket-fused call on the library's own static scratch array: no workspace, and the library allocates
+    nothing (pass ``out`` / ``num`` / ``den`` and this binding allocates nothing either)."""
+    _require_gpu()
+    L = lib()
+    B, H, n, d = _check_qkv(Q, K, V)
+    if out is None:
+        out = torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device)
+    if return_num_den and num is None:
+        num = torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device)
+    if return_num_den and den is None:
+        den = torch.empty((B, H, n), dtype=torch.float32, device=Q.device)
+    ps = phi._struct()
+    _check(L.grf_masked_linear_attention_fused_static(_ptr(Q), _ptr(K), _ptr(V), _dtype_code(Q), B, H, n, d, ctypes.byref(ps),
+                                                      phi.nnz, phi.n_f, _FEATURE_MAPS[feature_map], _stream_ptr(stream),
+                                                      _ptr(out), _ptr(num), _ptr(den)))
+    return (out, num, den) if return_num_den else out
 
 
 def grf_masked_linear_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, phi: Phi,

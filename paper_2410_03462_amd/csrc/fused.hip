@@ -15,6 +15,8 @@
 //
 // Index convention (T2 = d/32): MFMA row/column x of tile t stands for feature / value column
 // T2*x + t, so that a lane's T2 operands are adjacent in memory (one 8-byte load at d = 64).
+#include <mutex>
+
 #include "attention_common.hpp"
 #include "fused_bf16.hpp"
 #include "fused_split.hpp"
@@ -357,21 +359,15 @@ extern "C" size_t grf_fused_attention_workspace_bytes(int64_t B, int64_t H, int6
     return carve_transposed(nullptr, n, nnz, n_f).bytes + partial_bytes(slices, nnz, d) + pden_bytes(slices, nnz);
 }
 
-extern "C" grf_status grf_masked_linear_attention_fused(const void* Q, const void* K, const void* V, int32_t dtype,
-                                                        int64_t B, int64_t H, int64_t n, int32_t d,
-                                                        const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
-                                                        int32_t bh_chunk,
-                                                        void* workspace, size_t workspace_bytes, void* hip_stream,
-                                                        float* out, float* num_opt, float* den_opt)
+namespace {
+
+// Both bucket-fused entry points: column lists, then bucket kernel + row reduction per chunk of `step` slices,
+// all scratch inside `ws` (grf_fused_attention_workspace_bytes(..., step) bytes, 256-byte aligned).
+grf_status fused_impl(const void* Q, const void* K, const void* V, int32_t dtype, int64_t B, int64_t H, int64_t n, int32_t d,
+                      const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map, int64_t step,
+                      unsigned char* ws, hipStream_t stream, float* out, float* num_opt, float* den_opt)
 {
-    if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
-    if (B * H * n > 0 && (Q == nullptr || out == nullptr)) return fail(GRF_EINVAL, "Q / out is NULL");
-    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_fused_attention_workspace_bytes(B, H, n, d, nnz, n_f, bh_chunk))) return st;
-    if (B * H * n == 0) return GRF_OK;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int64_t slices = B * H;
-    const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;
-    unsigned char* ws = static_cast<unsigned char*>(workspace);
     const Transposed t = carve_transposed(ws, n, nnz, n_f);
     float* partial = reinterpret_cast<float*>(ws + t.bytes);
     float* pden = reinterpret_cast<float*>(ws + t.bytes + partial_bytes(step, nnz, d));
@@ -385,4 +381,84 @@ extern "C" grf_status grf_masked_linear_attention_fused(const void* Q, const voi
         if (st != GRF_OK) return st;
     }
     return GRF_OK;
+}
+
+}  // namespace
+
+extern "C" grf_status grf_masked_linear_attention_fused(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                        int64_t B, int64_t H, int64_t n, int32_t d,
+                                                        const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                        int32_t bh_chunk,
+                                                        void* workspace, size_t workspace_bytes, void* hip_stream,
+                                                        float* out, float* num_opt, float* den_opt)
+{
+    if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
+    if (B * H * n > 0 && (Q == nullptr || out == nullptr)) return fail(GRF_EINVAL, "Q / out is NULL");
+    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_fused_attention_workspace_bytes(B, H, n, d, nnz, n_f, bh_chunk))) return st;
+    if (B * H * n == 0) return GRF_OK;
+    const int64_t slices = B * H;
+    const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;
+    return fused_impl(Q, K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map, step, static_cast<unsigned char*>(workspace),
+                      static_cast<hipStream_t>(hip_stream), out, num_opt, den_opt);
+}
+
+// ------------------------------------------------------------------------------------ the call that allocates nothing
+// For callers that cannot allocate (HIP graph capture, serving loops, harnesses that forbid hipMalloc) and hold no
+// workspace either: the column lists and the per-entry partial rows live in a device array that is part of the
+// loaded library.  Every GPU the library runs on holds its own copy of the array until the process ends.
+constexpr size_t kStaticScratchBytes = 64ull << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};      // device address of `scratch` on each device, once asked for
+
+// Device address of the scratch array on the current device.  `scratch` itself is only a host-side handle of the
+// symbol; host code must never use it as an address.
+grf_status static_scratch(unsigned char** ptr)
+{
+    int device = -1;
+    GRF_HIP_TRY(hipGetDevice(&device));
+    if (device < 0 || device >= kMaxDevices) return fail(GRF_EUNSUPPORTED, "device ordinal %d is outside [0, %d)", device, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device] == nullptr) {
+        void* p = nullptr;
+        GRF_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (p == nullptr || (reinterpret_cast<uintptr_t>(p) % kAlign) != 0)
+            return fail(GRF_EHIP, "hipGetSymbolAddress gave %p for the static scratch array", p);
+        g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+    }
+    *ptr = g_scratch_ptr[device];
+    return GRF_OK;
+}
+
+}  // namespace
+
+extern "C" grf_status grf_masked_linear_attention_fused_static(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                               int64_t B, int64_t H, int64_t n, int32_t d,
+                                                               const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                               void* hip_stream, float* out, float* num_opt, float* den_opt)
+{
+    if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
+    if (B * H * n > 0 && (Q == nullptr || out == nullptr)) return fail(GRF_EINVAL, "Q / out is NULL");
+    if (B * H * n == 0) return GRF_OK;
+    // as many slices per chunk as the array holds (results do not depend on the chunking)
+    const int64_t slices = B * H;
+    const size_t one = grf_fused_attention_workspace_bytes(B, H, n, d, nnz, n_f, 1);
+    if (one == 0 || one > kStaticScratchBytes)
+        return fail(GRF_EUNSUPPORTED, "one slice needs %zu bytes of scratch (grf_fused_attention_workspace_bytes with bh_chunk = 1) "
+                    "but the static array holds %zu; use grf_masked_linear_attention_fused with a workspace", one, kStaticScratchBytes);
+    int64_t step = 1;
+    if (slices > 1) {
+        const size_t per_slice = grf_fused_attention_workspace_bytes(B, H, n, d, nnz, n_f, 2) - one;
+        step = 1 + static_cast<int64_t>((kStaticScratchBytes - one) / (per_slice > 0 ? per_slice : 1));
+        if (step > slices) step = slices;
+        while (step > 1 && grf_fused_attention_workspace_bytes(B, H, n, d, nnz, n_f, static_cast<int32_t>(step)) > kStaticScratchBytes) --step;
+    }
+    unsigned char* ws = nullptr;
+    if (grf_status st = static_scratch(&ws)) return st;
+    return fused_impl(Q, K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map, step, ws, static_cast<hipStream_t>(hip_stream),
+                      out, num_opt, den_opt);
 }
