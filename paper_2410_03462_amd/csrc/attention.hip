@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256) void column_scatter_kernel(const int32_t* __re
 __global__ __launch_bounds__(256) void column_sort_kernel(const int32_t* __restrict__ col_ptr, int32_t n, int32_t nnz,
                                                           const int32_t* __restrict__ u_row, const int32_t* __restrict__ u_src,
                                                           int32_t* __restrict__ s_row, int32_t* __restrict__ s_src,
-                                                          int32_t* __restrict__ csr_to_csc)
+                                                          int32_t* __restrict__ csr_to_csc, int32_t* __restrict__ span)
 {
     const long long p = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (p >= nnz || p >= col_ptr[n]) return;      // nnz may be an upper bound: the lists end at col_ptr[n]
@@ -81,6 +81,7 @@ __global__ __launch_bounds__(256) void column_sort_kernel(const int32_t* __restr
         s_row[beg + rank] = key;
         s_src[beg + rank] = src;
         csr_to_csc[src] = beg + rank;
+        span[beg + rank] = rank | (min(len, 255) << 8);
     }
 }
 
@@ -94,6 +95,54 @@ __global__ __launch_bounds__(256) void column_values_kernel(const int32_t* __res
     if (pos >= nnz || pos >= col_ptr[n]) return;
     const int32_t src = s_src[pos];
     for (int h = 0; h < n_f; ++h) s_val[h * nnz + pos] = val[h * val_stride + src];
+}
+
+// Work items of the short-list kernels and the list of the long buckets.  One thread per window of kGramWindow
+// consecutive list entries: the buckets whose lists start inside the window are consecutive, and only the last of
+// them can be longer than kGramPackMax (a longer list reaches beyond the window).  The lists up to that one form one
+// run; the last one joins it, is a run by itself or goes to the list of long buckets, by its length.  Runs and long
+// buckets are appended with one atomic per wavefront; their order is not fixed and nothing depends on it.
+__global__ __launch_bounds__(256) void window_plan_kernel(const int32_t* __restrict__ col_ptr, int32_t n, long long n_windows,
+                                                          int2* __restrict__ items, int32_t* __restrict__ long_list,
+                                                          int32_t* __restrict__ counts)
+{
+    const long long w = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    // first bucket in [0, n) whose list starts at or after entry x (n if none)
+    auto first_from = [&](long long x) {
+        int32_t lo = 0, hi = n;
+        while (lo < hi) {
+            const int32_t mid = lo + (hi - lo) / 2;
+            if (col_ptr[mid] >= x) hi = mid; else lo = mid + 1;
+        }
+        return lo;
+    };
+    int2 packed = make_int2(0, 0), alone = make_int2(0, 0);
+    int32_t long_bucket = -1;
+    if (w < n_windows) {
+        const int32_t la = first_from(w * kGramWindow), lb = first_from((w + 1) * kGramWindow);
+        if (la < lb) {
+            const int32_t last_beg = col_ptr[lb - 1], last_end = col_ptr[lb];
+            const int32_t last_len = last_end - last_beg;
+            packed = make_int2(col_ptr[la], last_len > kGramPackMax ? last_beg : last_end);
+            if (packed.y - packed.x > kGramTile) packed = make_int2(0, 0);      // cannot happen for a monotone col_ptr
+            if (last_len > kGramMaxList) long_bucket = lb - 1;
+            else if (last_len > kGramPackMax) alone = make_int2(last_beg, last_end);
+        }
+    }
+    auto append = [&](bool have, int32_t* counter) -> int32_t {
+        const unsigned long long mask = __ballot(have);
+        int32_t base = 0;
+        if (lane_id() == 0 && mask != 0ull) base = atomicAdd(counter, __popcll(mask));
+        base = __shfl(base, 0, kWave);
+        return base + prefix_popcount(mask);
+    };
+    const bool has_packed = packed.y > packed.x, has_alone = alone.y > alone.x;
+    const int32_t at_packed = append(has_packed, counts + kPlanItems);
+    if (has_packed) items[at_packed] = packed;
+    const int32_t at_alone = append(has_alone, counts + kPlanItems);
+    if (has_alone) items[at_alone] = alone;
+    const int32_t at_long = append(long_bucket >= 0, counts + kPlanLong);
+    if (long_bucket >= 0) long_list[at_long] = long_bucket;
 }
 
 // ------------------------------------------------------------------------------------ buckets
@@ -256,6 +305,12 @@ Transposed carve_transposed(unsigned char* ws, int64_t n, int64_t nnz, int32_t n
     t.csr_to_csc = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
     t.arrival = t.csr_to_csc;      // the arrival indices are dead before the positions are written
     t.s_val = reinterpret_cast<float*>(take(sizeof(float) * entries * static_cast<size_t>(n_f > 0 ? n_f : 1)));
+    t.span = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
+    t.n_windows = static_cast<long long>((entries + kGramWindow - 1) / kGramWindow);
+    t.item_capacity = 2 * t.n_windows;      // a window yields at most one run of packed lists and one list alone
+    t.items = reinterpret_cast<int2*>(take(sizeof(int2) * static_cast<size_t>(t.item_capacity)));
+    t.long_list = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n > 0 ? n : 1)));
+    t.plan_counts = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * kPlanCounters));
     t.total = reinterpret_cast<long long*>(take(sizeof(long long)));
     t.bytes = off;
     return t;
@@ -265,6 +320,7 @@ grf_status transpose(const grf_phi* phi, int64_t nnz, int32_t n_f, const Transpo
 {
     const int64_t n = phi->n;
     if (grf_status st = fill_i32(t.col_ptr, n + 1, 0, stream)) return st;
+    if (grf_status st = fill_i32(t.plan_counts, kPlanCounters, 0, stream)) return st;
     if (nnz > 0) {
         if (grf_status st = fill_i32(t.s_row, nnz, 0, stream)) return st;
         if (grf_status st = fill_i32(t.s_src, nnz, 0, stream)) return st;
@@ -285,8 +341,12 @@ grf_status transpose(const grf_phi* phi, int64_t nnz, int32_t n_f, const Transpo
         hipLaunchKernelGGL(column_sort_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, stream,
                            static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n), static_cast<int32_t>(nnz),
                            static_cast<const int32_t*>(t.u_row), static_cast<const int32_t*>(t.u_src), t.s_row, t.s_src,
-                           t.csr_to_csc);
+                           t.csr_to_csc, t.span);
         GRF_LAUNCH_CHECK("column_sort_kernel");
+        hipLaunchKernelGGL(window_plan_kernel, dim3(blocks_for(t.n_windows, 256)), dim3(256), 0, stream,
+                           static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n), t.n_windows, t.items, t.long_list,
+                           t.plan_counts);
+        GRF_LAUNCH_CHECK("window_plan_kernel");
         hipLaunchKernelGGL(column_values_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, stream,
                            static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n),
                            static_cast<const int32_t*>(t.s_src), static_cast<long long>(nnz), static_cast<int>(n_f),

@@ -95,6 +95,15 @@ __device__ __forceinline__ void load_run(const T* __restrict__ p, float (&out)[N
     }
 }
 
+// Lists of at most kGramMaxList entries are evaluated in runs of at most kGramTile consecutive entries of the column
+// lists (gram_split.hpp): the lists of at most kGramPackMax entries that start inside one window of kGramWindow entries
+// form one run (it spans at most kGramWindow - 1 + kGramPackMax = kGramTile entries), a longer one is a run by itself.
+constexpr int kGramWindow = 16;
+constexpr int kGramTile = 32;
+constexpr int kGramPackMax = kGramTile - kGramWindow + 1;      // 17
+constexpr int kGramMaxList = kGramTile;                        // longer lists go through S_l, one bucket per wavefront
+enum : int { kPlanItems = 0, kPlanLong = 1, kPlanCounters = 2 };      // device-side counts written by the plan
+
 // Column lists of Phi_hat, carved out of the caller's workspace.
 struct Transposed {
     int32_t* col_ptr;   // [n+1]
@@ -105,6 +114,11 @@ struct Transposed {
     int32_t* csr_to_csc;  // [nnz] position in the column lists of CSR entry e
     int32_t* arrival;     // [nnz] arrival index of entry e within its column while the lists are built (same memory)
     float* s_val;       // [n_f][nnz] value planes permuted into column-list order
+    int32_t* span;      // [nnz] per list position: its index inside its list | min(list length, 255) << 8
+    int2* items;        // [item_capacity] entry ranges of the runs of short lists, in no particular order (see gram_split.hpp)
+    int32_t* long_list; // [n] the buckets whose lists are longer than kGramMaxList, in no particular order
+    int32_t* plan_counts;   // [kPlanCounters] how many of each, on the device
+    long long n_windows, item_capacity;
     long long* total;
     size_t bytes;
 };
@@ -357,6 +371,10 @@ __device__ __forceinline__ void bucket_first_contraction(const TA* __restrict__ 
 unsigned resident_wave_grid(const void* kernel, long long items);
 
 inline unsigned blocks_for(long long items, int per_block) { return static_cast<unsigned>((items + per_block - 1) / per_block); }
+
+// Launch shape of the d = 64 S_l kernels (for_each_long_bucket): true when the mean list length says that few lists are
+// longer than kGramMaxList.  Either shape is correct for any input and gives the same bits.
+inline bool few_long_lists(int64_t n, int64_t nnz) { return nnz < 48 * n; }
 
 // True when a [n][d] slice may span 4 GiB or more (or the test hook forces it): the bucket kernels then use
 // 64-bit row offsets (row_elem_ptr).

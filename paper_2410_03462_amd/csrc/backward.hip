@@ -24,6 +24,7 @@
 
 #include "attention_common.hpp"
 #include "backward_split.hpp"
+#include "gram_split.hpp"
 
 namespace grf {
 
@@ -376,6 +377,8 @@ grf_status launch_backward_chunk(const void* Qv, const void* Kv, const void* Vv,
     const T* V = static_cast<const T*>(Vv);
     const long long waves = static_cast<long long>(n_slices) * n;
     if (waves == 0) return GRF_OK;
+    if (D == 64 && static_cast<long long>(n_slices) * t.item_capacity >= 2147483647ll)
+        return fail(GRF_EUNSUPPORTED, "slices * nnz / 8 = %lld * %lld must be < 2^31", (long long)n_slices, t.item_capacity);
     if (grf_status st = launch_backward_seed(D, out, den, d_out, static_cast<long long>(bh_first) * n, waves, b.G, b.gd, stream)) return st;
 
     const dim3 bucket_grid(blocks_for(waves, 1)), reduce_grid(blocks_for(waves, 4));
@@ -393,11 +396,25 @@ grf_status launch_backward_chunk(const void* Qv, const void* Kv, const void* Vv,
     const int spread = 8ll * n * D * (3 * static_cast<long long>(sizeof(T)) + 4) <= (64ll << 20) ? 1 : 0;
     auto bucket_pass = [&](auto mode) {
         auto launch = [&](auto w) {
-            if constexpr (D == 64) {      // on the bf16 matrix cores
-                hipLaunchKernelGGL((backward_bucket_split_kernel<T, decltype(mode)::value, decltype(w)::value>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
-                                   static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),
-                                   static_cast<int>(H), static_cast<int>(n_f), col_ptr, s_row, s_val, fmap,
-                                   static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), spread, b.partial);
+            if constexpr (D == 64) {      // on the bf16 matrix cores: short lists several buckets per wavefront, the others one each
+                auto gram = gram_bucket_kernel<T, decltype(mode)::value, decltype(w)::value>;
+                hipLaunchKernelGGL(gram, dim3(resident_wave_grid(reinterpret_cast<const void*>(gram), static_cast<long long>(n_slices) * t.item_capacity)),
+                                   dim3(kWave), 0, stream,
+                                   Q, K, V, static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),
+                                   static_cast<int>(H), static_cast<int>(n_f), static_cast<const int2*>(t.items),
+                                   static_cast<const int32_t*>(t.plan_counts), s_row, static_cast<const int32_t*>(t.span), s_val, fmap,
+                                   static_cast<long long>(bh_first), static_cast<uint32_t>(n_slices), static_cast<int32_t>(nnz), spread,
+                                   b.partial, static_cast<float*>(nullptr));
+                auto go = [&](auto kernel, bool listed) {
+                    const dim3 grid = listed ? dim3(resident_wave_grid(reinterpret_cast<const void*>(kernel), waves)) : bucket_grid;
+                    hipLaunchKernelGGL(kernel, grid, dim3(kWave), 0, stream, Q, K, V,
+                                       static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),
+                                       static_cast<int>(H), static_cast<int>(n_f), col_ptr, s_row, s_val, fmap,
+                                       static_cast<long long>(bh_first), waves, static_cast<int32_t>(nnz), spread,
+                                       static_cast<const int32_t*>(t.long_list), static_cast<const int32_t*>(t.plan_counts), b.partial);
+                };
+                if (few_long_lists(n, nnz)) go(backward_bucket_split_kernel<T, decltype(mode)::value, decltype(w)::value, true>, true);
+                else go(backward_bucket_split_kernel<T, decltype(mode)::value, decltype(w)::value, false>, false);
             } else {
                 hipLaunchKernelGGL((backward_bucket_kernel<D, T, decltype(mode)::value, decltype(w)::value>), bucket_grid, dim3(kWave), 0, stream, Q, K, V,
                                    static_cast<const float*>(b.G), static_cast<const float*>(b.gd), static_cast<long long>(n),

@@ -15,8 +15,6 @@
 
 namespace grf {
 
-enum : int { kQuerySide = 0, kKeySide = 1, kValueSide = 2 };
-
 // One wavefront per (slice, bucket l), one wavefront per workgroup; every global load is unconditional (members
 // past the end of the column list re-read its last entry with weight 0).  16 members of the list per step of the
 // first contraction (lane (g, f) takes members 8 g + 0..7 and loads elements 2f, 2f + 1 of their two rows), 32
@@ -24,20 +22,18 @@ enum : int { kQuerySide = 0, kKeySide = 1, kValueSide = 2 };
 // once per bucket.  The extra row x is summed on the vector ALU beside the first contraction; its column 2f + c
 // ends up in lane f, which is the column that lane's output registers hold, so the output tile starts from
 // coefficient * x (the coefficients of the registers' consumers come over with ds_bpermute) instead of from zero.
-template <typename T, int MODE, bool WIDE>
+template <typename T, int MODE, bool WIDE, bool LISTED>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void backward_bucket_split_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, const float* __restrict__ G, const float* __restrict__ gd,
     long long n, int H, int n_f, const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row,
     const float* __restrict__ csc_val, int fmap, long long bh_first, long long n_waves, int32_t nnz, int spread_xcds,
-    float* __restrict__ partial)
+    const int32_t* __restrict__ long_list, const int32_t* __restrict__ plan_counts, float* __restrict__ partial)
 {
     constexpr int D = 64;
     // pieces per operand: fp32-grade products for fp32 inputs; with bf16 inputs (bar 2e-2) two pieces, three products
     constexpr int NP = sizeof(T) == 2 ? 2 : 3;
-    if (blockIdx.x >= n_waves) return;
-    const BucketId bucket = bucket_of_workgroup(n, spread_xcds);
-    const uint32_t l32 = bucket.l;
-    const long long slice = bucket.slice;
+    for_each_long_bucket<LISTED>(n, n_waves, spread_xcds, long_list, plan_counts, [&](uint32_t slice32, uint32_t l32) {
+    const long long slice = slice32;
     const long long bh = bh_first + slice;
     const long long plane = n_f > 1 ? (static_cast<uint32_t>(bh) % static_cast<uint32_t>(H)) : 0u;
     const T* Qb = Q + bh * n * D;
@@ -53,7 +49,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
 
     const int32_t beg = __builtin_amdgcn_readfirstlane(col_ptr[l32]);
     const int32_t end = __builtin_amdgcn_readfirstlane(col_ptr[l32 + 1]);
-    if (beg >= end) return;
+    if (end - beg <= kGramMaxList) return;      // short lists (and empty ones) belong to gram_bucket_kernel
 
     // consumer f's operand of the second contraction at the elements of depth slots (g, .): elements 2 rho,
     // 2 rho + 1 for rho = 8 hr + 4 g + 0..3; and its coefficient of the extra row
@@ -222,6 +218,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void ba
 
         store_consumer_tile(partial, pbase + tile, min(end - tile, 32), g, f, pc[0], pc[1]);
     }
+    });
 }
 
 }  // namespace grf

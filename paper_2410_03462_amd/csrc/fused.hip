@@ -20,6 +20,7 @@
 #include "attention_common.hpp"
 #include "fused_bf16.hpp"
 #include "fused_split.hpp"
+#include "gram_split.hpp"
 
 namespace grf {
 
@@ -303,6 +304,8 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
 {
     const long long waves = static_cast<long long>(n_slices) * n;
     if (waves == 0) return GRF_OK;
+    if (D == 64 && static_cast<long long>(n_slices) * t.item_capacity >= 2147483647ll)
+        return fail(GRF_EUNSUPPORTED, "slices * nnz / 8 = %lld * %lld must be < 2^31", (long long)n_slices, t.item_capacity);
     // eight slices' Q, K, V within a quarter of the 256 MB Infinity Cache: see the kernel
     const int spread = 8ll * 3 * n * D * static_cast<long long>(sizeof(T)) <= (64ll << 20) ? 1 : 0;
     auto launch = [&](auto wide) {
@@ -310,18 +313,36 @@ grf_status launch_fused(const void* Q, const void* K, const void* V, int64_t n, 
         if constexpr (D == 64) {
             // d = 64 runs on the bf16 matrix cores: bf16 inputs under a feature map that keeps bf16 values bf16 with
             // two-piece fp32 operands, everything else with three-piece operands and six products
-            auto go = [&](auto kernel) {
-                hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(waves)), dim3(kWave), 0, stream,
+            // lists of at most kGramMaxList entries, several buckets per wavefront; the kernels below skip them
+            hipLaunchKernelGGL((gram_bucket_kernel<T, kForwardSide, W>),
+                               dim3(resident_wave_grid(reinterpret_cast<const void*>(&gram_bucket_kernel<T, kForwardSide, W>), static_cast<long long>(n_slices) * t.item_capacity)),
+                               dim3(kWave), 0, stream,
+                               static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+                               static_cast<const float*>(nullptr), static_cast<const float*>(nullptr),
+                               static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
+                               static_cast<const int2*>(t.items), static_cast<const int32_t*>(t.plan_counts),
+                               static_cast<const int32_t*>(t.s_row), static_cast<const int32_t*>(t.span),
+                               static_cast<const float*>(t.s_val), fmap, static_cast<long long>(bh_first),
+                               static_cast<uint32_t>(n_slices), static_cast<int32_t>(nnz), spread, partial, pden);
+            // the longer lists: one workgroup per bucket when most lists are long, else a resident grid over the listed ones
+            auto go = [&](auto kernel, bool listed) {
+                const unsigned grid = listed ? resident_wave_grid(reinterpret_cast<const void*>(kernel), waves) : static_cast<unsigned>(waves);
+                hipLaunchKernelGGL(kernel, dim3(grid), dim3(kWave), 0, stream,
                                    static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                                    static_cast<long long>(n), static_cast<int>(H), static_cast<int>(n_f),
                                    static_cast<const int32_t*>(t.col_ptr), static_cast<const int32_t*>(t.s_row),
                                    static_cast<const float*>(t.s_val), fmap, static_cast<long long>(bh_first), waves,
-                                   static_cast<int32_t>(nnz), spread, partial, pden);
+                                   static_cast<int32_t>(nnz), spread, static_cast<const int32_t*>(t.long_list),
+                                   static_cast<const int32_t*>(t.plan_counts), partial, pden);
             };
+            const bool listed = few_long_lists(n, nnz);
             if constexpr (std::is_same<T, bf16_t>::value) {
-                if (fmap != GRF_PHI_ELU1) { go(fused_bucket_bf16_kernel<W>); return; }
+                if (fmap != GRF_PHI_ELU1) {
+                    if (listed) go(fused_bucket_bf16_kernel<W, true>, true); else go(fused_bucket_bf16_kernel<W, false>, false);
+                    return;
+                }
             }
-            go(fused_bucket_split_kernel<T, W>);
+            if (listed) go(fused_bucket_split_kernel<T, W, true>, true); else go(fused_bucket_split_kernel<T, W, false>, false);
         } else {
             hipLaunchKernelGGL((fused_bucket_kernel<D, T, W>), dim3(resident_wave_grid(reinterpret_cast<const void*>(&fused_bucket_kernel<D, T, W>), waves)), dim3(kWave), 0, stream,
                                static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),

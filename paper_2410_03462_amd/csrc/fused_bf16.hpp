@@ -30,17 +30,16 @@ namespace grf {
 // are the B operand of depth slots (g, 0..7): S rows 2 (16 h + 8 (j / 4) + 4 g + j % 4) + a.  The A operand is
 // consumer f's phi(q) at the same features: two 16-byte loads per h.  The partial denominator is the same
 // product the other way round (the z tile as A, phi(Q) as B), which leaves it in register 0 of lanes 0..31.
-template <bool WIDE>
+template <bool WIDE, bool LISTED>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fused_bucket_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, long long n, int H, int n_f,
     const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row, const float* __restrict__ csc_val, int fmap,
-    long long bh_first, long long n_waves, int32_t nnz, int spread_xcds, float* __restrict__ partial, float* __restrict__ pden)
+    long long bh_first, long long n_waves, int32_t nnz, int spread_xcds, const int32_t* __restrict__ long_list,
+    const int32_t* __restrict__ plan_counts, float* __restrict__ partial, float* __restrict__ pden)
 {
     constexpr int D = 64;
-    if (blockIdx.x >= n_waves) return;
-    const BucketId bucket = bucket_of_workgroup(n, spread_xcds);
-    const uint32_t l32 = bucket.l;
-    const long long slice = bucket.slice;
+    for_each_long_bucket<LISTED>(n, n_waves, spread_xcds, long_list, plan_counts, [&](uint32_t slice32, uint32_t l32) {
+    const long long slice = slice32;
     const long long bh = bh_first + slice;
     const long long plane = n_f > 1 ? (static_cast<uint32_t>(bh) % static_cast<uint32_t>(H)) : 0u;
     const bf16_t* Qb = Q + bh * n * D;
@@ -54,7 +53,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
 
     const int32_t beg = __builtin_amdgcn_readfirstlane(col_ptr[l32]);
     const int32_t end = __builtin_amdgcn_readfirstlane(col_ptr[l32 + 1]);
-    if (beg >= end) return;      // nobody visits this node: no partial rows belong to it
+    if (end - beg <= kGramMaxList) return;      // short lists (and empty ones) belong to gram_bucket_kernel
 
     const uint32_t floor16 = fmap == GRF_PHI_RELU ? 0u : 0x80008000u;
 
@@ -176,6 +175,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
 
         store_consumer_tile(partial, pbase + tile, min(end - tile, 32), g, f, pc[0], pc[1]);
     }
+    });
 }
 
 }  // namespace grf

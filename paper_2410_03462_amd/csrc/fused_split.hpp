@@ -91,17 +91,16 @@ __device__ __forceinline__ void bucket_first_contraction_split(const T* __restri
 // the accumulators' registers 8 h + 0..7 split into pieces once per bucket.  z_l is summed on the vector ALU
 // beside the first contraction and handed to the lanes in the order of their depth slots with ds_bpermute; the
 // partial denominator phi(q) . z_l is 32 fused multiply-adds per lane and tile.
-template <typename T, bool WIDE>
+template <typename T, bool WIDE, bool LISTED>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fused_bucket_split_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, long long n, int H, int n_f,
     const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ csc_row, const float* __restrict__ csc_val, int fmap,
-    long long bh_first, long long n_waves, int32_t nnz, int spread_xcds, float* __restrict__ partial, float* __restrict__ pden)
+    long long bh_first, long long n_waves, int32_t nnz, int spread_xcds, const int32_t* __restrict__ long_list,
+    const int32_t* __restrict__ plan_counts, float* __restrict__ partial, float* __restrict__ pden)
 {
     constexpr int D = 64;
-    if (blockIdx.x >= n_waves) return;
-    const BucketId bucket = bucket_of_workgroup(n, spread_xcds);
-    const uint32_t l32 = bucket.l;
-    const long long slice = bucket.slice;
+    for_each_long_bucket<LISTED>(n, n_waves, spread_xcds, long_list, plan_counts, [&](uint32_t slice32, uint32_t l32) {
+    const long long slice = slice32;
     const long long bh = bh_first + slice;
     const long long plane = n_f > 1 ? (static_cast<uint32_t>(bh) % static_cast<uint32_t>(H)) : 0u;
     const T* Qb = Q + bh * n * D;
@@ -115,7 +114,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
 
     const int32_t beg = __builtin_amdgcn_readfirstlane(col_ptr[l32]);
     const int32_t end = __builtin_amdgcn_readfirstlane(col_ptr[l32 + 1]);
-    if (beg >= end) return;      // nobody visits this node: no partial rows belong to it
+    if (end - beg <= kGramMaxList) return;      // short lists (and empty ones) belong to gram_bucket_kernel
 
     // consumer f's q at the features of depth slots (g, .): elements 2 rho, 2 rho + 1 for rho = 8 hr + 4 g + 0..3
     auto fetch_q = [&](int32_t row, float (&qw)[4][8]) {
@@ -200,6 +199,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void fu
 
         store_consumer_tile(partial, pbase + tile, min(end - tile, 32), g, f, pc[0], pc[1]);
     }
+    });
 }
 
 }  // namespace grf

@@ -11,6 +11,9 @@
 
 namespace grf {
 
+// The bucket passes: the forward pass and the three passes of the backward pass (see backward_split.hpp).
+enum : int { kQuerySide = 0, kKeySide = 1, kValueSide = 2, kForwardSide = 3 };
+
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
@@ -129,6 +132,30 @@ __device__ __forceinline__ void store_consumer_tile(float* __restrict__ partial,
     for (int r = 0; r < 16; ++r) {
         const uintx2 v = {__float_as_uint(p0[r]), __float_as_uint(p1[r])};
         __builtin_amdgcn_raw_buffer_store_b64(v, window, lane_off + (8 * (r / 4) + (r % 4)) * D * 4, 0, 0);
+    }
+}
+
+// Which bucket(s) a one-wavefront workgroup of the d = 64 S_l kernels takes.  Unless LISTED, the grid has one workgroup
+// per (slice, bucket) and short lists return at once: right when most lists are long.  LISTED: a resident grid strides
+// through the (slice, long bucket) pairs of the plan's list of long buckets: right when few lists are long, where a
+// grid of mostly empty workgroups costs more than the work (0.2 us each).  The arithmetic per bucket is the same.
+template <bool LISTED, typename Body>
+__device__ __forceinline__ void for_each_long_bucket(long long n, long long n_waves, int spread_xcds,
+                                                     const int32_t* __restrict__ long_list, const int32_t* __restrict__ plan_counts,
+                                                     Body&& body)
+{
+    if constexpr (LISTED) {
+        const uint32_t n_long = static_cast<uint32_t>(plan_counts[kPlanLong]);
+        if (n_long == 0) return;
+        const uint32_t total = static_cast<uint32_t>(n_waves / n) * n_long;      // <= B*H*n < 2^31
+        for (uint32_t t = blockIdx.x; t < total; t += gridDim.x) {
+            const uint32_t slice = t / n_long;
+            body(slice, static_cast<uint32_t>(long_list[t - slice * n_long]));
+        }
+    } else {
+        if (blockIdx.x >= n_waves) return;
+        const BucketId bucket = bucket_of_workgroup(n, spread_xcds);
+        body(bucket.slice, bucket.l);
     }
 }
 

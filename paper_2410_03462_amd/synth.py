@@ -215,6 +215,26 @@ def one_long_column(length, rng):
 
 
 
+def columns_of_lengths(lengths, rng):
+    """A hand-made n x n feature matrix in CSR whose column l has exactly ``lengths[l]`` entries (n = len(lengths)), for
+    tests of how column lists of given lengths sit next to each other: the rows are dealt out along a random permutation,
+    so the entries of a column lie in distinct rows and, if the lengths sum to at least n, no row is empty; values uniform
+    in 0.2 .. 1.  Returns (n, row_ptr, col, val[1, nnz])."""
+    lengths = np.asarray(lengths, dtype=np.int64)
+    n = int(lengths.shape[0])
+    assert lengths.max() <= n
+    perm = rng.permutation(n)
+    cols = np.repeat(np.arange(n), lengths)
+    rows = perm[np.arange(cols.shape[0]) % n]
+    order = np.lexsort((cols, rows))
+    rows, cols = rows[order], cols[order]
+    rp = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(rp, rows + 1, 1)
+    rp = np.cumsum(rp).astype(np.int32)
+    val = rng.uniform(0.2, 1.0, size=(1, len(cols))).astype(np.float32)
+    return n, rp, cols.astype(np.int32), val
+
+
 def modulation(f_len: int, rng: np.random.Generator, kind: str = "decay", n_f: int = 1, std: float = 1.0) -> np.ndarray:
     """f of shape [n_f, f_len], float32.  ``decay``: N(0,1)/(k+1); ``normal``: N(0, std)."""
     g = rng.standard_normal((n_f, f_len))
