@@ -141,8 +141,9 @@ size_t grf_sample_workspace_bytes(int64_t n, int32_t n_walks, int32_t f_len, int
  *              a first call with capacity 0 (col = val = NULL allowed) is a way to learn nnz.
  * nnz_out      HOST pointer; receives the number of entries.  The call blocks on the stream for this.
  *
- * GRF_EUNSUPPORTED if 1 + n_walks*(f_len-1) exceeds what one wavefront can stage in LDS (currently
- * 8192 deposits) or if the number of entries does not fit int32.
+ * Rows are assembled in LDS: by one wavefront per node while 1 + n_walks*(f_len-1), the largest possible number of
+ * deposits of a row, is at most 768, by a workgroup of 1024 threads per node (a bitonic sorting network) beyond.
+ * GRF_EUNSUPPORTED if 1 + n_walks*(f_len-1) exceeds 16384 or if the number of entries does not fit int32.
  */
 grf_status grf_sample(const grf_graph* g,
                       const float* f, int32_t f_len, int32_t n_f,
@@ -338,8 +339,8 @@ grf_status grf_asymmetric_masked_attention_backward(const void* Q, const void* K
  * phi        the pattern sampled with those arguments (row_ptr, col; val is not read), nnz its entries.
  * dphi_val   device fp32 [n_f][phi->capacity].
  * df         device fp32 [n_f][f_len], overwritten.  Sums run in a fixed order (bitwise reproducible).
- * Workspace: n * n_f * f_len floats of per-node partial sums. */
-size_t grf_sample_backward_workspace_bytes(int64_t n, int32_t f_len, int32_t n_f);
+ * Workspace: n * n_f * f_len floats of per-node partial sums (plus staging areas when rows are assembled by workgroups). */
+size_t grf_sample_backward_workspace_bytes(int64_t n, int32_t n_walks, int32_t f_len, int32_t n_f);
 
 grf_status grf_sample_backward(const grf_graph* g, int32_t f_len, int32_t n_f,
                                double p_halt, int32_t n_walks, uint64_t seed,

@@ -120,7 +120,7 @@ def lib() -> ctypes.CDLL:
         L.grf_asymmetric_masked_attention_backward.restype = ctypes.c_int32
         L.grf_asymmetric_masked_attention_backward.argtypes = L.grf_masked_linear_attention_backward.argtypes
         L.grf_sample_backward_workspace_bytes.restype = ctypes.c_size_t
-        L.grf_sample_backward_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
+        L.grf_sample_backward_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
         L.grf_sample_backward.restype = ctypes.c_int32
         L.grf_sample_backward.argtypes = [ctypes.POINTER(_Graph), ctypes.c_int32, ctypes.c_int32, ctypes.c_double,
                                           ctypes.c_int32, ctypes.c_uint64, ctypes.POINTER(_Phi), ctypes.c_int64,
@@ -578,7 +578,7 @@ def grf_sample_backward(graph: DeviceGraph, f_len: int, p_halt: float, n_walks: 
     if tuple(dphi_val.shape) != (phi.n_f, phi.capacity) or dphi_val.dtype != torch.float32 or not dphi_val.is_contiguous():
         raise ValueError("dphi_val must be a contiguous fp32 tensor [n_f, capacity]")
     dev = graph.row_ptr.device
-    ws = _workspace(L.grf_sample_backward_workspace_bytes(graph.n, f_len, phi.n_f), dev)
+    ws = _workspace(L.grf_sample_backward_workspace_bytes(graph.n, int(n_walks), int(f_len), phi.n_f), dev)
     df = torch.empty((phi.n_f, f_len), dtype=torch.float32, device=dev)
     gs, ps = graph._struct(), phi._struct()
     _check(L.grf_sample_backward(ctypes.byref(gs), int(f_len), phi.n_f, float(p_halt), int(n_walks),

@@ -267,6 +267,305 @@ grf_status launch_rows(const GraphView& gv, const WalkLaw& law, int n_walks, int
     return launch(std::integral_constant<int, 64>{});
 }
 
+// ------------------------------------------------------------------------------------ rows with many deposits
+// Rows whose deposits exceed what one wavefront can order by counting: one workgroup of kLargeBlock threads per node
+// (a resident grid strides over the nodes), threads = walks.
+//   1. Every walk is simulated twice from its counter-based stream: first for its number of hops, then, after a prefix
+//      sum over the walks, to write its deposits at their slots, so that the deposits stand in (walk, hop) order.
+//      Columns go to LDS with the slot number as a 16-bit tag; loads and hops go to a staging area of the workgroup in
+//      the caller's workspace (they are only needed again once, by slot).
+//   2. (column, slot) pairs are ordered by a bitonic sorting network in LDS (all comparators ascending, so that the
+//      positions past the last deposit behave as +infinity and are skipped: no padding to a power of two).
+//   3. Every thread owns a run of consecutive sorted positions: heads of equal-column runs are counted, a prefix sum
+//      gives each run its entry number, and the runs' sums Sum load * f[hop] are formed per thread in sorted order and
+//      joined across threads by a segmented prefix sum: a fixed order, bitwise reproducible.
+// LDS: 6 bytes per possible deposit, so 16384 deposits take 96 KB.
+constexpr int kLargeBlock = 1024;
+constexpr int kLargeWaves = kLargeBlock / kWave;
+constexpr int kLargeMaxGrid = 512;         // workgroups (and staging areas) at most
+constexpr int kLargeMaxDeposits = 16384;   // 16-bit slot tags; 96 KB of LDS
+
+// Exclusive prefix sum of one int per thread over the workgroup; *total = sum of all.  `scratch` holds kLargeWaves ints.
+__device__ __forceinline__ int block_exclusive_scan(int v, int* scratch, int* total)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int up = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += up;
+    }
+    __syncthreads();      // scratch may still be read from a previous call
+    if (lane == kWave - 1) scratch[wave] = incl;
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kLargeWaves; ++w) {
+        const int t = scratch[w];
+        if (w < wave) before += t;
+        all += t;
+    }
+    *total = all;
+    return before + incl - v;
+}
+
+// Segmented exclusive prefix sum over the workgroup's threads, in thread order: each thread contributes (value, flag);
+// a set flag starts a new segment at that thread.  Returns the sum of the values of the threads before this one back to
+// and including the nearest thread with a set flag (or from thread 0).
+__device__ __forceinline__ float block_segmented_exclusive_sum(float v, bool flag, float* scratch_v, int* scratch_f)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    // inclusive segmented scan inside the wavefront
+    float sv = v;
+    int sf = flag ? 1 : 0;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const float uv = __shfl_up(sv, off, kWave);
+        const int uf = __shfl_up(sf, off, kWave);
+        if (lane >= off) {
+            if (!sf) sv += uv;
+            sf |= uf;
+        }
+    }
+    __syncthreads();
+    if (lane == kWave - 1) { scratch_v[wave] = sv; scratch_f[wave] = sf; }
+    __syncthreads();
+    // carry into this wavefront: the wavefronts before it, back to the nearest one that holds a flag
+    float carry = 0.0f;
+    for (int w = 0; w < wave; ++w) {
+        if (scratch_f[w]) carry = scratch_v[w]; else carry += scratch_v[w];
+    }
+    // exclusive value of this thread: the inclusive value of the previous lane, joined with the carry
+    float pv = __shfl_up(sv, 1, kWave);
+    int pf = __shfl_up(sf, 1, kWave);
+    if (lane == 0) { pv = 0.0f; pf = 0; }
+    return pf ? pv : carry + pv;
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kLargeBlock) void rows_large_kernel(GraphView g, WalkLaw law, int n_walks, int f_len, int n_f,
+                                                                 const float* __restrict__ f, int cap,
+                                                                 int32_t* __restrict__ row_ptr, int32_t* __restrict__ col_out,
+                                                                 float* __restrict__ val_out, long long val_stride,
+                                                                 const float* __restrict__ dphi, float* __restrict__ df_part,
+                                                                 float* __restrict__ stage_load, uint16_t* __restrict__ stage_hop)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    uint32_t* dcol = reinterpret_cast<uint32_t*>(lds);               // [cap] column of the deposit at a sorted position
+    uint16_t* dslot = reinterpret_cast<uint16_t*>(dcol + cap);       // [cap] its slot in (walk, hop) order
+    __shared__ int scan_i[kLargeWaves];
+    __shared__ float scan_v[kLargeWaves];
+    __shared__ int scan_f[kLargeWaves];
+    const int tid = threadIdx.x;
+    float* my_load = stage_load + static_cast<size_t>(blockIdx.x) * cap;
+    uint16_t* my_hop = stage_hop + static_cast<size_t>(blockIdx.x) * cap;
+    const float n_float = static_cast<float>(n_walks);
+
+    // hops of walk `walk` out of `node` (deposit == nullptr), or its deposits written from slot `at` on
+    auto run_walk = [&](uint32_t node, uint32_t walk, bool write, int at) -> int {
+        int32_t u = static_cast<int32_t>(node);
+        float load = 1.0f;
+        uint32_t x[4] = {0, 0, 0, 0};
+        int hops = 0;
+        for (int t = 1; t < f_len; ++t) {
+            if (((t - 1) & 1) == 0) philox4x32_10(node, walk, static_cast<uint32_t>((t - 1) >> 1), 0u, law.key0, law.key1, x);
+            if (!walk_hop(g, law, t, x, u, load)) break;
+            if (write) {
+                const int slot = at + hops;
+                dcol[slot] = static_cast<uint32_t>(u);
+                dslot[slot] = static_cast<uint16_t>(slot);
+                my_load[slot] = load;
+                my_hop[slot] = static_cast<uint16_t>(t);
+            }
+            ++hops;
+        }
+        return hops;
+    };
+
+    for (long long node_ll = blockIdx.x; node_ll < g.n; node_ll += gridDim.x) {
+        const uint32_t node = static_cast<uint32_t>(node_ll);
+        __syncthreads();      // the previous node's arrays are no longer read
+        // ---- 1. deposits in (walk, hop) order; the n_walks zero-hop prefixes are one deposit of load n_walks
+        if (tid == 0) { dcol[0] = node; dslot[0] = 0; my_load[0] = n_float; my_hop[0] = 0; }
+        int base = 1;
+        for (int first = 0; first < n_walks; first += kLargeBlock) {
+            const uint32_t walk = static_cast<uint32_t>(first + tid);
+            const bool active = static_cast<int>(walk) < n_walks;
+            const int hops = active ? run_walk(node, walk, false, 0) : 0;
+            int total = 0;
+            const int off = block_exclusive_scan(hops, scan_i, &total);
+            if (active && hops > 0) run_walk(node, walk, true, base + off);
+            base += total;
+        }
+        const int D = base;      // <= cap
+        __syncthreads();
+
+        // ---- 2. sort (column, slot) ascending
+        int d_pad = 1;
+        while (d_pad < D) d_pad <<= 1;
+        auto compare_exchange = [&](int i, int j) {
+            const uint32_t ci = dcol[i], cj = dcol[j];
+            const uint16_t si = dslot[i], sj = dslot[j];
+            if (ci > cj || (ci == cj && si > sj)) { dcol[i] = cj; dcol[j] = ci; dslot[i] = sj; dslot[j] = si; }
+        };
+        for (int k = 2; k <= d_pad; k <<= 1) {
+            const int half = k >> 1;
+            for (int p = tid; p < (d_pad >> 1); p += kLargeBlock) {      // first step of a merge: i against its mirror image
+                const int blk = p / half, o = p - blk * half;
+                const int i = blk * k + o, j = blk * k + k - 1 - o;
+                if (j < D) compare_exchange(i, j);
+            }
+            __syncthreads();
+            for (int j2 = half >> 1; j2 > 0; j2 >>= 1) {
+                for (int p = tid; p < (d_pad >> 1); p += kLargeBlock) {
+                    const int i = ((p / j2) * (j2 << 1)) + (p % j2);
+                    if (i + j2 < D) compare_exchange(i, i + j2);
+                }
+                __syncthreads();
+            }
+        }
+
+        // ---- 3. runs of equal columns; thread `tid` owns sorted positions [lo, hi)
+        const int per = (D + kLargeBlock - 1) / kLargeBlock;
+        const int lo = min(tid * per, D), hi = min(lo + per, D);
+        auto is_head = [&](int r) { return r == 0 || dcol[r - 1] != dcol[r]; };
+        int heads_mine = 0;
+        for (int r = lo; r < hi; ++r) heads_mine += is_head(r) ? 1 : 0;
+        int heads_total = 0;
+        const int heads_before = block_exclusive_scan(heads_mine, scan_i, &heads_total);
+        if (MODE == kCount) {
+            if (tid == 0) row_ptr[node] = heads_total;
+            continue;
+        }
+        const int32_t row_start = row_ptr[node];
+
+        if (MODE == kFill) {
+            const int t_last = (D - 1) / per;      // the thread that owns the last position
+            for (int h = 0; h < n_f; ++h) {
+                const float* fh = f + static_cast<long long>(h) * f_len;
+                // sums of this thread's positions: `pre` up to its first head, then one sum per run that starts here
+                float acc = 0.0f, pre = 0.0f;
+                int k = 0;      // heads met so far
+                for (int r = lo; r < hi; ++r) {
+                    const int slot = dslot[r];
+                    const float v = my_load[slot] * fh[my_hop[slot]];
+                    if (is_head(r)) {
+                        if (k == 0) pre = acc;
+                        else {      // the run that started at this thread's head k - 1 ends before r
+                            const long long pos = static_cast<long long>(row_start) + heads_before + k - 1;
+                            if (h == 0) col_out[pos] = static_cast<int32_t>(dcol[r - 1]);
+                            val_out[h * val_stride + pos] = acc / n_float;
+                        }
+                        acc = v;
+                        ++k;
+                    } else {
+                        acc += v;
+                    }
+                }
+                if (k == 0) pre = acc;
+                // what flows into this thread from the threads before it: their sums since the nearest head
+                const float carry = block_segmented_exclusive_sum(k > 0 ? acc : pre, k > 0, scan_v, scan_f);
+                if (lo < hi) {
+                    if (k > 0 && lo > 0) {      // the run that was open at lo ends before this thread's first head
+                        const long long pos = static_cast<long long>(row_start) + heads_before - 1;
+                        if (h == 0) col_out[pos] = static_cast<int32_t>(dcol[lo - 1]);
+                        val_out[h * val_stride + pos] = (carry + pre) / n_float;
+                    }
+                    if (tid == t_last) {        // the last run of the row ends at D
+                        const long long pos = static_cast<long long>(row_start) + heads_total - 1;
+                        if (h == 0) col_out[pos] = static_cast<int32_t>(dcol[D - 1]);
+                        val_out[h * val_stride + pos] = (k > 0 ? acc : carry + pre) / n_float;
+                    }
+                }
+            }
+        }
+
+        if (MODE == kGrad) {
+            // entry of Phi_hat of every deposit, by slot: overwrites the columns once everybody has its heads
+            uint32_t ent_mine[kLargeMaxDeposits / kLargeBlock];
+            {
+                int k = 0;
+                for (int r = lo, q = 0; r < hi; ++r, ++q) {
+                    k += is_head(r) ? 1 : 0;
+                    ent_mine[q] = static_cast<uint32_t>(row_start + heads_before + k - 1);
+                }
+            }
+            __syncthreads();
+            uint32_t* ent = dcol;
+            for (int r = lo, q = 0; r < hi; ++r, ++q) ent[dslot[r]] = ent_mine[q];
+            __syncthreads();
+            // first slot of every walk (n_walks + 1 offsets, 16 bits each, where the slot tags were)
+            uint16_t* first_slot = dslot;
+            int base2 = 1;
+            for (int first = 0; first < n_walks; first += kLargeBlock) {
+                const uint32_t walk = static_cast<uint32_t>(first + tid);
+                const bool active = static_cast<int>(walk) < n_walks;
+                const int hops = active ? run_walk(node, walk, false, 0) : 0;
+                int total = 0;
+                const int off = block_exclusive_scan(hops, scan_i, &total);
+                if (active) first_slot[walk] = static_cast<uint16_t>(base2 + off);
+                base2 += total;
+            }
+            if (tid == 0) first_slot[n_walks] = static_cast<uint16_t>(base2);
+            __syncthreads();
+            const int32_t row_end = row_ptr[node + 1];
+            const int lane = tid & (kWave - 1), wave = tid >> 6;
+            for (int h = 0; h < n_f; ++h) {
+                // one wavefront per hop count t: lanes stride over the walks with at least t hops, then a fixed tree
+                for (int t = wave; t < f_len; t += kLargeWaves) {
+                    float acc = 0.0f;
+                    if (t == 0) {
+                        const uint32_t e = ent[0];
+                        if (lane == 0 && e < static_cast<uint32_t>(row_end) && static_cast<long long>(e) < val_stride) acc = my_load[0] * dphi[h * val_stride + e];
+                    } else {
+                        for (int w = lane; w < n_walks; w += kWave) {
+                            const int s0 = first_slot[w], s1 = first_slot[w + 1];
+                            if (s1 - s0 >= t) {
+                                const int slot = s0 + t - 1;
+                                const uint32_t e = ent[slot];
+                                if (e < static_cast<uint32_t>(row_end) && static_cast<long long>(e) < val_stride) acc += my_load[slot] * dphi[h * val_stride + e];
+                            }
+                        }
+                    }
+                    acc = wave_sum(acc);
+                    if (lane == 0) df_part[(static_cast<long long>(node) * n_f + h) * f_len + t] = acc / n_float;
+                }
+            }
+        }
+    }
+}
+
+// Rows of more than kLargeThreshold possible deposits take rows_large_kernel: its ordering costs D log^2 D against the
+// D^2 / 64 of the wavefront kernel's ranking by counting.  Measured on a 32 x 32 grid, rows filled to the bound: equal at
+// 800 deposits (0.3 ms), 0.66 against 4.3 ms at 2049, 1.5 against 46 ms at 4951, 1.7 against 245 ms at 8191.
+constexpr int kLargeThreshold = 768;
+inline bool large_rows(long long cap) { return cap > kLargeThreshold; }
+inline long long large_grid(long long n) { return n < kLargeMaxGrid ? (n > 0 ? n : 1) : kLargeMaxGrid; }
+// bytes of the workgroups' staging areas (loads, then hops), 0 when the wavefront kernel serves
+inline size_t large_stage_bytes(int64_t n, long long cap)
+{
+    if (!large_rows(cap)) return 0;
+    const size_t slots = static_cast<size_t>(large_grid(n)) * static_cast<size_t>(cap);
+    return align_up(slots * sizeof(float)) + align_up(slots * sizeof(uint16_t));
+}
+
+template <int MODE>
+grf_status launch_rows_large(const GraphView& gv, const WalkLaw& law, int n_walks, int f_len, int n_f, const float* f, int cap,
+                             int32_t* row_ptr, int32_t* col_out, float* val_out, long long val_stride, const float* dphi,
+                             float* df_part, unsigned char* stage, hipStream_t stream)
+{
+    const size_t lds = static_cast<size_t>(cap) * 6;
+    if (lds > 64 * 1024)
+        GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_large_kernel<MODE>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+    const long long grid = large_grid(gv.n);
+    float* stage_load = reinterpret_cast<float*>(stage);
+    uint16_t* stage_hop = reinterpret_cast<uint16_t*>(stage + align_up(static_cast<size_t>(grid) * cap * sizeof(float)));
+    hipLaunchKernelGGL((rows_large_kernel<MODE>), dim3(static_cast<unsigned>(grid)), dim3(kLargeBlock), lds, stream, gv, law, n_walks, f_len, n_f, f,
+                       cap, row_ptr, col_out, val_out, val_stride, dphi, df_part, stage_load, stage_hop);
+    GRF_LAUNCH_CHECK("rows_large_kernel");
+    return GRF_OK;
+}
+
 // df[x] = sum over nodes of df_part[node][x], x in [0, n_f * f_len): one workgroup per x, fixed order.
 __global__ __launch_bounds__(256) void df_reduce_kernel(const float* __restrict__ df_part, long long n, int width, float* __restrict__ df)
 {
@@ -386,7 +685,6 @@ grf_status fill_i32(int32_t* data, int64_t n, int32_t value, hipStream_t stream)
 // ------------------------------------------------------------------------------------ host side
 namespace {
 
-constexpr int kMaxDeposits = 8192;   // 8192 * 16 B = 128 KB of the 160 KB of LDS of one gfx950 compute unit; also the range of a uint16 index
 
 grf_status check_graph(const grf_graph* g)
 {
@@ -430,7 +728,8 @@ extern "C" int64_t grf_sample_nnz_bound(int64_t n, int32_t n_walks, int32_t f_le
 extern "C" size_t grf_sample_workspace_bytes(int64_t n, int32_t n_walks, int32_t f_len, int32_t n_f)
 {
     if (n < 0 || n_walks < 1 || f_len < 1 || n_f < 1) return 0;
-    return align_up(sizeof(float) * static_cast<size_t>(n_f) * f_len) + kAlign;
+    const long long cap = 1 + static_cast<long long>(n_walks) * (f_len - 1);
+    return align_up(sizeof(float) * static_cast<size_t>(n_f) * f_len) + kAlign + large_stage_bytes(n, cap);
 }
 
 extern "C" grf_status grf_sample_walks(const grf_graph* g, double p_halt, int32_t n_walks, int32_t max_nodes,
@@ -475,8 +774,8 @@ grf_status sample_impl(const grf_graph* g, const float* f_host, const float* f_d
     if (phi_out->capacity > 0 && (phi_out->col == nullptr || phi_out->val == nullptr))
         return fail(GRF_EINVAL, "phi_out->col / val is NULL with capacity %lld", (long long)phi_out->capacity);
     const long long cap_ll = 1 + static_cast<long long>(n_walks) * (f_len - 1);
-    if (cap_ll > kMaxDeposits)
-        return fail(GRF_EUNSUPPORTED, "1 + n_walks*(f_len-1) = %lld deposits per node exceed the %d that fit in LDS", cap_ll, kMaxDeposits);
+    if (cap_ll > kLargeMaxDeposits)
+        return fail(GRF_EUNSUPPORTED, "1 + n_walks*(f_len-1) = %lld deposits per node exceed the %d that a workgroup orders in LDS", cap_ll, kLargeMaxDeposits);
     const size_t need = grf_sample_workspace_bytes(g->n, n_walks, f_len, n_f);
     if (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
         return fail(GRF_EWORKSPACE, "workspace must be non-NULL, 256-byte aligned and >= %zu bytes (got %zu)", need, workspace_bytes);
@@ -504,9 +803,15 @@ grf_status sample_impl(const grf_graph* g, const float* f_host, const float* f_d
     const int cap = static_cast<int>(cap_ll);
     const GraphView gv = view_of(g);
 
+    // rows with many possible deposits: a workgroup per node, staging areas behind f and the counter
+    const bool large = large_rows(cap_ll);
+    unsigned char* stage = ws + align_up(sizeof(float) * static_cast<size_t>(n_f) * f_len) + kAlign;
+
     // pass 1: entries per row, then offsets
-    if (grf_status st = launch_rows<kCount>(gv, law, n_walks, f_len, n_f, f_dev, cap, phi_out->row_ptr, nullptr, nullptr, 0ll,
-                                            nullptr, nullptr, stream)) return st;
+    if (grf_status st = large ? launch_rows_large<kCount>(gv, law, n_walks, f_len, n_f, f_dev, cap, phi_out->row_ptr, nullptr, nullptr, 0ll,
+                                                          nullptr, nullptr, stage, stream)
+                              : launch_rows<kCount>(gv, law, n_walks, f_len, n_f, f_dev, cap, phi_out->row_ptr, nullptr, nullptr, 0ll,
+                                                    nullptr, nullptr, stream)) return st;
     if (grf_status st = exclusive_scan_inplace(phi_out->row_ptr, g->n, total_dev, stream)) return st;
     if (nnz_out != nullptr) {
         long long total = 0;
@@ -519,8 +824,10 @@ grf_status sample_impl(const grf_graph* g, const float* f_host, const float* f_d
     }
 
     // pass 2: same walks again, entries written at their offsets
-    if (grf_status st = launch_rows<kFill>(gv, law, n_walks, f_len, n_f, f_dev, cap, phi_out->row_ptr, phi_out->col, phi_out->val,
-                                           static_cast<long long>(phi_out->capacity), nullptr, nullptr, stream)) return st;
+    if (grf_status st = large ? launch_rows_large<kFill>(gv, law, n_walks, f_len, n_f, f_dev, cap, phi_out->row_ptr, phi_out->col, phi_out->val,
+                                                         static_cast<long long>(phi_out->capacity), nullptr, nullptr, stage, stream)
+                              : launch_rows<kFill>(gv, law, n_walks, f_len, n_f, f_dev, cap, phi_out->row_ptr, phi_out->col, phi_out->val,
+                                                   static_cast<long long>(phi_out->capacity), nullptr, nullptr, stream)) return st;
     return GRF_OK;
 }
 
@@ -548,10 +855,18 @@ extern "C" grf_status grf_sample_async(const grf_graph* g, const float* f_device
                        static_cast<hipStream_t>(hip_stream), phi_out, nullptr);
 }
 
-extern "C" size_t grf_sample_backward_workspace_bytes(int64_t n, int32_t f_len, int32_t n_f)
+namespace {
+size_t df_part_bytes(int64_t n, int32_t f_len, int32_t n_f)
 {
-    if (n < 0 || f_len < 1 || n_f < 1) return 0;
     return align_up(sizeof(float) * static_cast<size_t>(n > 0 ? n : 1) * static_cast<size_t>(n_f) * static_cast<size_t>(f_len));
+}
+}  // namespace
+
+extern "C" size_t grf_sample_backward_workspace_bytes(int64_t n, int32_t n_walks, int32_t f_len, int32_t n_f)
+{
+    if (n < 0 || n_walks < 1 || f_len < 1 || n_f < 1) return 0;
+    const long long cap = 1 + static_cast<long long>(n_walks) * (f_len - 1);
+    return df_part_bytes(n, f_len, n_f) + large_stage_bytes(n, cap);
 }
 
 extern "C" grf_status grf_sample_backward(const grf_graph* g, int32_t f_len, int32_t n_f,
@@ -570,9 +885,9 @@ extern "C" grf_status grf_sample_backward(const grf_graph* g, int32_t f_len, int
     if (nnz < 0 || nnz > phi->capacity || nnz >= 2147483647ll) return fail(GRF_EINVAL, "nnz=%lld must lie in [0, phi->capacity=%lld]", (long long)nnz, (long long)phi->capacity);
     if (phi->row_ptr == nullptr || (nnz > 0 && dphi_val == nullptr)) return fail(GRF_EINVAL, "phi->row_ptr / dphi_val is NULL");
     const long long cap_ll = 1 + static_cast<long long>(n_walks) * (f_len - 1);
-    if (cap_ll > kMaxDeposits)
-        return fail(GRF_EUNSUPPORTED, "1 + n_walks*(f_len-1) = %lld deposits per node exceed the %d that fit in LDS", cap_ll, kMaxDeposits);
-    const size_t need = grf_sample_backward_workspace_bytes(g->n, f_len, n_f);
+    if (cap_ll > kLargeMaxDeposits)
+        return fail(GRF_EUNSUPPORTED, "1 + n_walks*(f_len-1) = %lld deposits per node exceed the %d that a workgroup orders in LDS", cap_ll, kLargeMaxDeposits);
+    const size_t need = grf_sample_backward_workspace_bytes(g->n, n_walks, f_len, n_f);
     if (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
         return fail(GRF_EWORKSPACE, "workspace must be non-NULL, 256-byte aligned and >= %zu bytes (got %zu)", need, workspace_bytes);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -583,8 +898,11 @@ extern "C" grf_status grf_sample_backward(const grf_graph* g, int32_t f_len, int
     }
     float* df_part = static_cast<float*>(workspace);
     const int cap = static_cast<int>(cap_ll);
-    if (grf_status st = launch_rows<kGrad>(view_of(g), law, n_walks, f_len, n_f, nullptr, cap, phi->row_ptr, nullptr, nullptr,
-                                           static_cast<long long>(phi->capacity), dphi_val, df_part, stream)) return st;
+    unsigned char* stage = static_cast<unsigned char*>(workspace) + df_part_bytes(g->n, f_len, n_f);
+    if (grf_status st = large_rows(cap_ll) ? launch_rows_large<kGrad>(view_of(g), law, n_walks, f_len, n_f, nullptr, cap, phi->row_ptr, nullptr, nullptr,
+                                                                      static_cast<long long>(phi->capacity), dphi_val, df_part, stage, stream)
+                                           : launch_rows<kGrad>(view_of(g), law, n_walks, f_len, n_f, nullptr, cap, phi->row_ptr, nullptr, nullptr,
+                                                                static_cast<long long>(phi->capacity), dphi_val, df_part, stream)) return st;
     hipLaunchKernelGGL(df_reduce_kernel, dim3(static_cast<unsigned>(width)), dim3(256), 0, stream,
                        static_cast<const float*>(df_part), static_cast<long long>(g->n), width, df);
     GRF_LAUNCH_CHECK("df_reduce_kernel");
