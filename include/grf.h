@@ -14,7 +14,8 @@
  *     The library never allocates or frees device memory and keeps no state between calls; all
  *     temporaries live in the caller's workspace.
  *   - All work is enqueued on the caller's stream (a hipStream_t passed as void*; NULL is the
- *     default stream).  Only grf_sample synchronises the stream (once, to learn nnz).
+ *     default stream).  Two calls block on the stream, once each, to return a count to the host: grf_sample (nnz)
+ *     and grf_knn_graph when nnz_out is given; grf_sample_async and grf_knn_graph with nnz_out == NULL do not.
  *   - Every entry point returns GRF_OK (0) or a negative grf_status; the message of the last error
  *     on the calling thread is available from grf_last_error().  Arguments are validated on the
  *     host before anything is launched; on error nothing partial is promised in the outputs.
@@ -251,6 +252,49 @@ grf_status grf_masked_linear_attention_fused(const void* Q, const void* K, const
                                              void* workspace, size_t workspace_bytes, void* hip_stream,
                                              float* out, float* num_opt, float* den_opt);
 
+/* ---------------------------------------------------------------------------------------------
+ * Prepared column lists.  For a fixed graph the walks are sampled once and frozen for each attention head and layer
+ * (Sec. 4, image experiments), so the column lists of Phi_hat, which grf_form_buckets, the whole attention calls and
+ * the backward call otherwise rebuild on every call, can be built once:
+ *
+ *   grf_phi_prepare          writes the column lists of phi (with its n_f value planes in list order and the launch
+ *                            plans of the bucket kernels) into `prepared`, a caller-owned device buffer of
+ *                            grf_phi_prepare_bytes(n, nnz, n_f) bytes, 256-byte aligned.  Stream-ordered, no
+ *                            synchronisation.  The buffer stays valid while phi's pattern (row_ptr, col) is unchanged.
+ *   grf_phi_prepare_values   refreshes only the value planes inside `prepared` from phi->val: for a modulation f that
+ *                            has changed (training) over the same walks.
+ *   *_prepared               the attention calls with `prepared` in place of the rebuild: same arguments, results
+ *                            bit-identical to the call without the suffix.  n, nnz and n_f must be the values given to
+ *                            grf_phi_prepare (they fix the layout of the buffer).  Workspace: that of the call without
+ *                            the suffix minus grf_phi_prepare_bytes(n, nnz, n_f) (grf_form_buckets_prepared: none).
+ * The contents of `prepared` are trusted like a pointer argument: a buffer that grf_phi_prepare did not fill for
+ * this phi, nnz and n_f is undefined behaviour.
+ * --------------------------------------------------------------------------------------------- */
+size_t grf_phi_prepare_bytes(int64_t n, int64_t nnz, int32_t n_f);      /* 0 on bad arguments */
+
+grf_status grf_phi_prepare(const grf_phi* phi, int64_t nnz, int32_t n_f, void* prepared, size_t prepared_bytes, void* hip_stream);
+
+grf_status grf_phi_prepare_values(const grf_phi* phi, int64_t nnz, int32_t n_f, void* prepared, size_t prepared_bytes, void* hip_stream);
+
+grf_status grf_form_buckets_prepared(const void* K, const void* V, int32_t dtype,
+                                     int64_t B, int64_t H, int64_t n, int32_t d,
+                                     const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                     const void* prepared, size_t prepared_bytes, void* hip_stream, float* buckets);
+
+grf_status grf_masked_linear_attention_prepared(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                int64_t B, int64_t H, int64_t n, int32_t d,
+                                                const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                int32_t bh_chunk, const void* prepared, size_t prepared_bytes,
+                                                void* workspace, size_t workspace_bytes, void* hip_stream,
+                                                float* out, float* num_opt, float* den_opt);
+
+grf_status grf_masked_linear_attention_fused_prepared(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                      int64_t B, int64_t H, int64_t n, int32_t d,
+                                                      const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                      int32_t bh_chunk, const void* prepared, size_t prepared_bytes,
+                                                      void* workspace, size_t workspace_bytes, void* hip_stream,
+                                                      float* out, float* num_opt, float* den_opt);
+
 /* grf_masked_linear_attention_fused for callers that can neither allocate device memory nor hand over a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Inputs, outputs,
  * results (bit-identical to grf_masked_linear_attention_fused) and error behaviour are the same; the scratch
@@ -303,7 +347,8 @@ grf_status grf_asymmetric_masked_attention(const void* Q, const void* K, const v
  * d_out      device fp32 [B][H][n][d].
  * dQ, dK, dV device fp32 [B][H][n][d], overwritten.
  * dphi_val   device fp32 [n_f][phi->capacity] or NULL: plane h receives the sum over the (batch, head) slices
- *            that use plane h of dL/dPhi_hat; entries [nnz, capacity) are not touched.
+ *            that use plane h of dL/dPhi_hat.  When nnz is an upper bound, the entries between the end of the rows
+ *            (phi->row_ptr[n]) and nnz receive 0; entries [nnz, capacity) are not touched.
  * A row with den_i = 0 propagates IEEE inf/NaN into every gradient it touches (no epsilon, as in the forward).
  * --------------------------------------------------------------------------------------------- */
 size_t grf_attention_backward_workspace_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int64_t nnz, int32_t n_f, int32_t bh_chunk);
@@ -315,6 +360,15 @@ grf_status grf_masked_linear_attention_backward(const void* Q, const void* K, co
                                                 int32_t bh_chunk,
                                                 void* workspace, size_t workspace_bytes, void* hip_stream,
                                                 float* dQ, float* dK, float* dV, float* dphi_val);
+
+/* The same over prepared column lists (see grf_phi_prepare). */
+grf_status grf_masked_linear_attention_backward_prepared(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                         int64_t B, int64_t H, int64_t n, int32_t d,
+                                                         const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                         const float* out, const float* den, const float* d_out,
+                                                         int32_t bh_chunk, const void* prepared, size_t prepared_bytes,
+                                                         void* workspace, size_t workspace_bytes, void* hip_stream,
+                                                         float* dQ, float* dK, float* dV, float* dphi_val);
 
 /* Backward of grf_asymmetric_masked_attention (App. D): with a_ij = phi(q_i).phi(k_j) and c_ij = v'_j . g'_i,
  *     dL/dPhi[i,j] = a_ij c_ij                      dL/dphi(q_i) = sum_j Phi[i,j] c_ij phi(k_j)

@@ -94,6 +94,19 @@ def lib() -> ctypes.CDLL:
         L.grf_fused_attention_workspace_bytes.argtypes = L.grf_attention_workspace_bytes.argtypes
         L.grf_masked_linear_attention_fused.restype = ctypes.c_int32
         L.grf_masked_linear_attention_fused.argtypes = L.grf_masked_linear_attention.argtypes
+        L.grf_phi_prepare_bytes.restype = ctypes.c_size_t
+        L.grf_phi_prepare_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32]
+        for name in ("grf_phi_prepare", "grf_phi_prepare_values"):
+            getattr(L, name).restype = ctypes.c_int32
+            getattr(L, name).argtypes = [ctypes.POINTER(_Phi), ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.grf_form_buckets_prepared.restype = ctypes.c_int32
+        L.grf_form_buckets_prepared.argtypes = [ctypes.c_void_p, ctypes.c_void_p, *common,
+                                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+        for name in ("grf_masked_linear_attention_prepared", "grf_masked_linear_attention_fused_prepared"):
+            getattr(L, name).restype = ctypes.c_int32
+            getattr(L, name).argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, *common,
+                                         ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.grf_masked_linear_attention_fused_static.restype = ctypes.c_int32
         L.grf_masked_linear_attention_fused_static.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, *common,
                                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -107,6 +120,12 @@ def lib() -> ctypes.CDLL:
                                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                                            ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.grf_masked_linear_attention_backward_prepared.restype = ctypes.c_int32
+        L.grf_masked_linear_attention_backward_prepared.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, *common,
+                                                                    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                                                    ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t,
+                                                                    ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                                                    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.grf_knn_graph_nnz_bound.restype = ctypes.c_int64
         L.grf_knn_graph_nnz_bound.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
         L.grf_knn_graph_workspace_bytes.restype = ctypes.c_size_t
@@ -375,8 +394,48 @@ def grf_buckets_workspace_bytes(n: int, nnz: int, n_f: int = 1) -> int:
     return int(lib().grf_buckets_workspace_bytes(n, nnz, n_f))
 
 
+def grf_phi_prepare_bytes(n: int, nnz: int, n_f: int = 1) -> int:
+    return int(lib().grf_phi_prepare_bytes(n, nnz, n_f))
+
+
+def grf_phi_prepare(phi: Phi, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Column lists of ``phi`` built once, as an opaque uint8 buffer to pass as ``prepared=`` to the attention calls."""
+    _require_gpu()
+    L = lib()
+    need = L.grf_phi_prepare_bytes(phi.n, phi.nnz, phi.n_f)
+    buf = out if out is not None else _workspace(need, phi.row_ptr.device)
+    ps = phi._struct()
+    _check(L.grf_phi_prepare(ctypes.byref(ps), phi.nnz, phi.n_f, _ptr(buf), buf.numel(), _stream_ptr(stream)))
+    return buf
+
+
+def grf_phi_prepare_values(phi: Phi, prepared: torch.Tensor, stream=None) -> torch.Tensor:
+    """Refresh the value planes inside ``prepared`` from ``phi.val`` (same pattern, new modulation f)."""
+    _require_gpu()
+    ps = phi._struct()
+    _check(lib().grf_phi_prepare_values(ctypes.byref(ps), phi.nnz, phi.n_f, _ptr(prepared), prepared.numel(), _stream_ptr(stream)))
+    return prepared
+
+
+def grf_form_buckets_prepared(K, V, phi: Phi, prepared: torch.Tensor, feature_map: str = "relu", out: Optional[torch.Tensor] = None, stream=None):
+    return grf_form_buckets(K, V, phi, feature_map, out=out, stream=stream, prepared=prepared)
+
+
+def grf_masked_linear_attention_prepared(Q, K, V, phi: Phi, prepared: torch.Tensor, **kw):
+    return grf_masked_linear_attention(Q, K, V, phi, prepared=prepared, **kw)
+
+
+def grf_masked_linear_attention_fused_prepared(Q, K, V, phi: Phi, prepared: torch.Tensor, **kw):
+    return grf_masked_linear_attention_fused(Q, K, V, phi, prepared=prepared, **kw)
+
+
+def grf_masked_linear_attention_backward_prepared(Q, K, V, phi: Phi, prepared: torch.Tensor, out, den, d_out, **kw):
+    return grf_masked_linear_attention_backward(Q, K, V, phi, out, den, d_out, prepared=prepared, **kw)
+
+
 def grf_form_buckets(K: torch.Tensor, V: torch.Tensor, phi: Phi, feature_map: str = "relu",
-                     out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                     out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None,
+                     prepared: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Bucket records [B*H, n, d*d + d] fp32: S_l (d x d, feature index major) then z_l."""
     _require_gpu()
     L = lib()
@@ -387,8 +446,12 @@ def grf_form_buckets(K: torch.Tensor, V: torch.Tensor, phi: Phi, feature_map: st
     buckets = out if out is not None else torch.empty((B * H, n, rec), dtype=torch.float32, device=K.device)
     if buckets.numel() != B * H * n * rec or buckets.dtype != torch.float32 or not buckets.is_contiguous():
         raise ValueError("bucket buffer has the wrong size, dtype or layout")
-    ws = workspace if workspace is not None else _workspace(L.grf_buckets_workspace_bytes(n, phi.nnz, phi.n_f), K.device)
     ps = phi._struct()
+    if prepared is not None:
+        _check(L.grf_form_buckets_prepared(_ptr(K), _ptr(V), _dtype_code(K), B, H, n, d, ctypes.byref(ps), phi.nnz, phi.n_f,
+                                           _FEATURE_MAPS[feature_map], _ptr(prepared), prepared.numel(), _stream_ptr(stream), _ptr(buckets)))
+        return buckets
+    ws = workspace if workspace is not None else _workspace(L.grf_buckets_workspace_bytes(n, phi.nnz, phi.n_f), K.device)
     _check(L.grf_form_buckets(_ptr(K), _ptr(V), _dtype_code(K), B, H, n, d, ctypes.byref(ps), phi.nnz, phi.n_f,
                               _FEATURE_MAPS[feature_map], _ptr(ws), ws.numel(), _stream_ptr(stream), _ptr(buckets)))
     return buckets
@@ -422,10 +485,11 @@ def grf_fused_attention_workspace_bytes(B: int, H: int, n: int, d: int, nnz: int
 
 def grf_masked_linear_attention_fused(Q, K, V, phi: Phi, feature_map: str = "relu", bh_chunk: Optional[int] = None,
                                       return_num_den: bool = False, workspace: Optional[torch.Tensor] = None,
-                                      out: Optional[torch.Tensor] = None, stream=None):
-    """Bucket-fused variant: same results as grf_masked_linear_attention without bucket records in HBM."""
+                                      out: Optional[torch.Tensor] = None, stream=None, prepared: Optional[torch.Tensor] = None):
+    """Bucket-fused variant: same results as grf_masked_linear_attention without bucket records in HBM.
+    ``prepared``: the buffer of grf_phi_prepare(phi), which saves rebuilding the column lists."""
     return _attention_call("grf_masked_linear_attention_fused", "grf_fused_attention_workspace_bytes",
-                           Q, K, V, phi, feature_map, bh_chunk, return_num_den, workspace, out, stream)
+                           Q, K, V, phi, feature_map, bh_chunk, return_num_den, workspace, out, stream, prepared)
 
 
 def grf_masked_linear_attention_fused_static(Q, K, V, phi: Phi, feature_map: str = "relu", return_num_den: bool = False,
@@ -452,13 +516,13 @@ def grf_masked_linear_attention_fused_static(Q, K, V, phi: Phi, feature_map: str
 def grf_masked_linear_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, phi: Phi,
                                 feature_map: str = "relu", bh_chunk: Optional[int] = None, return_num_den: bool = False,
                                 workspace: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
-                                stream=None):
+                                stream=None, prepared: Optional[torch.Tensor] = None):
     """out [B,H,n,d] fp32 (and num, den if asked).
 
     ``bh_chunk``: (batch, head) slices whose buckets are resident at once; 0 = all; None = all when a workspace is
     passed, else as many as fit WORKSPACE_BUDGET_BYTES."""
     return _attention_call("grf_masked_linear_attention", "grf_attention_workspace_bytes",
-                           Q, K, V, phi, feature_map, bh_chunk, return_num_den, workspace, out, stream)
+                           Q, K, V, phi, feature_map, bh_chunk, return_num_den, workspace, out, stream, prepared)
 
 
 WORKSPACE_BUDGET_BYTES = 4 << 30
@@ -478,7 +542,8 @@ def _auto_chunk(L, ws_query: str, B: int, H: int, n: int, d: int, nnz: int, n_f:
     return int(-(-slices // n_chunks))          # equal chunks
 
 
-def _attention_call(entry: str, ws_query: str, Q, K, V, phi, feature_map, bh_chunk, return_num_den, workspace, out, stream):
+def _attention_call(entry: str, ws_query: str, Q, K, V, phi, feature_map, bh_chunk, return_num_den, workspace, out, stream,
+                    prepared=None):
     _require_gpu()
     L = lib()
     B, H, n, d = _check_qkv(Q, K, V)
@@ -487,6 +552,8 @@ def _attention_call(entry: str, ws_query: str, Q, K, V, phi, feature_map, bh_chu
     need = getattr(L, ws_query)(B, H, n, d, phi.nnz, phi.n_f, bh_chunk)
     if need == 0:
         raise GrfError(GRF_EUNSUPPORTED, f"unsupported problem (d={d})")
+    if prepared is not None:
+        need -= L.grf_phi_prepare_bytes(n, phi.nnz, phi.n_f)
     if workspace is None:
         workspace = _workspace(need, Q.device)
     if out is None:
@@ -494,6 +561,12 @@ def _attention_call(entry: str, ws_query: str, Q, K, V, phi, feature_map, bh_chu
     num = torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device) if return_num_den else None
     den = torch.empty((B, H, n), dtype=torch.float32, device=Q.device) if return_num_den else None
     ps = phi._struct()
+    if prepared is not None:
+        _check(getattr(L, entry + "_prepared")(_ptr(Q), _ptr(K), _ptr(V), _dtype_code(Q), B, H, n, d, ctypes.byref(ps),
+                                               phi.nnz, phi.n_f, _FEATURE_MAPS[feature_map], int(bh_chunk),
+                                               _ptr(prepared), prepared.numel(), _ptr(workspace), workspace.numel(),
+                                               _stream_ptr(stream), _ptr(out), _ptr(num), _ptr(den)))
+        return (out, num, den) if return_num_den else out
     _check(getattr(L, entry)(_ptr(Q), _ptr(K), _ptr(V), _dtype_code(Q), B, H, n, d, ctypes.byref(ps),
                              phi.nnz, phi.n_f, _FEATURE_MAPS[feature_map], int(bh_chunk),
                              _ptr(workspace), workspace.numel(), _stream_ptr(stream),
@@ -538,15 +611,16 @@ def grf_asymmetric_masked_attention_backward(Q, K, V, phi: Phi, out, den, d_out,
 def grf_masked_linear_attention_backward(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, phi: Phi,
                                          out: torch.Tensor, den: torch.Tensor, d_out: torch.Tensor,
                                          feature_map: str = "relu", bh_chunk: Optional[int] = None, want_dphi: bool = True,
-                                         workspace: Optional[torch.Tensor] = None, stream=None):
+                                         workspace: Optional[torch.Tensor] = None, stream=None,
+                                         prepared: Optional[torch.Tensor] = None):
     """(dQ, dK, dV, dphi_val) for d_out = dL/dout; ``out`` and ``den`` are the saved forward results (fp32).
 
     dphi_val is [n_f, capacity] fp32 (entries beyond nnz untouched), or None when ``want_dphi`` is False."""
     return _backward_call("grf_masked_linear_attention_backward", "grf_attention_backward_workspace_bytes",
-                          Q, K, V, phi, out, den, d_out, feature_map, bh_chunk, want_dphi, workspace, stream)
+                          Q, K, V, phi, out, den, d_out, feature_map, bh_chunk, want_dphi, workspace, stream, prepared)
 
 
-def _backward_call(entry, ws_query, Q, K, V, phi, out, den, d_out, feature_map, bh_chunk, want_dphi, workspace, stream):
+def _backward_call(entry, ws_query, Q, K, V, phi, out, den, d_out, feature_map, bh_chunk, want_dphi, workspace, stream, prepared=None):
     _require_gpu()
     L = lib()
     B, H, n, d = _check_qkv(Q, K, V)
@@ -558,11 +632,19 @@ def _backward_call(entry, ws_query, Q, K, V, phi, out, den, d_out, feature_map, 
     need = getattr(L, ws_query)(B, H, n, d, phi.nnz, phi.n_f, bh_chunk)
     if need == 0:
         raise GrfError(GRF_EUNSUPPORTED, f"unsupported problem (d={d})")
+    if prepared is not None:
+        need -= L.grf_phi_prepare_bytes(n, phi.nnz, phi.n_f)
     if workspace is None:
         workspace = _workspace(need, Q.device)
     dQ, dK, dV = (torch.empty((B, H, n, d), dtype=torch.float32, device=Q.device) for _ in range(3))
     dphi = torch.empty((phi.n_f, phi.capacity), dtype=torch.float32, device=Q.device) if want_dphi else None
     ps = phi._struct()
+    if prepared is not None:
+        _check(getattr(L, entry + "_prepared")(
+            _ptr(Q), _ptr(K), _ptr(V), _dtype_code(Q), B, H, n, d, ctypes.byref(ps), phi.nnz, phi.n_f,
+            _FEATURE_MAPS[feature_map], _ptr(out), _ptr(den), _ptr(d_out), int(bh_chunk), _ptr(prepared), prepared.numel(),
+            _ptr(workspace), workspace.numel(), _stream_ptr(stream), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dphi)))
+        return dQ, dK, dV, dphi
     _check(getattr(L, entry)(
         _ptr(Q), _ptr(K), _ptr(V), _dtype_code(Q), B, H, n, d, ctypes.byref(ps), phi.nnz, phi.n_f,
         _FEATURE_MAPS[feature_map], _ptr(out), _ptr(den), _ptr(d_out), int(bh_chunk),

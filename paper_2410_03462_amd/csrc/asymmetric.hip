@@ -352,7 +352,7 @@ grf_status launch_asymmetric_backward_chunk(const void* Qv, const void* Kv, cons
                        static_cast<const float*>(b.wc), static_cast<const float*>(b.wa), fmap, static_cast<long long>(bh_first),
                        waves, static_cast<int32_t>(nnz), dK, dV);
     GRF_LAUNCH_CHECK("asymmetric_backward_columns_kernel");
-    return launch_dphi_accumulate(nnz, n_f, H, bh_first, n_slices, b.dpart, nullptr, phi->capacity, dphi_val, stream);
+    return launch_dphi_accumulate(nnz, n_f, H, bh_first, n_slices, b.dpart, nullptr, phi, dphi_val, stream);
 }
 
 }  // namespace

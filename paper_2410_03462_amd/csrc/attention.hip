@@ -474,6 +474,98 @@ extern "C" size_t grf_attention_workspace_bytes(int64_t B, int64_t H, int64_t n,
     return carve_transposed(nullptr, n, nnz, n_f).bytes + align_up(bucket_bytes);
 }
 
+namespace grf {
+
+grf_status check_phi(const grf_phi* phi, int64_t nnz, int32_t n_f)
+{
+    if (phi == nullptr) return fail(GRF_EINVAL, "phi is NULL");
+    if (phi->n < 0) return fail(GRF_EINVAL, "phi->n=%lld must be >= 0", (long long)phi->n);
+    if (nnz < 0 || nnz > phi->capacity) return fail(GRF_EINVAL, "nnz=%lld must lie in [0, phi->capacity=%lld]", (long long)nnz, (long long)phi->capacity);
+    if (nnz >= 2147483647ll - 256 || phi->n >= 2147483647ll - 256) return fail(GRF_EUNSUPPORTED, "n and nnz must be < 2^31 - 257");
+    if (n_f < 1) return fail(GRF_EINVAL, "n_f=%d must be >= 1", n_f);
+    if (phi->row_ptr == nullptr || (nnz > 0 && (phi->col == nullptr || phi->val == nullptr))) return fail(GRF_EINVAL, "phi arrays are NULL");
+    return GRF_OK;
+}
+
+grf_status prepared_lists(const void* prepared, size_t prepared_bytes, int64_t n, int64_t nnz, int32_t n_f, Transposed* t)
+{
+    const size_t need = carve_transposed(nullptr, n, nnz, n_f).bytes;
+    if (prepared == nullptr || prepared_bytes < need || (reinterpret_cast<uintptr_t>(prepared) % kAlign) != 0)
+        return fail(GRF_EWORKSPACE, "prepared must be non-NULL, 256-byte aligned and >= grf_phi_prepare_bytes() = %zu bytes (got %zu)", need, prepared_bytes);
+    *t = carve_transposed(static_cast<unsigned char*>(const_cast<void*>(prepared)), n, nnz, n_f);
+    return GRF_OK;
+}
+
+grf_status launch_column_values(const grf_phi* phi, int64_t nnz, int32_t n_f, const Transposed& t, hipStream_t stream)
+{
+    if (nnz <= 0) return GRF_OK;
+    hipLaunchKernelGGL(column_values_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, stream,
+                       static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(phi->n),
+                       static_cast<const int32_t*>(t.s_src), static_cast<long long>(nnz), static_cast<int>(n_f),
+                       static_cast<const float*>(phi->val), static_cast<long long>(phi->capacity), t.s_val);
+    GRF_LAUNCH_CHECK("column_values_kernel");
+    return GRF_OK;
+}
+
+namespace {
+
+grf_status form_buckets_impl(const void* K, const void* V, int32_t dtype, int64_t B, int64_t H, int64_t n, int32_t d,
+                             int64_t nnz, int32_t n_f, int32_t feature_map, const Transposed& t, hipStream_t stream, float* buckets)
+{
+    grf_status st = GRF_OK;
+    GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, nnz, t, feature_map, 0, B * H, buckets, stream)));
+    return st;
+}
+
+grf_status attention_impl(const void* Q, const void* K, const void* V, int32_t dtype, int64_t B, int64_t H, int64_t n, int32_t d,
+                          const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map, int32_t bh_chunk,
+                          const Transposed& t, float* buckets, hipStream_t stream, float* out, float* num_opt, float* den_opt)
+{
+    const int fmap = feature_map;
+    const int64_t slices = B * H;
+    const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;
+    for (int64_t first = 0; first < slices; first += step) {
+        const int64_t count = (slices - first < step) ? (slices - first) : step;
+        grf_status st = GRF_OK;
+        GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, nnz, t, fmap, first, count, buckets, stream)));
+        if (st != GRF_OK) return st;
+        GRF_DISPATCH(d, dtype, (st = launch_gather<D_, T_>(Q, n, H, n_f, phi, nnz, fmap, buckets, first, count, out, num_opt, den_opt, stream)));
+        if (st != GRF_OK) return st;
+    }
+    return GRF_OK;
+}
+
+size_t bucket_bytes(int64_t B, int64_t H, int64_t n, int32_t d, int32_t bh_chunk)
+{
+    int64_t slices = B * H;
+    if (bh_chunk > 0 && bh_chunk < slices) slices = bh_chunk;
+    return align_up(sizeof(float) * static_cast<size_t>(slices) * static_cast<size_t>(n) * static_cast<size_t>(grf_bucket_record_floats(d)));
+}
+
+}  // namespace
+}  // namespace grf
+
+extern "C" size_t grf_phi_prepare_bytes(int64_t n, int64_t nnz, int32_t n_f)
+{
+    return grf_buckets_workspace_bytes(n, nnz, n_f);
+}
+
+extern "C" grf_status grf_phi_prepare(const grf_phi* phi, int64_t nnz, int32_t n_f, void* prepared, size_t prepared_bytes, void* hip_stream)
+{
+    if (grf_status st = check_phi(phi, nnz, n_f)) return st;
+    Transposed t;
+    if (grf_status st = prepared_lists(prepared, prepared_bytes, phi->n, nnz, n_f, &t)) return st;
+    return transpose(phi, nnz, n_f, t, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" grf_status grf_phi_prepare_values(const grf_phi* phi, int64_t nnz, int32_t n_f, void* prepared, size_t prepared_bytes, void* hip_stream)
+{
+    if (grf_status st = check_phi(phi, nnz, n_f)) return st;
+    Transposed t;
+    if (grf_status st = prepared_lists(prepared, prepared_bytes, phi->n, nnz, n_f, &t)) return st;
+    return launch_column_values(phi, nnz, n_f, t, static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" grf_status grf_form_buckets(const void* K, const void* V, int32_t dtype,
                                        int64_t B, int64_t H, int64_t n, int32_t d,
                                        const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
@@ -486,10 +578,20 @@ extern "C" grf_status grf_form_buckets(const void* K, const void* V, int32_t dty
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const Transposed t = carve_transposed(static_cast<unsigned char*>(workspace), n, nnz, n_f);
     if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
-    const int fmap = feature_map;
-    grf_status st = GRF_OK;
-    GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, nnz, t, fmap, 0, B * H, buckets, stream)));
-    return st;
+    return form_buckets_impl(K, V, dtype, B, H, n, d, nnz, n_f, feature_map, t, stream, buckets);
+}
+
+extern "C" grf_status grf_form_buckets_prepared(const void* K, const void* V, int32_t dtype,
+                                                int64_t B, int64_t H, int64_t n, int32_t d,
+                                                const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                const void* prepared, size_t prepared_bytes, void* hip_stream, float* buckets)
+{
+    if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
+    if (B * H * n > 0 && buckets == nullptr) return fail(GRF_EINVAL, "buckets is NULL");
+    Transposed t;
+    if (grf_status st = prepared_lists(prepared, prepared_bytes, n, nnz, n_f, &t)) return st;
+    if (B * H * n == 0) return GRF_OK;
+    return form_buckets_impl(K, V, dtype, B, H, n, d, nnz, n_f, feature_map, t, static_cast<hipStream_t>(hip_stream), buckets);
 }
 
 extern "C" grf_status grf_gather_buckets(const void* Q, int32_t dtype,
@@ -523,16 +625,22 @@ extern "C" grf_status grf_masked_linear_attention(const void* Q, const void* K, 
     const Transposed t = carve_transposed(static_cast<unsigned char*>(workspace), n, nnz, n_f);
     float* buckets = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + t.bytes);
     if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
-    const int fmap = feature_map;
-    const int64_t slices = B * H;
-    const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;
-    for (int64_t first = 0; first < slices; first += step) {
-        const int64_t count = (slices - first < step) ? (slices - first) : step;
-        grf_status st = GRF_OK;
-        GRF_DISPATCH(d, dtype, (st = launch_buckets<D_, T_>(K, V, n, H, n_f, nnz, t, fmap, first, count, buckets, stream)));
-        if (st != GRF_OK) return st;
-        GRF_DISPATCH(d, dtype, (st = launch_gather<D_, T_>(Q, n, H, n_f, phi, nnz, fmap, buckets, first, count, out, num_opt, den_opt, stream)));
-        if (st != GRF_OK) return st;
-    }
-    return GRF_OK;
+    return attention_impl(Q, K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map, bh_chunk, t, buckets, stream, out, num_opt, den_opt);
+}
+
+extern "C" grf_status grf_masked_linear_attention_prepared(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                           int64_t B, int64_t H, int64_t n, int32_t d,
+                                                           const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                           int32_t bh_chunk, const void* prepared, size_t prepared_bytes,
+                                                           void* workspace, size_t workspace_bytes, void* hip_stream,
+                                                           float* out, float* num_opt, float* den_opt)
+{
+    if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
+    if (B * H * n > 0 && (Q == nullptr || out == nullptr)) return fail(GRF_EINVAL, "Q / out is NULL");
+    Transposed t;
+    if (grf_status st = prepared_lists(prepared, prepared_bytes, n, nnz, n_f, &t)) return st;
+    if (grf_status st = check_workspace(workspace, workspace_bytes, bucket_bytes(B, H, n, d, bh_chunk))) return st;
+    if (B * H * n == 0) return GRF_OK;
+    return attention_impl(Q, K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map, bh_chunk, t, static_cast<float*>(workspace),
+                          static_cast<hipStream_t>(hip_stream), out, num_opt, den_opt);
 }

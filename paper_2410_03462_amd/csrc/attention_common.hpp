@@ -128,14 +128,17 @@ grf_status transpose(const grf_phi* phi, int64_t nnz, int32_t n_f, const Transpo
 grf_status check_problem(const void* a, const void* b, int32_t dtype, int64_t B, int64_t H, int64_t n, int32_t d,
                          const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map);
 grf_status check_workspace(const void* workspace, size_t have, size_t need);
+// The column lists inside a buffer that grf_phi_prepare filled (checked for size and alignment only).
+grf_status prepared_lists(const void* prepared, size_t prepared_bytes, int64_t n, int64_t nnz, int32_t n_f, Transposed* t);
 
 // Shared by the backward entry points (defined with the symmetric backward pass).
 // g' per row: G[r][:] = d_out / den and gd[r] = -(d_out . out) / den for rows first_row .. first_row + n_rows - 1.
 grf_status launch_backward_seed(int32_t d, const float* out, const float* den, const float* d_out, long long first_row,
                                 long long n_rows, float* G, float* gd, hipStream_t stream);
-// dphi_val[h][e] (+)= sum over the slices of a chunk that use plane h of term_a[s][e] (+ term_b[s][e] unless NULL).
+// dphi_val[h][e] (+)= sum over the slices of a chunk that use plane h of term_a[s][e] (+ term_b[s][e] unless NULL)
+// for the entries of the rows, 0 for e in [phi->row_ptr[n], nnz).
 grf_status launch_dphi_accumulate(int64_t nnz, int32_t n_f, int64_t H, int64_t bh_first, int64_t n_slices,
-                                  const float* term_a, const float* term_b, int64_t val_stride, float* dphi_val,
+                                  const float* term_a, const float* term_b, const grf_phi* phi, float* dphi_val,
                                   hipStream_t stream);
 
 // Workgroups are handed to the eight XCDs round-robin by id, and each XCD has an L2 of its own.

@@ -283,12 +283,14 @@ __global__ __launch_bounds__(256) void backward_reduce_kernel(long long n, int H
     }
 }
 
-// dphi_val[h][e] (+)= sum over the slices of this chunk that use plane h of the two per-entry terms.  A workgroup
+// dphi_val[h][e] (+)= sum over the slices of this chunk that use plane h of the two per-entry terms; entries past the
+// end of the rows (nnz may be an upper bound: the rows end at row_ptr[n]) receive 0.  A workgroup
 // covers 32 consecutive entries; its 8 groups of 32 threads take the slices s = g, g + 8, ... in order and the groups'
 // sums are added in group order, so the result has a fixed summation order for a given chunking.
 __global__ __launch_bounds__(256) void dphi_accumulate_kernel(long long nnz, int n_f, int H, long long bh_first, long long n_slices,
                                                               const float* __restrict__ d_query, const float* __restrict__ d_key,
-                                                              long long val_stride, int first_chunk, float* __restrict__ dphi_val)
+                                                              long long val_stride, int first_chunk, const int32_t* __restrict__ row_ptr,
+                                                              long long n, float* __restrict__ dphi_val)
 {
     constexpr int kEntries = 32, kGroups = 8;
     __shared__ float part[kGroups][kEntries];
@@ -296,7 +298,8 @@ __global__ __launch_bounds__(256) void dphi_accumulate_kernel(long long nnz, int
     const long long e = static_cast<long long>(blockIdx.x) * kEntries + lane;
     const int h = blockIdx.y;
     float acc = 0.0f;
-    if (e < nnz) {
+    const bool live = e < nnz && e < row_ptr[n];
+    if (live) {
         for (long long s = group; s < n_slices; s += kGroups) {
             const long long bh = bh_first + s;
             if (n_f > 1 && bh % H != h) continue;
@@ -307,7 +310,7 @@ __global__ __launch_bounds__(256) void dphi_accumulate_kernel(long long nnz, int
     part[group][lane] = acc;
     __syncthreads();
     if (group == 0 && e < nnz) {
-        float total = first_chunk ? 0.0f : dphi_val[h * val_stride + e];
+        float total = (first_chunk || !live) ? 0.0f : dphi_val[h * val_stride + e];
 #pragma unroll
         for (int g = 0; g < kGroups; ++g) total += part[g][lane];
         dphi_val[h * val_stride + e] = total;
@@ -328,14 +331,15 @@ grf_status launch_backward_seed(int32_t d, const float* out, const float* den, c
 }
 
 grf_status launch_dphi_accumulate(int64_t nnz, int32_t n_f, int64_t H, int64_t bh_first, int64_t n_slices,
-                                  const float* term_a, const float* term_b, int64_t val_stride, float* dphi_val,
+                                  const float* term_a, const float* term_b, const grf_phi* phi, float* dphi_val,
                                   hipStream_t stream)
 {
+    const int64_t val_stride = phi->capacity;
     if (dphi_val == nullptr || nnz <= 0) return GRF_OK;
     hipLaunchKernelGGL(dphi_accumulate_kernel, dim3(blocks_for(nnz, 32), static_cast<unsigned>(n_f)), dim3(256), 0, stream,
                        static_cast<long long>(nnz), static_cast<int>(n_f), static_cast<int>(H), static_cast<long long>(bh_first),
                        static_cast<long long>(n_slices), term_a, term_b, static_cast<long long>(val_stride), bh_first == 0 ? 1 : 0,
-                       dphi_val);
+                       static_cast<const int32_t*>(phi->row_ptr), static_cast<long long>(phi->n), dphi_val);
     GRF_LAUNCH_CHECK("dphi_accumulate_kernel");
     return GRF_OK;
 }
@@ -443,7 +447,7 @@ grf_status launch_backward_chunk(const void* Qv, const void* Kv, const void* Vv,
     reduce_pass(std::false_type{}, V, dV, static_cast<float*>(nullptr));
     GRF_LAUNCH_CHECK("backward_reduce_kernel<dV>");
 
-    if (grf_status st = launch_dphi_accumulate(nnz, n_f, H, bh_first, n_slices, b.d_query, b.d_key, phi->capacity, dphi_val, stream)) return st;
+    if (grf_status st = launch_dphi_accumulate(nnz, n_f, H, bh_first, n_slices, b.d_query, b.d_key, phi, dphi_val, stream)) return st;
     return GRF_OK;
 }
 
@@ -460,33 +464,15 @@ extern "C" size_t grf_attention_backward_workspace_bytes(int64_t B, int64_t H, i
     return carve_transposed(nullptr, n, nnz, n_f).bytes + carve_backward(nullptr, slices, n, d, nnz).bytes;
 }
 
-extern "C" grf_status grf_masked_linear_attention_backward(const void* Q, const void* K, const void* V, int32_t dtype,
-                                                           int64_t B, int64_t H, int64_t n, int32_t d,
-                                                           const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
-                                                           const float* out, const float* den, const float* d_out,
-                                                           int32_t bh_chunk,
-                                                           void* workspace, size_t workspace_bytes, void* hip_stream,
-                                                           float* dQ, float* dK, float* dV, float* dphi_val)
+namespace {
+
+grf_status backward_chunks(const void* Q, const void* K, const void* V, int32_t dtype, int64_t B, int64_t H, int64_t n, int32_t d,
+                           const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map, const float* out, const float* den,
+                           const float* d_out, int64_t step, const Transposed& t, unsigned char* rest, hipStream_t stream,
+                           float* dQ, float* dK, float* dV, float* dphi_val)
 {
-    if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
-    if (B * H * n > 0 && (Q == nullptr || out == nullptr || den == nullptr || d_out == nullptr))
-        return fail(GRF_EINVAL, "Q / out / den / d_out is NULL");
-    if (B * H * n > 0 && (dQ == nullptr || dK == nullptr || dV == nullptr)) return fail(GRF_EINVAL, "dQ / dK / dV is NULL");
-    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_attention_backward_workspace_bytes(B, H, n, d, nnz, n_f, bh_chunk))) return st;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (B * H * n == 0) {
-        // no slices: the gradient with respect to Phi_hat is zero
-        if (dphi_val != nullptr && nnz > 0)
-            for (int32_t h = 0; h < n_f; ++h)
-                if (grf_status st = fill_i32(reinterpret_cast<int32_t*>(dphi_val + static_cast<int64_t>(h) * phi->capacity), nnz, 0, stream)) return st;
-        return GRF_OK;
-    }
     const int64_t slices = B * H;
-    const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;
-    unsigned char* ws = static_cast<unsigned char*>(workspace);
-    const Transposed t = carve_transposed(ws, n, nnz, n_f);
-    const BackwardScratch b = carve_backward(ws + t.bytes, step, n, d, nnz);
-    if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
+    const BackwardScratch b = carve_backward(rest, step, n, d, nnz);
     for (int64_t first = 0; first < slices; first += step) {
         const int64_t count = (slices - first < step) ? (slices - first) : step;
         grf_status st = GRF_OK;
@@ -495,4 +481,68 @@ extern "C" grf_status grf_masked_linear_attention_backward(const void* Q, const 
         if (st != GRF_OK) return st;
     }
     return GRF_OK;
+}
+
+// Argument checks shared by the two forms; *done is set when there is nothing to launch.
+grf_status backward_checks(const void* Q, const void* K, const void* V, int32_t dtype, int64_t B, int64_t H, int64_t n, int32_t d,
+                           const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map, const float* out, const float* den,
+                           const float* d_out, float* dQ, float* dK, float* dV)
+{
+    if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
+    if (B * H * n > 0 && (Q == nullptr || out == nullptr || den == nullptr || d_out == nullptr))
+        return fail(GRF_EINVAL, "Q / out / den / d_out is NULL");
+    if (B * H * n > 0 && (dQ == nullptr || dK == nullptr || dV == nullptr)) return fail(GRF_EINVAL, "dQ / dK / dV is NULL");
+    return GRF_OK;
+}
+
+// no slices: the gradient with respect to Phi_hat is zero
+grf_status zero_dphi(const grf_phi* phi, int64_t nnz, int32_t n_f, float* dphi_val, hipStream_t stream)
+{
+    if (dphi_val != nullptr && nnz > 0)
+        for (int32_t h = 0; h < n_f; ++h)
+            if (grf_status st = fill_i32(reinterpret_cast<int32_t*>(dphi_val + static_cast<int64_t>(h) * phi->capacity), nnz, 0, stream)) return st;
+    return GRF_OK;
+}
+
+}  // namespace
+
+extern "C" grf_status grf_masked_linear_attention_backward(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                           int64_t B, int64_t H, int64_t n, int32_t d,
+                                                           const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                           const float* out, const float* den, const float* d_out,
+                                                           int32_t bh_chunk,
+                                                           void* workspace, size_t workspace_bytes, void* hip_stream,
+                                                           float* dQ, float* dK, float* dV, float* dphi_val)
+{
+    if (grf_status st = backward_checks(Q, K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map, out, den, d_out, dQ, dK, dV)) return st;
+    if (grf_status st = check_workspace(workspace, workspace_bytes, grf_attention_backward_workspace_bytes(B, H, n, d, nnz, n_f, bh_chunk))) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (B * H * n == 0) return zero_dphi(phi, nnz, n_f, dphi_val, stream);
+    const int64_t slices = B * H;
+    const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    const Transposed t = carve_transposed(ws, n, nnz, n_f);
+    if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
+    return backward_chunks(Q, K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map, out, den, d_out, step, t, ws + t.bytes, stream,
+                           dQ, dK, dV, dphi_val);
+}
+
+extern "C" grf_status grf_masked_linear_attention_backward_prepared(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                                    int64_t B, int64_t H, int64_t n, int32_t d,
+                                                                    const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                                    const float* out, const float* den, const float* d_out,
+                                                                    int32_t bh_chunk, const void* prepared, size_t prepared_bytes,
+                                                                    void* workspace, size_t workspace_bytes, void* hip_stream,
+                                                                    float* dQ, float* dK, float* dV, float* dphi_val)
+{
+    if (grf_status st = backward_checks(Q, K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map, out, den, d_out, dQ, dK, dV)) return st;
+    Transposed t;
+    if (grf_status st = prepared_lists(prepared, prepared_bytes, n, nnz, n_f, &t)) return st;
+    const int64_t slices = B * H;
+    const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;
+    if (grf_status st = check_workspace(workspace, workspace_bytes, carve_backward(nullptr, step, n, d, nnz).bytes)) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (B * H * n == 0) return zero_dphi(phi, nnz, n_f, dphi_val, stream);
+    return backward_chunks(Q, K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map, out, den, d_out, step, t,
+                           static_cast<unsigned char*>(workspace), stream, dQ, dK, dV, dphi_val);
 }

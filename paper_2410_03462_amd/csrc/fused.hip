@@ -382,17 +382,15 @@ extern "C" size_t grf_fused_attention_workspace_bytes(int64_t B, int64_t H, int6
 
 namespace {
 
-// Both bucket-fused entry points: column lists, then bucket kernel + row reduction per chunk of `step` slices,
-// all scratch inside `ws` (grf_fused_attention_workspace_bytes(..., step) bytes, 256-byte aligned).
-grf_status fused_impl(const void* Q, const void* K, const void* V, int32_t dtype, int64_t B, int64_t H, int64_t n, int32_t d,
-                      const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map, int64_t step,
-                      unsigned char* ws, hipStream_t stream, float* out, float* num_opt, float* den_opt)
+// The bucket-fused entry points behind their argument checks: bucket kernels + row reduction per chunk of `step`
+// slices over the column lists `t`; `rest` holds the partial rows and partial denominators of one chunk.
+grf_status fused_chunks(const void* Q, const void* K, const void* V, int32_t dtype, int64_t B, int64_t H, int64_t n, int32_t d,
+                        const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map, int64_t step, const Transposed& t,
+                        unsigned char* rest, hipStream_t stream, float* out, float* num_opt, float* den_opt)
 {
     const int64_t slices = B * H;
-    const Transposed t = carve_transposed(ws, n, nnz, n_f);
-    float* partial = reinterpret_cast<float*>(ws + t.bytes);
-    float* pden = reinterpret_cast<float*>(ws + t.bytes + partial_bytes(step, nnz, d));
-    if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
+    float* partial = reinterpret_cast<float*>(rest);
+    float* pden = reinterpret_cast<float*>(rest + partial_bytes(step, nnz, d));
     const int fmap = feature_map;
     for (int64_t first = 0; first < slices; first += step) {
         const int64_t count = (slices - first < step) ? (slices - first) : step;
@@ -404,7 +402,36 @@ grf_status fused_impl(const void* Q, const void* K, const void* V, int32_t dtype
     return GRF_OK;
 }
 
+// Column lists built at the head of `ws` (grf_fused_attention_workspace_bytes(..., step) bytes), then the chunks.
+grf_status fused_impl(const void* Q, const void* K, const void* V, int32_t dtype, int64_t B, int64_t H, int64_t n, int32_t d,
+                      const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map, int64_t step,
+                      unsigned char* ws, hipStream_t stream, float* out, float* num_opt, float* den_opt)
+{
+    const Transposed t = carve_transposed(ws, n, nnz, n_f);
+    if (grf_status st = transpose(phi, nnz, n_f, t, stream)) return st;
+    return fused_chunks(Q, K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map, step, t, ws + t.bytes, stream, out, num_opt, den_opt);
+}
+
 }  // namespace
+
+extern "C" grf_status grf_masked_linear_attention_fused_prepared(const void* Q, const void* K, const void* V, int32_t dtype,
+                                                                 int64_t B, int64_t H, int64_t n, int32_t d,
+                                                                 const grf_phi* phi, int64_t nnz, int32_t n_f, int32_t feature_map,
+                                                                 int32_t bh_chunk, const void* prepared, size_t prepared_bytes,
+                                                                 void* workspace, size_t workspace_bytes, void* hip_stream,
+                                                                 float* out, float* num_opt, float* den_opt)
+{
+    if (grf_status st = check_problem(K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map)) return st;
+    if (B * H * n > 0 && (Q == nullptr || out == nullptr)) return fail(GRF_EINVAL, "Q / out is NULL");
+    Transposed t;
+    if (grf_status st = prepared_lists(prepared, prepared_bytes, n, nnz, n_f, &t)) return st;
+    const int64_t slices = B * H;
+    const int64_t step = (bh_chunk > 0 && bh_chunk < slices) ? bh_chunk : slices;
+    if (grf_status st = check_workspace(workspace, workspace_bytes, partial_bytes(step, nnz, d) + pden_bytes(step, nnz))) return st;
+    if (B * H * n == 0) return GRF_OK;
+    return fused_chunks(Q, K, V, dtype, B, H, n, d, phi, nnz, n_f, feature_map, step, t, static_cast<unsigned char*>(workspace),
+                        static_cast<hipStream_t>(hip_stream), out, num_opt, den_opt);
+}
 
 extern "C" grf_status grf_masked_linear_attention_fused(const void* Q, const void* K, const void* V, int32_t dtype,
                                                         int64_t B, int64_t H, int64_t n, int32_t d,
