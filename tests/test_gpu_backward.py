@@ -2,7 +2,10 @@
 
 Both sides receive the same saved forward results (the checker's out and den rounded to fp32), so the
 comparison isolates the backward arithmetic.  Bars as for the forward pass: 1e-5 (fp32) / 2e-2 (bf16
-inputs) in the norm  max|x - ref| / max|ref|  per tensor.
+inputs) in the norm  max|x - ref| / max|ref|  per tensor (dQ, dK, dV, dPhi_hat).  df is computed on each side from
+that side's own dPhi_hat (the chain of both backward calls): every entry within the same normwise bar, or within the
+image of dPhi_hat's bar under the sampler's backward map (df is a sum of dPhi_hat's entries with the walks' loads as
+coefficients, which can cancel to far less than its terms).
 """
 import numpy as np
 import pytest
@@ -31,6 +34,16 @@ def relerr(x, ref):
     ref = np.asarray(ref, dtype=np.float64)
     scale = np.abs(ref).max()
     return float(np.abs(x - ref).max() / scale) if scale > 0 else float(np.abs(x).max())
+
+
+def df_within_chain_bar(oracle, wl, rp, col, df, df_ref, dphi_ref, tol):
+    """See the module docstring: tol * max|df_ref| per plane, or tol * max|dphi_ref| pushed through sample_backward."""
+    ones = np.ones_like(np.asarray(dphi_ref, dtype=np.float64))
+    push = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp, col, ones)
+    for h in range(df.shape[0]):
+        err = np.abs(df[h] - df_ref[h])
+        allow = np.maximum(tol * np.abs(df_ref[h]).max(), tol * np.abs(dphi_ref[h]).max() * push[h])
+        assert np.all(err <= allow), (h, float((err / allow).max()))
 
 
 def to_dev(x, dtype="f32"):
@@ -91,8 +104,7 @@ def compare_backward(grf, oracle, wl, feature_map="relu", bh_chunk=0):
     df = grf.grf_sample_backward(g, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, phi, got[3]).cpu().numpy()
     df_ref = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp, col, ref[3])
     assert df.shape == df_ref.shape
-    for h in range(wl.n_f):
-        assert relerr(df[h], df_ref[h]) <= 10 * tol, (h, relerr(df[h], df_ref[h]))
+    df_within_chain_bar(oracle, wl, rp, col, df, df_ref, ref[3], tol)
     return host, df
 
 
@@ -213,8 +225,7 @@ def compare_asymmetric_backward(grf, oracle, wl, feature_map="relu", bh_chunk=0)
     g = grf.DeviceGraph.from_host(wl.graph)
     df = grf.grf_sample_backward(g, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, phi, got[3]).cpu().numpy()
     df_ref = oracle.sample_backward(wl.graph, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, rp, col, ref[3])
-    for h in range(wl.n_f):
-        assert relerr(df[h], df_ref[h]) <= 10 * tol
+    df_within_chain_bar(oracle, wl, rp, col, df, df_ref, ref[3], tol)
     return host
 
 

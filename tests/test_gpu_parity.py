@@ -1,12 +1,14 @@
 """HIP library against the CPU checker on identical seeded inputs (needs the GPU).
 
 Bars: walk trajectories and the sparsity pattern of Phi_hat bit-exact; Phi_hat values, buckets,
-num and den within 1e-5 in the norm  max|x - ref| / max|ref|  (fp32; 2e-2 for bf16 inputs);
+num and den within 1e-5 in the norm  max|x - ref| / max|ref|  (fp32; 2e-2 for bf16 inputs) and, element by
+element, within 1e-5 |ref| + 2^-20 * (the sum of the magnitudes of the element's terms) (see bars.py);
 out = num/den is compared on rows whose denominator is not a near-total cancellation.
 """
 import numpy as np
 import pytest
 
+from bars import FLOOR_BF16, FLOOR_F32, elementwise_excess, magnitude_inputs
 from paper_2410_03462_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -192,16 +194,24 @@ def _compare_attention(grf, oracle, wl, rp, col, val, feature_map="relu", bh_chu
     Qd, Kd, Vd = (to_dev(x, wl.dtype) for x in (Q, K, V))
     B, H, n, d = Q.shape
 
+    mQ, mK, mV, mval = magnitude_inputs(Q, K, V, val, feature_map)
+    mag = oracle.masked_linear_attention(mQ, mK, mV, rp, col, mval, feature_map=fm, return_buckets=True)
+    floor = FLOOR_BF16 if wl.dtype == "bf16" else FLOOR_F32
+
     rec = grf.grf_form_buckets(Kd, Vd, phi, feature_map).cpu().numpy().reshape(B, H, n, d * d + d)
     S = rec[..., : d * d].reshape(B, H, n, d, d)
     z = rec[..., d * d:]
     assert relerr(S, ref["S"]) <= tol
     assert relerr(z, ref["z"]) <= tol
+    assert elementwise_excess(S, ref["S"], mag["S"], tol, floor) <= 1.0
+    assert elementwise_excess(z, ref["z"], mag["z"], tol, floor) <= 1.0
 
     out, num, den = grf.grf_masked_linear_attention(Qd, Kd, Vd, phi, feature_map, bh_chunk=bh_chunk, return_num_den=True)
     out, num, den = out.cpu().numpy(), num.cpu().numpy(), den.cpu().numpy()
     assert relerr(num, ref["num"]) <= tol
     assert relerr(den, ref["den"]) <= tol
+    assert elementwise_excess(num, ref["num"], mag["num"], tol, floor) <= 1.0
+    assert elementwise_excess(den, ref["den"], mag["den"], tol, floor) <= 1.0
     # out on rows whose denominator is not a near-total cancellation
     n_good = 0
     for b in range(B):
@@ -375,6 +385,36 @@ def test_headline_workload_full_size(grf, oracle):
     torch.cuda.empty_cache()
 
 
+def test_headline_workload_one_whole_head(grf, oracle):
+    """cloud_32k: every bucket (S, z) and every row (num, den) of one head against the checker, normwise and element
+    by element, for the bucket + gather pair and the fused call."""
+    import torch
+    wl = synth.workload("cloud_32k")
+    rp0, col0, val0 = _oracle_phi(oracle, wl)
+    n, d, h = wl.graph.n, wl.d, 5
+    Q, K, V = wl.qkv()
+    Q1, K1, V1 = (np.ascontiguousarray(x[:, h:h + 1]) for x in (Q, K, V))
+    S0, z0 = oracle.buckets(K1[0, 0], V1[0, 0], rp0, col0, val0[0])
+    num0, den0 = oracle.gather(Q1[0, 0], rp0, col0, val0[0], S0, z0)
+    Sm, zm = oracle.buckets(K1[0, 0], np.abs(V1[0, 0]), rp0, col0, np.abs(val0[0]))
+    numm, denm = oracle.gather(Q1[0, 0], rp0, col0, np.abs(val0[0]), Sm, zm)
+    phi = grf.Phi.from_host(n, rp0, col0, val0)
+    Qd, Kd, Vd = to_dev(Q1), to_dev(K1), to_dev(V1)
+    rec = grf.grf_form_buckets(Kd, Vd, phi).cpu().numpy().reshape(n, d * d + d)
+    S, z = rec[:, : d * d].reshape(n, d, d), rec[:, d * d:]
+    assert relerr(S, S0) <= TOL_F32 and relerr(z, z0) <= TOL_F32
+    assert elementwise_excess(S, S0, Sm, TOL_F32, FLOOR_F32) <= 1.0
+    assert elementwise_excess(z, z0, zm, TOL_F32, FLOOR_F32) <= 1.0
+    del rec, S, S0, Sm
+    for call in (grf.grf_masked_linear_attention, grf.grf_masked_linear_attention_fused):
+        _, num, den = call(Qd, Kd, Vd, phi, return_num_den=True)
+        num, den = num.cpu().numpy()[0, 0], den.cpu().numpy()[0, 0]
+        assert relerr(num, num0) <= TOL_F32 and relerr(den, den0) <= TOL_F32, call.__name__
+        assert elementwise_excess(num, num0, numm, TOL_F32, FLOOR_F32) <= 1.0, call.__name__
+        assert elementwise_excess(den, den0, denm, TOL_F32, FLOOR_F32) <= 1.0, call.__name__
+    torch.cuda.empty_cache()
+
+
 def _spot_check_full_size(grf, oracle, wl, heads, n_rows, tol):
     """Pattern bit-exact, values close, and sampled output rows against Eq. (2) evaluated directly."""
     import torch
@@ -430,6 +470,11 @@ def _compare_fused(grf, oracle, wl, rp, col, val, feature_map="relu", bh_chunk=0
     out, num, den = out.cpu().numpy(), num.cpu().numpy(), den.cpu().numpy()
     assert relerr(num, ref["num"]) <= tol
     assert relerr(den, ref["den"]) <= tol
+    mQ, mK, mV, mval = magnitude_inputs(Q, K, V, val, feature_map)
+    mag = oracle.masked_linear_attention(mQ, mK, mV, rp, col, mval, feature_map=fm)
+    floor = FLOOR_BF16 if wl.dtype == "bf16" else FLOOR_F32
+    assert elementwise_excess(num, ref["num"], mag["num"], tol, floor) <= 1.0
+    assert elementwise_excess(den, ref["den"], mag["den"], tol, floor) <= 1.0
     with np.errstate(divide="ignore", invalid="ignore"):
         assert np.array_equal(np.nan_to_num(out, nan=7.0, posinf=8.0, neginf=9.0),
                               np.nan_to_num(num / den[..., None], nan=7.0, posinf=8.0, neginf=9.0))
