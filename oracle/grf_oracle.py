@@ -23,18 +23,34 @@ _lib = None
 RELU, IDENTITY, ELU1 = 0, 1, 2
 
 
-def build(force: bool = False) -> str:
-    """Compile grf_oracle.c with gcc (-O2, no fast-math)."""
-    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fPIC", "-shared", "-o", _LIB_PATH, _SRC, "-lm"])
-    return _LIB_PATH
+_SAN_LIB_PATH = os.path.join(_HERE, "libgrf_oracle_san.so")
+
+
+def sanitized() -> bool:
+    """True when GRF_ORACLE_SANITIZE=1 selects the build with AddressSanitizer and UndefinedBehaviorSanitizer (CPU only).
+
+    The sanitizer runtime has to be in the process before Python starts:
+        GRF_ORACLE_SANITIZE=1 ASAN_OPTIONS=detect_leaks=0 LD_PRELOAD=$(gcc -print-file-name=libasan.so) \
+            python -m pytest tests -m "not gpu"
+    Any invalid access or undefined operation inside the checker then aborts the run with a report."""
+    return os.environ.get("GRF_ORACLE_SANITIZE", "") == "1"
+
+
+def build(force: bool = False, sanitize: bool = None) -> str:
+    """Compile grf_oracle.c with gcc (-O2, no fast-math); ``sanitize`` (default: sanitized()) adds
+    -fsanitize=address,undefined and writes a library of its own."""
+    sanitize = sanitized() if sanitize is None else sanitize
+    path = _SAN_LIB_PATH if sanitize else _LIB_PATH
+    if force or not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_SRC):
+        flags = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=all"] if sanitize else ["-O2"]
+        subprocess.check_call(["gcc", *flags, "-std=c11", "-ffp-contract=off", "-fPIC", "-shared", "-o", path, _SRC, "-lm"])
+    return path
 
 
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB_PATH)
+        _lib = ctypes.CDLL(build())
         _lib.grf_ref_sample.restype = ctypes.c_int64
         _lib.grf_ref_dphi_entry_direct.restype = ctypes.c_double
         _lib.grf_ref_knn_graph.restype = ctypes.c_int64
