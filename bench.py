@@ -6,10 +6,12 @@ grf_gather_buckets (gather, contraction, normalisation) on the headline workload
 16 Gaussian clusters, symmetrised 16-NN graph, 32 walks per node, p_halt = 0.2, f of length 16,
 batch 1, 8 heads, d = 64, fp32.  Inputs are resident in HBM before the timed region.
 
-Prints ONE JSON line.  `value` is tokens/s/head = N*B*H / step time.  `roofline` is for the gather
-kernel (the dominant one): algorithmic bytes per launch over its mean duration between HIP events
-recorded on the launch stream inside the timed region.  `cpu_baseline` times the CPU checker on one
-head of the same workload on this machine's host cores.
+Prints ONE JSON line.  `value` is tokens/s/head = N*B*H / step time (wall clock over the timed steps, sampler
+included).  `attention_call` is the metric's own definition: the median device time of grf_masked_linear_attention
+alone; `sampler` reports the walks in hops per second.  `roofline` is for the gather kernel (the dominant one):
+algorithmic bytes per launch over its mean duration between HIP events recorded on the launch stream inside the timed
+region; its `traffic` and the byte counts of the variants' rooflines come from profiles/hbm_traffic_per_launch.md.
+`cpu_baseline` times the CPU checker on one head of the same workload on this machine's host cores.
 """
 import argparse
 import json
@@ -23,10 +25,24 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
-# Bytes moved between L2 and the fabric per gather launch, from rocprofv3 --pmc runs of this file
-# (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from --copy-calibration under the same
-# counters).  A stored measurement, not recomputed here; absent workloads report null.
-MEASURED_TRAFFIC_BYTES = {"cloud_32k": 322188156585, "vit_grid": 23538457990, "cloud_8k": 224494242686, "cloud_128k": 2542783367655}
+# Bytes moved between L2 and the fabric per launch, counted by rocprofv3 --pmc runs of this file (FETCH_SIZE and
+# WRITE_SIZE, scaled by what the same counters read for a plain copy): a stored measurement, read from the table that
+# those runs produced, not recomputed here; kernels or workloads that the table does not hold report null.
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.md")
+
+
+def counted_traffic(workload, kernel_prefixes):
+    """Sum over the table's rows of `workload` whose kernel name starts with one of `kernel_prefixes` of the bytes per
+    launch (rows: | workload | kernel | read bytes | written bytes | total bytes |), or None."""
+    total, found = 0, False
+    try:
+        for line in open(TRAFFIC_TABLE):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) == 5 and cells[0] == workload and any(cells[1].startswith(k) for k in kernel_prefixes):
+                total += int(cells[4]); found = True
+    except OSError:
+        return None
+    return total if found else None
 
 
 def main() -> int:
@@ -208,123 +224,143 @@ def main() -> int:
     del cp_src, cp_dst
     roofline = {"kernel": "gather_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                "traffic": counted_traffic(args.workload, ["grf::gather_kernel"]),
                 "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": round(gather_ms, 4),
                 "copy_1GiB_GBs": round(copy_gbs, 1), "frac_of_copy": round(achieved / copy_gbs, 4)}
 
-    # the bucket-fused variant of the attention call on the same inputs: its own numbers, never `value`
+    def event_times(fn, steps=None, warmup=None):
+        """Per-call device times of fn (ms): HIP events on the launch stream around each of `steps` calls."""
+        steps = args.steps if steps is None else steps
+        for _ in range(args.warmup if warmup is None else warmup):
+            fn()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for a, b in ev:
+            a.record(stream); fn(); b.record(stream)
+        torch.cuda.synchronize()
+        return np.array([a.elapsed_time(b) for a, b in ev])
+
+    def rate(nbytes, ms):
+        return round(nbytes / (ms * 1e-3) / 1e9, 1)
+
+    elem = 2 if wl.dtype == "bf16" else 4
+
+    # ---- the attention call alone (column lists + buckets + gather), the quantity the metric is defined on: median of
+    # the per-call device times
+    aws = torch.empty(grf.grf_attention_workspace_bytes(B, H, N, d, nnz, phi.n_f), dtype=torch.uint8, device=dev)
+    att = event_times(lambda: grf.grf_masked_linear_attention(Qd, Kd, Vd, phi, workspace=aws, out=out))
+    del aws
+    attention_call = {"entry_point": "grf_masked_linear_attention", "calls": int(att.size),
+                      "median_ms": round(float(np.median(att)), 4), "mean_ms": round(float(att.mean()), 4),
+                      "tokens_per_s_per_head": round(tokens / (float(np.median(att)) * 1e-3), 1)}
+
+    # ---- the sampler: walk hops per second.  Hops are counted exactly from the trajectories (every entry >= 0 beyond a
+    # walk's start is one hop); the call simulates every walk twice (count pass, fill pass).
+    traj = grf.grf_sample_walks(g, wl.p_halt, wl.n_walks, wl.f_len, wl.walk_seed)
+    hops = int((traj[:, :, 1:] >= 0).sum().item())
+    del traj
+    smp = event_times(lambda: grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed, out=phi))
+    sample_med = float(np.median(smp))
+    # bound from the vector ALU: per hop and walk about 20 32-bit multiplies (Philox, two per round, ten rounds per two
+    # hops; a quarter-rate instruction) and 45 full-rate integer/float instructions = 125 lane slots; 256 compute units x 4
+    # SIMDs x 16 lanes x 2.4 GHz = 39.3e12 lane slots/s; two passes
+    alu_hops_per_s = 39.3e12 / 125 / 2
+    sampler = {"entry_point": "grf_sample", "median_ms": round(sample_med, 4), "hops": hops, "walks": N * wl.n_walks,
+               "hops_per_s": round(hops / (sample_med * 1e-3), 1),
+               "alu_bound_hops_per_s": round(alu_hops_per_s, 1), "frac_of_alu_bound": round(hops / (sample_med * 1e-3) / alu_hops_per_s, 4),
+               "note": "latency-bound: a hop is two dependent cache-resident loads per wavefront (row_ptr pair, then col/w), the walks of a "
+                       "node hop in lock step and the kernel runs twice; includes the one host synchronisation that returns nnz"}
+
+    # ---- the bucket-fused variant of the attention call on the same inputs: its own numbers, never `value`
     fws = torch.empty(grf.grf_fused_attention_workspace_bytes(B, H, N, d, nnz, phi.n_f), dtype=torch.uint8, device=dev)
     fout = torch.empty_like(out)
-
-    def fused_step(events=None):
-        if events: events[0].record(stream)
-        grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed, out=phi)
-        if events: events[1].record(stream)
-        grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, workspace=fws, out=fout)
-        if events: events[2].record(stream)
-
-    for _ in range(args.warmup):
-        fused_step()
-    torch.cuda.synchronize()
-    fevents = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    f0 = time.perf_counter()
-    for k in range(args.steps):
-        fused_step(fevents[k])
-    torch.cuda.synchronize()
-    f1 = time.perf_counter()
-    fused_ms_per_step = (f1 - f0) * 1e3 / args.steps
-    fused_attn_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in fevents]))
+    fus = event_times(lambda: grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, workspace=fws, out=fout))
+    fused_attn_ms = float(np.median(fus))
+    prepared = grf.grf_phi_prepare(phi)
+    prep_bytes = grf.grf_phi_prepare_bytes(N, nnz, phi.n_f)
+    fus_p = event_times(lambda: grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, workspace=fws[prep_bytes:], out=fout, prepared=prepared))
+    prep_ms = float(np.median(event_times(lambda: grf.grf_phi_prepare(phi, out=prepared))))
     # two contractions per entry of Phi_hat: S_l += a v^T and P = qw S_l, 2*d*d flops each
     fused_flops = 4.0 * nnz * d * d * B * H
+    # compulsory HBM bytes of the call: Q, K, V read once, out written once, one partial row per entry of Phi_hat and slice
+    # written by the bucket kernels and read back by the row reduction, Phi_hat and its column lists read per slice
+    fused_compulsory = B * H * (3 * N * d * elem + N * d * 4 + 2 * nnz * (d + 1) * 4 + nnz * 16)
+    fused_counted = counted_traffic(args.workload, ["grf::fused_bucket", "grf::gram_bucket_kernel<float, 3", "grf::gram_bucket_kernel<grf::bf16_t, 3", "grf::fused_reduce"])
+    fused_bytes = fused_counted if fused_counted is not None else fused_compulsory
     fused = {
         "entry_point": "grf_masked_linear_attention_fused",
-        "ms_per_step": round(fused_ms_per_step, 4),
-        "tokens_per_s_per_head": round(tokens / (fused_ms_per_step * 1e-3), 1),
-        "attention_ms": round(fused_attn_ms, 4),
+        "attention_ms": round(fused_attn_ms, 4), "attention_mean_ms": round(float(fus.mean()), 4),
         "attention_only_tokens_per_s_per_head": round(tokens / (fused_attn_ms * 1e-3), 1),
-        "roofline": {"bound": "mfma", "unit": "TFLOP/s", "peak": 157.3,
-                     "achieved_whole_call": round(fused_flops / (fused_attn_ms * 1e-3) / 1e12, 2),
-                     "flops_per_call": fused_flops,
-                     "note": "whole attention call (column lists + fused buckets + row reduce); per-kernel times in profiles/"},
+        "prepared": {"entry_point": "grf_masked_linear_attention_fused_prepared", "attention_ms": round(float(np.median(fus_p)), 4),
+                     "attention_only_tokens_per_s_per_head": round(tokens / (float(np.median(fus_p)) * 1e-3), 1),
+                     "grf_phi_prepare_ms": round(prep_ms, 4)},
+        "roofline": {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
+                     "achieved": rate(fused_bytes, fused_attn_ms), "frac": round(rate(fused_bytes, fused_attn_ms) / HBM_PEAK_GBS, 4),
+                     "bytes": "counted (profiles/hbm_traffic_per_launch.md: bucket kernels + row reduction)" if fused_counted is not None else "compulsory",
+                     "bytes_per_call": fused_bytes, "compulsory_bytes_per_call": fused_compulsory,
+                     "useful_flops_per_call": fused_flops, "useful_TFLOPs": round(fused_flops / (fused_attn_ms * 1e-3) / 1e12, 2),
+                     "note": "whole call over the time of the whole call; rows of Q, K, V re-read per entry of Phi_hat are served by L2 / Infinity "
+                             "Cache and are not HBM traffic; per-kernel times in profiles/"},
     }
-    elem = 2 if wl.dtype == "bf16" else 4
-    if d == 64:
-        # at d = 64 the bucket kernels run on the bf16 matrix instructions (fp32 operands in two or three bf16 pieces) and
-        # are bound by the rows read and the partial rows written and read back, not by the matrix pipe
-        fused_bytes = float(nnz) * B * H * (3 * d * elem + 2 * (d + 1) * 4)
-        fused["roofline"] = {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
-                             "achieved_whole_call": round(fused_bytes / (fused_attn_ms * 1e-3) / 1e9, 1),
-                             "bytes_per_call": fused_bytes, "useful_flops_per_call": fused_flops,
-                             "useful_TFLOPs_whole_call": round(fused_flops / (fused_attn_ms * 1e-3) / 1e12, 2),
-                             "note": "whole attention call; bytes = per entry of Phi_hat and slice three input rows, the partial "
-                                     "row written by the bucket kernel and read by the row reduce; re-read input rows are partly "
-                                     "served by L2 / Infinity Cache; per-kernel times in profiles/"}
 
-    # asymmetric GRFs (App. D): the same sampled matrix used directly as the mask estimate
+    # ---- asymmetric GRFs (App. D): the same sampled matrix used directly as the mask estimate
     aout = torch.empty_like(out)
-    for _ in range(args.warmup):
-        grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi, out=aout)
-    torch.cuda.synchronize()
-    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a0.record(stream)
-    for _ in range(args.steps):
-        grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi, out=aout)
-    a1.record(stream)
-    torch.cuda.synchronize()
-    asym_ms = a0.elapsed_time(a1) / args.steps
-    elem = 2 if wl.dtype == "bf16" else 4
-    asym_bytes = B * H * (nnz * (2 * d * elem + 8) + N * d * (elem + 4))     # k_j, v_j, (col, val) per entry; q_i in, out_i out
+    asy = event_times(lambda: grf.grf_asymmetric_masked_attention(Qd, Kd, Vd, phi, out=aout))
+    asym_ms = float(np.median(asy))
+    asym_requested = B * H * (nnz * (2 * d * elem + 8) + N * d * (elem + 4))     # k_j, v_j, (col, val) per entry; q_i in, out_i out
+    asym_compulsory = B * H * (3 * N * d * elem + N * d * 4 + nnz * 8)            # every tensor once
+    asym_counted = counted_traffic(args.workload, ["grf::asymmetric_kernel"])
+    asym_bytes = asym_counted if asym_counted is not None else asym_compulsory
     asymmetric = {
         "entry_point": "grf_asymmetric_masked_attention",
         "attention_ms": round(asym_ms, 4),
         "attention_only_tokens_per_s_per_head": round(tokens / (asym_ms * 1e-3), 1),
         "roofline": {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
-                     "achieved": round(asym_bytes / (asym_ms * 1e-3) / 1e9, 1),
-                     "frac": round(asym_bytes / (asym_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                     "algorithmic_bytes_per_launch": asym_bytes,
-                     "note": "K and V of one head (16.8 MB) are re-read from L2 / Infinity Cache, so the algorithmic rate may exceed the HBM peak"},
+                     "achieved": rate(asym_bytes, asym_ms), "frac": round(rate(asym_bytes, asym_ms) / HBM_PEAK_GBS, 4),
+                     "bytes": "counted (profiles/hbm_traffic_per_launch.md)" if asym_counted is not None else "compulsory",
+                     "bytes_per_launch": asym_bytes, "compulsory_bytes_per_launch": asym_compulsory,
+                     "requested_bytes_per_launch": asym_requested, "requested_GBs": rate(asym_requested, asym_ms),
+                     "note": "requested = rows of K and V per entry of Phi_hat, most of which L2 serves (one head's K and V are 16.8 MB at the "
+                             "headline size): a cache rate, not part of the HBM fraction"},
     }
 
-    # gradients (training with learnable f): backward of the attention call and of the sampler, on the fused
-    # forward's saved out and den; six MFMA contractions of 2*nnz*d*d flops per slice
+    # ---- gradients (training with learnable f): backward of the attention call and of the sampler, on the fused
+    # forward's saved out and den; six contractions of 2*nnz*d*d flops per slice
     _, _, fden = grf.grf_masked_linear_attention_fused(Qd, Kd, Vd, phi, workspace=fws, return_num_den=True, out=fout)
     d_out = torch.randn((B, H, N, d), dtype=torch.float32, device=dev, generator=torch.Generator(device=dev).manual_seed(0))
     bws = torch.empty(grf.grf_attention_backward_workspace_bytes(B, H, N, d, nnz, phi.n_f), dtype=torch.uint8, device=dev)
 
-    def backward_step():
-        grads = grf.grf_masked_linear_attention_backward(Qd, Kd, Vd, phi, fout, fden, d_out, workspace=bws)
+    def backward_step(prep=None):
+        if prep is None:
+            grads = grf.grf_masked_linear_attention_backward(Qd, Kd, Vd, phi, fout, fden, d_out, workspace=bws)
+        else:
+            grads = grf.grf_masked_linear_attention_backward(Qd, Kd, Vd, phi, fout, fden, d_out, workspace=bws[prep_bytes:], prepared=prep)
         return grf.grf_sample_backward(g, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, phi, grads[3])
 
-    for _ in range(args.warmup):
-        backward_step()
-    torch.cuda.synchronize()
-    b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    b0.record(stream)
-    for _ in range(args.steps):
-        backward_step()
-    b1.record(stream)
-    torch.cuda.synchronize()
-    bwd_ms = b0.elapsed_time(b1) / args.steps
+    bwd = event_times(backward_step)
+    bwd_p = event_times(lambda: backward_step(prepared))
+    bwd_ms = float(np.median(bwd))
     bwd_flops = 12.0 * nnz * d * d * B * H
+    # three passes, each writing one fp32 partial row per entry of Phi_hat and slice and reading it back; Q, K, V, out, den,
+    # d_out read and dQ, dK, dV written once; the seed rows written and read per pass
+    bwd_compulsory = B * H * (3 * 2 * nnz * d * 4 + 4 * nnz * 4 + 3 * N * d * elem + 5 * N * d * 4 + 4 * N * (d + 1) * 4 + nnz * 16)
+    bwd_counted = counted_traffic(args.workload, ["grf::backward_", "grf::gram_bucket_kernel<float, 0", "grf::gram_bucket_kernel<float, 1", "grf::gram_bucket_kernel<float, 2",
+                                                  "grf::gram_bucket_kernel<grf::bf16_t, 0", "grf::gram_bucket_kernel<grf::bf16_t, 1", "grf::gram_bucket_kernel<grf::bf16_t, 2",
+                                                  "grf::dphi_accumulate", "grf::rows_kernel<2", "grf::df_reduce"])
+    bwd_bytes = bwd_counted if bwd_counted is not None else bwd_compulsory
     backward = {
         "entry_points": "grf_masked_linear_attention_backward + grf_sample_backward",
-        "ms": round(bwd_ms, 4),
+        "ms": round(bwd_ms, 4), "mean_ms": round(float(bwd.mean()), 4),
         "tokens_per_s_per_head": round(tokens / (bwd_ms * 1e-3), 1),
-        "roofline": {"bound": "mfma", "unit": "TFLOP/s", "peak": 157.3,
-                     "achieved_whole_call": round(bwd_flops / (bwd_ms * 1e-3) / 1e12, 2), "flops_per_call": bwd_flops,
-                     "note": "whole backward (seed, column lists, three bucket passes with their row reductions, dphi, df)"},
+        "prepared": {"entry_points": "grf_masked_linear_attention_backward_prepared + grf_sample_backward", "ms": round(float(np.median(bwd_p)), 4)},
+        "roofline": {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
+                     "achieved": rate(bwd_bytes, bwd_ms), "frac": round(rate(bwd_bytes, bwd_ms) / HBM_PEAK_GBS, 4),
+                     "bytes": "counted (profiles/hbm_traffic_per_launch.md: all kernels of both calls)" if bwd_counted is not None else "compulsory",
+                     "bytes_per_call": bwd_bytes, "compulsory_bytes_per_call": bwd_compulsory,
+                     "useful_flops_per_call": bwd_flops, "useful_TFLOPs": round(bwd_flops / (bwd_ms * 1e-3) / 1e12, 2),
+                     "note": "whole backward (seed, column lists, three bucket passes with their row reductions, dphi, df) over its whole time; "
+                             "per-kernel times in profiles/"},
     }
-    if d == 64:
-        # three passes, each reading two input rows and one fp32 seed row per entry of Phi_hat and slice, writing one
-        # fp32 partial row and reading it back in the row reduction
-        bwd_bytes = float(nnz) * B * H * 3 * (2 * d * elem + d * 4 + 2 * d * 4)
-        backward["roofline"] = {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
-                                "achieved_whole_call": round(bwd_bytes / (bwd_ms * 1e-3) / 1e9, 1),
-                                "bytes_per_call": bwd_bytes, "useful_flops_per_call": bwd_flops,
-                                "useful_TFLOPs_whole_call": round(bwd_flops / (bwd_ms * 1e-3) / 1e12, 2),
-                                "note": "whole backward (seed, column lists, three bucket passes on the bf16 matrix instructions "
-                                        "with their row reductions, dphi, df); re-read input rows are partly served by L2 / "
-                                        "Infinity Cache; per-kernel times in profiles/"}
 
     dynamic = dynamic_section(aout)
 
@@ -339,6 +375,8 @@ def main() -> int:
                    "feature_map": "relu", "step": "grf_sample + grf_form_buckets + grf_gather_buckets"},
         "stage_ms": {"sample": round(sample_ms, 4), "buckets": round(buckets_ms, 4), "gather": round(gather_ms, 4)},
         "attention_only_tokens_per_s_per_head": round(tokens / ((buckets_ms + gather_ms) * 1e-3), 1),
+        "attention_call": attention_call,
+        "sampler": sampler,
         "roofline": roofline,
         "fused_variant": fused,
         "asymmetric_variant": asymmetric,
