@@ -97,16 +97,34 @@ __global__ __launch_bounds__(256) void column_values_kernel(const int32_t* __res
     for (int h = 0; h < n_f; ++h) s_val[h * nnz + pos] = val[h * val_stride + src];
 }
 
-// Work items of the short-list kernels and the list of the long buckets.  One thread per window of kGramWindow
-// consecutive list entries: the buckets whose lists start inside the window are consecutive, and only the last of
-// them can be longer than kGramPackMax (a longer list reaches beyond the window).  The lists up to that one form one
-// run; the last one joins it, is a run by itself or goes to the list of long buckets, by its length.  Runs and long
-// buckets are appended with one atomic per wavefront; their order is not fixed and nothing depends on it.
+// Longest list among those of at most kGramPackMax entries (0 if there is none): it sets the width of the plan's windows.
+__global__ __launch_bounds__(256) void short_list_max_kernel(const int32_t* __restrict__ col_ptr, int32_t n, int32_t* __restrict__ counts)
+{
+    const long long l = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    int32_t len = 0;
+    if (l < n) {
+        len = col_ptr[l + 1] - col_ptr[l];
+        if (len > kGramPackMax) len = 0;
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) len = max(len, __shfl_xor(len, off, kWave));
+    if (lane_id() == 0 && len > 0) atomicMax(counts + kPlanMaxShort, len);
+}
+
+// Work items of the short-list kernels and the list of the long buckets.  With L the longest list of at most
+// kGramPackMax entries, the entry sequence is cut into windows of W = kGramTile + 1 - L entries (at least kGramWindow): the
+// lists of at most kGramPackMax entries that start inside one window span at most W - 1 + L = kGramTile entries, and
+// the shorter the graph's lists, the wider the windows and the fuller the runs.  One thread per window walks the
+// buckets that start in it: consecutive short lists form a run; a list of up to kGramMaxList entries is a run by itself;
+// a longer one goes to the list of long buckets.  Runs and long buckets are appended with one atomic per wavefront and
+// round (a window yields one run and at most one other bucket in nearly all cases); their order is not fixed and nothing
+// depends on it.
 __global__ __launch_bounds__(256) void window_plan_kernel(const int32_t* __restrict__ col_ptr, int32_t n, long long n_windows,
-                                                          int2* __restrict__ items, int32_t* __restrict__ long_list,
-                                                          int32_t* __restrict__ counts)
+                                                          int2* __restrict__ items, long long item_capacity,
+                                                          int32_t* __restrict__ long_list, int32_t* __restrict__ counts)
 {
     const long long w = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int32_t width = min(max(kGramTile + 1 - counts[kPlanMaxShort], kGramWindow), kGramTile);
     // first bucket in [0, n) whose list starts at or after entry x (n if none)
     auto first_from = [&](long long x) {
         int32_t lo = 0, hi = n;
@@ -116,19 +134,6 @@ __global__ __launch_bounds__(256) void window_plan_kernel(const int32_t* __restr
         }
         return lo;
     };
-    int2 packed = make_int2(0, 0), alone = make_int2(0, 0);
-    int32_t long_bucket = -1;
-    if (w < n_windows) {
-        const int32_t la = first_from(w * kGramWindow), lb = first_from((w + 1) * kGramWindow);
-        if (la < lb) {
-            const int32_t last_beg = col_ptr[lb - 1], last_end = col_ptr[lb];
-            const int32_t last_len = last_end - last_beg;
-            packed = make_int2(col_ptr[la], last_len > kGramPackMax ? last_beg : last_end);
-            if (packed.y - packed.x > kGramTile) packed = make_int2(0, 0);      // cannot happen for a monotone col_ptr
-            if (last_len > kGramMaxList) long_bucket = lb - 1;
-            else if (last_len > kGramPackMax) alone = make_int2(last_beg, last_end);
-        }
-    }
     auto append = [&](bool have, int32_t* counter) -> int32_t {
         const unsigned long long mask = __ballot(have);
         int32_t base = 0;
@@ -136,13 +141,28 @@ __global__ __launch_bounds__(256) void window_plan_kernel(const int32_t* __restr
         base = __shfl(base, 0, kWave);
         return base + prefix_popcount(mask);
     };
-    const bool has_packed = packed.y > packed.x, has_alone = alone.y > alone.x;
-    const int32_t at_packed = append(has_packed, counts + kPlanItems);
-    if (has_packed) items[at_packed] = packed;
-    const int32_t at_alone = append(has_alone, counts + kPlanItems);
-    if (has_alone) items[at_alone] = alone;
-    const int32_t at_long = append(long_bucket >= 0, counts + kPlanLong);
-    if (long_bucket >= 0) long_list[at_long] = long_bucket;
+    int32_t l = 0, lb = 0;
+    if (w < n_windows && w * width < col_ptr[n]) { l = first_from(w * width); lb = first_from((w + 1) * width); }
+    while (__ballot(l < lb) != 0ull) {      // the same number of rounds for the whole wavefront
+        int2 run = make_int2(0, 0);
+        int32_t long_bucket = -1;
+        while (l < lb) {      // short lists from l on
+            const int32_t b = col_ptr[l], e = col_ptr[l + 1];
+            if (e - b > kGramPackMax) break;
+            if (e > b) { if (run.y == run.x) run.x = b; run.y = e; }
+            ++l;
+        }
+        if (l < lb) {         // the bucket that ended the run: to the long ones at once, else a run of its own (next round if one is pending)
+            const int32_t b = col_ptr[l], e = col_ptr[l + 1];
+            if (e - b > kGramMaxList) { long_bucket = l; ++l; }
+            else if (run.y == run.x) { run = make_int2(b, e); ++l; }
+        }
+        const bool has_run = run.y > run.x && run.y - run.x <= kGramTile;
+        const int32_t at_run = append(has_run, counts + kPlanItems);
+        if (has_run && at_run < item_capacity) items[at_run] = run;
+        const int32_t at_long = append(long_bucket >= 0, counts + kPlanLong);
+        if (long_bucket >= 0 && at_long < n) long_list[at_long] = long_bucket;
+    }
 }
 
 // ------------------------------------------------------------------------------------ buckets
@@ -307,7 +327,7 @@ Transposed carve_transposed(unsigned char* ws, int64_t n, int64_t nnz, int32_t n
     t.s_val = reinterpret_cast<float*>(take(sizeof(float) * entries * static_cast<size_t>(n_f > 0 ? n_f : 1)));
     t.span = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * entries));
     t.n_windows = static_cast<long long>((entries + kGramWindow - 1) / kGramWindow);
-    t.item_capacity = 2 * t.n_windows;      // a window yields at most one run of packed lists and one list alone
+    t.item_capacity = static_cast<long long>(nnz < n ? (nnz > 0 ? nnz : 1) : (n > 0 ? n : 1));      // a run holds at least one non-empty list
     t.items = reinterpret_cast<int2*>(take(sizeof(int2) * static_cast<size_t>(t.item_capacity)));
     t.long_list = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * static_cast<size_t>(n > 0 ? n : 1)));
     t.plan_counts = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * kPlanCounters));
@@ -343,9 +363,12 @@ grf_status transpose(const grf_phi* phi, int64_t nnz, int32_t n_f, const Transpo
                            static_cast<const int32_t*>(t.u_row), static_cast<const int32_t*>(t.u_src), t.s_row, t.s_src,
                            t.csr_to_csc, t.span);
         GRF_LAUNCH_CHECK("column_sort_kernel");
+        hipLaunchKernelGGL(short_list_max_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, stream,
+                           static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n), t.plan_counts);
+        GRF_LAUNCH_CHECK("short_list_max_kernel");
         hipLaunchKernelGGL(window_plan_kernel, dim3(blocks_for(t.n_windows, 256)), dim3(256), 0, stream,
-                           static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n), t.n_windows, t.items, t.long_list,
-                           t.plan_counts);
+                           static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n), t.n_windows, t.items, t.item_capacity,
+                           t.long_list, t.plan_counts);
         GRF_LAUNCH_CHECK("window_plan_kernel");
         hipLaunchKernelGGL(column_values_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, stream,
                            static_cast<const int32_t*>(t.col_ptr), static_cast<int32_t>(n),

@@ -96,13 +96,13 @@ __device__ __forceinline__ void load_run(const T* __restrict__ p, float (&out)[N
 }
 
 // Lists of at most kGramMaxList entries are evaluated in runs of at most kGramTile consecutive entries of the column
-// lists (gram_split.hpp): the lists of at most kGramPackMax entries that start inside one window of kGramWindow entries
-// form one run (it spans at most kGramWindow - 1 + kGramPackMax = kGramTile entries), a longer one is a run by itself.
+// lists (gram_split.hpp): the lists of at most kGramPackMax entries that start inside one window of the entry sequence
+// form one run (windows of at least kGramWindow entries, see window_plan_kernel), a longer one is a run by itself.
 constexpr int kGramWindow = 16;
 constexpr int kGramTile = 32;
 constexpr int kGramPackMax = kGramTile - kGramWindow + 1;      // 17
 constexpr int kGramMaxList = kGramTile;                        // longer lists go through S_l, one bucket per wavefront
-enum : int { kPlanItems = 0, kPlanLong = 1, kPlanCounters = 2 };      // device-side counts written by the plan
+enum : int { kPlanItems = 0, kPlanLong = 1, kPlanMaxShort = 2, kPlanCounters = 3 };      // device-side counts written by the plan
 
 // Column lists of Phi_hat, carved out of the caller's workspace.
 struct Transposed {
