@@ -79,20 +79,13 @@ __device__ __forceinline__ bf16x8 as_operand(const uint32_t (&w)[4])
 // under this step's arithmetic, with scheduling barriers between request and arithmetic (the compiler would
 // otherwise reorder them).  The steps come in pairs: the second one is contracted also when it lies past the end of
 // the list (its members then have weight 0), since a skipped step's loads would be moved into the branch, next to
-// their use; past a block's last step the request is redundant and re-reads entries of the block.  A list of one
-// step (most lists of a grid graph) takes one request and one contraction.
+// their use; past a block's last step the request is redundant and re-reads entries of the block.  (Lists of at most
+// kGramMaxList entries never come here: gram_bucket_kernel takes them.)
 template <typename Members, bool SCALED, typename Request, typename Contract>
 __device__ __forceinline__ void walk_column_list(const int32_t* __restrict__ csc_row, const float* __restrict__ vals,
                                                  const float* __restrict__ escale, int32_t beg, int32_t end,
                                                  Request&& request, Contract&& contract)
 {
-    if (end - beg <= 16) {
-        const ListBlock lb = load_list_block<SCALED>(csc_row, vals, escale, beg, end);
-        Members only;
-        request(lb.j_a, lb.g_a, lb.e_a, 0, only);
-        contract(only, lb.g_a, lb.e_a, 0);
-        return;
-    }
     for (int32_t block = beg; block < end; block += 2 * kWave) {
         ListBlock lb = load_list_block<SCALED>(csc_row, vals, escale, block, end);
         // all of the block's loads are taken here, where the first are needed anyway: requested later (the compiler
