@@ -136,3 +136,60 @@ def test_prepared_buffer_too_small_is_refused(grf):
     with pytest.raises(grf.GrfError) as e:
         grf.grf_masked_linear_attention_fused_prepared(Q, K, V, phi, small)
     assert e.value.status == grf.GRF_EWORKSPACE
+
+
+def test_training_step_over_frozen_walks_replays_from_a_hip_graph(grf):
+    """The use the prepared lists are for (Sec. 4: walks frozen, f learnable): per step the values of Phi_hat follow f
+    (grf_sample_async over the same walks), the prepared buffer takes them over (grf_phi_prepare_values), then the
+    fused forward, the backward and the sampler's backward run over the prepared lists.  Captured once into a HIP graph
+    (nothing in it touches the host) and replayed with other f: the bits of the eager, rebuilding calls every time."""
+    import torch
+    rng = np.random.default_rng(33)
+    g_host = synth.grid_graph(24, 24, 8)
+    n, n_walks, f_len, p_halt, seed = g_host.n, 8, 10, 0.5, 5
+    g = grf.DeviceGraph.from_host(g_host)
+    f_h = [np.abs(synth.modulation(f_len, rng, n_f=2)) + 0.01 for _ in range(3)]      # positive: no vanishing denominators
+    f = torch.from_numpy(f_h[0]).cuda()
+    Q, K, V = (to_dev(x) for x in synth.qkv(2, 2, n, 64, rng))
+    d_out = torch.randn(Q.shape, device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(3))
+    phi = grf.grf_sample_async(g, f, p_halt, n_walks, seed)
+    sws = torch.empty(4096, dtype=torch.uint8, device="cuda:0")
+    prepared = grf.grf_phi_prepare(phi)
+    prep_bytes = grf.grf_phi_prepare_bytes(n, phi.nnz, phi.n_f)
+    fws = torch.empty(grf.grf_fused_attention_workspace_bytes(2, 2, n, 64, phi.nnz, 2) - prep_bytes, dtype=torch.uint8, device="cuda:0")
+    bws = torch.empty(grf.grf_attention_backward_workspace_bytes(2, 2, n, 64, phi.nnz, 2) - prep_bytes, dtype=torch.uint8, device="cuda:0")
+    results = {}
+
+    def step():
+        grf.grf_sample_async(g, f, p_halt, n_walks, seed, out=phi, workspace=sws)
+        grf.grf_phi_prepare_values(phi, prepared)
+        out, _, den = grf.grf_masked_linear_attention_fused(Q, K, V, phi, "elu1", workspace=fws, prepared=prepared, return_num_den=True)
+        dQ, dK, dV, dphi = grf.grf_masked_linear_attention_backward(Q, K, V, phi, out, den, d_out, "elu1", workspace=bws, prepared=prepared)
+        df = grf.grf_sample_backward(g, f_len, p_halt, n_walks, seed, phi, dphi)
+        results["got"] = (out, dQ, dK, dV, df)
+
+    def reference(ff):
+        ph = grf.grf_sample(g, ff, p_halt, n_walks, seed)
+        out, _, den = grf.grf_masked_linear_attention_fused(Q, K, V, ph, "elu1", return_num_den=True)
+        dQ, dK, dV, dphi = grf.grf_masked_linear_attention_backward(Q, K, V, ph, out, den, d_out, "elu1")
+        return out, dQ, dK, dV, grf.grf_sample_backward(g, f_len, p_halt, n_walks, seed, ph, dphi)
+
+    step()
+    torch.cuda.synchronize()
+    for a, b in zip(results["got"], reference(f_h[0])):
+        assert same(a, b)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    captured = results["got"]
+    for trial in (1, 2, 0, 1):
+        f.copy_(torch.from_numpy(f_h[trial]).cuda())
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in captured]
+        for a, b in zip(got, reference(f_h[trial])):
+            assert same(a, b), trial
