@@ -84,8 +84,12 @@ __global__ __launch_bounds__(256) void asymmetric_kernel(const T* __restrict__ Q
                 p = fmaf(q4.y, feature(k4[u].y, fmap), p);
                 p = fmaf(q4.z, feature(k4[u].z, fmap), p);
                 p = fmaf(q4.w, feature(k4[u].w, fmap), p);
+                if constexpr (LPE == 16) {
+                    p = row_sum16(p);
+                } else {
 #pragma unroll
-                for (int off = 1; off < LPE; off <<= 1) p += __shfl_xor(p, off, kWave);
+                    for (int off = 1; off < LPE; off <<= 1) p += __shfl_xor(p, off, kWave);
+                }
                 const float a = w[u] * p;
                 acc.x = fmaf(a, v4[u].x, acc.x);
                 acc.y = fmaf(a, v4[u].y, acc.y);
@@ -186,10 +190,15 @@ __global__ __launch_bounds__(256) void asymmetric_backward_rows_kernel(const T* 
                 a = fmaf(fq.y, fk.y, a); a = fmaf(fq.z, fk.z, a); a = fmaf(fq.w, fk.w, a);
                 float c = g4.x * (v4[u].x - o4.x);
                 c = fmaf(g4.y, v4[u].y - o4.y, c); c = fmaf(g4.z, v4[u].z - o4.z, c); c = fmaf(g4.w, v4[u].w - o4.w, c);
+                if constexpr (LPE == 16) {
+                    a = row_sum16(a);
+                    c = row_sum16(c);
+                } else {
 #pragma unroll
-                for (int off = 1; off < LPE; off <<= 1) {
-                    a += __shfl_xor(a, off, kWave);
-                    c += __shfl_xor(c, off, kWave);
+                    for (int off = 1; off < LPE; off <<= 1) {
+                        a += __shfl_xor(a, off, kWave);
+                        c += __shfl_xor(c, off, kWave);
+                    }
                 }
                 const float wc = w[u] * c;
                 acc.x = fmaf(wc, fk.x, acc.x);

@@ -55,6 +55,24 @@ __device__ __forceinline__ float feature_grad(float x, int fmap)
     return fmap == GRF_PHI_RELU ? relu : (fmap == GRF_PHI_ELU1 ? elu1 : 1.0f);
 }
 
+// Sum of x over the 16 lanes of a row of the wavefront (lanes 16k .. 16k+15), left in every lane of the row: four
+// row rotations (by 8, 4, 2, 1 lanes) on the vector ALU, no trip through the LDS crossbar.  Every lane adds the same
+// pairs at each step, so the 16 results are one bit pattern.
+template <int CTRL>
+__device__ __forceinline__ float row_rotated(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+
+__device__ __forceinline__ float row_sum16(float x)
+{
+    x += row_rotated<0x128>(x);      // row_ror:8
+    x += row_rotated<0x124>(x);      // row_ror:4
+    x += row_rotated<0x122>(x);      // row_ror:2
+    x += row_rotated<0x121>(x);      // row_ror:1
+    return x;
+}
+
 // N consecutive elements starting at p (p aligned to N elements), widened to fp32.
 template <typename T, int N>
 __device__ __forceinline__ void load_run(const T* __restrict__ p, float (&out)[N])

@@ -288,12 +288,6 @@ __global__ __launch_bounds__(256) void backward_reduce_kernel(long long n, int H
 // row of the wavefront, formed with four row rotations on the vector ALU (no trips through the LDS crossbar, which the
 // one-lane-per-column layout needs ten of per eight entries: with them the kernel ran at 3.8 TB/s against the 5.4 TB/s
 // of its sibling without dot products).
-template <int CTRL>
-__device__ __forceinline__ float row_rotated(float x)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
-}
-
 template <typename T, bool WEIGHTED>
 __global__ __launch_bounds__(256) void backward_reduce64_kernel(long long n, int H, int n_f, long long val_stride,
                                                                 const int32_t* __restrict__ row_ptr, const float* __restrict__ phi_val,
@@ -351,10 +345,7 @@ __global__ __launch_bounds__(256) void backward_reduce64_kernel(long long n, int
                 acc[3] = fmaf(w[u], v[u].w, acc[3]);
                 if constexpr (WEIGHTED) {
                     float dot = fmaf(fx[0], v[u].x, fmaf(fx[1], v[u].y, fmaf(fx[2], v[u].z, fx[3] * v[u].w)));
-                    dot += row_rotated<0x128>(dot);      // row_ror:8, 4, 2, 1: every lane of the row holds the sum
-                    dot += row_rotated<0x124>(dot);
-                    dot += row_rotated<0x122>(dot);
-                    dot += row_rotated<0x121>(dot);
+                    dot = row_sum16(dot);
                     const int t = t0 + GROUPS * u + grp;
                     if (cl == 0 && t < cnt) dphi_part[slice * static_cast<long long>(nnz) + chunk + t] = dot;
                 }
