@@ -107,3 +107,41 @@ def test_backward_short_lists(grf, oracle, name, dtype, feature_map):
     for label, x, r in zip(("dQ", "dK", "dV", "dphi"), host, ref):
         assert np.isfinite(x).all(), label
         assert relerr(x, r) <= TOL[dtype], (label, relerr(x, r))
+
+
+@pytest.mark.parametrize("name", ["1_to_17_and_back", "short_between_long", "window_edges", "random_0_40"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_short_lists_with_one_value_plane_per_head(grf, oracle, name, dtype):
+    """Per-head modulation (Sec. 4): the heads share the pattern, each has its own values, and the planes' stride is the
+    capacity of Phi_hat's buffers, here larger than nnz.  Forward and backward against the CPU checker, head by head."""
+    import torch
+    rng = np.random.default_rng([len(name), 6])
+    n, rp, col, val = synth.columns_of_lengths(PATTERNS[name], rng)
+    if (np.diff(rp) == 0).any():
+        pytest.skip("a row without entries has den = 0: no gradient to compare")
+    H = 3
+    val = np.ravel(val)
+    vals = np.stack([val * rng.uniform(0.5, 1.5, size=val.shape).astype(np.float32) for _ in range(H)])
+    Q, K, V = synth.qkv(2, H, n, 64, np.random.default_rng([len(name), 7]), dtype)
+    ref = oracle.masked_linear_attention(Q, K, V, rp, col, vals)
+    nnz, cap = col.shape[0], col.shape[0] + 37
+    col_pad = np.concatenate([col, np.full(37, -1, np.int32)])
+    vals_pad = np.concatenate([vals, np.full((H, 37), np.nan, np.float32)], axis=1)
+    phi = grf.Phi.from_host(n, rp, col_pad, vals_pad)
+    phi.nnz = nnz
+    assert phi.capacity == cap
+    dev = [to_dev(x, dtype) for x in (Q, K, V)]
+    out, num, den = grf.grf_masked_linear_attention_fused(*dev, phi, "relu", return_num_den=True)
+    tol = TOL[dtype]
+    assert relerr(num.cpu().numpy(), ref["num"]) <= tol and relerr(den.cpu().numpy(), ref["den"]) <= tol
+    out32, den32 = ref["out"].astype(np.float32), ref["den"].astype(np.float32)
+    assert np.isfinite(out32).all() and (den32 > 0).all()
+    d_out = np.random.default_rng([len(name), 8]).standard_normal(Q.shape).astype(np.float32)
+    gref = oracle.masked_linear_attention_backward(Q, K, V, rp, col, vals, out32, den32, d_out, 0)
+    got = grf.grf_masked_linear_attention_backward(*dev, phi, to_dev(out32), to_dev(den32), to_dev(d_out), "relu")
+    host = [t.cpu().numpy() for t in got]
+    assert host[3].shape[0] == H
+    host[3] = host[3][:, :nnz]
+    for label, x, r in zip(("dQ", "dK", "dV", "dphi"), host, gref):
+        assert np.isfinite(x).all(), label
+        assert relerr(x, r) <= tol, (label, relerr(x, r))
