@@ -142,8 +142,11 @@ size_t grf_sample_workspace_bytes(int64_t n, int32_t n_walks, int32_t f_len, int
  *              a first call with capacity 0 (col = val = NULL allowed) is a way to learn nnz.
  * nnz_out      HOST pointer; receives the number of entries.  The call blocks on the stream for this.
  *
- * Rows are assembled in LDS: by one wavefront per node while 1 + n_walks*(f_len-1), the largest possible number of
- * deposits of a row, is at most 768, by a workgroup of 1024 threads per node (a bitonic sorting network) beyond.
+ * Rows are assembled in LDS, by one wavefront per node (ranking by counting) or by a workgroup of 1024 threads per node
+ * (a bitonic sorting network).  With cap = 1 + n_walks*(f_len-1), the largest possible number of deposits of a row: the
+ * wavefront kernel serves cap <= 768, the workgroup kernel cap > 8192, and in between the one that a cost model in n,
+ * n_walks, f_len and p_halt (the expected deposits and hops) says is faster.  The pattern does not depend on the
+ * choice; values differ by the order of their sums.
  * GRF_EUNSUPPORTED if 1 + n_walks*(f_len-1) exceeds 16384 or if the number of entries does not fit int32.
  */
 grf_status grf_sample(const grf_graph* g,
@@ -413,6 +416,14 @@ grf_status grf_sample_backward(const grf_graph* g, int32_t f_len, int32_t n_f,
  * otherwise; on != 0 makes every later call in this process take the 64-bit form, so that it can be tested at small
  * sizes.  Results are the same bits either way. */
 void grf_debug_force_wide_offsets(int32_t on);
+
+/* Testing and tuning aid, not part of the method.  grf_sample, grf_sample_async and grf_sample_backward assemble the
+ * rows of a node with one of two kernels (one wavefront per node, ranking by counting; one workgroup per node, sorting
+ * network), chosen by a cost model from n, n_walks, f_len and p_halt wherever both can serve, that is between 769 and
+ * 8192 possible deposits per node.  which = 1 / 2 makes every later call in this process take the wavefront / the
+ * workgroup kernel in that range, 0 restores the choice.  Pattern and row_ptr are the same bits either way; values
+ * differ by the order of their sums (the workgroup kernel adds in (walk, hop) order). */
+void grf_debug_force_row_kernel(int32_t which);
 
 #ifdef __cplusplus
 }

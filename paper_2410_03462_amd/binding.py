@@ -71,6 +71,8 @@ def lib() -> ctypes.CDLL:
                                        ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]
         L.grf_debug_force_wide_offsets.restype = None
         L.grf_debug_force_wide_offsets.argtypes = [ctypes.c_int32]
+        L.grf_debug_force_row_kernel.restype = None
+        L.grf_debug_force_row_kernel.argtypes = [ctypes.c_int32]
         L.grf_bucket_record_floats.restype = ctypes.c_int64
         L.grf_bucket_record_floats.argtypes = [ctypes.c_int32]
         L.grf_attention_workspace_bytes.restype = ctypes.c_size_t
@@ -380,6 +382,11 @@ def _check_qkv(*ts):
 
 def grf_debug_force_wide_offsets(on: bool) -> None:
     lib().grf_debug_force_wide_offsets(1 if on else 0)
+
+
+def grf_debug_force_row_kernel(which: int) -> None:
+    """0: the library chooses; 1 / 2: the sampler's wavefront / workgroup kernel wherever both can serve."""
+    lib().grf_debug_force_row_kernel(int(which))
 
 
 def grf_bucket_record_floats(d: int) -> int:

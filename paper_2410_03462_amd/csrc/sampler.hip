@@ -6,6 +6,8 @@
 // after an exclusive scan, to write them at their final place, so no worst-case staging buffer
 // exists in HBM.  Walk decisions are integer-only (Philox words, a threshold compare and a
 // multiply-high), hence trajectories and the sparsity pattern do not depend on floating point.
+#include <atomic>
+#include <cmath>
 #include <type_traits>
 
 #include "common.hpp"
@@ -201,12 +203,17 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
             col_out[pos] = c;
             for (int h = 0; h < n_f; ++h) {
                 const float* fh = f + static_cast<long long>(h) * f_len;
-                float acc = 0.0f;
+                // a run is summed in blocks of 32 deposits, so that the rounding of a long run (thousands of walks
+                // ending at one node) grows with run / 32 + 32 terms instead of with the run
+                float acc = 0.0f, part = 0.0f;
+                int in_part = 0;
                 for (int e = r; e < D; ++e) {
                     const int s = perm[e];
                     if (dcol[s] != c) break;
-                    acc = fmaf(dload[s], fh[dhop[s]], acc);
+                    part = fmaf(dload[s], fh[dhop[s]], part);
+                    if (++in_part == 32) { acc += part; part = 0.0f; in_part = 0; }
                 }
+                acc += part;
                 val_out[h * val_stride + pos] = acc / n_float;
             }
         }
@@ -229,8 +236,13 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
             __syncthreads();
             if (has_node) {
                 for (int t = sl; t < f_len; t += W) {
-                    float acc = 0.0f;
-                    for (int r = 0; r < D; ++r) acc += dhop[perm[r]] == t ? gval[r] : 0.0f;
+                    float acc = 0.0f;      // blocks of 64 deposits, as for the values
+                    for (int r0 = 0; r0 < D; r0 += 64) {
+                        const int r1 = min(D, r0 + 64);
+                        float part = 0.0f;
+                        for (int r = r0; r < r1; ++r) part += dhop[perm[r]] == t ? gval[r] : 0.0f;
+                        acc += part;
+                    }
                     df_part[(static_cast<long long>(node) * n_f + h) * f_len + t] = acc / n_float;
                 }
             }
@@ -535,16 +547,56 @@ __global__ __launch_bounds__(kLargeBlock) void rows_large_kernel(GraphView g, Wa
     }
 }
 
-// Rows of more than kLargeThreshold possible deposits take rows_large_kernel: its ordering costs D log^2 D against the
-// D^2 / 64 of the wavefront kernel's ranking by counting.  Measured on a 32 x 32 grid, rows filled to the bound: equal at
-// 800 deposits (0.3 ms), 0.66 against 4.3 ms at 2049, 1.5 against 46 ms at 4951, 1.7 against 245 ms at 8191.
+// Which kernel assembles the rows.  Up to kLargeThreshold possible deposits the wavefront kernel always serves (and the
+// workspace holds no staging areas); beyond kWaveMaxDeposits (its LDS area: 12, in the gradient mode 16 bytes per
+// possible deposit) only the workgroup kernel can.  In between the cheaper one by a cost model, in microseconds per
+// pass, fitted to timings of both kernels on graphs of 1024, 8192 and 32768 nodes, bounds of 769 .. 8191 deposits, with
+// and without halting (it is within 30 % of them, on the high side for both kernels):
+//   wavefront kernel   rounds of (compute units x resident wavefronts) nodes; a round costs the node's hops (the lanes'
+//                      scattered loads: 0.18 per hop) plus the ranking by counting (0.00055 D^2 for D deposits);
+//   workgroup kernel   rounds of kLargeMaxGrid nodes; a round costs the two simulations of the walks (2.0 per step of the
+//                      longest walk, 1.5 per hop of the average one), the barriers of the sorting network (0.4 per
+//                      stage, a stage repeated for every 2048 positions) and 10 of fixed work.
+// D, the hops and the longest walk are expectations under the halting law, so sparse rows of a large bound (many walks
+// that halt early) stay with the wavefront kernel where it is faster (headline graph, 64 walks of up to 15 hops,
+// p_halt = 0.2, bound 961, about 250 deposits: 1.4 against 7.6 ms per call) and rows filled to a large bound go to the
+// workgroup kernel (32 x 32 grid, no halting, 2049 deposits: 0.68 against 4.4 ms; 8191: 1.9 against 244 ms).
 constexpr int kLargeThreshold = 768;
-inline bool large_rows(long long cap) { return cap > kLargeThreshold; }
+constexpr int kWaveMaxDeposits = 8192;
+std::atomic<int> g_force_row_kernel{0};      // testing aid: 1 = wavefront kernel, 2 = workgroup kernel, wherever both can serve
+inline bool large_rows_possible(long long cap) { return cap > kLargeThreshold; }
+inline bool large_rows(long long n, long long cap, int n_walks, int f_len, double p_halt, int bytes_per_deposit)
+{
+    if (cap <= kLargeThreshold) return false;
+    if (cap > kWaveMaxDeposits) return true;
+    const int forced = g_force_row_kernel.load(std::memory_order_relaxed);
+    if (forced == 1) return false;
+    if (forced == 2) return true;
+    const double longest = f_len - 1;
+    const double q = 1.0 - p_halt;
+    double mean_hops = longest, steps = longest;
+    if (p_halt > 0.0) {
+        mean_hops = q > 0.0 ? q * (1.0 - std::pow(q, longest)) / p_halt : 0.0;
+        const double expected_max = q > 0.0 ? std::log(static_cast<double>(n_walks < 2 ? 2 : n_walks)) / -std::log(q) + 1.0 : 1.0;
+        steps = expected_max < longest ? expected_max : longest;
+    }
+    const double hops = n_walks * mean_hops, deposits = 1.0 + hops;
+
+    double resident = std::floor(160.0 * 1024.0 / (static_cast<double>(cap) * bytes_per_deposit));
+    resident = resident < 1.0 ? 1.0 : (resident > 32.0 ? 32.0 : resident);
+    const double wave_us = std::ceil(static_cast<double>(n) / (256.0 * resident)) * (0.18 * hops + 0.00055 * deposits * deposits);
+
+    double positions = 64.0, log_positions = 6.0;      // the network's size: the power of two that covers the deposits
+    while (positions < deposits) { positions *= 2.0; log_positions += 1.0; }
+    const double stages = 0.5 * log_positions * (log_positions + 1.0) * (positions > 2048.0 ? positions / 2048.0 : 1.0);
+    const double large_us = std::ceil(static_cast<double>(n) / kLargeMaxGrid) * (10.0 + 2.0 * steps + 1.5 * mean_hops + 0.4 * stages);
+    return large_us < wave_us;
+}
 inline long long large_grid(long long n) { return n < kLargeMaxGrid ? (n > 0 ? n : 1) : kLargeMaxGrid; }
 // bytes of the workgroups' staging areas (loads, then hops), 0 when the wavefront kernel serves
 inline size_t large_stage_bytes(int64_t n, long long cap)
 {
-    if (!large_rows(cap)) return 0;
+    if (!large_rows_possible(cap)) return 0;
     const size_t slots = static_cast<size_t>(large_grid(n)) * static_cast<size_t>(cap);
     return align_up(slots * sizeof(float)) + align_up(slots * sizeof(uint16_t));
 }
@@ -804,7 +856,7 @@ grf_status sample_impl(const grf_graph* g, const float* f_host, const float* f_d
     const GraphView gv = view_of(g);
 
     // rows with many possible deposits: a workgroup per node, staging areas behind f and the counter
-    const bool large = large_rows(cap_ll);
+    const bool large = large_rows(g->n, cap_ll, n_walks, f_len, p_halt, kDepositBytes);
     unsigned char* stage = ws + align_up(sizeof(float) * static_cast<size_t>(n_f) * f_len) + kAlign;
 
     // pass 1: entries per row, then offsets
@@ -899,7 +951,7 @@ extern "C" grf_status grf_sample_backward(const grf_graph* g, int32_t f_len, int
     float* df_part = static_cast<float*>(workspace);
     const int cap = static_cast<int>(cap_ll);
     unsigned char* stage = static_cast<unsigned char*>(workspace) + df_part_bytes(g->n, f_len, n_f);
-    if (grf_status st = large_rows(cap_ll) ? launch_rows_large<kGrad>(view_of(g), law, n_walks, f_len, n_f, nullptr, cap, phi->row_ptr, nullptr, nullptr,
+    if (grf_status st = large_rows(g->n, cap_ll, n_walks, f_len, p_halt, kDepositBytesGrad) ? launch_rows_large<kGrad>(view_of(g), law, n_walks, f_len, n_f, nullptr, cap, phi->row_ptr, nullptr, nullptr,
                                                                       static_cast<long long>(phi->capacity), dphi_val, df_part, stage, stream)
                                            : launch_rows<kGrad>(view_of(g), law, n_walks, f_len, n_f, nullptr, cap, phi->row_ptr, nullptr, nullptr,
                                                                 static_cast<long long>(phi->capacity), dphi_val, df_part, stream)) return st;
@@ -907,4 +959,9 @@ extern "C" grf_status grf_sample_backward(const grf_graph* g, int32_t f_len, int
                        static_cast<const float*>(df_part), static_cast<long long>(g->n), width, df);
     GRF_LAUNCH_CHECK("df_reduce_kernel");
     return GRF_OK;
+}
+
+extern "C" void grf_debug_force_row_kernel(int32_t which)
+{
+    g_force_row_kernel.store(which == 1 || which == 2 ? which : 0, std::memory_order_relaxed);
 }

@@ -1,7 +1,9 @@
 """Rows of Phi_hat with many possible deposits (needs the GPU): beyond 768 possible deposits per node a workgroup per
-node orders the deposits with a sorting network instead of one wavefront ranking them by counting.  Pattern bit-exact,
-values within 1e-5, against the CPU checker, on both sides of the switch, at the largest supported size, with more nodes
-than workgroups, and through the gradient with respect to f."""
+node can order the deposits with a sorting network instead of one wavefront ranking them by counting; up to 8192 both
+kernels can serve and the library picks one by a cost model, beyond that only the workgroup kernel.  Every test runs
+three times: with the library's choice and with either kernel forced wherever both can serve.  Pattern bit-exact, values
+within 1e-5, against the CPU checker, on both sides of the limits, at the largest supported size, with more nodes than
+workgroups, and through the gradient with respect to f."""
 import numpy as np
 import pytest
 
@@ -20,6 +22,13 @@ def grf():
     from paper_2410_03462_amd import binding
     binding.lib()
     return binding
+
+
+@pytest.fixture(autouse=True, params=["chosen", "wavefront", "workgroup"])
+def row_kernel(request, grf):
+    grf.grf_debug_force_row_kernel({"chosen": 0, "wavefront": 1, "workgroup": 2}[request.param])
+    yield request.param
+    grf.grf_debug_force_row_kernel(0)
 
 
 def relerr(x, ref):
@@ -99,3 +108,23 @@ def test_gradient_with_respect_to_f(grf, oracle, n_walks, f_len, p_halt):
     assert np.all(np.abs(df - want) <= TOL_F32 * np.abs(want) + 2.0 ** -20 * mag)
     df2 = grf.grf_sample_backward(g, f_len, p_halt, n_walks, 21, phi, torch.from_numpy(dphi).cuda()).cpu().numpy()
     assert np.array_equal(df, df2)
+
+
+@pytest.mark.parametrize("n_walks,f_len,p_halt", [(64, 16, 0.2), (100, 51, 0.1), (64, 33, 0.0)])
+def test_both_kernels_give_the_same_pattern(grf, n_walks, f_len, p_halt, row_kernel):
+    """Where both kernels can serve (769 .. 8192 possible deposits): row_ptr and col are the same bits, the values differ
+    by the order of their sums only; the library's own choice is one of the two, bit for bit."""
+    if row_kernel != "chosen":
+        pytest.skip("forces the kernels itself")
+    rng = np.random.default_rng(n_walks)
+    g_host = synth.knn_graph(rng.random((700, 3)), 6, "exp")
+    g = grf.DeviceGraph.from_host(g_host)
+    f = synth.modulation(f_len, rng, n_f=2)
+    got = {}
+    for which in (0, 1, 2):
+        grf.grf_debug_force_row_kernel(which)
+        got[which] = grf.grf_sample(g, f, p_halt, n_walks, 11).to_host()
+    grf.grf_debug_force_row_kernel(0)
+    assert np.array_equal(got[1][0], got[2][0]) and np.array_equal(got[1][1], got[2][1])
+    assert relerr(got[1][2], got[2][2]) <= 2e-6
+    assert any(all(np.array_equal(a, b) for a, b in zip(got[0], got[k])) for k in (1, 2))
