@@ -227,6 +227,8 @@ def main() -> int:
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": round(gather_ms, 4),
                 "copy_1GiB_GBs": round(copy_gbs, 1), "frac_of_copy": round(achieved / copy_gbs, 4)}
+    if traffic is not None:      # the counted bytes over the same time: the counter-based fraction of the HBM peak
+        roofline["frac_counted"] = round(traffic / (gather_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     if traffic is not None and traffic < 0.9 * gather_bytes:
         # a workload whose bucket records of one slice fit L2 re-reads them there: the algorithmic bytes are then a
         # cache rate, and the HBM fraction is the one of the bytes that were counted beyond L2
