@@ -294,6 +294,34 @@ def test_autograd_wrapper_trains_the_modulation(grf, oracle, asymmetric):
     assert loss_of(fv) < l0
 
 
+@pytest.mark.parametrize("asymmetric,per_head", [(False, False), (False, True), (True, False)])
+def test_frozen_walk_attention_equals_the_resampling_wrapper(grf, asymmetric, per_head):
+    """FrozenWalkAttention keeps the pattern of Phi_hat and its column lists between calls and refreshes the values from f
+    on the device; outputs and all gradients are the bits of grf_attention, which samples and rebuilds on every call."""
+    import torch
+    from paper_2410_03462_amd.autograd import FrozenWalkAttention, grf_attention
+    rng = np.random.default_rng(12)
+    g_host = synth.with_weights(synth.grid_graph(17, 19, 8), "sym_norm")
+    g = grf.DeviceGraph.from_host(g_host)
+    H, f_len = 2, 7
+    Q, K, V = (to_dev(x) for x in synth.qkv(2, H, g_host.n, 64, rng))
+    target = to_dev(rng.standard_normal((2, H, g_host.n, 64)).astype(np.float32))
+    layer = FrozenWalkAttention(g, f_len, H if per_head else 1, 0.3, 8, 5, feature_map="elu1", asymmetric=asymmetric)
+    for step in range(3):
+        f0 = np.abs(synth.modulation(f_len, rng, n_f=H if per_head else 1)) + 0.1
+        f0 = f0 if per_head else f0[0]
+        got, want = [], []
+        for fn, sink in ((lambda q, k, v, f: layer(q, k, v, f), got),
+                         (lambda q, k, v, f: grf_attention(q, k, v, f, g, 0.3, 8, 5, "elu1", asymmetric), want)):
+            q, k, v = (x.clone().requires_grad_(True) for x in (Q, K, V))
+            f = torch.tensor(f0, dtype=torch.float32, device="cuda:0", requires_grad=True)
+            out = fn(q, k, v, f)
+            ((out - target) ** 2).sum().backward()
+            sink.extend([out.detach(), q.grad, k.grad, v.grad, f.grad])
+        for a, b in zip(got, want):
+            assert a.shape == b.shape and torch.equal(a, b.to(a.device)), step
+
+
 def test_backward_headline_workload_full_size(grf, oracle):
     """cloud_32k in the launch configuration the benchmark times.
 
