@@ -422,7 +422,9 @@ void grf_debug_force_wide_offsets(int32_t on);
  * network), chosen by a cost model from n, n_walks, f_len and p_halt wherever both can serve, that is between 769 and
  * 8192 possible deposits per node.  which = 1 / 2 makes every later call in this process take the wavefront / the
  * workgroup kernel in that range, 0 restores the choice.  Pattern and row_ptr are the same bits either way; values
- * differ by the order of their sums (the workgroup kernel adds in (walk, hop) order). */
+ * differ by the order of their sums (the workgroup kernel adds in (walk, hop) order).  which = 3 is 1 with the
+ * wavefront kernel ordering deposits by (column, slot) as two words instead of one packed 32-bit key, the form it
+ * otherwise takes only when n * 2^ceil(log2(cap)) exceeds 2^32; same bits as which = 1. */
 void grf_debug_force_row_kernel(int32_t which);
 
 #ifdef __cplusplus

@@ -102,7 +102,17 @@ __global__ __launch_bounds__(256) void walks_kernel(GraphView g, WalkLaw law, in
 // kernel is bound by the latency of the hops' dependent loads, so what matters is how many wavefronts fit a
 // compute unit.
 constexpr int kDepositBytes = 12;
+// testing aid (grf_debug_force_row_kernel): 1 = wavefront kernel, 2 = workgroup kernel wherever both can serve;
+// 3 = wavefront kernel ordering by (column, slot) as two words, the form it takes when they do not fit one
+std::atomic<int> g_force_row_kernel{0};
 constexpr int kDepositBytesGrad = 16;
+
+// rank += (a < b), unsigned, as a compare into the carry flag and an add with carry: two vector instructions (written
+// as `rank += a < b` the comparison goes through a scalar register pair and a select: four, with a wait in between).
+__device__ __forceinline__ void count_below(int& rank, uint32_t a, uint32_t b)
+{
+    asm("v_cmp_lt_u32 vcc, %1, %2\n\tv_addc_co_u32 %0, vcc, 0, %0, vcc" : "+v"(rank) : "v"(a), "v"(b) : "vcc");
+}
 
 // MODE kCount: row_ptr[node] = number of entries of the row.  kFill: entries written at row_ptr[node].
 // kGrad: instead of values, the row's share of dL/df is written to df_part[node][n_f][f_len], where
@@ -112,9 +122,9 @@ enum : int { kCount = 0, kFill = 1, kGrad = 2 };
 // A wavefront serves 64 / W start nodes, W lanes each (W = the smallest of 8, 16, 32, 64 that covers n_walks, so
 // that few lanes idle: the kernel is bound by the latency of the hops' dependent loads, and a wavefront's hops
 // cost the same however many of its lanes walk).  `sub` is the node's slot in the wavefront, `sl` the lane in it.
-template <int MODE, int W>
+template <int MODE, int W, bool PACKED>
 __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int n_walks, int f_len, int n_f,
-                                                  const float* __restrict__ f, int cap,
+                                                  const float* __restrict__ f, int cap, int slot_bits,
                                                   int32_t* __restrict__ row_ptr, int32_t* __restrict__ col_out,
                                                   float* __restrict__ val_out, long long val_stride,
                                                   const float* __restrict__ dphi, float* __restrict__ df_part)
@@ -145,7 +155,16 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
     const uint32_t node = static_cast<uint32_t>(has_node ? node_ll : 0);
 
     // The n_walks zero-hop prefixes all deposit load 1 at the start node: one merged deposit.
-    if (sl == 0 && has_node) { dcol[0] = static_cast<int32_t>(node); dload[0] = static_cast<float>(n_walks); dhop[0] = 0; }
+    // PACKED: dcol holds (column << slot_bits | slot), one unsigned key whose order is the order (column, slot)
+    auto stored = [&](int32_t column, int slot) -> int32_t {
+        if constexpr (PACKED) return static_cast<int32_t>((static_cast<uint32_t>(column) << slot_bits) | static_cast<uint32_t>(slot));
+        else return column;
+    };
+    auto column_of = [&](int32_t held) -> int32_t {
+        if constexpr (PACKED) return static_cast<int32_t>(static_cast<uint32_t>(held) >> slot_bits);
+        else return held;
+    };
+    if (sl == 0 && has_node) { dcol[0] = stored(static_cast<int32_t>(node), 0); dload[0] = static_cast<float>(n_walks); dhop[0] = 0; }
     int base = has_node ? 1 : 0;
     for (int first = 0; first < n_walks; first += W) {
         const uint32_t walk = static_cast<uint32_t>(first + sl);
@@ -161,7 +180,7 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
             const unsigned long long mine = share(mask);
             if (alive) {
                 const int pos = base + below(mine);
-                dcol[pos] = u; dload[pos] = load; dhop[pos] = static_cast<uint16_t>(t);
+                dcol[pos] = stored(u, pos); dload[pos] = load; dhop[pos] = static_cast<uint16_t>(t);
             }
             base += __popcll(mine);
         }
@@ -170,17 +189,38 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
     int d_max = D;        // the largest D of the wavefront: bound of the loops that hold a ballot
 #pragma unroll
     for (int off = W; off < kWave; off <<= 1) d_max = max(d_max, __shfl_xor(d_max, off, kWave));
+    if constexpr (PACKED) {
+        // the ranking reads sixteen keys at a time: the last group is filled up with keys above all others
+        for (int j = D + sl; j < ((D + 15) & ~15); j += W) dcol[j] = -1;
+    }
     __syncthreads();
 
     // Rank by counting: position of deposit s in the order (column, s).
-    for (int s = sl; s < D; s += W) {
-        const int32_t c = dcol[s];
-        int rank = 0;
-        for (int s2 = 0; s2 < D; ++s2) {
-            const int32_t c2 = dcol[s2];
-            rank += static_cast<int>((c2 < c) | ((c2 == c) & (s2 < s)));
+    if constexpr (PACKED) {
+        const uint32_t* key = reinterpret_cast<const uint32_t*>(dcol);
+        for (int s = sl; s < D; s += W) {
+            const uint32_t k = key[s];
+            int rank = 0;
+            for (int s2 = 0; s2 < D; s2 += 16) {      // the region is 16-byte aligned (cap is a multiple of 16)
+                const uint4* k4 = reinterpret_cast<const uint4*>(key + s2);
+                const uint4 a = k4[0], b = k4[1], c = k4[2], d = k4[3];      // four reads in flight, then 32 instructions
+                count_below(rank, a.x, k); count_below(rank, a.y, k); count_below(rank, a.z, k); count_below(rank, a.w, k);
+                count_below(rank, b.x, k); count_below(rank, b.y, k); count_below(rank, b.z, k); count_below(rank, b.w, k);
+                count_below(rank, c.x, k); count_below(rank, c.y, k); count_below(rank, c.z, k); count_below(rank, c.w, k);
+                count_below(rank, d.x, k); count_below(rank, d.y, k); count_below(rank, d.z, k); count_below(rank, d.w, k);
+            }
+            perm[rank] = static_cast<uint16_t>(s);
         }
-        perm[rank] = static_cast<uint16_t>(s);
+    } else {
+        for (int s = sl; s < D; s += W) {
+            const int32_t c = dcol[s];
+            int rank = 0;
+            for (int s2 = 0; s2 < D; ++s2) {
+                const int32_t c2 = dcol[s2];
+                rank += static_cast<int>((c2 < c) | ((c2 == c) & (s2 < s)));
+            }
+            perm[rank] = static_cast<uint16_t>(s);
+        }
     }
     __syncthreads();
 
@@ -191,8 +231,8 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
     for (int r0 = 0; r0 < d_max; r0 += W) {
         const int r = r0 + sl;
         const bool valid = r < D;
-        const int32_t c = valid ? dcol[perm[r]] : -1;
-        const bool head = valid && (r == 0 || dcol[perm[r - 1]] != c);
+        const int32_t c = valid ? column_of(dcol[perm[r]]) : -1;
+        const bool head = valid && (r == 0 || column_of(dcol[perm[r - 1]]) != c);
         const unsigned long long mine = share(__ballot(head));
         if (MODE == kGrad && valid) {
             // entry of Phi_hat that sorted position r belongs to: runs up to and including this lane, minus one
@@ -209,7 +249,7 @@ __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int 
                 int in_part = 0;
                 for (int e = r; e < D; ++e) {
                     const int s = perm[e];
-                    if (dcol[s] != c) break;
+                    if (column_of(dcol[s]) != c) break;
                     part = fmaf(dload[s], fh[dhop[s]], part);
                     if (++in_part == 32) { acc += part; part = 0.0f; in_part = 0; }
                 }
@@ -257,17 +297,25 @@ grf_status launch_rows(const GraphView& gv, const WalkLaw& law, int n_walks, int
                        float* df_part, hipStream_t stream)
 {
     constexpr int kBytes = MODE == kGrad ? kDepositBytesGrad : kDepositBytes;
+    cap = (cap + 15) & ~15;      // the ranking reads sixteen keys at a time, in 16-byte reads: whole groups, aligned areas
+    // (column, slot) as one 32-bit key while the node numbers leave room for the slot bits
+    int slot_bits = 0;
+    while ((1ll << slot_bits) < cap) ++slot_bits;
+    const bool packed = (static_cast<long long>(gv.n) << slot_bits) <= (1ll << 32) && g_force_row_kernel.load(std::memory_order_relaxed) != 3;
     auto launch = [&](auto width) -> grf_status {
         constexpr int W = decltype(width)::value;
         constexpr int P = kWave / W;
         const size_t lds = static_cast<size_t>(P) * cap * kBytes;
-        if (lds > 64 * 1024)
-            GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&rows_kernel<MODE, W>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
         const unsigned blocks = static_cast<unsigned>((static_cast<long long>(gv.n) + P - 1) / P);
-        hipLaunchKernelGGL((rows_kernel<MODE, W>), dim3(blocks), dim3(kWave), lds, stream, gv, law, n_walks, f_len, n_f, f, cap,
-                           row_ptr, col_out, val_out, val_stride, dphi, df_part);
-        GRF_LAUNCH_CHECK("rows_kernel");
-        return GRF_OK;
+        auto go = [&](auto kernel) -> grf_status {
+            if (lds > 64 * 1024)
+                GRF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+            hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kWave), lds, stream, gv, law, n_walks, f_len, n_f, f, cap, slot_bits,
+                               row_ptr, col_out, val_out, val_stride, dphi, df_part);
+            GRF_LAUNCH_CHECK("rows_kernel");
+            return GRF_OK;
+        };
+        return packed ? go(&rows_kernel<MODE, W, true>) : go(&rows_kernel<MODE, W, false>);
     };
     // several nodes per wavefront only while their deposit areas together stay within 5 KB, a wavefront slot's share of
     // a compute unit's 160 KB of LDS: beyond that the areas, not the slots, bound the nodes in flight, and sharing a
@@ -551,26 +599,27 @@ __global__ __launch_bounds__(kLargeBlock) void rows_large_kernel(GraphView g, Wa
 // workspace holds no staging areas); beyond kWaveMaxDeposits (its LDS area: 12, in the gradient mode 16 bytes per
 // possible deposit) only the workgroup kernel can.  In between the cheaper one by a cost model, in microseconds per
 // pass, fitted to timings of both kernels on graphs of 1024, 8192 and 32768 nodes, bounds of 769 .. 8191 deposits, with
-// and without halting (it is within 30 % of them, on the high side for both kernels):
+// and without halting (it is within 25 % of them):
 //   wavefront kernel   rounds of (compute units x resident wavefronts) nodes; a round costs the node's hops (the lanes'
-//                      scattered loads: 0.18 per hop) plus the ranking by counting (0.00055 D^2 for D deposits);
+//                      scattered loads: 0.103 per hop) plus the ranking by counting of its D deposits: 0.000112 D^2 when
+//                      a SIMD holds one wavefront (the LDS reads' latency shows), 0.000013 D^2 per resident wavefront
+//                      of the compute unit when it holds several (two instructions per comparison, no waits);
 //   workgroup kernel   rounds of kLargeMaxGrid nodes; a round costs the two simulations of the walks (2.0 per step of the
 //                      longest walk, 1.5 per hop of the average one), the barriers of the sorting network (0.4 per
 //                      stage, a stage repeated for every 2048 positions) and 10 of fixed work.
 // D, the hops and the longest walk are expectations under the halting law, so sparse rows of a large bound (many walks
 // that halt early) stay with the wavefront kernel where it is faster (headline graph, 64 walks of up to 15 hops,
-// p_halt = 0.2, bound 961, about 250 deposits: 1.4 against 7.6 ms per call) and rows filled to a large bound go to the
-// workgroup kernel (32 x 32 grid, no halting, 2049 deposits: 0.68 against 4.4 ms; 8191: 1.9 against 244 ms).
+// p_halt = 0.2, bound 961, about 250 deposits: 0.8 against 7.6 ms per call) and rows filled to a large bound go to the
+// workgroup kernel (32 x 32 grid, no halting, 2049 deposits: 0.66 against 1.45 ms; 8191: 1.9 against 68 ms).
 constexpr int kLargeThreshold = 768;
 constexpr int kWaveMaxDeposits = 8192;
-std::atomic<int> g_force_row_kernel{0};      // testing aid: 1 = wavefront kernel, 2 = workgroup kernel, wherever both can serve
 inline bool large_rows_possible(long long cap) { return cap > kLargeThreshold; }
 inline bool large_rows(long long n, long long cap, int n_walks, int f_len, double p_halt, int bytes_per_deposit)
 {
     if (cap <= kLargeThreshold) return false;
     if (cap > kWaveMaxDeposits) return true;
     const int forced = g_force_row_kernel.load(std::memory_order_relaxed);
-    if (forced == 1) return false;
+    if (forced == 1 || forced == 3) return false;
     if (forced == 2) return true;
     const double longest = f_len - 1;
     const double q = 1.0 - p_halt;
@@ -582,9 +631,12 @@ inline bool large_rows(long long n, long long cap, int n_walks, int f_len, doubl
     }
     const double hops = n_walks * mean_hops, deposits = 1.0 + hops;
 
-    double resident = std::floor(160.0 * 1024.0 / (static_cast<double>(cap) * bytes_per_deposit));
+    double resident = std::floor(160.0 * 1024.0 / (static_cast<double>((cap + 15) & ~15ll) * bytes_per_deposit));
     resident = resident < 1.0 ? 1.0 : (resident > 32.0 ? 32.0 : resident);
-    const double wave_us = std::ceil(static_cast<double>(n) / (256.0 * resident)) * (0.18 * hops + 0.00055 * deposits * deposits);
+    const double per_unit = std::ceil(static_cast<double>(n) / 256.0);      // nodes of a compute unit: fewer than fit, on a small graph
+    const double sharing = resident < per_unit ? resident : per_unit;
+    const double rank_us = 0.000013 * sharing > 0.000112 ? 0.000013 * sharing : 0.000112;
+    const double wave_us = std::ceil(static_cast<double>(n) / (256.0 * resident)) * (0.103 * hops + rank_us * deposits * deposits);
 
     double positions = 64.0, log_positions = 6.0;      // the network's size: the power of two that covers the deposits
     while (positions < deposits) { positions *= 2.0; log_positions += 1.0; }
@@ -963,5 +1015,5 @@ extern "C" grf_status grf_sample_backward(const grf_graph* g, int32_t f_len, int
 
 extern "C" void grf_debug_force_row_kernel(int32_t which)
 {
-    g_force_row_kernel.store(which == 1 || which == 2 ? which : 0, std::memory_order_relaxed);
+    g_force_row_kernel.store(which >= 1 && which <= 3 ? which : 0, std::memory_order_relaxed);
 }

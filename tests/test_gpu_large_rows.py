@@ -1,7 +1,8 @@
 """Rows of Phi_hat with many possible deposits (needs the GPU): beyond 768 possible deposits per node a workgroup per
 node can order the deposits with a sorting network instead of one wavefront ranking them by counting; up to 8192 both
 kernels can serve and the library picks one by a cost model, beyond that only the workgroup kernel.  Every test runs
-three times: with the library's choice and with either kernel forced wherever both can serve.  Pattern bit-exact, values
+four times: with the library's choice, with either kernel forced wherever both can serve, and with the wavefront kernel
+ordering by (column, slot) as two words (the form it takes when they do not fit one 32-bit key).  Pattern bit-exact, values
 within 1e-5, against the CPU checker, on both sides of the limits, at the largest supported size, with more nodes than
 workgroups, and through the gradient with respect to f."""
 import numpy as np
@@ -24,9 +25,9 @@ def grf():
     return binding
 
 
-@pytest.fixture(autouse=True, params=["chosen", "wavefront", "workgroup"])
+@pytest.fixture(autouse=True, params=["chosen", "wavefront", "workgroup", "wavefront_two_word_keys"])
 def row_kernel(request, grf):
-    grf.grf_debug_force_row_kernel({"chosen": 0, "wavefront": 1, "workgroup": 2}[request.param])
+    grf.grf_debug_force_row_kernel({"chosen": 0, "wavefront": 1, "workgroup": 2, "wavefront_two_word_keys": 3}[request.param])
     yield request.param
     grf.grf_debug_force_row_kernel(0)
 
@@ -121,10 +122,11 @@ def test_both_kernels_give_the_same_pattern(grf, n_walks, f_len, p_halt, row_ker
     g = grf.DeviceGraph.from_host(g_host)
     f = synth.modulation(f_len, rng, n_f=2)
     got = {}
-    for which in (0, 1, 2):
+    for which in (0, 1, 2, 3):
         grf.grf_debug_force_row_kernel(which)
         got[which] = grf.grf_sample(g, f, p_halt, n_walks, 11).to_host()
     grf.grf_debug_force_row_kernel(0)
     assert np.array_equal(got[1][0], got[2][0]) and np.array_equal(got[1][1], got[2][1])
     assert relerr(got[1][2], got[2][2]) <= 2e-6
+    assert all(np.array_equal(a, b) for a, b in zip(got[1], got[3]))      # one key or two words: the same order, the same bits
     assert any(all(np.array_equal(a, b) for a, b in zip(got[0], got[k])) for k in (1, 2))

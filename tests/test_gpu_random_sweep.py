@@ -231,3 +231,25 @@ def test_wide_row_offsets_give_the_same_bits(grf, oracle, index):
     # and the fused forward is right in the first place
     ref = oracle.masked_linear_attention(Q, K, V, rp, col, val, feature_map=2)
     assert relerr(narrow[2], ref["num"]) <= TOL[wl.dtype]
+
+
+@pytest.mark.parametrize("index", [3, 9, 17, 26, 41, 77])
+def test_two_word_deposit_keys_give_the_same_bits(grf, index):
+    """The wavefront kernel orders a node's deposits by (column, slot), as one packed 32-bit key where the node numbers
+    leave room for the slot bits and as two words otherwise (graphs of millions of nodes); forced at small sizes, the
+    two-word form returns the bits of the packed one, for Phi_hat and for the gradient with respect to f."""
+    import torch
+    wl, _ = draw_case(index)
+    g = grf.DeviceGraph.from_host(wl.graph)
+    got = {}
+    try:
+        for which in (1, 3):
+            grf.grf_debug_force_row_kernel(which)
+            phi = grf.grf_sample(g, wl.f, wl.p_halt, wl.n_walks, wl.walk_seed)
+            dphi = torch.linspace(-1.0, 1.0, steps=max(phi.capacity, 1) * phi.n_f, device="cuda:0").reshape(phi.n_f, -1)[:, : phi.capacity].contiguous()
+            df = grf.grf_sample_backward(g, wl.f_len, wl.p_halt, wl.n_walks, wl.walk_seed, phi, dphi)
+            got[which] = phi.to_host() + (df.cpu().numpy(),)
+    finally:
+        grf.grf_debug_force_row_kernel(0)
+    for a, b in zip(got[1], got[3]):
+        assert np.array_equal(a, b)
