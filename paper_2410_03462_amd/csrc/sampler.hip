@@ -688,44 +688,59 @@ __global__ __launch_bounds__(256) void df_reduce_kernel(const float* __restrict_
 
 // ------------------------------------------------------------------------------------ scan / fill
 // Exclusive prefix sum by one workgroup of 1024 threads (the inputs are row, column or cell counts: a few hundred
-// thousand elements at most in practice) over tiles of 1024 * PER elements, which the workgroup holds in registers:
-// every thread requests its PER consecutive elements of the tile at once, as 16-byte loads (one memory round trip per
-// tile, and most inputs are one or two tiles), scans them, and the threads' totals are scanned across the wavefront
-// and the workgroup.
+// thousand elements at most in practice) over tiles of 1024 * PER elements, which the workgroup holds in registers.
+// A wavefront owns 64 * PER consecutive elements of the tile and reads them in PER / 4 steps of one kilobyte, lane l
+// taking the 16 bytes at 4 l of the step (coalesced; all steps' loads are requested at once: one memory round trip per
+// tile, and the next tile's loads are requested before the current one is worked on).  Per step the lanes' sums are scanned across the wavefront and carried into
+// the next step; the wavefronts' totals are scanned through LDS.  Sums are kept in 64 bits so that a total beyond int32
+// is reported as such (outputs saturate).
 template <int PER>
 __global__ __launch_bounds__(1024) void scan_resident_kernel(int32_t* __restrict__ data, long long n, long long* __restrict__ total64)
 {
+    constexpr int STEPS = PER / 4;
     __shared__ long long wave_total[2][16];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid >> 6;
     const bool aligned = (reinterpret_cast<uintptr_t>(data) & 15u) == 0;
+    auto saturated = [](long long x) { return x > 2147483647ll ? 2147483647 : static_cast<int32_t>(x); };
     long long carry = 0;
     int parity = 0;
-    for (long long tile = 0; tile < n; tile += 1024ll * PER, parity ^= 1) {
-        const long long base = tile + static_cast<long long>(tid) * PER;
-        int32_t v[PER];
+    const long long in_tile = static_cast<long long>(wave) * (kWave * PER) + 4 * lane;
+    auto load_tile = [&](long long tile, int32_t (&v)[STEPS][4]) {
 #pragma unroll
-        for (int k = 0; k < PER; k += 4) {
-            const long long idx = base + k;
+        for (int j = 0; j < STEPS; ++j) {
+            const long long idx = tile + in_tile + static_cast<long long>(j) * (4 * kWave);
             if (aligned && idx + 3 < n) {
                 const int4 q = *reinterpret_cast<const int4*>(data + idx);
-                v[k] = q.x; v[k + 1] = q.y; v[k + 2] = q.z; v[k + 3] = q.w;
+                v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
             } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) v[k + j] = (idx + j < n) ? data[idx + j] : 0;
+                for (int k = 0; k < 4; ++k) v[j][k] = (idx + k < n) ? data[idx + k] : 0;
             }
         }
-        long long local = 0;
+    };
+    int32_t v[STEPS][4], ahead[STEPS][4];
+    load_tile(0, v);
+    for (long long tile = 0; tile < n; tile += 1024ll * PER, parity ^= 1) {
+        const long long base = tile + in_tile;
+        // the next tile is requested before this one is worked on (its elements are not written by this tile's stores)
+        if (tile + 1024ll * PER < n) load_tile(tile + 1024ll * PER, ahead);
+        long long before_lane[STEPS];      // sum of the wavefront's elements that precede this lane's four of step j
+        long long wave_sum = 0;
 #pragma unroll
-        for (int k = 0; k < PER; ++k) local += v[k];
-        long long incl = local;
+        for (int j = 0; j < STEPS; ++j) {
+            const long long mine = static_cast<long long>(v[j][0]) + v[j][1] + v[j][2] + v[j][3];
+            long long incl = mine;
 #pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            const long long up = __shfl_up(incl, off, kWave);
-            if (lane >= off) incl += up;
+            for (int off = 1; off < kWave; off <<= 1) {
+                const long long up = __shfl_up(incl, off, kWave);
+                if (lane >= off) incl += up;
+            }
+            before_lane[j] = wave_sum + incl - mine;
+            wave_sum += __shfl(incl, kWave - 1, kWave);
         }
-        if (lane == kWave - 1) wave_total[parity][wave] = incl;
+        if (lane == 0) wave_total[parity][wave] = wave_sum;
         __syncthreads();          // one barrier per tile: the two halves of wave_total alternate
         long long before = 0, tile_total = 0;
 #pragma unroll
@@ -734,28 +749,32 @@ __global__ __launch_bounds__(1024) void scan_resident_kernel(int32_t* __restrict
             if (w < wave) before += t;
             tile_total += t;
         }
-        long long run = carry + before + incl - local;
 #pragma unroll
-        for (int k = 0; k < PER; k += 4) {
-            const long long idx = base + k;
+        for (int j = 0; j < STEPS; ++j) {
+            const long long idx = base + static_cast<long long>(j) * (4 * kWave);
+            long long run = carry + before + before_lane[j];
             int32_t o[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                o[j] = run > 2147483647ll ? 2147483647 : static_cast<int32_t>(run);
-                run += v[k + j];
+            for (int k = 0; k < 4; ++k) {
+                o[k] = saturated(run);
+                run += v[j][k];
             }
             if (aligned && idx + 3 < n) {
                 *reinterpret_cast<int4*>(data + idx) = make_int4(o[0], o[1], o[2], o[3]);
             } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (idx + j < n) data[idx + j] = o[j];
+                for (int k = 0; k < 4; ++k)
+                    if (idx + k < n) data[idx + k] = o[k];
             }
         }
         carry += tile_total;
+#pragma unroll
+        for (int j = 0; j < STEPS; ++j)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[j][k] = ahead[j][k];
     }
     if (tid == 0) {
-        data[n] = carry > 2147483647ll ? 2147483647 : static_cast<int32_t>(carry);
+        data[n] = saturated(carry);
         if (total64 != nullptr) *total64 = carry;
     }
 }
@@ -769,10 +788,7 @@ __global__ __launch_bounds__(256) void fill_kernel(int32_t* __restrict__ data, l
 grf_status exclusive_scan_inplace(int32_t* counts, int64_t n, long long* total64, hipStream_t stream)
 {
     const long long count = static_cast<long long>(n);
-    if (count <= 1024 * 16)
-        hipLaunchKernelGGL(scan_resident_kernel<16>, dim3(1), dim3(1024), 0, stream, counts, count, total64);
-    else
-        hipLaunchKernelGGL(scan_resident_kernel<32>, dim3(1), dim3(1024), 0, stream, counts, count, total64);
+    hipLaunchKernelGGL(scan_resident_kernel<16>, dim3(1), dim3(1024), 0, stream, counts, count, total64);
     GRF_LAUNCH_CHECK("scan_resident_kernel");
     return GRF_OK;
 }

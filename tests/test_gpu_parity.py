@@ -104,10 +104,10 @@ def test_phi_pattern_bit_exact_values_close(grf, oracle, name):
     assert np.array_equal(rp2, rp) and np.array_equal(col2, col) and np.array_equal(val2, val)
 
 
-@pytest.mark.parametrize("n", [1023, 16383, 16384, 16385, 32767, 32769, 65536 + 77, 3 * 32768 + 1])
+@pytest.mark.parametrize("n", [255, 257, 1023, 1025, 16383, 16384, 16385, 32767, 32769, 65536 + 77, 3 * 32768 + 1])
 def test_row_pointers_around_the_prefix_sum_tile_edges(grf, oracle, n):
-    """The row counts go through a prefix sum that works in tiles of 16384 (short inputs) or 32768 elements: node
-    counts on both sides of the tile edges, one tile with a ragged tail, several tiles."""
+    """The row counts go through a prefix sum that works in tiles of 16384 elements, a wavefront on 1024 of them in steps
+    of 256: node counts on both sides of the step, wavefront and tile edges, one tile with a ragged tail, several tiles."""
     g_host = synth.ring_graph(n)
     f = synth.modulation(4, np.random.default_rng(n))
     g = grf.DeviceGraph.from_host(g_host)
@@ -121,6 +121,13 @@ def test_row_pointers_around_the_prefix_sum_tile_edges(grf, oracle, n):
     _, num, den = grf.grf_masked_linear_attention(to_dev(Q), to_dev(K), to_dev(V), grf.Phi.from_host(n, rp0, col0, val0),
                                                   "relu", return_num_den=True)
     assert relerr(num.cpu().numpy(), ref["num"]) <= TOL_F32 and relerr(den.cpu().numpy(), ref["den"]) <= TOL_F32
+    # row pointers that do not start at a multiple of 16 bytes take the prefix sum's element-wise loads: same bits
+    import torch
+    shifted = grf.Phi(n, 0, torch.empty(n + 2, dtype=torch.int32, device="cuda:0")[1:], torch.empty(len(col0), dtype=torch.int32, device="cuda:0"),
+                      torch.empty((1, len(col0)), dtype=torch.float32, device="cuda:0"))
+    assert shifted.row_ptr.data_ptr() % 16 != 0
+    rp3, col3, val3 = grf.grf_sample(g, f, 0.4, 3, 11 + n, out=shifted).to_host()
+    assert np.array_equal(rp3, rp) and np.array_equal(col3, col) and np.array_equal(val3, val)
 
 
 def test_phi_special_cases(grf, oracle):
