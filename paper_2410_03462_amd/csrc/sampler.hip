@@ -317,10 +317,12 @@ grf_status launch_rows(const GraphView& gv, const WalkLaw& law, int n_walks, int
         };
         return packed ? go(&rows_kernel<MODE, W, true>) : go(&rows_kernel<MODE, W, false>);
     };
-    // several nodes per wavefront only while their deposit areas together stay within 5 KB, a wavefront slot's share of
-    // a compute unit's 160 KB of LDS: beyond that the areas, not the slots, bound the nodes in flight, and sharing a
-    // wavefront only stretches each node's sort over fewer lanes (0.68 instead of 0.46 ms at the headline size)
-    auto fits = [&](int width) { return n_walks <= width && static_cast<size_t>(kWave / width) * cap * kBytes <= 5 * 1024; };
+    // several nodes per wavefront only while their deposit areas together stay within 8 KB, somewhat more than a wavefront
+    // slot's share of a compute unit's 160 KB of LDS: beyond that the areas, not the slots, bound the nodes in flight, and
+    // sharing a wavefront only stretches each node's ranking over fewer lanes (measured at the headline graph: 16 walks of
+    // up to 15 hops 0.19 ms with two nodes per wavefront against 0.22 with one; the headline's 32 walks, 12 KB for two
+    // nodes, 0.39 against 0.33 ms)
+    auto fits = [&](int width) { return n_walks <= width && static_cast<size_t>(kWave / width) * cap * kBytes <= 8 * 1024; };
     if (fits(8)) return launch(std::integral_constant<int, 8>{});
     if (fits(16)) return launch(std::integral_constant<int, 16>{});
     if (fits(32)) return launch(std::integral_constant<int, 32>{});
