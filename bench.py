@@ -278,8 +278,9 @@ def main() -> int:
     sampler = {"entry_point": "grf_sample", "median_ms": round(sample_med, 4), "hops": hops, "walks": N * wl.n_walks,
                "hops_per_s": round(hops / (sample_med * 1e-3), 1),
                "alu_bound_hops_per_s": round(alu_hops_per_s, 1), "frac_of_alu_bound": round(hops / (sample_med * 1e-3) / alu_hops_per_s, 4),
-               "note": "latency-bound: a hop is two dependent cache-resident loads per wavefront (row_ptr pair, then col/w), the walks of a "
-                       "node hop in lock step and the kernel runs twice; includes the one host synchronisation that returns nnz"}
+               "note": "bound by vector-instruction issue at low lane use (profiles/sampler_counters_cloud_32k.md): the walks of a node "
+                       "hop in lock step, a wavefront executes every hop and Philox block while few of its lanes still walk, and the "
+                       "kernel runs twice; includes the one host synchronisation that returns nnz"}
 
     # ---- the bucket-fused variant of the attention call on the same inputs: its own numbers, never `value`
     fws = torch.empty(grf.grf_fused_attention_workspace_bytes(B, H, N, d, nnz, phi.n_f), dtype=torch.uint8, device=dev)

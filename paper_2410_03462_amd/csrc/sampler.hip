@@ -24,8 +24,11 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     constexpr uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
-        const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
-        const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+        // both halves of a product from one 32 x 32 -> 64 bit multiply (a quarter-rate instruction, as each of a
+        // separate high and low multiply would be: the walks' arithmetic is mostly these)
+        const uint64_t p0 = static_cast<uint64_t>(M0) * c0, p1 = static_cast<uint64_t>(M1) * c2;
+        const uint32_t hi0 = static_cast<uint32_t>(p0 >> 32), lo0 = static_cast<uint32_t>(p0);
+        const uint32_t hi1 = static_cast<uint32_t>(p1 >> 32), lo1 = static_cast<uint32_t>(p1);
         c0 = hi1 ^ c1 ^ k0;
         c1 = lo1;
         c2 = hi0 ^ c3 ^ k1;
@@ -98,9 +101,8 @@ __global__ __launch_bounds__(256) void walks_kernel(GraphView g, WalkLaw law, in
 // ------------------------------------------------------------------------------------ rows of Phi_hat
 // LDS layout for `cap` deposits: dcol[cap] dload[cap] (4 B each), dhop[cap] perm[cap] (2 B each) = 12 B per
 // deposit, plus dent[cap] (4 B) in the gradient mode.  The deposits stay where the walks put them; the column
-// order is an index permutation (perm[r] = deposit at sorted position r), which keeps the footprint small: the
-// kernel is bound by the latency of the hops' dependent loads, so what matters is how many wavefronts fit a
-// compute unit.
+// order is an index permutation (perm[r] = deposit at sorted position r), which keeps the footprint small, so that
+// enough wavefronts fit a compute unit to cover the hops' dependent loads and keep its vector ALUs issuing.
 constexpr int kDepositBytes = 12;
 // testing aid (grf_debug_force_row_kernel): 1 = wavefront kernel, 2 = workgroup kernel wherever both can serve;
 // 3 = wavefront kernel ordering by (column, slot) as two words, the form it takes when they do not fit one
@@ -120,8 +122,8 @@ __device__ __forceinline__ void count_below(int& rank, uint32_t a, uint32_t b)
 enum : int { kCount = 0, kFill = 1, kGrad = 2 };
 
 // A wavefront serves 64 / W start nodes, W lanes each (W = the smallest of 8, 16, 32, 64 that covers n_walks, so
-// that few lanes idle: the kernel is bound by the latency of the hops' dependent loads, and a wavefront's hops
-// cost the same however many of its lanes walk).  `sub` is the node's slot in the wavefront, `sl` the lane in it.
+// that few lanes idle: the kernel is bound by vector-instruction issue, and a wavefront's hops and Philox blocks
+// cost the same instructions however many of its lanes walk).  `sub` is the node's slot in the wavefront, `sl` the lane in it.
 template <int MODE, int W, bool PACKED>
 __global__ __launch_bounds__(64) void rows_kernel(GraphView g, WalkLaw law, int n_walks, int f_len, int n_f,
                                                   const float* __restrict__ f, int cap, int slot_bits,
